@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the layer-shard hot path on one MI355X.
+
+One "step" = forward + backward of ONE GPU's share (shard 0 of p) of a model-parallel transformer layer plus the
+vocabulary-parallel loss: the replicated layer norms / combines / bias-gradient sums and every shard-0 call
+(QKV GEMM, attention, projection, MLP GEMMs, logits GEMM fused with the cross-entropy partials, and all their
+gradients).  Workload: the 8.3B-shape 1/8 shard (b=8, s=1024, H=3072, 4 local heads of 96, FFN 1536 local, vocab 6400
+local), bf16 storage with fp32 accumulation, synthetic inputs resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job throughput in model TFLOP/s (FLOP convention: GEMM = 2MKN, backward = 2x forward,
+causal attention counted at its algorithmic half, recomputation not counted), a `roofline` object for the dominant
+kernel (the logits GEMM fused with the cross-entropy partials) and a `cpu_baseline` object (the fp64 oracle timed on
+the host cores on a bounded sample).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "layer-shard fwd+bwd TFLOP/s (bf16) and % MFMA peak, 8.3B-shape 1/8 shard"
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (published)
+PEAK_HBM_GBS = 8000.0
+
+
+def shard_flops(cfg, causal_algorithmic=True):
+    """Model FLOPs of one shard's fwd+bwd (same convention as the docstring)."""
+    T, H, d, p = cfg.T, cfg.H, cfg.H // cfg.h, cfg.p
+    hl, Fl, Vl = cfg.h // p, cfg.F // p, cfg.V // p
+    Hl = hl * d
+    gemm = lambda M, K, N: 2.0 * M * K * N
+    att = 2.0 * (2.0 * cfg.b * hl * cfg.s * cfg.s * d)
+    if cfg.causal and causal_algorithmic:
+        att *= 0.5
+    fwd = gemm(T, H, 3 * Hl) + gemm(T, Hl, H) + gemm(T, H, Fl) + gemm(T, Fl, H) + gemm(T, H, Vl) + att
+    return 3.0 * fwd, gemm(T, H, Vl)
+
+
+def cpu_baseline(cfg, sample_b=1):
+    """Time the fp64 oracle (as it stands) on the host cores on a bounded sample: the UNSHARDED layer + loss of the
+    same model shape with batch `sample_b` (all p shards' work for that batch)."""
+    import numpy as np
+    from oracle import layer_oracle as O
+    from paper_1909_08053_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    small = synth.with_batch(cfg, sample_b)
+    inp = synth.make_inputs(small)
+    spec = O.Spec(b=small.b, s=small.s, H=small.H, h=small.h, F=small.F, V=small.V, causal=small.causal,
+                  final_ln=small.final_ln, gelu_tanh=small.gelu_tanh, ln_eps=small.ln_eps)
+    t0 = time.perf_counter()
+    c = O.forward(inp, spec)
+    g = O.backward(inp, c, spec)
+    dt = time.perf_counter() - t0
+    flops = O.model_flops(spec, p=1)["fwd_bwd"]
+    assert np.isfinite(c["loss"]) and np.all(np.isfinite(g["dX"]))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"unsharded {cfg.name} layer+loss fwd+bwd in fp64, batch {sample_b} of {cfg.b} "
+                      f"({flops / 1e12:.3f} model TFLOP in {dt:.1f} s)", "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="gpt2_8p3b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="print per-call timings to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1")
+
+    import torch
+    from paper_1909_08053_amd import binding as B
+    from paper_1909_08053_amd import synth
+    from paper_1909_08053_amd.pipeline import LayerShards
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.lib()   # fail loudly if the HIP library is missing
+    cfg = synth.CONFIGS[args.config]
+    dev = "cuda:0"
+    L = LayerShards(cfg, [0], dev, store_logits=True)
+    L.load_random(seed=cfg.seed)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        L.step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(args.steps):
+        L.step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    loss = float(L.act["loss"][0].item())
+    flops, logits_flops = shard_flops(cfg)
+    dense_flops, _ = shard_flops(cfg, causal_algorithmic=False)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel: the logits GEMM fused with the cross-entropy partials, timed with events on the launch stream
+    # (the bracket also contains the few-microsecond partial-merge kernel that the same call enqueues)
+    a, rep, w0, s0 = L.act, L.rep, L.w[0], L.sh[0]
+    hf = L._hf
+    reps = max(10, args.steps)
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps)]
+    for i in range(reps):
+        e[2 * i].record()
+        B.mlm_vocab_ce_shard_fwd(L.dims[0], hf, w0["E"], rep["tgt"], a["m"][0], a["s"][0], a["t"][0], s0["logits"], L.ws)
+        e[2 * i + 1].record()
+    torch.cuda.synchronize()
+    k_ms = sum(e[2 * i].elapsed_time(e[2 * i + 1]) for i in range(reps)) / reps
+    achieved = logits_flops / (k_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.config, {}).get("logits_ce_fwd_bytes")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                "kernel": "gemm_bf16_kernel<...,EPI_CE> (logits GEMM + cross-entropy partials)",
+                "kernel_ms": k_ms, "flops_per_launch": logits_flops}
+
+    if args.breakdown:
+        breakdown(L, B, cfg)
+
+    out = {"metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"{cfg.name} shard 0 of {cfg.p}: b={cfg.b} s={cfg.s} H={cfg.H} local heads="
+                                  f"{cfg.h // cfg.p} d={cfg.H // cfg.h} F_local={cfg.F // cfg.p} V_local={cfg.V // cfg.p}, "
+                                  f"causal={cfg.causal}, fwd+bwd layer shard + vocab-parallel CE",
+                      "model_tflop_per_step": flops / 1e12, "dense_equivalent_tflop_per_step": dense_flops / 1e12,
+                      "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS, "loss": loss},
+           "roofline": roofline}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+def breakdown(L, B, cfg):
+    """Per-call event timings of one step (stderr); diagnostic only."""
+    import torch
+    names, evs = [], []
+
+    def mark(name):
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record()
+        names.append(name)
+        evs.append(ev)
+
+    orig = {}
+    calls = ["mlm_layernorm_fwd", "mlm_layernorm_bwd", "mlm_combine", "mlm_colsum", "mlm_attn_shard_fwd",
+             "mlm_attn_shard_bwd", "mlm_mlp_shard_fwd", "mlm_mlp_shard_bwd", "mlm_vocab_ce_shard_fwd",
+             "mlm_vocab_ce_merge", "mlm_vocab_ce_shard_bwd"]
+    for c in calls:
+        orig[c] = getattr(B, c)
+
+        def wrap(*a, _c=c, **k):
+            r = orig[_c](*a, **k)
+            mark(_c)
+            return r
+        setattr(B, c, wrap)
+    try:
+        tot = {}
+        for _ in range(5):
+            names.clear(); evs.clear()
+            mark("start")
+            L.step()
+            torch.cuda.synchronize()
+            for i in range(1, len(evs)):
+                tot.setdefault((i, names[i]), []).append(evs[i - 1].elapsed_time(evs[i]))
+        total = 0.0
+        for (i, n), v in sorted(tot.items()):
+            ms = sorted(v)[len(v) // 2]
+            total += ms
+            print(f"  {i:2d} {n:28s} {ms * 1e3:9.1f} us", file=sys.stderr)
+        print(f"  sum {total * 1e3:.1f} us", file=sys.stderr)
+    finally:
+        for c in calls:
+            setattr(B, c, orig[c])
+
+
+if __name__ == "__main__":
+    main()

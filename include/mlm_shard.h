@@ -1,0 +1,235 @@
+/*
+ * mlm_shard.h -- C ABI of the MI355X (gfx950) layer-shard library.
+ *
+ * One GPU's share of a tensor-parallel transformer layer and of the
+ * vocabulary-parallel loss, forward and backward, as formulated in Section 3 of
+ * "Megatron-LM: Training Multi-Billion Parameter Language Models Using Model
+ * Parallelism" (arXiv 1909.08053):
+ *   - MLP block:  Y_r = GeLU(X A_r)  with A split by columns (Eq. 1 and Eq. 3),
+ *                 Z   = sum_r Y_r B_r with B split by rows (partials, then reduce);
+ *   - attention:  Q/K/V GEMMs split by columns so that each head is local to a
+ *                 shard, output projection split by rows (Section 3, Fig. 3b);
+ *   - loss:       logits split by vocabulary, [Y_1, Y_2] = [X E_1, X E_2], fused
+ *                 with the cross entropy so that only b x s scalars are exchanged;
+ *   - f / g:      the conjugate operators (identity / all-reduce) are replaced
+ *                 on a single GPU by mlm_combine and mlm_vocab_ce_merge.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless the comment says "host".
+ *   - Matrices are row-major and dense (leading dimension = number of columns).
+ *     Activations are [T, .] with T = b*s and token index t = batch*s + position.
+ *     Weights are stored [in, out], exactly as the paper writes X A: a column-
+ *     parallel shard is a block of columns, a row-parallel shard a block of rows,
+ *     each passed as its own dense matrix.
+ *   - dims.dtype selects the storage type of every activation / weight / gradient
+ *     tensor: MLM_F32 (float) or MLM_BF16 (bfloat16 storage, fp32 accumulation).
+ *     Statistics (mean, rstd, lse, m, s, t, ce, M, S, loss) are always float.
+ *   - Ownership: the caller owns every buffer, the workspace included.  The library
+ *     allocates nothing, creates no streams and never synchronises; kernels are
+ *     enqueued on the given stream (a hipStream_t passed as void*, NULL = default).
+ *     Inputs are read-only; outputs are fully overwritten unless stated otherwise.
+ *   - Errors: every call returns 0 (MLM_OK) or a negative mlm_status.  Arguments are
+ *     validated on the host before anything is launched, so a failing call has
+ *     launched nothing.  No exceptions cross the ABI and there is no global state.
+ *   - MLM_BF16 requires H, H/p, F/p, V/p and the head size to be multiples of 8 and
+ *     16-byte aligned pointers (MLM_E_ALIGN otherwise).  Supported head sizes:
+ *     64, 96, 128 (MLM_BF16); any multiple of 4 up to 128 (MLM_F32).
+ */
+#ifndef MLM_SHARD_H
+#define MLM_SHARD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Every entry point is exported from the shared library with default visibility. */
+#define MLM_API __attribute__((visibility("default")))
+
+typedef enum mlm_status {
+  MLM_OK = 0,
+  MLM_E_NULL = -1,       /* a required pointer is NULL                              */
+  MLM_E_SHAPE = -2,      /* non-positive size, h % p, F % p, V % p, H % h != 0, r outside [0,p) */
+  MLM_E_DTYPE = -3,      /* dtype is neither MLM_F32 nor MLM_BF16                   */
+  MLM_E_WORKSPACE = -4,  /* workspace smaller than mlm_workspace_bytes reports      */
+  MLM_E_ALIGN = -5,      /* size or pointer alignment requirement of MLM_BF16 violated */
+  MLM_E_HIP = -6,        /* a HIP call or kernel launch failed                      */
+  MLM_E_UNSUPPORTED = -7 /* e.g. head size not compiled in                          */
+} mlm_status;
+
+enum { MLM_F32 = 0, MLM_BF16 = 1 };
+
+/* Global (unsharded) sizes in the paper's notation plus the shard id. */
+typedef struct mlm_dims {
+  int32_t b;         /* batch size                                            */
+  int32_t s;         /* sequence length                                       */
+  int32_t H;         /* hidden size                                           */
+  int32_t h;         /* attention heads (global); head size d = H / h         */
+  int32_t F;         /* MLP inner width (4H in the paper's models)            */
+  int32_t V;         /* padded vocabulary size v                              */
+  int32_t p;         /* number of model-parallel shards                       */
+  int32_t r;         /* this shard, 0 <= r < p                                */
+  int32_t dtype;     /* MLM_F32 or MLM_BF16                                   */
+  int32_t causal;    /* 1: key j visible to query i iff j <= i (GPT-2); 0: bidirectional (BERT) */
+  int32_t gelu_tanh; /* 1: tanh form of GeLU; 0: exact (erf) form             */
+  float ln_eps;      /* layer-norm epsilon                                    */
+} mlm_dims;
+
+/* Which call a workspace size is asked for. */
+enum {
+  MLM_WS_LAYERNORM_BWD = 0,
+  MLM_WS_ATTN_FWD = 1,
+  MLM_WS_ATTN_BWD = 2,
+  MLM_WS_MLP_FWD = 3,
+  MLM_WS_MLP_BWD = 4,
+  MLM_WS_COLSUM = 5,
+  MLM_WS_VOCAB_CE_FWD = 6,
+  MLM_WS_VOCAB_CE_BWD = 7,
+  MLM_WS_COUNT = 8
+};
+
+/* ---- host-side integer helpers ------------------------------------------------ */
+
+/* Shard r's contiguous index range [begin, end) of n items split p ways (Section 3:
+ * heads, MLP columns/rows and vocabulary are all split into equal contiguous blocks;
+ * Section 5.1 pads the vocabulary so that it divides).  begin/end: host pointers.
+ * MLM_E_SHAPE if p <= 0, r outside [0,p), n < 0 or n % p != 0. */
+MLM_API int mlm_shard_range(int64_t n, int32_t p, int32_t r, int64_t* begin, int64_t* end);
+
+/* Bytes of workspace call `which` (MLM_WS_*) needs for `dims`; *bytes is a host
+ * pointer.  A workspace must be 256-byte aligned.  A size of 0 means the call accepts
+ * ws == NULL. */
+MLM_API int mlm_workspace_bytes(const mlm_dims* dims, int32_t which, size_t* bytes);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+MLM_API const char* mlm_status_string(int code);
+
+/* ---- replicated work (Section 3: layer norm and residual are duplicated on every
+ *      GPU rather than computed once and broadcast) ------------------------------- */
+
+/* y = (x - mean) * rstd * gamma + beta per token over H (Section 2.2: layer norm on the
+ * input of the attention and MLP blocks).  x, y: [T,H] dtype; gamma, beta: [H] dtype;
+ * mean, rstd: [T] float outputs (biased variance, rstd = 1/sqrt(var + ln_eps)). */
+MLM_API int mlm_layernorm_fwd(const mlm_dims* dims, const void* x, const void* gamma, const void* beta,
+                      void* y, float* mean, float* rstd, void* stream);
+
+/* Backward of mlm_layernorm_fwd fused with the residual branch:
+ *   dx = residual_grad + d(LN)/dx applied to dy      (residual_grad may be NULL = 0)
+ *   dgamma = sum_t dy * xhat,  dbeta = sum_t dy       ([H] dtype outputs)
+ * dy, x, residual_grad, dx: [T,H] dtype (dx may alias residual_grad or dy).
+ * ws: MLM_WS_LAYERNORM_BWD bytes. */
+MLM_API int mlm_layernorm_bwd(const mlm_dims* dims, const void* dy, const void* x, const void* gamma,
+                      const float* mean, const float* rstd, const void* residual_grad,
+                      void* dx, void* dgamma, void* dbeta, void* ws, size_t ws_bytes, void* stream);
+
+/* The reduction that stands in for the all-reduce of g (forward) and f (backward) on one
+ * GPU (Section 3, Fig. 3): out = sum_i partials[i] + bias + residual.
+ * partials: HOST array of n_partials device pointers, each [T,H] dtype (1 <= n_partials <= 16);
+ * bias: [H] dtype or NULL -- the row-parallel bias, added once after the sum;
+ * residual: [T,H] dtype or NULL; out: [T,H] dtype (may alias residual or a partial). */
+MLM_API int mlm_combine(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                const void* bias, const void* residual, void* out, void* stream);
+
+/* Column sums over tokens, dbias[j] = sum_t dy[t,j]: the gradient of a replicated bias
+ * (output-projection bias, second MLP bias).  dy: [T,H] dtype; dbias: [H] dtype.
+ * ws: MLM_WS_COLSUM bytes. */
+MLM_API int mlm_colsum(const mlm_dims* dims, const void* dy, void* dbias, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- self-attention block of shard r (Section 3, Fig. 3b) ---------------------- */
+
+/* Forward.  h_l = h/p local heads, H_l = h_l * d.
+ *   qkv_r = u Wqkv_r + bqkv_r                [T, 3 H_l]  columns = [Q heads | K heads | V heads],
+ *                                                        each head d contiguous columns
+ *   ctx_r = softmax(mask(Q K^T / sqrt(d))) V  per local head, [T, H_l]
+ *   lse_r = log sum_j exp(score_ij) over the allowed keys, [b, h_l, s] float
+ *   partial_r = ctx_r Wo_r                    [T, H]  (row-parallel partial sum, NO bias)
+ * u: [T,H]; Wqkv_r: [H, 3 H_l]; bqkv_r: [3 H_l] or NULL; Wo_r: [H_l, H];
+ * key_len: [b] int32 or NULL -- keys j >= key_len[batch] are excluded for every query
+ * (BERT-style padding); with causal also j > i is excluded.  Excluded keys get probability
+ * exactly 0.  Every query row must keep at least one key (key_len >= 1).
+ * qkv_r, ctx_r, lse_r are saved for the backward call.  ws: MLM_WS_ATTN_FWD bytes. */
+MLM_API int mlm_attn_shard_fwd(const mlm_dims* dims, const void* u, const void* Wqkv_r, const void* bqkv_r,
+                       const void* Wo_r, const int32_t* key_len,
+                       void* qkv_r, void* ctx_r, float* lse_r, void* partial_r,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Backward.  dx1: [T,H] gradient w.r.t. the block's (already combined) output.
+ * Outputs: dWqkv_r [H, 3 H_l], dbqkv_r [3 H_l], dWo_r [H_l, H], and
+ * du_partial_r [T,H] = d(loss)/du through this shard only (the operand of f's all-reduce).
+ * ws: MLM_WS_ATTN_BWD bytes. */
+MLM_API int mlm_attn_shard_bwd(const mlm_dims* dims, const void* dx1, const void* u, const void* Wqkv_r,
+                       const void* Wo_r, const int32_t* key_len,
+                       const void* qkv_r, const void* ctx_r, const float* lse_r,
+                       void* dWqkv_r, void* dbqkv_r, void* dWo_r, void* du_partial_r,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* ---- MLP block of shard r (Section 3, Eq. 1 and Eq. 3, Fig. 3a) ---------------- */
+
+/* Forward.  F_l = F/p.
+ *   g_r = u2 A_r + a_r       [T, F_l]  pre-activation (saved)
+ *   y_r = GeLU(g_r)          [T, F_l]  (saved)
+ *   partial_r = y_r B_r      [T, H]    (row-parallel partial sum, NO bias)
+ * u2: [T,H]; A_r: [H, F_l]; a_r: [F_l] or NULL; B_r: [F_l, H].  ws: MLM_WS_MLP_FWD bytes. */
+MLM_API int mlm_mlp_shard_fwd(const mlm_dims* dims, const void* u2, const void* A_r, const void* a_r,
+                      const void* B_r, void* g_r, void* y_r, void* partial_r,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* Backward.  dx2: [T,H] gradient w.r.t. the block's combined output.
+ * Outputs: dA_r [H, F_l], da_r [F_l], dB_r [F_l, H], du2_partial_r [T,H].
+ * ws: MLM_WS_MLP_BWD bytes. */
+MLM_API int mlm_mlp_shard_bwd(const mlm_dims* dims, const void* dx2, const void* u2, const void* A_r,
+                      const void* B_r, const void* g_r, const void* y_r,
+                      void* dA_r, void* da_r, void* dB_r, void* du2_partial_r,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---- vocabulary-parallel output embedding fused with the loss (Section 3) ------ */
+
+/* Forward of shard r.  V_l = V/p, shard r owns vocabulary ids [r V_l, (r+1) V_l).
+ *   L_r = hf E_r                               [T, V_l]
+ *   m_r[t] = max_j L_r[t,j];  s_r[t] = sum_j exp(L_r[t,j] - m_r[t])
+ *   t_r[t] = L_r[t, targets[t] - r V_l] if the target id lies in the shard's range, else 0
+ * hf: [T,H]; E_r: [H, V_l]; targets: [T] int32 GLOBAL ids in [0,V);
+ * m_r, s_r, t_r: [T] float outputs -- the only values a multi-GPU run would exchange;
+ * logits_r: [T, V_l] dtype output kept for the backward call, or NULL (backward then
+ * recomputes the logits).  ws: MLM_WS_VOCAB_CE_FWD bytes. */
+MLM_API int mlm_vocab_ce_shard_fwd(const mlm_dims* dims, const void* hf, const void* E_r, const int32_t* targets,
+                           float* m_r, float* s_r, float* t_r, void* logits_r,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* Merge of the per-shard partials (stands in for the all-reduces of the b x s scalars):
+ *   M = max_r m_r;  S = sum_r s_r exp(m_r - M);  ce = log S + M - sum_r t_r;
+ *   loss_out[0] = sum_t w_t ce_t / sum_t w_t;  loss_out[1] = sum_t w_t.
+ * m, s, t: [n_shards, T] float (shard-major, contiguous); loss_w: [T] float weights in {0,1}
+ * or NULL (all ones); ce, M, S: [T] float outputs; loss_out: [2] float output. */
+MLM_API int mlm_vocab_ce_merge(const mlm_dims* dims, const float* m, const float* s, const float* t,
+                       int32_t n_shards, const float* loss_w, float* ce, float* M, float* S,
+                       float* loss_out, void* stream);
+
+/* Backward of shard r.
+ *   dL_r[t,j] = w_t / sum(w) * (exp(L_r[t,j] - M[t]) / S[t] - [j == targets[t] - r V_l])
+ *   dE_r = hf^T dL_r            [H, V_l]
+ *   dhf_partial_r = dL_r E_r^T  [T, H]   (operand of f's all-reduce)
+ * M, S: [T] from mlm_vocab_ce_merge; loss_stats: the [2] array loss_out of the merge (device);
+ * logits_r: the array saved by the forward call -- it is OVERWRITTEN with dL_r -- or NULL,
+ * in which case the logits are recomputed into the workspace.  ws: MLM_WS_VOCAB_CE_BWD bytes. */
+MLM_API int mlm_vocab_ce_shard_bwd(const mlm_dims* dims, const void* hf, const void* E_r, const int32_t* targets,
+                           const float* loss_w, const float* M, const float* S, const float* loss_stats,
+                           void* logits_r, void* dE_r, void* dhf_partial_r,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* ---- the GEMM building block (Section 3: "XA", "YB", "XE") --------------------- */
+
+/* C = op(A) op(B) (+ bias per column), row-major, fp32 accumulation.
+ *   trans_a == 0: A is [M,K] (lda = K);  trans_a == 1: A is stored [K,M] (lda = M)
+ *   trans_b == 0: B is [K,N] (ldb = N);  trans_b == 1: B is stored [N,K] (ldb = K)
+ * C: [M,N]; bias: [N] or NULL.  dtype as in mlm_dims.  This is the kernel the block calls
+ * above are built from (forward: 0/0, input gradient: 0/1, weight gradient: 1/0). */
+MLM_API int mlm_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K,
+             const void* A, const void* B, void* C, const void* bias, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLM_SHARD_H */

@@ -1,0 +1,169 @@
+"""Thin ctypes binding of libmlm_shard.so: same names as include/mlm_shard.h, argument marshalling only.
+
+Tensors are torch CUDA tensors (PyTorch is used for device memory and streams, nothing else); every
+call is enqueued on torch's current stream.  There is no fallback: if the HIP library is missing the
+import of a function raises, loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+MLM_F32, MLM_BF16 = 0, 1
+(WS_LAYERNORM_BWD, WS_ATTN_FWD, WS_ATTN_BWD, WS_MLP_FWD, WS_MLP_BWD, WS_COLSUM,
+ WS_VOCAB_CE_FWD, WS_VOCAB_CE_BWD) = range(8)
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmlm_shard.so")
+
+EXPORTS = ("mlm_shard_range", "mlm_workspace_bytes", "mlm_status_string", "mlm_layernorm_fwd", "mlm_layernorm_bwd",
+           "mlm_combine", "mlm_colsum", "mlm_attn_shard_fwd", "mlm_attn_shard_bwd", "mlm_mlp_shard_fwd",
+           "mlm_mlp_shard_bwd", "mlm_vocab_ce_shard_fwd", "mlm_vocab_ce_merge", "mlm_vocab_ce_shard_bwd", "mlm_gemm")
+
+
+class MlmError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+class Dims(ctypes.Structure):
+    _fields_ = [("b", ctypes.c_int32), ("s", ctypes.c_int32), ("H", ctypes.c_int32), ("h", ctypes.c_int32),
+                ("F", ctypes.c_int32), ("V", ctypes.c_int32), ("p", ctypes.c_int32), ("r", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32), ("gelu_tanh", ctypes.c_int32),
+                ("ln_eps", ctypes.c_float)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_1909_08053_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.mlm_status_string.restype = ctypes.c_char_p
+        L.mlm_status_string.argtypes = [ctypes.c_int]
+        for name in EXPORTS:
+            if name != "mlm_status_string":
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().mlm_status_string(int(code)).decode()
+
+
+def make_dims(b, s, H, h, F, V, p, r, dtype, causal=True, gelu_tanh=True, ln_eps=1e-5) -> Dims:
+    return Dims(int(b), int(s), int(H), int(h), int(F), int(V), int(p), int(r), int(dtype), int(bool(causal)),
+                int(bool(gelu_tanh)), float(ln_eps))
+
+
+def _p(t: Optional[torch.Tensor]):
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _st(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    return ctypes.c_void_p(int(stream))
+
+
+def _ws(ws: Optional[torch.Tensor]):
+    if ws is None:
+        return ctypes.c_void_p(0), ctypes.c_size_t(0)
+    return _p(ws), ctypes.c_size_t(ws.numel() * ws.element_size())
+
+
+def _chk(rc: int, where: str):
+    if rc != 0:
+        raise MlmError(rc, where)
+
+
+def mlm_shard_range(n: int, p: int, r: int):
+    b, e = ctypes.c_int64(0), ctypes.c_int64(0)
+    _chk(lib().mlm_shard_range(ctypes.c_int64(n), ctypes.c_int32(p), ctypes.c_int32(r), ctypes.byref(b),
+                               ctypes.byref(e)), "mlm_shard_range")
+    return b.value, e.value
+
+
+def mlm_workspace_bytes(dims: Dims, which: int) -> int:
+    n = ctypes.c_size_t(0)
+    _chk(lib().mlm_workspace_bytes(ctypes.byref(dims), ctypes.c_int32(which), ctypes.byref(n)), "mlm_workspace_bytes")
+    return n.value
+
+
+def mlm_layernorm_fwd(dims, x, gamma, beta, y, mean, rstd, stream=None):
+    _chk(lib().mlm_layernorm_fwd(ctypes.byref(dims), _p(x), _p(gamma), _p(beta), _p(y), _p(mean), _p(rstd),
+                                 _st(stream)), "mlm_layernorm_fwd")
+
+
+def mlm_layernorm_bwd(dims, dy, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, stream=None):
+    _chk(lib().mlm_layernorm_bwd(ctypes.byref(dims), _p(dy), _p(x), _p(gamma), _p(mean), _p(rstd), _p(residual_grad),
+                                 _p(dx), _p(dgamma), _p(dbeta), *_ws(ws), _st(stream)), "mlm_layernorm_bwd")
+
+
+def mlm_combine(dims, partials: Sequence[torch.Tensor], bias, residual, out, stream=None):
+    n = len(partials)
+    arr = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t in partials])
+    for t in partials:
+        _p(t)
+    _chk(lib().mlm_combine(ctypes.byref(dims), arr, ctypes.c_int32(n), _p(bias), _p(residual), _p(out), _st(stream)),
+         "mlm_combine")
+
+
+def mlm_colsum(dims, dy, dbias, ws, stream=None):
+    _chk(lib().mlm_colsum(ctypes.byref(dims), _p(dy), _p(dbias), *_ws(ws), _st(stream)), "mlm_colsum")
+
+
+def mlm_attn_shard_fwd(dims, u, Wqkv_r, bqkv_r, Wo_r, key_len, qkv_r, ctx_r, lse_r, partial_r, ws=None, stream=None):
+    _chk(lib().mlm_attn_shard_fwd(ctypes.byref(dims), _p(u), _p(Wqkv_r), _p(bqkv_r), _p(Wo_r), _p(key_len), _p(qkv_r),
+                                  _p(ctx_r), _p(lse_r), _p(partial_r), *_ws(ws), _st(stream)), "mlm_attn_shard_fwd")
+
+
+def mlm_attn_shard_bwd(dims, dx1, u, Wqkv_r, Wo_r, key_len, qkv_r, ctx_r, lse_r, dWqkv_r, dbqkv_r, dWo_r,
+                       du_partial_r, ws, stream=None):
+    _chk(lib().mlm_attn_shard_bwd(ctypes.byref(dims), _p(dx1), _p(u), _p(Wqkv_r), _p(Wo_r), _p(key_len), _p(qkv_r),
+                                  _p(ctx_r), _p(lse_r), _p(dWqkv_r), _p(dbqkv_r), _p(dWo_r), _p(du_partial_r),
+                                  *_ws(ws), _st(stream)), "mlm_attn_shard_bwd")
+
+
+def mlm_mlp_shard_fwd(dims, u2, A_r, a_r, B_r, g_r, y_r, partial_r, ws=None, stream=None):
+    _chk(lib().mlm_mlp_shard_fwd(ctypes.byref(dims), _p(u2), _p(A_r), _p(a_r), _p(B_r), _p(g_r), _p(y_r),
+                                 _p(partial_r), *_ws(ws), _st(stream)), "mlm_mlp_shard_fwd")
+
+
+def mlm_mlp_shard_bwd(dims, dx2, u2, A_r, B_r, g_r, y_r, dA_r, da_r, dB_r, du2_partial_r, ws, stream=None):
+    _chk(lib().mlm_mlp_shard_bwd(ctypes.byref(dims), _p(dx2), _p(u2), _p(A_r), _p(B_r), _p(g_r), _p(y_r), _p(dA_r),
+                                 _p(da_r), _p(dB_r), _p(du2_partial_r), *_ws(ws), _st(stream)), "mlm_mlp_shard_bwd")
+
+
+def mlm_vocab_ce_shard_fwd(dims, hf, E_r, targets, m_r, s_r, t_r, logits_r, ws, stream=None):
+    _chk(lib().mlm_vocab_ce_shard_fwd(ctypes.byref(dims), _p(hf), _p(E_r), _p(targets), _p(m_r), _p(s_r), _p(t_r),
+                                      _p(logits_r), *_ws(ws), _st(stream)), "mlm_vocab_ce_shard_fwd")
+
+
+def mlm_vocab_ce_merge(dims, m, s, t, n_shards, loss_w, ce, M, S, loss_out, stream=None):
+    _chk(lib().mlm_vocab_ce_merge(ctypes.byref(dims), _p(m), _p(s), _p(t), ctypes.c_int32(n_shards), _p(loss_w),
+                                  _p(ce), _p(M), _p(S), _p(loss_out), _st(stream)), "mlm_vocab_ce_merge")
+
+
+def mlm_vocab_ce_shard_bwd(dims, hf, E_r, targets, loss_w, M, S, loss_stats, logits_r, dE_r, dhf_partial_r, ws,
+                           stream=None):
+    _chk(lib().mlm_vocab_ce_shard_bwd(ctypes.byref(dims), _p(hf), _p(E_r), _p(targets), _p(loss_w), _p(M), _p(S),
+                                      _p(loss_stats), _p(logits_r), _p(dE_r), _p(dhf_partial_r), *_ws(ws),
+                                      _st(stream)), "mlm_vocab_ce_shard_bwd")
+
+
+def mlm_gemm(dtype, trans_a, trans_b, M, N, K, A, B, C, bias=None, stream=None):
+    _chk(lib().mlm_gemm(ctypes.c_int32(dtype), ctypes.c_int32(trans_a), ctypes.c_int32(trans_b), ctypes.c_int64(M),
+                        ctypes.c_int64(N), ctypes.c_int64(K), _p(A), _p(B), _p(C), _p(bias), _st(stream)), "mlm_gemm")

@@ -1,0 +1,497 @@
+// bf16 MFMA attention over a shard's local heads (gfx950): forward with a streaming softmax, and a
+// two-kernel backward (dQ per query block; dK/dV per key block) that recomputes the probabilities from
+// the saved log-sum-exp.  Nothing of size s x s touches HBM and no atomics are used, so results are
+// deterministic.
+//
+// Layout trick shared by the three kernels: score tiles are computed TRANSPOSED relative to the row that a
+// wave owns, so that v_mfma_f32_32x32x16_bf16 leaves, in every lane, 16 score values that all belong to ONE
+// owned row (a query in forward / dQ, a key in dK/dV).  Row statistics (max, sum, lse, delta) are then
+// per-lane scalars (plus one cross-half shuffle), and the probability registers are already in the operand
+// layout of the second MFMA (k index = the other sequence axis) -- P never goes through LDS.  The operand
+// that must be read with k along the sequence axis (V, K, Q, dO "transposed") is transposed in registers
+// (8x8 byte-permute blocks) on its way from HBM to LDS.
+//
+// Mask: allowed(i, j) = (j < key_len[b]) && (!causal || j <= i); excluded entries get probability exactly 0.
+#include "gemm_bf16.h"   // transpose8x8
+
+namespace mlm {
+
+constexpr int ATILE = 64;           // rows of the streamed tile (keys in fwd/dQ, queries in dK/dV)
+constexpr int ATS = ATILE + 8;      // LDS stride of a transposed tile [D][ATILE]
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// A [64][D] tile (row stride ld in HBM) fetched as 8x8 blocks: eight 16-byte row pieces per block.
+template <int D>
+struct TileBlocks {
+  static constexpr int BLKS = (ATILE / 8) * (D / 8);
+  static constexpr int PER = (BLKS + 255) / 256;
+  uint4 reg[PER][8];
+  // rows >= nvalid (relative to row0 = 0 of P) are zero-filled
+  __device__ __forceinline__ void load(const bf16* __restrict__ P, int ld, int row0, int nrows, int tid) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int blk = tid + i * 256;
+      if (blk < BLKS) {
+        const int rb = blk & 7, cb = blk >> 3;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int r = row0 + rb * 8 + j;
+          if (r < nrows) reg[i][j] = *reinterpret_cast<const uint4*>(P + (size_t)r * ld + cb * 8);
+          else reg[i][j] = make_uint4(0, 0, 0, 0);
+        }
+      }
+    }
+  }
+  __device__ __forceinline__ void store_rows(bf16* s, int tid) const {   // s: [64][D+8]
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int blk = tid + i * 256;
+      if (blk < BLKS) {
+        const int rb = blk & 7, cb = blk >> 3;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<uint4*>(s + (rb * 8 + j) * (D + 8) + cb * 8) = reg[i][j];
+      }
+    }
+  }
+  __device__ __forceinline__ void store_transposed(bf16* s, int tid) const {   // s: [D][ATS]
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int blk = tid + i * 256;
+      if (blk < BLKS) {
+        const int rb = blk & 7, cb = blk >> 3;
+        uint4 o[8];
+        transpose8x8(reg[i], o);
+#pragma unroll
+        for (int n = 0; n < 8; ++n) *reinterpret_cast<uint4*>(s + (cb * 8 + n) * ATS + rb * 8) = o[n];
+      }
+    }
+  }
+};
+
+// MFMA operand whose k index runs along the tile's 64 rows (transposed LDS tile [D][ATS]): 16-row chunk c,
+// k-slot (lh, e) <-> row 16c + 8 (e/4) + 4 lh + e%4, which is exactly how a score accumulator lays out its rows.
+__device__ __forceinline__ bf16x8 read_tr_frag(const bf16* st, int col, int c, int lh) {
+  const bf16x4 lo = *reinterpret_cast<const bf16x4*>(st + col * ATS + 16 * c + 4 * lh);
+  const bf16x4 hi = *reinterpret_cast<const bf16x4*>(st + col * ATS + 16 * c + 8 + 4 * lh);
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { r[e] = lo[e]; r[4 + e] = hi[e]; }
+  return r;
+}
+
+__device__ __forceinline__ bf16x8 pack8(const floatx16& v, int off) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (bf16)v[off + e];
+  return r;
+}
+
+// ------------------------------------------------------------------------------------------ forward
+template <int D>
+__global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnArgs a) {
+  constexpr int BQ = 128, KS = D + 8;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16* sK = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
+  bf16* sVt = sK + ATILE * KS;                    // [D][72]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int nqb = (a.s + BQ - 1) / BQ;
+  const int qb = nqb - 1 - blockIdx.x;            // longest (causal) blocks first
+  const int hd = blockIdx.y, bi = blockIdx.z;
+  const int ld = 3 * a.hl * D;
+  const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
+  const int klen = a.key_len ? min(a.key_len[bi], a.s) : a.s;
+  const int q0 = qb * BQ, qw0 = q0 + wave * 32, qi = qw0 + l32;
+
+  bf16x8 qf[D / 16];
+  {
+    const bf16* qrow = base + (size_t)min(qi, a.s - 1) * ld + hd * D;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + lh * 8);
+  }
+  floatx16 o[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+  int kv_end = klen;
+  if (a.causal) kv_end = min(kv_end, q0 + BQ);
+  const int nt = (kv_end + ATILE - 1) / ATILE;
+  const float sc = kLog2e / sqrtf((float)D);
+  const bf16* Kb = base + (a.hl + hd) * D;
+  const bf16* Vb = base + (2 * a.hl + hd) * D;
+  TileBlocks<D> lk, lv;
+  lk.load(Kb, ld, 0, a.s, tid);
+  lv.load(Vb, ld, 0, a.s, tid);
+  for (int t = 0; t < nt; ++t) {
+    const int k0 = t * ATILE;
+    __syncthreads();
+    lk.store_rows(sK, tid);
+    lv.store_transposed(sVt, tid);
+    __syncthreads();
+    if (t + 1 < nt) {
+      lk.load(Kb, ld, k0 + ATILE, a.s, tid);
+      lv.load(Vb, ld, k0 + ATILE, a.s, tid);
+    }
+    if (a.causal && k0 > qw0 + 31) continue;     // tile entirely above this wave's diagonal (wave-uniform)
+    floatx16 sacc[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[kt][e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (kt * 32 + l32) * KS + ks * 16 + lh * 8);
+        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kt], 0, 0, 0);
+      }
+    }
+    const bool need_mask = (a.causal && k0 + ATILE - 1 > qw0) || (k0 + ATILE > klen);
+    float mt = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        float v = sacc[kt][e] * sc;
+        if (need_mask) {
+          const int key = k0 + kt * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+          if (key >= klen || (a.causal && key > qi)) v = -INFINITY;
+        }
+        sacc[kt][e] = v;
+        mt = fmaxf(mt, v);
+      }
+    mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+    const float mn = fmaxf(m, mt);               // finite from the first tile on: key 0 is allowed for every query
+    const float corr = __builtin_amdgcn_exp2f(m - mn);
+    lsum *= corr;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float p = __builtin_amdgcn_exp2f(sacc[kt][e] - mn);
+        sacc[kt][e] = p;
+        lsum += p;
+      }
+    m = mn;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[dt][e] *= corr;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bf16x8 pf = pack8(sacc[c >> 1], 8 * (c & 1));
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) {
+        const bf16x8 vf = read_tr_frag(sVt, dt * 32 + l32, c, lh);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[dt], 0, 0, 0);
+      }
+    }
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  if (qi < a.s) {
+    const float inv = 1.0f / lsum;
+    bf16* crow = (bf16*)a.ctx + ((size_t)bi * a.s + qi) * (a.hl * D) + hd * D;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ov[e] = (bf16)(o[dt][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(crow + dt * 32 + 8 * g + 4 * lh) = ov;
+      }
+    if (lh == 0) a.lse[((size_t)bi * a.hl + hd) * a.s + qi] = (m + log2f(lsum)) * kLn2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ backward: dQ
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
+  constexpr int BQ = 128, KS = D + 8;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16* sK = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
+  bf16* sV = sK + ATILE * KS;                     // [64][D+8]
+  bf16* sKt = sV + ATILE * KS;                    // [D][72]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int nqb = (a.s + BQ - 1) / BQ;
+  const int qb = nqb - 1 - blockIdx.x;
+  const int hd = blockIdx.y, bi = blockIdx.z;
+  const int ld = 3 * a.hl * D;
+  const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
+  const int klen = a.key_len ? min(a.key_len[bi], a.s) : a.s;
+  const int q0 = qb * BQ, qw0 = q0 + wave * 32, qi = qw0 + l32;
+  const int qc = min(qi, a.s - 1);
+
+  bf16x8 qf[D / 16], dof[D / 16];
+  {
+    const bf16* qrow = base + (size_t)qc * ld + hd * D;
+    const bf16* drow = (const bf16*)a.dctx + ((size_t)bi * a.s + qc) * (a.hl * D) + hd * D;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + lh * 8);
+      dof[ks] = *reinterpret_cast<const bf16x8*>(drow + ks * 16 + lh * 8);
+    }
+  }
+  const float lse2 = a.lse[((size_t)bi * a.hl + hd) * a.s + qc] * kLog2e;
+  const float dl = a.delta[((size_t)bi * a.hl + hd) * a.s + qc];
+  floatx16 dq[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dq[dt][e] = 0.f;
+  int kv_end = klen;
+  if (a.causal) kv_end = min(kv_end, q0 + BQ);
+  const int nt = (kv_end + ATILE - 1) / ATILE;
+  const float scale = 1.0f / sqrtf((float)D);
+  const float sc = kLog2e * scale;
+  const bf16* Kb = base + (a.hl + hd) * D;
+  const bf16* Vb = base + (2 * a.hl + hd) * D;
+  TileBlocks<D> lk, lv;
+  lk.load(Kb, ld, 0, a.s, tid);
+  lv.load(Vb, ld, 0, a.s, tid);
+  for (int t = 0; t < nt; ++t) {
+    const int k0 = t * ATILE;
+    __syncthreads();
+    lk.store_rows(sK, tid);
+    lk.store_transposed(sKt, tid);
+    lv.store_rows(sV, tid);
+    __syncthreads();
+    if (t + 1 < nt) {
+      lk.load(Kb, ld, k0 + ATILE, a.s, tid);
+      lv.load(Vb, ld, k0 + ATILE, a.s, tid);
+    }
+    if (a.causal && k0 > qw0 + 31) continue;
+    floatx16 sacc[2], pacc[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { sacc[kt][e] = 0.f; pacc[kt][e] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (kt * 32 + l32) * KS + ks * 16 + lh * 8);
+        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sV + (kt * 32 + l32) * KS + ks * 16 + lh * 8);
+        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kt], 0, 0, 0);    // S^T[key][query]
+        pacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], pacc[kt], 0, 0, 0);   // dP^T[key][query]
+      }
+    }
+    const bool need_mask = (a.causal && k0 + ATILE - 1 > qw0) || (k0 + ATILE > klen);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        float p = __builtin_amdgcn_exp2f(sacc[kt][e] * sc - lse2);
+        if (need_mask) {
+          const int key = k0 + kt * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+          if (key >= klen || (a.causal && key > qi)) p = 0.f;
+        }
+        sacc[kt][e] = p * (pacc[kt][e] - dl);     // dS^T
+      }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bf16x8 dsf = pack8(sacc[c >> 1], 8 * (c & 1));
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) {
+        const bf16x8 ktf = read_tr_frag(sKt, dt * 32 + l32, c, lh);
+        dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf, dq[dt], 0, 0, 0);          // dQ^T[dcol][query]
+      }
+    }
+  }
+  if (qi < a.s) {
+    bf16* orow = (bf16*)a.dqkv + ((size_t)bi * a.s + qi) * ld + hd * D;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ov[e] = (bf16)(dq[dt][4 * g + e] * scale);
+        *reinterpret_cast<bf16x4*>(orow + dt * 32 + 8 * g + 4 * lh) = ov;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ backward: dK, dV
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
+  constexpr int BKB = 128, KS = D + 8;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16* sQ = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
+  bf16* sdO = sQ + ATILE * KS;                    // [64][D+8]
+  bf16* sQt = sdO + ATILE * KS;                   // [D][72]
+  bf16* sdOt = sQt + D * ATS;                     // [D][72]
+  float* sLse = reinterpret_cast<float*>(sdOt + D * ATS);   // [64] (log2 units; +inf for rows past s)
+  float* sDl = sLse + ATILE;                                // [64]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int kb = blockIdx.x;                       // key block; for causal, block 0 has the most queries: first
+  const int hd = blockIdx.y, bi = blockIdx.z;
+  const int ld = 3 * a.hl * D;
+  const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
+  const int klen = a.key_len ? min(a.key_len[bi], a.s) : a.s;
+  const int kb0 = kb * BKB, kw0 = kb0 + wave * 32, kj = kw0 + l32;
+  const int kc = min(kj, a.s - 1);
+
+  bf16x8 kf[D / 16], vf[D / 16];
+  {
+    const bf16* krow = base + (size_t)kc * ld + (a.hl + hd) * D;
+    const bf16* vrow = base + (size_t)kc * ld + (2 * a.hl + hd) * D;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8*>(krow + ks * 16 + lh * 8);
+      vf[ks] = *reinterpret_cast<const bf16x8*>(vrow + ks * 16 + lh * 8);
+    }
+  }
+  floatx16 dk[D / 32], dv[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dk[dt][e] = 0.f; dv[dt][e] = 0.f; }
+  const float scale = 1.0f / sqrtf((float)D);
+  const float sc = kLog2e * scale;
+  const int nqt = (a.s + ATILE - 1) / ATILE;
+  int qt0 = a.causal ? kb0 / ATILE : 0;
+  if (kb0 >= klen) qt0 = nqt;                     // every key of the block is padding: gradients are zero
+  const bf16* Qb = base + hd * D;
+  const bf16* dOb = (const bf16*)a.dctx + (size_t)bi * a.s * (a.hl * D) + hd * D;
+  const float* lse_b = a.lse + ((size_t)bi * a.hl + hd) * a.s;
+  const float* dl_b = a.delta + ((size_t)bi * a.hl + hd) * a.s;
+  TileBlocks<D> lq, ldo;
+  float lse_next = 0.f, dl_next = 0.f;
+  if (qt0 < nqt) {
+    lq.load(Qb, ld, qt0 * ATILE, a.s, tid);
+    ldo.load(dOb, a.hl * D, qt0 * ATILE, a.s, tid);
+    if (tid < ATILE) {
+      const int q = qt0 * ATILE + tid;
+      lse_next = q < a.s ? lse_b[q] * kLog2e : INFINITY;
+      dl_next = q < a.s ? dl_b[q] : 0.f;
+    }
+  }
+  for (int qt = qt0; qt < nqt; ++qt) {
+    const int q0 = qt * ATILE;
+    __syncthreads();
+    lq.store_rows(sQ, tid);
+    lq.store_transposed(sQt, tid);
+    ldo.store_rows(sdO, tid);
+    ldo.store_transposed(sdOt, tid);
+    if (tid < ATILE) { sLse[tid] = lse_next; sDl[tid] = dl_next; }
+    __syncthreads();
+    if (qt + 1 < nqt) {
+      lq.load(Qb, ld, q0 + ATILE, a.s, tid);
+      ldo.load(dOb, a.hl * D, q0 + ATILE, a.s, tid);
+      if (tid < ATILE) {
+        const int q = q0 + ATILE + tid;
+        lse_next = q < a.s ? lse_b[q] * kLog2e : INFINITY;
+        dl_next = q < a.s ? dl_b[q] : 0.f;
+      }
+    }
+    if (a.causal && q0 + ATILE - 1 < kw0) continue;   // every query of the tile precedes this wave's keys
+    floatx16 sacc[2], pacc[2];
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { sacc[qs][e] = 0.f; pacc[qs][e] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8 qfr = *reinterpret_cast<const bf16x8*>(sQ + (qs * 32 + l32) * KS + ks * 16 + lh * 8);
+        const bf16x8 dofr = *reinterpret_cast<const bf16x8*>(sdO + (qs * 32 + l32) * KS + ks * 16 + lh * 8);
+        sacc[qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr, kf[ks], sacc[qs], 0, 0, 0);    // S[query][key]
+        pacc[qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dofr, vf[ks], pacc[qs], 0, 0, 0);   // dP[query][key]
+      }
+    }
+    const bool need_mask = a.causal && q0 < kw0 + 31;
+    const bool key_ok = kj < klen;
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int qoff = qs * 32 + 8 * g + 4 * lh;
+        const float4 l4 = *reinterpret_cast<const float4*>(sLse + qoff);
+        const float4 d4 = *reinterpret_cast<const float4*>(sDl + qoff);
+        const float lv4[4] = {l4.x, l4.y, l4.z, l4.w};
+        const float dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float p = __builtin_amdgcn_exp2f(sacc[qs][4 * g + e] * sc - lv4[e]);
+          if (!key_ok || (need_mask && kj > q0 + qoff + e)) p = 0.f;
+          sacc[qs][4 * g + e] = p;                                   // P
+          pacc[qs][4 * g + e] = p * (pacc[qs][4 * g + e] - dv4[e]);  // dS
+        }
+      }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bf16x8 pf = pack8(sacc[c >> 1], 8 * (c & 1));
+      const bf16x8 dsf = pack8(pacc[c >> 1], 8 * (c & 1));
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) {
+        const bf16x8 dotf = read_tr_frag(sdOt, dt * 32 + l32, c, lh);
+        const bf16x8 qtf = read_tr_frag(sQt, dt * 32 + l32, c, lh);
+        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dotf, pf, dv[dt], 0, 0, 0);    // dV^T[dcol][key]
+        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, dsf, dk[dt], 0, 0, 0);    // dK^T[dcol][key]
+      }
+    }
+  }
+  if (kj < a.s) {
+    bf16* krow = (bf16*)a.dqkv + ((size_t)bi * a.s + kj) * ld + (a.hl + hd) * D;
+    bf16* vrow = (bf16*)a.dqkv + ((size_t)bi * a.s + kj) * ld + (2 * a.hl + hd) * D;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 ok, ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          ok[e] = (bf16)(dk[dt][4 * g + e] * scale);
+          ov[e] = (bf16)dv[dt][4 * g + e];
+        }
+        *reinterpret_cast<bf16x4*>(krow + dt * 32 + 8 * g + 4 * lh) = ok;
+        *reinterpret_cast<bf16x4*>(vrow + dt * 32 + 8 * g + 4 * lh) = ov;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ launchers
+bool attn_bf16_supported(int d) { return d == 64 || d == 96 || d == 128; }
+
+template <int D>
+static hipError_t launch_fwd_d(const AttnArgs& a, hipStream_t st) {
+  const size_t lds = ((size_t)ATILE * (D + 8) + (size_t)D * ATS) * 2;
+  dim3 grid((a.s + 127) / 128, a.hl, a.b);
+  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), grid, dim3(256), lds, st, a);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_bwd_d(const AttnArgs& a, hipStream_t st) {
+  dim3 grid((a.s + 127) / 128, a.hl, a.b);
+  const size_t lds_q = ((size_t)2 * ATILE * (D + 8) + (size_t)D * ATS) * 2;
+  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), grid, dim3(256), lds_q, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t lds_kv = ((size_t)2 * ATILE * (D + 8) + (size_t)2 * D * ATS) * 2 + 2 * ATILE * sizeof(float);
+  if (lds_kv > 64 * 1024) {
+    e = hipFuncSetAttribute((const void*)attn_bwd_dkv_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_kv);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D>), grid, dim3(256), lds_kv, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t st) {
+  switch (a.d) {
+    case 64: return launch_fwd_d<64>(a, st);
+    case 96: return launch_fwd_d<96>(a, st);
+    case 128: return launch_fwd_d<128>(a, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_attn_bwd_bf16(const AttnArgs& a, hipStream_t st) {
+  switch (a.d) {
+    case 64: return launch_bwd_d<64>(a, st);
+    case 96: return launch_bwd_d<96>(a, st);
+    case 128: return launch_bwd_d<128>(a, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace mlm

@@ -1,0 +1,153 @@
+// Internal declarations shared by the HIP translation units of libmlm_shard (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "mlm_shard.h"
+
+namespace mlm {
+
+typedef __bf16 bf16;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }   // round to nearest even
+
+// 16-byte vector of storage elements: 4 floats or 8 bf16.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  float4 raw;
+  __device__ __forceinline__ void load(const float* p) { raw = *reinterpret_cast<const float4*>(p); }
+  __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = raw; }
+  __device__ __forceinline__ float get(int i) const { return reinterpret_cast<const float*>(&raw)[i]; }
+  __device__ __forceinline__ void set(int i, float v) { reinterpret_cast<float*>(&raw)[i] = v; }
+};
+template <> struct Vec16<bf16> {
+  static constexpr int N = 8;
+  bf16x8 raw;
+  __device__ __forceinline__ void load(const bf16* p) { raw = *reinterpret_cast<const bf16x8*>(p); }
+  __device__ __forceinline__ void store(bf16* p) const { *reinterpret_cast<bf16x8*>(p) = raw; }
+  __device__ __forceinline__ float get(int i) const { return (float)raw[i]; }
+  __device__ __forceinline__ void set(int i, float v) { raw[i] = (bf16)v; }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// GeLU and its derivative (tanh form: 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))); exact form: x Phi(x)).
+__device__ __forceinline__ float gelu_fwd(float x, bool tanh_form) {
+  if (tanh_form) {
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    // tanh(u) = 1 - 2 / (1 + exp(2u)); saturates cleanly for large |u|
+    const float t = 1.0f - 2.0f / (1.0f + __expf(2.0f * u));
+    return 0.5f * x * (1.0f + t);
+  }
+  return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f));
+}
+__device__ __forceinline__ float gelu_bwd(float x, bool tanh_form) {
+  if (tanh_form) {
+    const float x2 = x * x;
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x2);
+    const float t = 1.0f - 2.0f / (1.0f + __expf(2.0f * u));
+    const float du = 0.7978845608028654f * (1.0f + 0.134145f * x2);
+    return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * du;
+  }
+  return 0.5f * (1.0f + erff(x * 0.7071067811865476f)) + x * __expf(-0.5f * x * x) * 0.3989422804014327f;
+}
+
+// ---- epilogues a GEMM can fuse --------------------------------------------------
+enum Epilogue : int {
+  EPI_STORE = 0,      // C = acc (+ bias)
+  EPI_BIAS_GELU = 1,  // aux = acc + bias (pre-activation), C = GeLU(aux)
+  EPI_DGELU = 2,      // C = acc * GeLU'(aux)
+  EPI_CE = 3,         // per-row (max, sum-exp) partials per column tile, target logit; C = logits if C != NULL
+  EPI_DLOGITS = 4     // C = coef_row * (exp(acc - Mrow)/Srow - [col + v0 == target_row])
+};
+
+struct GemmArgs {
+  int M, N, K;
+  const void* A; int lda; int a_kc;   // a_kc: element (m,k) at A[m*lda + k]; else at A[k*lda + m]
+  const void* B; int ldb; int b_kc;   // b_kc: element (k,n) at B[n*ldb + k]; else at B[k*ldb + n]
+  void* C; int ldc;
+  int epi;
+  const void* bias;                    // [N] storage dtype or NULL
+  void* aux; int ldaux;                // EPI_BIAS_GELU: out pre-activation; EPI_DGELU: in pre-activation
+  int gelu_tanh;
+  // EPI_CE / EPI_DLOGITS
+  const int32_t* targets;              // [M] global vocabulary ids
+  int v0;                              // first vocabulary id of the shard
+  float* part_m; float* part_s;        // [n_col_tiles][M] partials (EPI_CE)
+  float* t_out;                        // [M] target logit, written by the owner tile only (EPI_CE)
+  const float* Mrow; const float* Srow; const float* loss_w; const float* loss_stats;  // EPI_DLOGITS
+};
+
+// Number of column tiles the bf16 CE epilogue produces partials for (depends on the tile config chosen for N).
+int gemm_bf16_ce_col_tiles(int M, int N, int K);
+hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t st);
+hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t st);
+
+// ---- attention ------------------------------------------------------------------
+struct AttnArgs {
+  int b, s, hl, d;          // batch, sequence, local heads, head size
+  int causal;
+  const int32_t* key_len;   // [b] or NULL
+  const void* qkv;          // [T, 3*hl*d]
+  void* ctx;                // fwd out / bwd in: [T, hl*d]
+  float* lse;               // [b, hl, s]
+  const void* dctx;         // bwd: [T, hl*d]
+  void* dqkv;               // bwd out: [T, 3*hl*d]
+  float* delta;             // bwd scratch: [b, hl, s]
+};
+bool attn_bf16_supported(int d);
+hipError_t launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_bwd_bf16(const AttnArgs& a, hipStream_t st);
+bool attn_f32_supported(int d);
+hipError_t launch_attn_fwd_f32(const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_bwd_f32(const AttnArgs& a, hipStream_t st);
+
+// ---- row / elementwise kernels (rowops.hip); dtype = MLM_F32 / MLM_BF16 ----------
+constexpr int kLnBwdRowsPerBlock = 32;
+constexpr int kColsumRowsPerBlock = 64;
+constexpr int kMaxPartials = 16;
+
+hipError_t launch_layernorm_fwd(int dtype, int T, int H, float eps, const void* x, const void* gamma,
+                                const void* beta, void* y, float* mean, float* rstd, hipStream_t st);
+// ws: [ceil(T/kLnBwdRowsPerBlock)][2][H] float
+hipError_t launch_layernorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
+                                const float* mean, const float* rstd, const void* residual_grad, void* dx,
+                                void* dgamma, void* dbeta, float* ws, hipStream_t st);
+hipError_t launch_combine(int dtype, int T, int H, const void* const* partials, int n, const void* bias,
+                          const void* residual, void* out, hipStream_t st);
+// ws: [ceil(T/kColsumRowsPerBlock)][N] float
+hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, float* ws, hipStream_t st);
+hipError_t launch_ce_tile_merge(int T, int ntiles, const float* part_m, const float* part_s, const float* t_ws,
+                                const int32_t* targets, int v0, int v1, float* m_r, float* s_r, float* t_r,
+                                hipStream_t st);
+hipError_t launch_ce_rows_f32(int T, int Vl, const float* logits, const int32_t* targets, int v0,
+                              float* m_r, float* s_r, float* t_r, hipStream_t st);
+hipError_t launch_ce_merge(int T, int n_shards, const float* m, const float* s, const float* t, const float* loss_w,
+                           float* ce, float* M, float* S, float* loss_out, hipStream_t st);
+hipError_t launch_dlogits_inplace(int dtype, int T, int Vl, void* logits, const int32_t* targets, int v0,
+                                  const float* M, const float* S, const float* loss_w, const float* loss_stats,
+                                  hipStream_t st);
+hipError_t launch_attn_delta(int dtype, int T, int hl, int d, int b, int s, const void* ctx, const void* dctx,
+                             float* delta, hipStream_t st);
+
+}  // namespace mlm

@@ -1,0 +1,46 @@
+// Dispatcher of the bf16 MFMA GEMM: operand layout -> translation unit, problem shape -> tile configuration.
+#include <stdlib.h>
+#include "gemm_bf16.h"
+
+namespace mlm {
+
+// Tile choice.  256 CUs; a 256x256 or 256x128 workgroup fills a CU's LDS (1 per CU), 128x128 fits twice.
+// Cost model: (number of scheduling rounds) x (tile area) / (relative efficiency of the tile shape); the larger
+// tiles reuse LDS data more per MFMA but quantise worse on small N.  MLM_GEMM_TILE=0/1/2 forces a configuration
+// (used by the tuning sweeps).
+int pick_tile(int M, int N, int K) {
+  (void)K;
+  static int forced = -2;
+  if (forced == -2) {
+    const char* e = getenv("MLM_GEMM_TILE");
+    forced = e ? atoi(e) : -1;
+  }
+  if (forced >= 0 && forced < TILE_COUNT) return forced;
+  const int bm[TILE_COUNT] = {256, 256, 128}, bn[TILE_COUNT] = {256, 128, 128};
+  const int per_cu[TILE_COUNT] = {1, 1, 2};
+  const double eff[TILE_COUNT] = {1.0, 0.9, 0.75};
+  int best = 0;
+  double best_cost = 1e300;
+  for (int t = 0; t < TILE_COUNT; ++t) {
+    const long tiles = (long)((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]);
+    const long slots = 256L * per_cu[t];
+    const long rounds = (tiles + slots - 1) / slots;
+    const double cost = (double)rounds * bm[t] * bn[t] * per_cu[t] / eff[t];
+    if (cost < best_cost) { best_cost = cost; best = t; }
+  }
+  return best;
+}
+
+int gemm_bf16_ce_col_tiles(int M, int N, int K) {
+  const int bn = kTileBN[pick_tile(M, N, K)];
+  return (N + bn - 1) / bn;
+}
+
+hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
+  if (a.a_kc && !a.b_kc) return launch_gemm_bf16_fwd(a, st);
+  if (a.a_kc && a.b_kc) return launch_gemm_bf16_dgrad(a, st);
+  if (!a.a_kc && !a.b_kc) return launch_gemm_bf16_wgrad(a, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace mlm

@@ -1,0 +1,497 @@
+// Bandwidth-bound kernels of the layer shard: layer norm (forward / backward), the single-GPU
+// stand-in for the all-reduce (combine), bias-gradient column sums, and the cross-entropy
+// partial merges (Section 3 of the paper: replicated LN/residual, g/f reductions, loss fused
+// with the vocabulary-parallel logits).  One wavefront (64 lanes) owns one token row; row
+// statistics are wave-level shuffles, HBM access is 16-byte vectors, coalesced along H.
+#include "common.h"
+
+namespace mlm {
+
+// ------------------------------------------------------------------------------ layer norm forward
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int H, float eps, const T* __restrict__ x,
+                                                     const T* __restrict__ gamma, const T* __restrict__ beta,
+                                                     T* __restrict__ y, float* __restrict__ mean,
+                                                     float* __restrict__ rstd) {
+  constexpr int VN = Vec16<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nvec = H / VN;
+  const T* xr = x + (size_t)row * H;
+  Vec16<T> v[NV];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int idx = lane + 64 * i;
+    if (idx < nvec) {
+      v[i].load(xr + (size_t)idx * VN);
+#pragma unroll
+      for (int e = 0; e < VN; ++e) sum += v[i].get(e);
+    }
+  }
+  const float mu = wave_sum(sum) / (float)H;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    if (lane + 64 * i < nvec) {
+#pragma unroll
+      for (int e = 0; e < VN; ++e) { const float d = v[i].get(e) - mu; sq += d * d; }
+    }
+  }
+  const float rs = 1.0f / sqrtf(wave_sum(sq) / (float)H + eps);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+  T* yr = y + (size_t)row * H;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int idx = lane + 64 * i;
+    if (idx < nvec) {
+      Vec16<T> g, b, o;
+      g.load(gamma + (size_t)idx * VN);
+      b.load(beta + (size_t)idx * VN);
+#pragma unroll
+      for (int e = 0; e < VN; ++e) o.set(e, (v[i].get(e) - mu) * rs * g.get(e) + b.get(e));
+      o.store(yr + (size_t)idx * VN);
+    }
+  }
+}
+
+template <typename T>
+static hipError_t ln_fwd_dispatch(int rows, int H, float eps, const void* x, const void* gamma, const void* beta,
+                                  void* y, float* mean, float* rstd, hipStream_t st) {
+  constexpr int VN = Vec16<T>::N;
+  const int nv = (H / VN + 63) / 64;
+  dim3 grid((rows + 3) / 4), block(256);
+#define MLM_LN_FWD(NVV)                                                                                    \
+  case NVV:                                                                                                \
+    hipLaunchKernelGGL((ln_fwd_kernel<T, NVV>), grid, block, 0, st, rows, H, eps, (const T*)x,             \
+                       (const T*)gamma, (const T*)beta, (T*)y, mean, rstd);                                \
+    break;
+  switch (nv) {
+    MLM_LN_FWD(1) MLM_LN_FWD(2) MLM_LN_FWD(3) MLM_LN_FWD(4) MLM_LN_FWD(5) MLM_LN_FWD(6) MLM_LN_FWD(7) MLM_LN_FWD(8)
+    default: return hipErrorInvalidValue;
+  }
+#undef MLM_LN_FWD
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm_fwd(int dtype, int T, int H, float eps, const void* x, const void* gamma,
+                                const void* beta, void* y, float* mean, float* rstd, hipStream_t st) {
+  return dtype == MLM_BF16 ? ln_fwd_dispatch<bf16>(T, H, eps, x, gamma, beta, y, mean, rstd, st)
+                           : ln_fwd_dispatch<float>(T, H, eps, x, gamma, beta, y, mean, rstd, st);
+}
+
+// ------------------------------------------------------------------------------ layer norm backward
+// Block = 4 waves, kLnBwdRowsPerBlock rows; each lane keeps the dgamma/dbeta partial sums of the columns it
+// owns across its rows, the four waves are then summed in a fixed order through LDS (deterministic) and the
+// block partial goes to the workspace; ln_bwd_reduce_kernel sums the block partials.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy,
+                                                     const T* __restrict__ x, const T* __restrict__ gamma,
+                                                     const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                     const T* residual, T* dx, float* __restrict__ ws) {
+  constexpr int VN = Vec16<T>::N;
+  extern __shared__ float red[];   // [2][H]
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int nvec = H / VN;
+  const float invH = 1.0f / (float)H;
+  float dg[NV][VN], db[NV][VN];
+  Vec16<T> gam[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    if (lane + 64 * i < nvec) gam[i].load(gamma + (size_t)(lane + 64 * i) * VN);
+#pragma unroll
+    for (int e = 0; e < VN; ++e) { dg[i][e] = 0.f; db[i][e] = 0.f; }
+  }
+  const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
+  for (int rr = wave; rr < kLnBwdRowsPerBlock; rr += 4) {
+    const int row = row0 + rr;
+    if (row >= rows) break;
+    const float mu = mean[row], rs = rstd[row];
+    Vec16<T> vdy[NV], vx[NV];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int idx = lane + 64 * i;
+      if (idx < nvec) {
+        vdy[i].load(dy + (size_t)row * H + (size_t)idx * VN);
+        vx[i].load(x + (size_t)row * H + (size_t)idx * VN);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) {
+          const float xh = (vx[i].get(e) - mu) * rs;
+          const float d = vdy[i].get(e);
+          const float g = d * gam[i].get(e);
+          s1 += g;
+          s2 += g * xh;
+          dg[i][e] += d * xh;
+          db[i][e] += d;
+        }
+      }
+    }
+    s1 = wave_sum(s1) * invH;
+    s2 = wave_sum(s2) * invH;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int idx = lane + 64 * i;
+      if (idx < nvec) {
+        Vec16<T> res, o;
+        if (residual) res.load(residual + (size_t)row * H + (size_t)idx * VN);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) {
+          const float xh = (vx[i].get(e) - mu) * rs;
+          const float g = vdy[i].get(e) * gam[i].get(e);
+          float v = rs * (g - s1 - xh * s2);
+          if (residual) v += res.get(e);
+          o.set(e, v);
+        }
+        o.store(dx + (size_t)row * H + (size_t)idx * VN);
+      }
+    }
+  }
+  // fixed-order sum of the four waves' column partials
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int idx = lane + 64 * i;
+        if (idx < nvec) {
+#pragma unroll
+          for (int e = 0; e < VN; ++e) {
+            const int c = idx * VN + e;
+            if (w == 0) { red[c] = dg[i][e]; red[H + c] = db[i][e]; }
+            else { red[c] += dg[i][e]; red[H + c] += db[i][e]; }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  float* out = ws + (size_t)blockIdx.x * 2 * H;
+  for (int c = threadIdx.x; c < 2 * H; c += 256) out[c] = red[c];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_reduce_kernel(int nblk, int H, const float* __restrict__ ws,
+                                                            T* __restrict__ dgamma, T* __restrict__ dbeta) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= 2 * H) return;
+  float acc = 0.f;
+  for (int k = 0; k < nblk; ++k) acc += ws[(size_t)k * 2 * H + c];
+  if (c < H) dgamma[c] = from_f32<T>(acc);
+  else dbeta[c - H] = from_f32<T>(acc);
+}
+
+template <typename T>
+static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x, const void* gamma,
+                                  const float* mean, const float* rstd, const void* residual, void* dx,
+                                  void* dgamma, void* dbeta, float* ws, hipStream_t st) {
+  constexpr int VN = Vec16<T>::N;
+  const int nv = (H / VN + 63) / 64;
+  const int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
+  dim3 grid(nblk), block(256);
+  const size_t lds = (size_t)2 * H * sizeof(float);
+#define MLM_LN_BWD(NVV)                                                                                    \
+  case NVV:                                                                                                \
+    hipLaunchKernelGGL((ln_bwd_kernel<T, NVV>), grid, block, lds, st, rows, H, (const T*)dy, (const T*)x,  \
+                       (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws);                       \
+    break;
+  switch (nv) {
+    MLM_LN_BWD(1) MLM_LN_BWD(2) MLM_LN_BWD(3) MLM_LN_BWD(4) MLM_LN_BWD(5) MLM_LN_BWD(6) MLM_LN_BWD(7) MLM_LN_BWD(8)
+    default: return hipErrorInvalidValue;
+  }
+#undef MLM_LN_BWD
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((ln_bwd_reduce_kernel<T>), dim3((2 * H + 255) / 256), dim3(256), 0, st, nblk, H, ws,
+                     (T*)dgamma, (T*)dbeta);
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
+                                const float* mean, const float* rstd, const void* residual_grad, void* dx,
+                                void* dgamma, void* dbeta, float* ws, hipStream_t st) {
+  return dtype == MLM_BF16
+             ? ln_bwd_dispatch<bf16>(T, H, dy, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, st)
+             : ln_bwd_dispatch<float>(T, H, dy, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, st);
+}
+
+// ------------------------------------------------------------------------------ combine (stand-in for g / f)
+struct PartialPtrs { const void* p[kMaxPartials]; };
+
+template <typename T>
+__global__ __launch_bounds__(256) void combine_kernel(size_t nvec, int hvec, PartialPtrs ptrs, int n,
+                                                      const T* __restrict__ bias, const T* residual, T* out) {
+  constexpr int VN = Vec16<T>::N;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= nvec) return;
+  float acc[VN];
+#pragma unroll
+  for (int e = 0; e < VN; ++e) acc[e] = 0.f;
+  for (int k = 0; k < n; ++k) {          // fixed order r = 0..n-1: deterministic
+    Vec16<T> v;
+    v.load((const T*)ptrs.p[k] + i * VN);
+#pragma unroll
+    for (int e = 0; e < VN; ++e) acc[e] += v.get(e);
+  }
+  if (bias) {
+    Vec16<T> v;
+    v.load(bias + (size_t)(i % hvec) * VN);
+#pragma unroll
+    for (int e = 0; e < VN; ++e) acc[e] += v.get(e);
+  }
+  if (residual) {
+    Vec16<T> v;
+    v.load(residual + i * VN);
+#pragma unroll
+    for (int e = 0; e < VN; ++e) acc[e] += v.get(e);
+  }
+  Vec16<T> o;
+#pragma unroll
+  for (int e = 0; e < VN; ++e) o.set(e, acc[e]);
+  o.store(out + i * VN);
+}
+
+hipError_t launch_combine(int dtype, int T, int H, const void* const* partials, int n, const void* bias,
+                          const void* residual, void* out, hipStream_t st) {
+  PartialPtrs pp;
+  for (int k = 0; k < kMaxPartials; ++k) pp.p[k] = k < n ? partials[k] : nullptr;
+  if (dtype == MLM_BF16) {
+    const size_t nvec = (size_t)T * H / 8;
+    hipLaunchKernelGGL((combine_kernel<bf16>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, nvec, H / 8,
+                       pp, n, (const bf16*)bias, (const bf16*)residual, (bf16*)out);
+  } else {
+    const size_t nvec = (size_t)T * H / 4;
+    hipLaunchKernelGGL((combine_kernel<float>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, nvec, H / 4,
+                       pp, n, (const float*)bias, (const float*)residual, (float*)out);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------ column sums (bias gradients)
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(int rows, int N, const T* __restrict__ dy,
+                                                             float* __restrict__ ws) {
+  constexpr int VN = Vec16<T>::N;
+  const int vcol = blockIdx.x * 256 + threadIdx.x;   // vector column
+  if (vcol * VN >= N) return;
+  const int r0 = blockIdx.y * kColsumRowsPerBlock;
+  const int r1 = min(rows, r0 + kColsumRowsPerBlock);
+  float acc[VN];
+#pragma unroll
+  for (int e = 0; e < VN; ++e) acc[e] = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    Vec16<T> v;
+    v.load(dy + (size_t)r * N + (size_t)vcol * VN);
+#pragma unroll
+    for (int e = 0; e < VN; ++e) acc[e] += v.get(e);
+  }
+#pragma unroll
+  for (int e = 0; e < VN; ++e) ws[(size_t)blockIdx.y * N + (size_t)vcol * VN + e] = acc[e];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_reduce_kernel(int nchunk, int N, const float* __restrict__ ws,
+                                                            T* __restrict__ out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= N) return;
+  float acc = 0.f;
+  for (int k = 0; k < nchunk; ++k) acc += ws[(size_t)k * N + c];
+  out[c] = from_f32<T>(acc);
+}
+
+hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, float* ws, hipStream_t st) {
+  const int nchunk = (T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
+  if (dtype == MLM_BF16) {
+    dim3 grid((N / 8 + 255) / 256, nchunk);
+    hipLaunchKernelGGL((colsum_partial_kernel<bf16>), grid, dim3(256), 0, st, T, N, (const bf16*)dy, ws);
+    hipLaunchKernelGGL((colsum_reduce_kernel<bf16>), dim3((N + 255) / 256), dim3(256), 0, st, nchunk, N, ws,
+                       (bf16*)dbias);
+  } else {
+    dim3 grid((N / 4 + 255) / 256, nchunk);
+    hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(256), 0, st, T, N, (const float*)dy, ws);
+    hipLaunchKernelGGL((colsum_reduce_kernel<float>), dim3((N + 255) / 256), dim3(256), 0, st, nchunk, N, ws,
+                       (float*)dbias);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------ cross-entropy partials
+// (max, sum-exp) pairs merge associatively: M = max(m_a, m_b), S = s_a e^{m_a-M} + s_b e^{m_b-M}.
+__global__ __launch_bounds__(256) void ce_tile_merge_kernel(int T, int ntiles, const float* __restrict__ part_m,
+                                                            const float* __restrict__ part_s,
+                                                            const float* __restrict__ t_ws,
+                                                            const int32_t* __restrict__ targets, int v0, int v1,
+                                                            float* m_r, float* s_r, float* t_r) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  float M = -INFINITY;
+  for (int k = 0; k < ntiles; ++k) M = fmaxf(M, part_m[(size_t)k * T + t]);
+  float S = 0.f;
+  for (int k = 0; k < ntiles; ++k) S += part_s[(size_t)k * T + t] * __expf(part_m[(size_t)k * T + t] - M);
+  m_r[t] = M;
+  s_r[t] = S;
+  const int tg = targets[t];
+  t_r[t] = (tg >= v0 && tg < v1) ? t_ws[t] : 0.f;
+}
+
+hipError_t launch_ce_tile_merge(int T, int ntiles, const float* part_m, const float* part_s, const float* t_ws,
+                                const int32_t* targets, int v0, int v1, float* m_r, float* s_r, float* t_r,
+                                hipStream_t st) {
+  hipLaunchKernelGGL(ce_tile_merge_kernel, dim3((T + 255) / 256), dim3(256), 0, st, T, ntiles, part_m, part_s, t_ws,
+                     targets, v0, v1, m_r, s_r, t_r);
+  return hipGetLastError();
+}
+
+// fp32 path: row partials straight from stored logits, one block per token.
+__global__ __launch_bounds__(256) void ce_rows_f32_kernel(int Vl, const float* __restrict__ logits,
+                                                          const int32_t* __restrict__ targets, int v0,
+                                                          float* m_r, float* s_r, float* t_r) {
+  __shared__ float red[4];
+  const int t = blockIdx.x;
+  const float* row = logits + (size_t)t * Vl;
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < Vl; j += 256) mx = fmaxf(mx, row[j]);
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float se = 0.f;
+  for (int j = threadIdx.x; j < Vl; j += 256) se += expf(row[j] - mx);
+  se = wave_sum(se);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = se;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    m_r[t] = mx;
+    s_r[t] = (red[0] + red[1]) + (red[2] + red[3]);
+    const int loc = targets[t] - v0;
+    t_r[t] = (loc >= 0 && loc < Vl) ? row[loc] : 0.f;
+  }
+}
+
+hipError_t launch_ce_rows_f32(int T, int Vl, const float* logits, const int32_t* targets, int v0, float* m_r,
+                              float* s_r, float* t_r, hipStream_t st) {
+  hipLaunchKernelGGL(ce_rows_f32_kernel, dim3(T), dim3(256), 0, st, Vl, logits, targets, v0, m_r, s_r, t_r);
+  return hipGetLastError();
+}
+
+// Merge over shards and the weighted mean: a single block (T is b*s, a few thousand) so that the loss is
+// summed in a fixed order.
+__global__ __launch_bounds__(1024) void ce_merge_kernel(int T, int n_shards, const float* __restrict__ m,
+                                                        const float* __restrict__ s, const float* __restrict__ tl,
+                                                        const float* __restrict__ loss_w, float* ce, float* Mo,
+                                                        float* So, float* loss_out) {
+  __shared__ float red_l[16], red_w[16];
+  float accl = 0.f, accw = 0.f;
+  for (int t = threadIdx.x; t < T; t += 1024) {
+    float M = -INFINITY;
+    for (int r = 0; r < n_shards; ++r) M = fmaxf(M, m[(size_t)r * T + t]);
+    float S = 0.f, tt = 0.f;
+    for (int r = 0; r < n_shards; ++r) {
+      S += s[(size_t)r * T + t] * expf(m[(size_t)r * T + t] - M);
+      tt += tl[(size_t)r * T + t];
+    }
+    const float c = logf(S) + M - tt;
+    ce[t] = c;
+    Mo[t] = M;
+    So[t] = S;
+    const float w = loss_w ? loss_w[t] : 1.0f;
+    accl += w * c;
+    accw += w;
+  }
+  accl = wave_sum(accl);
+  accw = wave_sum(accw);
+  if ((threadIdx.x & 63) == 0) { red_l[threadIdx.x >> 6] = accl; red_w[threadIdx.x >> 6] = accw; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float l = 0.f, w = 0.f;
+    for (int k = 0; k < 16; ++k) { l += red_l[k]; w += red_w[k]; }
+    loss_out[0] = l / w;
+    loss_out[1] = w;
+  }
+}
+
+hipError_t launch_ce_merge(int T, int n_shards, const float* m, const float* s, const float* t, const float* loss_w,
+                           float* ce, float* M, float* S, float* loss_out, hipStream_t st) {
+  hipLaunchKernelGGL(ce_merge_kernel, dim3(1), dim3(1024), 0, st, T, n_shards, m, s, t, loss_w, ce, M, S, loss_out);
+  return hipGetLastError();
+}
+
+// dL = w_t / sum(w) * (exp(L - M_t) / S_t - onehot), written over the stored logits.
+template <typename T>
+__global__ __launch_bounds__(256) void dlogits_inplace_kernel(int Vl, T* logits, const int32_t* __restrict__ targets,
+                                                              int v0, const float* __restrict__ M,
+                                                              const float* __restrict__ S,
+                                                              const float* __restrict__ loss_w,
+                                                              const float* __restrict__ loss_stats) {
+  constexpr int VN = Vec16<T>::N;
+  const int t = blockIdx.y;
+  const int vcol = blockIdx.x * 256 + threadIdx.x;
+  if (vcol * VN >= Vl) return;
+  const float coef = (loss_w ? loss_w[t] : 1.0f) / loss_stats[1];
+  const float Mt = M[t];
+  const float inv = coef / S[t];
+  const int loc = targets[t] - v0;
+  T* p = logits + (size_t)t * Vl + (size_t)vcol * VN;
+  Vec16<T> v, o;
+  v.load(p);
+#pragma unroll
+  for (int e = 0; e < VN; ++e) {
+    float g = __expf(v.get(e) - Mt) * inv;
+    if (vcol * VN + e == loc) g -= coef;
+    o.set(e, g);
+  }
+  o.store(p);
+}
+
+hipError_t launch_dlogits_inplace(int dtype, int T, int Vl, void* logits, const int32_t* targets, int v0,
+                                  const float* M, const float* S, const float* loss_w, const float* loss_stats,
+                                  hipStream_t st) {
+  if (dtype == MLM_BF16) {
+    dim3 grid((Vl / 8 + 255) / 256, T);
+    hipLaunchKernelGGL((dlogits_inplace_kernel<bf16>), grid, dim3(256), 0, st, Vl, (bf16*)logits, targets, v0, M, S,
+                       loss_w, loss_stats);
+  } else {
+    dim3 grid((Vl / 4 + 255) / 256, T);
+    hipLaunchKernelGGL((dlogits_inplace_kernel<float>), grid, dim3(256), 0, st, Vl, (float*)logits, targets, v0, M, S,
+                       loss_w, loss_stats);
+  }
+  return hipGetLastError();
+}
+
+// delta[b, head, i] = sum_c dctx[t, head*d + c] * ctx[t, head*d + c]  (row sum of dP o P in the softmax gradient)
+template <typename T>
+__global__ __launch_bounds__(256) void attn_delta_kernel(int Tn, int hl, int d, int s, const T* __restrict__ ctx,
+                                                         const T* __restrict__ dctx, float* __restrict__ delta) {
+  constexpr int VN = Vec16<T>::N;
+  const int idx = blockIdx.x * 256 + threadIdx.x;   // (t, head)
+  if (idx >= Tn * hl) return;
+  const int t = idx / hl, hd = idx % hl;
+  const size_t off = (size_t)t * hl * d + (size_t)hd * d;
+  float acc = 0.f;
+  for (int c = 0; c < d; c += VN) {
+    Vec16<T> a, g;
+    a.load(ctx + off + c);
+    g.load(dctx + off + c);
+#pragma unroll
+    for (int e = 0; e < VN; ++e) acc += a.get(e) * g.get(e);
+  }
+  const int bi = t / s, i = t % s;
+  delta[((size_t)bi * hl + hd) * s + i] = acc;
+}
+
+hipError_t launch_attn_delta(int dtype, int T, int hl, int d, int b, int s, const void* ctx, const void* dctx,
+                             float* delta, hipStream_t st) {
+  (void)b;
+  dim3 grid((T * hl + 255) / 256);
+  if (dtype == MLM_BF16)
+    hipLaunchKernelGGL((attn_delta_kernel<bf16>), grid, dim3(256), 0, st, T, hl, d, s, (const bf16*)ctx,
+                       (const bf16*)dctx, delta);
+  else
+    hipLaunchKernelGGL((attn_delta_kernel<float>), grid, dim3(256), 0, st, T, hl, d, s, (const float*)ctx,
+                       (const float*)dctx, delta);
+  return hipGetLastError();
+}
+
+}  // namespace mlm

@@ -1,0 +1,198 @@
+"""Sequencer of the layer-shard path on one GPU (allocation and call order only; all arithmetic is in the HIP library).
+
+Runs the forward and backward pass of a model-parallel transformer layer plus the vocabulary-parallel loss for a
+chosen set of shards, stage by stage, because shard r's MLP consumes the *combined* attention output (Section 3 of
+the paper: two reductions forward, two backward per layer; here ``mlm_combine`` / ``mlm_vocab_ce_merge`` stand in
+for them).  With ``shards = range(p)`` the result is the full layer (used to prove the sharding exact); with
+``shards = [0]`` it is one GPU's share at its real shape (what the benchmark times).
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .synth import LayerConfig
+
+
+def _tdtype(cfg: LayerConfig):
+    return torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+
+
+class LayerShards:
+    def __init__(self, cfg: LayerConfig, shards: Sequence[int], device: str = "cuda:0", store_logits: bool = True):
+        self.cfg, self.shards, self.dev = cfg, list(shards), torch.device(device)
+        self.dt = _tdtype(cfg)
+        self.code = B.MLM_BF16 if cfg.dtype == "bf16" else B.MLM_F32
+        self.store_logits = store_logits
+        p = cfg.p
+        self.T = cfg.T
+        self.d = cfg.H // cfg.h
+        self.Hl, self.Fl, self.Vl = cfg.H // p, cfg.F // p, cfg.V // p
+        self.hl = cfg.h // p
+        self.dims = {r: B.make_dims(cfg.b, cfg.s, cfg.H, cfg.h, cfg.F, cfg.V, p, r, self.code, cfg.causal,
+                                    cfg.gelu_tanh, cfg.ln_eps) for r in range(p)}
+        self.rep: Dict[str, torch.Tensor] = {}       # replicated parameters and inputs
+        self.w: Dict[int, Dict[str, torch.Tensor]] = {}   # per-shard parameters
+        self.act: Dict[str, torch.Tensor] = {}       # replicated activations / gradients
+        self.sh: Dict[int, Dict[str, torch.Tensor]] = {}  # per-shard activations / gradients
+        self._alloc()
+
+    # ------------------------------------------------------------------ inputs
+    def load_host_inputs(self, inp: Dict[str, np.ndarray]):
+        """Upload unsharded host arrays; weights are sliced with the library's own shard ranges."""
+        cfg = self.cfg
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev).to(self.dt).contiguous()
+        for k in ("g1", "b1", "bo", "g2", "b2", "c", "gf", "bf"):
+            self.rep[k] = up(inp[k])
+        self.rep["X"] = up(inp["X"].reshape(cfg.T, cfg.H))
+        self.rep["tgt"] = torch.from_numpy(inp["tgt"].reshape(-1).astype(np.int32)).to(self.dev)
+        self.rep["w"] = torch.from_numpy(inp["w"].reshape(-1).astype(np.float32)).to(self.dev)
+        self.rep["key_len"] = torch.from_numpy(inp["key_len"].astype(np.int32)).to(self.dev)
+        for r in self.shards:
+            c0, c1 = B.mlm_shard_range(cfg.H, cfg.p, r)
+            f0, f1 = B.mlm_shard_range(cfg.F, cfg.p, r)
+            v0, v1 = B.mlm_shard_range(cfg.V, cfg.p, r)
+            self.w[r] = {
+                "Wqkv": up(np.concatenate([inp["Wq"][:, c0:c1], inp["Wk"][:, c0:c1], inp["Wv"][:, c0:c1]], axis=1)),
+                "bqkv": up(np.concatenate([inp["bq"][c0:c1], inp["bk"][c0:c1], inp["bv"][c0:c1]])),
+                "Wo": up(inp["Wo"][c0:c1, :]),
+                "A": up(inp["A"][:, f0:f1]), "a": up(inp["a"][f0:f1]), "B": up(inp["B"][f0:f1, :]),
+                "E": up(inp["E"][:, v0:v1]),
+            }
+
+    def load_random(self, seed: int = 0):
+        """Synthetic inputs drawn on the device (benchmark use: same shapes and distributions as synth.make_inputs)."""
+        cfg = self.cfg
+        g = torch.Generator(device=self.dev)
+        g.manual_seed(seed)
+        rn = lambda *shape, std=0.02: (torch.randn(*shape, generator=g, device=self.dev) * std).to(self.dt)
+        ones = lambda n: torch.ones(n, device=self.dev, dtype=self.dt)
+        zeros = lambda n: torch.zeros(n, device=self.dev, dtype=self.dt)
+        H = cfg.H
+        self.rep.update(X=rn(cfg.T, H, std=1.0), g1=ones(H), b1=zeros(H), g2=ones(H), b2=zeros(H), gf=ones(H),
+                        bf=zeros(H), bo=zeros(H), c=zeros(H))
+        self.rep["tgt"] = torch.randint(0, cfg.V, (cfg.T,), generator=g, device=self.dev, dtype=torch.int32)
+        if cfg.masked_lm:
+            kl = torch.randint(max(1, cfg.s // 2), cfg.s + 1, (cfg.b,), generator=g, device=self.dev, dtype=torch.int32)
+            pos = torch.arange(cfg.s, device=self.dev)[None, :]
+            w = (torch.rand(cfg.b, cfg.s, generator=g, device=self.dev) < 0.15) & (pos < kl[:, None])
+            w[0, 0] = True
+            self.rep["key_len"], self.rep["w"] = kl, w.reshape(-1).float()
+        else:
+            self.rep["key_len"] = torch.full((cfg.b,), cfg.s, device=self.dev, dtype=torch.int32)
+            self.rep["w"] = torch.ones(cfg.T, device=self.dev)
+        for r in self.shards:
+            self.w[r] = {"Wqkv": rn(H, 3 * self.Hl), "bqkv": zeros(3 * self.Hl), "Wo": rn(self.Hl, H),
+                         "A": rn(H, self.Fl), "a": zeros(self.Fl), "B": rn(self.Fl, H), "E": rn(H, self.Vl)}
+
+    # ------------------------------------------------------------------ buffers
+    def _alloc(self):
+        cfg, T, H, dev, dt = self.cfg, self.T, self.cfg.H, self.dev, self.dt
+        e = lambda *shape, dtype=dt: torch.empty(*shape, device=dev, dtype=dtype)
+        f32 = torch.float32
+        a = self.act
+        for k in ("U", "X1", "U2", "X2", "Hf", "dHf", "dX2", "dU2", "dX1", "dU", "dX"):
+            a[k] = e(T, H)
+        for k in ("mu1", "rstd1", "mu2", "rstd2", "muf", "rstdf", "ce", "M", "S"):
+            a[k] = e(T, dtype=f32)
+        for k in ("dg1", "db1", "dg2", "db2", "dgf", "dbf", "dbo", "dc"):
+            a[k] = e(H)
+        n = len(self.shards)
+        a["m"], a["s"], a["t"] = e(n, T, dtype=f32), e(n, T, dtype=f32), e(n, T, dtype=f32)
+        a["loss"] = e(2, dtype=f32)
+        d0 = self.dims[self.shards[0]]
+        wsb = max(B.mlm_workspace_bytes(d0, k) for k in range(8))
+        self.ws = torch.empty(max(wsb, 256), device=dev, dtype=torch.uint8)
+        for r in self.shards:
+            self.sh[r] = {
+                "qkv": e(T, 3 * self.Hl), "ctx": e(T, self.Hl), "lse": e(cfg.b, self.hl, cfg.s, dtype=f32),
+                "attn_partial": e(T, H), "g": e(T, self.Fl), "y": e(T, self.Fl), "mlp_partial": e(T, H),
+                "logits": e(T, self.Vl) if self.store_logits else None,
+                "dE": e(H, self.Vl), "dhf_partial": e(T, H),
+                "dA": e(H, self.Fl), "da": e(self.Fl), "dB": e(self.Fl, H), "du2_partial": e(T, H),
+                "dWqkv": e(H, 3 * self.Hl), "dbqkv": e(3 * self.Hl), "dWo": e(self.Hl, H), "du_partial": e(T, H),
+            }
+
+    # ------------------------------------------------------------------ the path
+    def forward(self):
+        cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
+        d0 = self.dims[self.shards[0]]
+        kl = rep["key_len"] if cfg.masked_lm else None
+        B.mlm_layernorm_fwd(d0, rep["X"], rep["g1"], rep["b1"], a["U"], a["mu1"], a["rstd1"])
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_attn_shard_fwd(self.dims[r], a["U"], w["Wqkv"], w["bqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
+                                 s["attn_partial"], ws)
+        B.mlm_combine(d0, [self.sh[r]["attn_partial"] for r in self.shards], rep["bo"], rep["X"], a["X1"])
+        B.mlm_layernorm_fwd(d0, a["X1"], rep["g2"], rep["b2"], a["U2"], a["mu2"], a["rstd2"])
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_mlp_shard_fwd(self.dims[r], a["U2"], w["A"], w["a"], w["B"], s["g"], s["y"], s["mlp_partial"], ws)
+        B.mlm_combine(d0, [self.sh[r]["mlp_partial"] for r in self.shards], rep["c"], a["X1"], a["X2"])
+        if cfg.final_ln:
+            B.mlm_layernorm_fwd(d0, a["X2"], rep["gf"], rep["bf"], a["Hf"], a["muf"], a["rstdf"])
+            hf = a["Hf"]
+        else:
+            hf = a["X2"]
+        self._hf = hf
+        for i, r in enumerate(self.shards):
+            w, s = self.w[r], self.sh[r]
+            B.mlm_vocab_ce_shard_fwd(self.dims[r], hf, w["E"], rep["tgt"], a["m"][i], a["s"][i], a["t"][i], s["logits"],
+                                     ws)
+        B.mlm_vocab_ce_merge(d0, a["m"], a["s"], a["t"], len(self.shards), rep["w"], a["ce"], a["M"], a["S"],
+                             a["loss"])
+
+    def backward(self):
+        cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
+        d0 = self.dims[self.shards[0]]
+        kl = rep["key_len"] if cfg.masked_lm else None
+        hf = self._hf
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_vocab_ce_shard_bwd(self.dims[r], hf, w["E"], rep["tgt"], rep["w"], a["M"], a["S"], a["loss"],
+                                     s["logits"], s["dE"], s["dhf_partial"], ws)
+        B.mlm_combine(d0, [self.sh[r]["dhf_partial"] for r in self.shards], None, None, a["dHf"])
+        if cfg.final_ln:
+            B.mlm_layernorm_bwd(d0, a["dHf"], a["X2"], rep["gf"], a["muf"], a["rstdf"], None, a["dX2"], a["dgf"],
+                                a["dbf"], ws)
+            dx2 = a["dX2"]
+        else:
+            dx2 = a["dHf"]
+        B.mlm_colsum(d0, dx2, a["dc"], ws)
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_mlp_shard_bwd(self.dims[r], dx2, a["U2"], w["A"], w["B"], s["g"], s["y"], s["dA"], s["da"], s["dB"],
+                                s["du2_partial"], ws)
+        B.mlm_combine(d0, [self.sh[r]["du2_partial"] for r in self.shards], None, None, a["dU2"])
+        B.mlm_layernorm_bwd(d0, a["dU2"], a["X1"], rep["g2"], a["mu2"], a["rstd2"], dx2, a["dX1"], a["dg2"], a["db2"],
+                            ws)
+        B.mlm_colsum(d0, a["dX1"], a["dbo"], ws)
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_attn_shard_bwd(self.dims[r], a["dX1"], a["U"], w["Wqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
+                                 s["dWqkv"], s["dbqkv"], s["dWo"], s["du_partial"], ws)
+        B.mlm_combine(d0, [self.sh[r]["du_partial"] for r in self.shards], None, None, a["dU"])
+        B.mlm_layernorm_bwd(d0, a["dU"], rep["X"], rep["g1"], a["mu1"], a["rstd1"], a["dX1"], a["dX"], a["dg1"],
+                            a["db1"], ws)
+        self._dx2 = dx2
+
+    def step(self):
+        self.forward()
+        self.backward()
+
+    # ------------------------------------------------------------------ results (host copies, fp64)
+    def fetch(self) -> Dict[str, object]:
+        torch.cuda.synchronize(self.dev)
+        cp = lambda t: t.detach().float().cpu().numpy().astype(np.float64)
+        out: Dict[str, object] = {k: cp(v) for k, v in self.act.items()}
+        if getattr(self, "_dx2", None) is not None:
+            out["dX2"] = cp(self._dx2)
+        if getattr(self, "_hf", None) is not None:
+            out["Hf"] = cp(self._hf)
+        out["loss"] = float(self.act["loss"][0].item())
+        out["wsum"] = float(self.act["loss"][1].item())
+        out["shards"] = {r: {k: (cp(v) if v is not None else None) for k, v in self.sh[r].items()} for r in self.shards}
+        return out

@@ -1,0 +1,80 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header declares,
+its integer helpers are exact, and argument validation rejects bad calls before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import layer_oracle as O
+from paper_1909_08053_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "mlm_shard.h")).read()
+    return sorted(set(re.findall(r"MLM_API\s+(?:int|const char\*)\s+(mlm_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert len(names) >= 15 and set(names) == set(B.EXPORTS)
+    L = B.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_shard_range_bit_exact_against_brute_force():
+    for n, p in ((32, 8), (3072, 8), (12288, 8), (51200, 8), (30592, 4), (40, 4), (7, 1), (0, 3)):
+        covered = []
+        for r in range(p):
+            b, e = B.mlm_shard_range(n, p, r)
+            assert (b, e) == O.shard_range(n, p, r) if n else (b, e) == (0, 0)
+            covered.extend(range(b, e))
+        assert covered == list(range(n))
+    for bad in ((10, 3, 0), (8, 2, 2), (8, 0, 0), (8, 2, -1), (-8, 2, 0)):
+        with pytest.raises(B.MlmError) as ei:
+            B.mlm_shard_range(*bad)
+        assert ei.value.code == -2
+
+
+def _dims(**kw):
+    base = dict(b=2, s=128, H=256, h=4, F=1024, V=1024, p=2, r=0, dtype=B.MLM_F32)
+    base.update(kw)
+    return B.make_dims(**base)
+
+
+def test_validation_error_codes():
+    L = B.lib()
+    n = ctypes.c_size_t(0)
+    call = lambda d, which=0: L.mlm_workspace_bytes(ctypes.byref(d), which, ctypes.byref(n))
+    assert call(_dims()) == 0
+    assert call(_dims(h=3)) == -2            # H % h
+    assert call(_dims(p=3)) == -2            # h % p
+    assert call(_dims(r=2)) == -2            # r outside [0,p)
+    assert call(_dims(V=1023)) == -2         # V % p
+    assert call(_dims(b=0)) == -2
+    assert call(_dims(dtype=7)) == -3
+    assert call(_dims(V=1028)) == -5         # V/p = 514 not a multiple of 8
+    assert call(_dims(), 99) == -2
+    assert L.mlm_workspace_bytes(None, 0, ctypes.byref(n)) == -1
+    d = _dims()
+    # NULL pointers are rejected before any launch
+    assert L.mlm_layernorm_fwd(ctypes.byref(d), None, None, None, None, None, None, None) == -1
+    assert L.mlm_gemm(1, 1, 1, ctypes.c_int64(64), ctypes.c_int64(64), ctypes.c_int64(64), ctypes.c_void_p(256),
+                      ctypes.c_void_p(256), ctypes.c_void_p(256), None, None) == -7
+    assert L.mlm_gemm(1, 0, 0, ctypes.c_int64(64), ctypes.c_int64(60), ctypes.c_int64(64), ctypes.c_void_p(256),
+                      ctypes.c_void_p(256), ctypes.c_void_p(256), None, None) == -5
+    assert L.mlm_gemm(1, 0, 0, ctypes.c_int64(64), ctypes.c_int64(64), ctypes.c_int64(64), ctypes.c_void_p(8),
+                      ctypes.c_void_p(256), ctypes.c_void_p(256), None, None) == -5
+    for code in range(0, -9, -1):
+        assert B.status_string(code).startswith("MLM_")
+
+
+def test_workspace_sizes_are_positive_and_aligned():
+    d = _dims(b=8, s=1024, H=3072, h=32, F=12288, V=51200, p=8, dtype=B.MLM_BF16)
+    for which in range(8):
+        nbytes = B.mlm_workspace_bytes(d, which)
+        assert nbytes % 256 == 0
+    assert B.mlm_workspace_bytes(d, B.WS_VOCAB_CE_BWD) == 8192 * 6400 * 2

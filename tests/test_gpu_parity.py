@@ -1,0 +1,216 @@
+"""GPU parity: the HIP path (through the C-ABI binding) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL, check, relerr, spec_of
+from oracle import layer_oracle as O
+from paper_1909_08053_amd import binding as B
+from paper_1909_08053_amd import synth
+from paper_1909_08053_amd.pipeline import LayerShards
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _up(a, dt):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV).to(dt).contiguous()
+
+
+def _dn(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+# ------------------------------------------------------------------ GEMM building block
+GEMM_SHAPES = [(256, 256, 256), (512, 384, 192), (264, 136, 72), (1000, 520, 328), (128, 1152, 3072 // 4),
+               (8, 8, 8), (1032, 952, 640), (72, 7648, 136)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("layout", [(0, 0), (0, 1), (1, 0)])
+@pytest.mark.parametrize("shape", GEMM_SHAPES)
+def test_gemm_layouts_and_ragged_tiles(dtype, layout, shape):
+    M, N, K = shape
+    ta, tb = layout
+    rng = np.random.default_rng(M * 7 + N * 3 + K + ta * 2 + tb)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    Bm = (rng.standard_normal((K, N)) * 0.05).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    if dtype == "bf16":
+        A, Bm, bias = synth.round_to_bf16(A), synth.round_to_bf16(Bm), synth.round_to_bf16(bias)
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    code = B.MLM_BF16 if dtype == "bf16" else B.MLM_F32
+    dA = _up(A.T if ta else A, dt)
+    dB = _up(Bm.T if tb else Bm, dt)
+    C = torch.full((M + 1, N), 7.0, device=DEV, dtype=dt)   # one canary row after the output
+    use_bias = (M + N) % 16 == 0
+    B.mlm_gemm(code, ta, tb, M, N, K, dA, dB, C, _up(bias, dt) if use_bias else None)
+    torch.cuda.synchronize()
+    ref = A.astype(np.float64) @ Bm.astype(np.float64) + (bias.astype(np.float64) if use_bias else 0.0)
+    got = _dn(C)
+    assert np.all(got[M] == 7.0), "write past the end of C"
+    assert relerr(got[:M], ref) <= (TOL[dtype] if dtype == "fp32" else 1e-2)
+
+
+# ------------------------------------------------------------------ replicated row kernels
+@pytest.mark.parametrize("dtype,H", [("fp32", 256), ("bf16", 256), ("bf16", 3072), ("bf16", 1920), ("fp32", 136),
+                                     ("bf16", 2560)])
+def test_layernorm_combine_colsum(dtype, H):
+    T = 2 * 37                     # ragged against the 4-rows-per-block / 32-rows-per-block groupings
+    cfg_dims = B.make_dims(2, 37, H, 1, 4 * H, 8, 1, 0, B.MLM_BF16 if dtype == "bf16" else B.MLM_F32)
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rng = np.random.default_rng(H)
+    rnd = (lambda a: synth.round_to_bf16(a)) if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    x = rnd(rng.standard_normal((T, H)).astype(np.float32) * 2 + 0.5)
+    g = rnd((1 + 0.2 * rng.standard_normal(H)).astype(np.float32))
+    be = rnd((0.1 * rng.standard_normal(H)).astype(np.float32))
+    dy = rnd(rng.standard_normal((T, H)).astype(np.float32))
+    res = rnd(rng.standard_normal((T, H)).astype(np.float32))
+    tol = TOL[dtype]
+    y = torch.empty(T, H, device=DEV, dtype=dt); mean = torch.empty(T, device=DEV); rstd = torch.empty(T, device=DEV)
+    B.mlm_layernorm_fwd(cfg_dims, _up(x, dt), _up(g, dt), _up(be, dt), y, mean, rstd)
+    yr, mur, rsr = O.layernorm_fwd(x, g.astype(np.float64), be.astype(np.float64), 1e-5)
+    errs = []
+    check("ln.y", _dn(y), yr, tol, errs); check("ln.mean", _dn(mean), mur, 1e-5 + 0 * tol, errs)
+    check("ln.rstd", _dn(rstd), rsr, 1e-5, errs)
+    ws = torch.empty(B.mlm_workspace_bytes(cfg_dims, B.WS_LAYERNORM_BWD), device=DEV, dtype=torch.uint8)
+    dx = torch.empty(T, H, device=DEV, dtype=dt); dg = torch.empty(H, device=DEV, dtype=dt); db = torch.empty(H, device=DEV, dtype=dt)
+    B.mlm_layernorm_bwd(cfg_dims, _up(dy, dt), _up(x, dt), _up(g, dt), mean, rstd, _up(res, dt), dx, dg, db, ws)
+    dxr, dgr, dbr = O.layernorm_bwd(dy.astype(np.float64), x.astype(np.float64), g.astype(np.float64), mur, rsr)
+    check("ln.dx", _dn(dx), dxr + res, tol, errs); check("ln.dgamma", _dn(dg), dgr, tol, errs)
+    check("ln.dbeta", _dn(db), dbr, tol, errs)
+    # combine: sum of partials + bias + residual
+    parts = [rnd(rng.standard_normal((T, H)).astype(np.float32)) for _ in range(3)]
+    out = torch.empty(T, H, device=DEV, dtype=dt)
+    B.mlm_combine(cfg_dims, [_up(p_, dt) for p_ in parts], _up(be, dt), _up(res, dt), out)
+    check("combine", _dn(out), sum(p_.astype(np.float64) for p_ in parts) + be + res, tol, errs)
+    B.mlm_combine(cfg_dims, [_up(parts[0], dt)], None, None, out)
+    assert np.array_equal(_dn(out), parts[0].astype(np.float64))
+    # column sums
+    ws2 = torch.empty(B.mlm_workspace_bytes(cfg_dims, B.WS_COLSUM), device=DEV, dtype=torch.uint8)
+    cs = torch.empty(H, device=DEV, dtype=dt)
+    B.mlm_colsum(cfg_dims, _up(dy, dt), cs, ws2)
+    check("colsum", _dn(cs), dy.astype(np.float64).sum(0), tol, errs)
+
+
+# ------------------------------------------------------------------ whole layer, all shards, every tensor
+def run_layer_parity(cfg, nonzero_bias=True, random_ln=True, store_logits=True, scale_w=1.0, shards=None):
+    inp = synth.make_inputs(cfg, nonzero_bias=nonzero_bias, random_ln=random_ln)
+    if scale_w != 1.0:
+        for k in ("Wq", "Wk", "Wv", "Wo", "A", "B", "E"):
+            inp[k] = inp[k] * np.float32(scale_w)
+            if cfg.dtype == "bf16":
+                inp[k] = synth.round_to_bf16(inp[k])
+    spec = spec_of(cfg)
+    ref = O.sharded_reference(inp, spec, cfg.p)
+    shards = list(range(cfg.p)) if shards is None else shards
+    assert shards == list(range(cfg.p)), "full-layer parity needs every shard"
+    L = LayerShards(cfg, shards, DEV, store_logits=store_logits)
+    L.load_host_inputs(inp)
+    L.forward()
+    fwd = L.fetch()
+    L.backward()
+    out = L.fetch()
+    tol = TOL[cfg.dtype]
+    errs = []
+    # forward, replicated
+    for k in ("U", "X1", "U2", "X2", "Hf", "ce", "mu1", "rstd1", "mu2", "rstd2"):
+        check(k, fwd[k], ref[k], tol, errs)
+    check("M+logS", fwd["M"] + np.log(fwd["S"]), ref["M"] + np.log(ref["S"]), tol, errs)
+    assert abs(fwd["loss"] - ref["loss"]) <= tol * abs(ref["loss"]), (fwd["loss"], ref["loss"])
+    assert fwd["wsum"] == float(np.asarray(inp["w"]).sum())
+    tgt = inp["tgt"].reshape(-1)
+    for i, r in enumerate(shards):
+        g, rs = fwd["shards"][r], ref["shards"][r]
+        for k in ("qkv", "ctx", "lse", "attn_partial", "g", "y", "mlp_partial"):
+            check(f"shard{r}.{k}", g[k], rs[k], tol, errs)
+        if store_logits:
+            check(f"shard{r}.logits", g["logits"], rs["logits"], tol, errs)
+        check(f"shard{r}.m+log s", fwd["m"][i] + np.log(fwd["s"][i]), rs["m"] + np.log(rs["s"]), tol, errs)
+        check(f"shard{r}.t", fwd["t"][i], rs["t"], tol, errs)
+        # integer work: the target-in-shard test is exact -> t is exactly 0 outside the shard's range
+        assert np.array_equal(fwd["t"][i] == 0.0, ~rs["tgt_inside"] | (rs["t"] == 0.0))
+        assert np.all(fwd["t"][i][~rs["tgt_inside"]] == 0.0)
+    # backward, replicated
+    for k in ("dHf", "dX2", "dU2", "dX1", "dU", "dX", "dgf", "dbf", "dg2", "db2", "dg1", "db1", "dc", "dbo"):
+        if k in ("dgf", "dbf") and not cfg.final_ln:
+            continue
+        check(k, out[k], ref[k], tol, errs)
+    for r in shards:
+        g, rs = out["shards"][r], ref["shards"][r]
+        for k in ("dE", "dhf_partial", "dA", "da", "dB", "du2_partial", "dWqkv", "dbqkv", "dWo", "du_partial"):
+            check(f"shard{r}.{k}", g[k], rs[k], tol, errs)
+        if store_logits:
+            check(f"shard{r}.dlogits", g["logits"], rs["dlogits"], tol, errs)
+    return errs
+
+
+def test_tiny_config_fp32_full_layer():
+    errs = run_layer_parity(synth.CONFIGS["tiny"], nonzero_bias=False, random_ln=False)
+    print("worst:", sorted(errs, key=lambda e: -e[1])[:5])
+
+
+@pytest.mark.parametrize("variant", ["bias_ln", "bert", "no_final_ln_erf", "recompute_logits", "p4_d32"])
+def test_small_fp32_variants(variant):
+    kw = dict(b=2, s=80, H=128, h=4, F=512, V=256, p=2, dtype="fp32")
+    store = True
+    if variant == "bert":
+        kw.update(causal=False, masked_lm=True)
+    elif variant == "no_final_ln_erf":
+        kw.update(final_ln=False, gelu_tanh=False)
+    elif variant == "recompute_logits":
+        store = False
+    elif variant == "p4_d32":
+        kw.update(p=4, s=72)
+    run_layer_parity(synth.small_config(**kw), store_logits=store, scale_w=4.0)
+
+
+# ------------------------------------------------------------------ bf16 (MFMA) path: small layers spanning several tiles
+BF16_CASES = {
+    # name: (config overrides, store_logits, weight scale)
+    "d64_causal": (dict(b=2, s=200, H=128, h=2, F=512, V=640, p=2), True, 3.0),
+    "d96_causal": (dict(b=2, s=328, H=192, h=2, F=768, V=1088, p=2), True, 3.0),
+    "d128_causal_p1": (dict(b=1, s=264, H=256, h=2, F=1024, V=520, p=1), True, 3.0),
+    "d64_bert": (dict(b=3, s=176, H=256, h=4, F=1024, V=960, p=4, causal=False, masked_lm=True), True, 3.0),
+    "d96_bert_recompute": (dict(b=2, s=136, H=384, h=4, F=1536, V=512, p=2, causal=False, masked_lm=True), False, 3.0),
+    "d64_noln_erf": (dict(b=2, s=128, H=128, h=2, F=512, V=256, p=1, final_ln=False, gelu_tanh=False), True, 3.0),
+}
+
+
+@pytest.mark.parametrize("case", sorted(BF16_CASES))
+def test_small_bf16_layers(case):
+    kw, store, scale = BF16_CASES[case]
+    cfg = synth.small_config(name=case, dtype="bf16", **kw)
+    errs = run_layer_parity(cfg, store_logits=store, scale_w=scale)
+    print(case, "worst:", sorted(errs, key=lambda e: -e[1])[:4])
+
+
+def test_attention_integer_work_bf16():
+    """Causal row 0 sees only key 0: its context equals V[0] bit-exactly; padded keys get exactly zero weight,
+    so changing them cannot change any output bit."""
+    cfg = synth.small_config(dtype="bf16", b=2, s=160, H=128, h=2, F=512, V=256, p=1, causal=False, masked_lm=True)
+    inp = synth.make_inputs(cfg, nonzero_bias=True)
+    outs = []
+    for trial in range(2):
+        L = LayerShards(cfg, [0], DEV)
+        x = dict(inp)
+        if trial == 1:     # scramble X at padded key positions of batch 0 only beyond its key length
+            X = inp["X"].copy()
+            kl = int(inp["key_len"][0])
+            X[0, kl:, :] = synth.round_to_bf16(np.random.default_rng(5).standard_normal(X[0, kl:, :].shape).astype(np.float32))
+            x["X"] = X
+        L.load_host_inputs(x)
+        L.forward()
+        outs.append(L.fetch())
+    kl = int(inp["key_len"][0])
+    ctx0 = outs[0]["shards"][0]["ctx"].reshape(cfg.b, cfg.s, -1)
+    ctx1 = outs[1]["shards"][0]["ctx"].reshape(cfg.b, cfg.s, -1)
+    assert np.array_equal(ctx0[0, :kl], ctx1[0, :kl]) and np.array_equal(ctx0[1], ctx1[1])
+    cfg2 = synth.small_config(dtype="bf16", b=1, s=96, H=128, h=2, F=512, V=256, p=1)
+    inp2 = synth.make_inputs(cfg2)
+    L = LayerShards(cfg2, [0], DEV)
+    L.load_host_inputs(inp2)
+    L.forward()
+    o = L.fetch()["shards"][0]
+    v_row0 = o["qkv"][0, 2 * cfg2.H:]
+    assert np.array_equal(o["ctx"][0], v_row0)
