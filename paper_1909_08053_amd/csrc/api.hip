@@ -44,18 +44,22 @@ int attn_supported(const mlm_dims* dm, const Local& L) {
   return ok ? MLM_OK : MLM_E_UNSUPPORTED;
 }
 
+// fp32 scratch for the k-split of partially filled GEMM rounds (bf16 path only)
+constexpr size_t kSplitKBytes = (size_t)256 * 256 * 256 * sizeof(float);
+
 size_t ws_bytes_for(const mlm_dims* dm, const Local& L, int which) {
   const size_t T = (size_t)L.T;
   const size_t cs_rows = (T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
+  const size_t sk = dm->dtype == MLM_BF16 ? kSplitKBytes : 0;
   switch (which) {
     case MLM_WS_LAYERNORM_BWD:
       return align256(((T + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock) * 2 * (size_t)dm->H * 4);
-    case MLM_WS_ATTN_FWD: return 0;
+    case MLM_WS_ATTN_FWD: return sk;
     case MLM_WS_ATTN_BWD:
       return align256(T * L.Hl * L.esz) + align256(T * 3 * L.Hl * L.esz) +
-             align256((size_t)dm->b * L.hl * dm->s * 4) + align256(cs_rows * 3 * L.Hl * 4);
-    case MLM_WS_MLP_FWD: return 0;
-    case MLM_WS_MLP_BWD: return align256(T * L.Fl * L.esz) + align256(cs_rows * L.Fl * 4);
+             align256((size_t)dm->b * L.hl * dm->s * 4) + align256(cs_rows * 3 * L.Hl * 4) + sk;
+    case MLM_WS_MLP_FWD: return sk;
+    case MLM_WS_MLP_BWD: return align256(T * L.Fl * L.esz) + align256(cs_rows * L.Fl * 4) + sk;
     case MLM_WS_COLSUM: return align256(cs_rows * (size_t)dm->H * 4);
     case MLM_WS_VOCAB_CE_FWD:
       if (dm->dtype == MLM_BF16) {
@@ -63,7 +67,7 @@ size_t ws_bytes_for(const mlm_dims* dm, const Local& L, int which) {
         return 2 * align256(ntile * T * 4) + align256(T * 4);
       }
       return align256(T * L.Vl * 4);
-    case MLM_WS_VOCAB_CE_BWD: return align256(T * L.Vl * L.esz);
+    case MLM_WS_VOCAB_CE_BWD: return align256(T * L.Vl * L.esz) + sk;
     default: return 0;
   }
 }
@@ -82,7 +86,8 @@ GemmArgs gemm_args(int M, int N, int K, const void* A, int lda, int a_kc, const 
   return g;
 }
 
-hipError_t run_gemm(int dtype, const GemmArgs& g, hipStream_t st) {
+hipError_t run_gemm(int dtype, GemmArgs g, hipStream_t st, float* splitk = nullptr) {
+  g.splitk_ws = splitk;
   return dtype == MLM_BF16 ? launch_gemm_bf16(g, st) : launch_gemm_f32(g, st);
 }
 
@@ -199,7 +204,6 @@ MLM_API int mlm_colsum(const mlm_dims* dims, const void* dy, void* dbias, void* 
 MLM_API int mlm_attn_shard_fwd(const mlm_dims* dims, const void* u, const void* Wqkv_r, const void* bqkv_r, const void* Wo_r,
                        const int32_t* key_len, void* qkv_r, void* ctx_r, float* lse_r, void* partial_r, void* ws,
                        size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   Local L;
   int rc = check_dims(dims, &L);
   if (rc) return rc;
@@ -208,17 +212,20 @@ MLM_API int mlm_attn_shard_fwd(const mlm_dims* dims, const void* u, const void* 
       !aligned16(partial_r) || (bqkv_r && !aligned16(bqkv_r)))
     return MLM_E_ALIGN;
   if ((rc = attn_supported(dims, L))) return rc;
+  if (ws_bytes < ws_bytes_for(dims, L, MLM_WS_ATTN_FWD) || (ws_bytes && !ws)) return MLM_E_WORKSPACE;
+  if (ws && !aligned16(ws)) return MLM_E_ALIGN;
   hipStream_t st = (hipStream_t)stream;
   const int dt = dims->dtype;
+  float* sk = dt == MLM_BF16 ? (float*)ws : nullptr;
   GemmArgs g = gemm_fwd(L.T, 3 * L.Hl, dims->H, u, Wqkv_r, qkv_r);
   g.bias = bqkv_r;
-  MLM_TRY_HIP(run_gemm(dt, g, st));
+  MLM_TRY_HIP(run_gemm(dt, g, st, sk));
   AttnArgs a;
   memset(&a, 0, sizeof(a));
   a.b = dims->b; a.s = dims->s; a.hl = L.hl; a.d = L.d; a.causal = dims->causal; a.key_len = key_len;
   a.qkv = qkv_r; a.ctx = ctx_r; a.lse = lse_r;
   MLM_TRY_HIP(dt == MLM_BF16 ? launch_attn_fwd_bf16(a, st) : launch_attn_fwd_f32(a, st));
-  MLM_TRY_HIP(run_gemm(dt, gemm_fwd(L.T, dims->H, L.Hl, ctx_r, Wo_r, partial_r), st));
+  MLM_TRY_HIP(run_gemm(dt, gemm_fwd(L.T, dims->H, L.Hl, ctx_r, Wo_r, partial_r), st, sk));
   return MLM_OK;
 }
 
@@ -243,10 +250,11 @@ MLM_API int mlm_attn_shard_bwd(const mlm_dims* dims, const void* dx1, const void
   void* dctx = w;                 w += align256(T * L.Hl * L.esz);
   void* dqkv = w;                 w += align256(T * 3 * L.Hl * L.esz);
   float* delta = (float*)w;       w += align256((size_t)dims->b * L.hl * dims->s * 4);
-  float* csws = (float*)w;
+  float* csws = (float*)w;        w += align256(((T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock) * 3 * L.Hl * 4);
+  float* sk = dt == MLM_BF16 ? (float*)w : nullptr;
   // output projection: dWo_r = ctx^T dx1, dctx = dx1 Wo_r^T
-  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(L.Hl, dims->H, L.T, ctx_r, dx1, dWo_r), st));
-  MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, L.Hl, dims->H, dx1, Wo_r, dctx), st));
+  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(L.Hl, dims->H, L.T, ctx_r, dx1, dWo_r), st, sk));
+  MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, L.Hl, dims->H, dx1, Wo_r, dctx), st, sk));
   // attention core
   MLM_TRY_HIP(launch_attn_delta(dt, L.T, L.hl, L.d, dims->b, dims->s, ctx_r, dctx, delta, st));
   AttnArgs a;
@@ -256,15 +264,14 @@ MLM_API int mlm_attn_shard_bwd(const mlm_dims* dims, const void* dx1, const void
   a.dctx = dctx; a.dqkv = dqkv; a.delta = delta;
   MLM_TRY_HIP(dt == MLM_BF16 ? launch_attn_bwd_bf16(a, st) : launch_attn_bwd_f32(a, st));
   // QKV projection: dWqkv_r = u^T dqkv, dbqkv_r = column sums, du_partial_r = dqkv Wqkv_r^T
-  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, 3 * L.Hl, L.T, u, dqkv, dWqkv_r), st));
+  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, 3 * L.Hl, L.T, u, dqkv, dWqkv_r), st, sk));
   MLM_TRY_HIP(launch_colsum(dt, L.T, 3 * L.Hl, dqkv, dbqkv_r, csws, st));
-  MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, 3 * L.Hl, dqkv, Wqkv_r, du_partial_r), st));
+  MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, 3 * L.Hl, dqkv, Wqkv_r, du_partial_r), st, sk));
   return MLM_OK;
 }
 
 MLM_API int mlm_mlp_shard_fwd(const mlm_dims* dims, const void* u2, const void* A_r, const void* a_r, const void* B_r,
                       void* g_r, void* y_r, void* partial_r, void* ws, size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   Local L;
   int rc = check_dims(dims, &L);
   if (rc) return rc;
@@ -272,15 +279,18 @@ MLM_API int mlm_mlp_shard_fwd(const mlm_dims* dims, const void* u2, const void* 
   if (!aligned16(u2) || !aligned16(A_r) || !aligned16(B_r) || !aligned16(g_r) || !aligned16(y_r) ||
       !aligned16(partial_r) || (a_r && !aligned16(a_r)))
     return MLM_E_ALIGN;
+  if (ws_bytes < ws_bytes_for(dims, L, MLM_WS_MLP_FWD) || (ws_bytes && !ws)) return MLM_E_WORKSPACE;
+  if (ws && !aligned16(ws)) return MLM_E_ALIGN;
   hipStream_t st = (hipStream_t)stream;
   const int dt = dims->dtype;
+  float* sk = dt == MLM_BF16 ? (float*)ws : nullptr;
   GemmArgs g = gemm_fwd(L.T, L.Fl, dims->H, u2, A_r, y_r);   // Y_r = GeLU(X A_r + a_r), Eq. 3
   g.epi = EPI_BIAS_GELU;
   g.bias = a_r;
   g.aux = g_r; g.ldaux = L.Fl;
   g.gelu_tanh = dims->gelu_tanh;
   MLM_TRY_HIP(run_gemm(dt, g, st));
-  MLM_TRY_HIP(run_gemm(dt, gemm_fwd(L.T, dims->H, L.Fl, y_r, B_r, partial_r), st));   // partial of Z = Y B
+  MLM_TRY_HIP(run_gemm(dt, gemm_fwd(L.T, dims->H, L.Fl, y_r, B_r, partial_r), st, sk));   // partial of Z = Y B
   return MLM_OK;
 }
 
@@ -301,16 +311,17 @@ MLM_API int mlm_mlp_shard_bwd(const mlm_dims* dims, const void* dx2, const void*
   const size_t T = (size_t)L.T;
   char* w = (char*)ws;
   void* dg = w;                   w += align256(T * L.Fl * L.esz);
-  float* csws = (float*)w;
-  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(L.Fl, dims->H, L.T, y_r, dx2, dB_r), st));
+  float* csws = (float*)w;        w += align256(((T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock) * L.Fl * 4);
+  float* sk = dt == MLM_BF16 ? (float*)w : nullptr;
+  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(L.Fl, dims->H, L.T, y_r, dx2, dB_r), st, sk));
   GemmArgs g = gemm_dgrad(L.T, L.Fl, dims->H, dx2, B_r, dg);   // dG = (dX2 B_r^T) o GeLU'(G)
   g.epi = EPI_DGELU;
   g.aux = const_cast<void*>(g_r); g.ldaux = L.Fl;
   g.gelu_tanh = dims->gelu_tanh;
   MLM_TRY_HIP(run_gemm(dt, g, st));
   MLM_TRY_HIP(launch_colsum(dt, L.T, L.Fl, dg, da_r, csws, st));
-  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, L.Fl, L.T, u2, dg, dA_r), st));
-  MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, L.Fl, dg, A_r, du2_partial_r), st));
+  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, L.Fl, L.T, u2, dg, dA_r), st, sk));
+  MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, L.Fl, dg, A_r, du2_partial_r), st, sk));
   return MLM_OK;
 }
 
@@ -363,14 +374,15 @@ MLM_API int mlm_vocab_ce_shard_bwd(const mlm_dims* dims, const void* hf, const v
   int rc = check_dims(dims, &L);
   if (rc) return rc;
   if (!hf || !E_r || !targets || !M || !S || !loss_stats || !dE_r || !dhf_partial_r) return MLM_E_NULL;
-  if (!logits_r && !ws) return MLM_E_NULL;
+  if (!ws) return MLM_E_NULL;
   if (!aligned16(hf) || !aligned16(E_r) || !aligned16(dE_r) || !aligned16(dhf_partial_r) ||
-      (logits_r && !aligned16(logits_r)) || (ws && !aligned16(ws)))
+      (logits_r && !aligned16(logits_r)) || !aligned16(ws))
     return MLM_E_ALIGN;
-  if (!logits_r && ws_bytes < ws_bytes_for(dims, L, MLM_WS_VOCAB_CE_BWD)) return MLM_E_WORKSPACE;
+  if (ws_bytes < ws_bytes_for(dims, L, MLM_WS_VOCAB_CE_BWD)) return MLM_E_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const int dt = dims->dtype;
   const int v0 = dims->r * L.Vl;
+  float* sk = dt == MLM_BF16 ? (float*)((char*)ws + align256((size_t)L.T * L.Vl * L.esz)) : nullptr;
   void* dL = logits_r;
   if (logits_r) {
     MLM_TRY_HIP(launch_dlogits_inplace(dt, L.T, L.Vl, logits_r, targets, v0, M, S, loss_w, loss_stats, st));
@@ -382,8 +394,8 @@ MLM_API int mlm_vocab_ce_shard_bwd(const mlm_dims* dims, const void* hf, const v
     g.Mrow = M; g.Srow = S; g.loss_w = loss_w; g.loss_stats = loss_stats;
     MLM_TRY_HIP(run_gemm(dt, g, st));
   }
-  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, L.Vl, L.T, hf, dL, dE_r), st));
-  MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, L.Vl, dL, E_r, dhf_partial_r), st));
+  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, L.Vl, L.T, hf, dL, dE_r), st, sk));
+  MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, L.Vl, dL, E_r, dhf_partial_r), st, sk));
   return MLM_OK;
 }
 

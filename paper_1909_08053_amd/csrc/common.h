@@ -51,23 +51,25 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// GeLU and its derivative (tanh form: 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))); exact form: x Phi(x)).
+// GeLU and its derivative.  tanh form: 0.5 x (1 + tanh(u)) = x sigmoid(2u) with u = sqrt(2/pi)(x + 0.044715 x^3);
+// exact form: x Phi(x).  The sigmoid is one exp2 and one reciprocal; it saturates cleanly (exp2 -> 0 or inf).
+__device__ __forceinline__ float gelu_sigmoid2u(float x) {
+  // 2u log2(e) = x (c0 + c1 x^2)
+  const float c0 = 2.0f * 0.7978845608028654f * 1.4426950408889634f;
+  const float c1 = c0 * 0.044715f;
+  const float w = x * fmaf(c1, x * x, c0);
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-w));
+}
 __device__ __forceinline__ float gelu_fwd(float x, bool tanh_form) {
-  if (tanh_form) {
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    // tanh(u) = 1 - 2 / (1 + exp(2u)); saturates cleanly for large |u|
-    const float t = 1.0f - 2.0f / (1.0f + __expf(2.0f * u));
-    return 0.5f * x * (1.0f + t);
-  }
+  if (tanh_form) return x * gelu_sigmoid2u(x);
   return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f));
 }
 __device__ __forceinline__ float gelu_bwd(float x, bool tanh_form) {
   if (tanh_form) {
-    const float x2 = x * x;
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x2);
-    const float t = 1.0f - 2.0f / (1.0f + __expf(2.0f * u));
-    const float du = 0.7978845608028654f * (1.0f + 0.134145f * x2);
-    return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * du;
+    // d/dx [x s(2u)] = s + x s (1 - s) 2 u',  u' = sqrt(2/pi)(1 + 3 * 0.044715 x^2)
+    const float sg = gelu_sigmoid2u(x);
+    const float du2 = 2.0f * 0.7978845608028654f * fmaf(0.134145f, x * x, 1.0f);
+    return sg + x * sg * (1.0f - sg) * du2;
   }
   return 0.5f * (1.0f + erff(x * 0.7071067811865476f)) + x * __expf(-0.5f * x * x) * 0.3989422804014327f;
 }
@@ -96,6 +98,7 @@ struct GemmArgs {
   float* part_m; float* part_s;        // [n_col_tiles][M] partials (EPI_CE)
   float* t_out;                        // [M] target logit, written by the owner tile only (EPI_CE)
   const float* Mrow; const float* Srow; const float* loss_w; const float* loss_stats;  // EPI_DLOGITS
+  float* splitk_ws;                    // >= 64 MB of scratch for the tail split of the plain-store GEMM, or NULL
 };
 
 // Number of column tiles the bf16 CE epilogue produces partials for (depends on the tile config chosen for N).

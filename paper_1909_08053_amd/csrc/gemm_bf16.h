@@ -144,74 +144,19 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
   tn = in / gsz;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmArgs a) {
+// Epilogue shared by the GEMM kernels.  acc[i][j][e] holds row m = m0 + wm0 + 32 j + l32 and column
+// n = n0 + wn0 + 32 i + 8 (e/4) + 4 lh + (e%4) of the output tile.  Must be entered after a workgroup barrier that
+// follows the last LDS read of the main loop (the LDS is reused for the staging strips).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, floatx16 (&acc)[BN / WAVES_N / 32][BM / WAVES_M / 32],
+                                              unsigned char* lds_raw, int m0, int n0, int tile_n) {
   typedef GemmTile<BM, BN, WAVES_M, WAVES_N> Tcfg;
   constexpr int NT = Tcfg::NT, TM = Tcfg::TM, TN = Tcfg::TN, WM = Tcfg::WM, WN = Tcfg::WN;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   bf16* lds = reinterpret_cast<bf16*>(lds_raw);
-
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lh = lane >> 5;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
-  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-  int tile_m, tile_n;
-  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const bf16* A = (const bf16*)a.A;
-  const bf16* B = (const bf16*)a.B;
-
-  typename LoaderSel<BM, NT, A_KC>::type la;
-  typename LoaderSel<BN, NT, B_KC>::type lb;
-
-  floatx16 acc[TN][TM];
-#pragma unroll
-  for (int i = 0; i < TN; ++i)
-#pragma unroll
-    for (int j = 0; j < TM; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  const int nk = (a.K + GBK - 1) / GBK;
-  la.load(A, a.lda, m0, a.M, 0, a.K, tid);
-  lb.load(B, a.ldb, n0, a.N, 0, a.K, tid);
-  la.store(lds, tid);
-  lb.store(lds + BM * GLS, tid);
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; ++kt) {
-    bf16* sA = lds + (kt & 1) * Tcfg::STAGE;
-    bf16* sB = sA + BM * GLS;
-    if (kt + 1 < nk) {
-      la.load(A, a.lda, m0, a.M, (kt + 1) * GBK, a.K, tid);
-      lb.load(B, a.ldb, n0, a.N, (kt + 1) * GBK, a.K, tid);
-    }
-#pragma unroll
-    for (int ks = 0; ks < GBK / 16; ++ks) {
-      bf16x8 fa[TM], fb[TN];
-#pragma unroll
-      for (int j = 0; j < TM; ++j)
-        fa[j] = *reinterpret_cast<const bf16x8*>(sA + (wm0 + j * 32 + l32) * GLS + ks * 16 + lh * 8);
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-        fb[i] = *reinterpret_cast<const bf16x8*>(sB + (wn0 + i * 32 + l32) * GLS + ks * 16 + lh * 8);
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      bf16* dA = lds + ((kt + 1) & 1) * Tcfg::STAGE;
-      la.store(dA, tid);
-      lb.store(dA + BM * GLS, tid);
-    }
-    __syncthreads();
-  }
-
-  // ------------------------------------------------------------------ epilogue
-  // acc[i][j][e]: row m = m0 + wm0 + 32 j + l32, column n = n0 + wn0 + 32 i + 8 (e/4) + 4 lh + (e%4).
   bf16* strip = lds + wave * Tcfg::STRIP;
   bf16* C = (bf16*)a.C;
   const bf16* bias = (const bf16*)a.bias;
@@ -219,6 +164,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
   if (EPI == EPI_CE) {
     float* red_m = reinterpret_cast<float*>(lds_raw + (size_t)WAVES_M * WAVES_N * Tcfg::STRIP * 2);
     float* red_s = red_m + WAVES_N * BM;
+    if (n0 + BN > a.N) {
+      // ragged last column tile: columns past N take no part in the statistics (exp(-inf) = 0)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (n0 + wn0 + i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3) >= a.N) acc[i][j][e] = -INFINITY;
+    }
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
       const int row = m0 + wm0 + j * 32 + l32;
@@ -226,28 +181,27 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int n = n0 + wn0 + i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-          if (n < a.N) mx = fmaxf(mx, acc[i][j][e]);
-        }
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, acc[i][j][e]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      float se = 0.f;
-      const int loc = (row < a.M) ? a.targets[row] - a.v0 : -1;
+      // column of the target inside this lane's registers, or -1: integer test, then one select per value
+      const int loc = (row < a.M) ? a.targets[row] - a.v0 - (n0 + wn0 + 4 * lh) : -1;
+      const float mxl = mx * 1.4426950408889634f;
+      float se = 0.f, tv = 0.f;
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int n = n0 + wn0 + i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-          if (n < a.N) {
-            se += __expf(acc[i][j][e] - mx);
-            if (n == loc) a.t_out[row] = acc[i][j][e];
-          }
+          const float v = acc[i][j][e];
+          se += __builtin_amdgcn_exp2f(fmaf(v, 1.4426950408889634f, -mxl));
+          tv = (loc == i * 32 + 8 * (e >> 2) + (e & 3)) ? v : tv;
         }
       se += __shfl_xor(se, 32, 64);
+      if (loc >= 0 && loc < WN && ((loc >> 2) & 1) == 0) a.t_out[row] = tv;   // (loc & 4) == 0: column owned by this half
       if (lh == 0) {
         red_m[(wave % WAVES_N) * BM + wm0 + j * 32 + l32] = mx;
         red_s[(wave % WAVES_N) * BM + wm0 + j * 32 + l32] = se;
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
     for (int rloc = tid; rloc < BM; rloc += NT) {
@@ -320,6 +274,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
           for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
           *reinterpret_cast<bf16x4*>(strip + l32 * (WN + 8) + nl) = o;
         }
+      __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_wave_barrier();
       bf16* dst = (EPI == EPI_BIAS_GELU && pass == 0) ? (bf16*)a.aux : C;
       const int ldd = (EPI == EPI_BIAS_GELU && pass == 0) ? a.ldaux : a.ldc;
@@ -335,8 +290,78 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
               *reinterpret_cast<const uint4*>(strip + r * (WN + 8) + cv * 8);
       }
       __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmArgs a) {
+  typedef GemmTile<BM, BN, WAVES_M, WAVES_N> Tcfg;
+  constexpr int NT = Tcfg::NT, TM = Tcfg::TM, TN = Tcfg::TN, WM = Tcfg::WM, WN = Tcfg::WN;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16* lds = reinterpret_cast<bf16*>(lds_raw);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const bf16* A = (const bf16*)a.A;
+  const bf16* B = (const bf16*)a.B;
+
+  typename LoaderSel<BM, NT, A_KC>::type la;
+  typename LoaderSel<BN, NT, B_KC>::type lb;
+
+  floatx16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int nk = (a.K + GBK - 1) / GBK;
+  la.load(A, a.lda, m0, a.M, 0, a.K, tid);
+  lb.load(B, a.ldb, n0, a.N, 0, a.K, tid);
+  la.store(lds, tid);
+  lb.store(lds + BM * GLS, tid);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    bf16* sA = lds + (kt & 1) * Tcfg::STAGE;
+    bf16* sB = sA + BM * GLS;
+    if (kt + 1 < nk) {
+      la.load(A, a.lda, m0, a.M, (kt + 1) * GBK, a.K, tid);
+      lb.load(B, a.ldb, n0, a.N, (kt + 1) * GBK, a.K, tid);
+    }
+#pragma unroll
+    for (int ks = 0; ks < GBK / 16; ++ks) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+        fa[j] = *reinterpret_cast<const bf16x8*>(sA + (wm0 + j * 32 + l32) * GLS + ks * 16 + lh * 8);
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+        fb[i] = *reinterpret_cast<const bf16x8*>(sB + (wn0 + i * 32 + l32) * GLS + ks * 16 + lh * 8);
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      bf16* dA = lds + ((kt + 1) & 1) * Tcfg::STAGE;
+      la.store(dA, tid);
+      lb.store(dA + BM * GLS, tid);
+    }
+    __syncthreads();
+  }
+
+  gemm_epilogue<BM, BN, WAVES_M, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, int EPI>
@@ -358,6 +383,7 @@ hipError_t launch_gemm_bf16_cfg(const GemmArgs& a, hipStream_t st) {
 // Tile configurations; the launcher picks one per problem shape (see pick_tile in gemm_bf16.hip).
 enum TileId { TILE_256x256 = 0, TILE_256x128 = 1, TILE_128x128 = 2, TILE_COUNT = 3 };
 int pick_tile(int M, int N, int K);
+bool gemm_use_v2(const GemmArgs& a);   // direct-to-LDS kernel applicable (K % 32 == 0) and not disabled
 constexpr int kTileBN[TILE_COUNT] = {256, 128, 128};
 
 template <bool A_KC, bool B_KC, int EPI>

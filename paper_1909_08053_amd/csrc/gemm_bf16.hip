@@ -31,7 +31,20 @@ int pick_tile(int M, int N, int K) {
   return best;
 }
 
+// MLM_GEMM_V2=0 switches the direct-to-LDS kernel off (A/B comparisons).
+bool gemm_use_v2(const GemmArgs& a) {
+  static int enabled = -1;
+  if (enabled < 0) {
+    const char* e = getenv("MLM_GEMM_V2");
+    enabled = (e && atoi(e) == 0) ? 0 : 1;
+  }
+  return enabled && a.K % 32 == 0 && a.K >= 32;
+}
+
 int gemm_bf16_ce_col_tiles(int M, int N, int K) {
+  GemmArgs probe;
+  probe.K = K;
+  if (gemm_use_v2(probe)) return (N + 255) / 256;
   const int bn = kTileBN[pick_tile(M, N, K)];
   return (N + bn - 1) / bn;
 }

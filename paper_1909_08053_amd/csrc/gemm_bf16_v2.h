@@ -1,0 +1,280 @@
+// Second-generation bf16 MFMA GEMM main loop for gfx950, built on three CDNA4 features:
+//   * global_load_lds_dwordx4: tiles go from HBM/L2 straight into LDS (no VGPR staging, no LDS-write
+//     instructions, no VALU permutes), asynchronously, tracked by vmcnt.  Each wave instruction moves
+//     64 lanes x 16 B = 1 KB into one contiguous LDS kilobyte, so the bank-conflict swizzle is applied on
+//     the GLOBAL side: lane t fetches the 16-byte unit that belongs at LDS position t.
+//   * ds_read_b64_tr_b16: an operand that is contiguous along m or n in memory (weights [in,out] in the
+//     forward GEMM, both operands of the weight-gradient GEMM) stays in LDS in its natural [k][n] layout and
+//     is transposed by the LDS read itself: 16 lanes read a 4(k) x 16(n) patch and each lane receives four
+//     consecutive k of one column.  Two such reads give the same 8-consecutive-k operand registers that a
+//     16-byte read of a k-contiguous tile gives, so both kinds of tiles feed the same MFMA loop.
+//   * 160 KB LDS: a 256 x 256 block tile (2 x 2 waves, 128 x 128 per wave: 64 B of LDS traffic per clock per
+//     CU for 16 MFMAs per k-step) with a FOUR-stage ring of 32-deep k-slices (128 KB): three slices are in
+//     flight while one is consumed, i.e. about 3000 MFMA clocks of prefetch distance, one barrier per slice.
+// Requirements: K % 32 == 0 (the dispatcher falls back to the register-staged kernel otherwise).
+//
+// Tail split: when the tile count does not fill a whole number of rounds of the 256 CUs, the tiles of the last
+// partial round are split along k into f pieces (f = floor(256 / remainder)); each piece writes an fp32 partial
+// tile to a workspace and gemm_v2_fixup_kernel sums the pieces in a fixed order (deterministic) and applies
+// the bias.  Only the plain-store epilogue takes part.
+#pragma once
+#include "gemm_bf16.h"
+
+namespace mlm {
+
+constexpr int V2_B = 256;                   // block tile edge (M and N)
+constexpr int V2_BK = 32;                   // k per stage
+constexpr int V2_STAGES = 4;
+constexpr int V2_OP_BYTES = V2_B * V2_BK * 2;          // 16 KB per operand per stage
+constexpr int V2_STAGE_BYTES = 2 * V2_OP_BYTES;
+constexpr size_t V2_LDS_BYTES = (size_t)V2_STAGES * V2_STAGE_BYTES;   // 128 KB
+constexpr int V2_CUS = 256;
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) void glb_void_t;
+typedef short v4s_t __attribute__((ext_vector_type(4)));
+typedef short v8s_t __attribute__((ext_vector_type(8)));
+
+// One wave-wide 16-byte-per-lane copy HBM -> LDS: lane t's 16 bytes land at lds_addr + 16 t (lds_addr is the
+// wave-uniform LDS byte address, passed in M0).  Written as inline assembly so that the compiler's conservative
+// "LDS DMA may alias any LDS read" rule does not turn every fragment read into s_waitcnt vmcnt(0); completion is
+// tracked by hand with wait_vmcnt<> below.
+__device__ __forceinline__ void dma16(const bf16* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)p;
+}
+
+// s_waitcnt vmcnt(N) only (lgkmcnt / expcnt left at "no wait"): gfx9 encoding vmcnt[3:0] | expcnt<<4 | lgkm<<8 | vmcnt[5:4]<<14
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// Per-lane source pointers of one operand's four 1-KB DMA instructions per stage.
+template <bool KC>
+struct V2Src {
+  const bf16* p[4];
+  size_t step;     // elements to advance per k-slice
+  __device__ __forceinline__ void init(const bf16* P, int ld, int row0, int nrows, int k_begin, int wave, int lane) {
+    if (KC) {
+      // LDS layout [256 rows][32 k] (64 B rows, four 16-byte units); unit u of row r holds k-chunk u ^ ((r >> 2) & 3)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = (wave * 4 + q) * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((lane >> 4) & 3);
+        p[q] = P + (size_t)min(row0 + row, nrows - 1) * ld + k_begin + c * 8;
+      }
+      step = V2_BK;
+    } else {
+      // LDS layout [32 k][256 rows] (512 B per k, 32 units); unit u of k-row holds row-chunk u ^ ((k & 7) << 1)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int k = 2 * (wave * 4 + q) + (lane >> 5);
+        const int u = (lane & 31) ^ (((2 * q + (lane >> 5)) & 7) << 1);
+        p[q] = P + (size_t)(k_begin + k) * ld + min(row0 + u * 8, nrows - 8);
+      }
+      step = (size_t)V2_BK * ld;
+    }
+  }
+  // op_lds: LDS byte address of this operand's stage buffer; wave_u: wave index as a uniform (SGPR) value
+  __device__ __forceinline__ void issue(uint32_t op_lds, int wave_u, int kt_rel) const {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dma16(p[q] + (size_t)kt_rel * step, op_lds + (wave_u * 4 + q) * 1024);
+  }
+};
+
+// Operand registers (8 consecutive k of one row/column per lane) for the 32-row MFMA tile starting at row `r0`.
+template <bool KC>
+__device__ __forceinline__ bf16x8 v2_frag(const unsigned char* op_base, int r0, int ks, int lane) {
+  const int l32 = lane & 31, lh = lane >> 5;
+  if (KC) {
+    const int unit = (ks * 2 + lh) ^ ((l32 >> 2) & 3);
+    return *reinterpret_cast<const bf16x8*>(op_base + (r0 + l32) * 64 + unit * 16);
+  } else {
+    const int g = lane >> 4, i16 = lane & 15;
+    const int u = (r0 >> 3) + 2 * (g & 1) + ((i16 & 3) >> 1);
+    v4s_t h[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int k7 = 4 * r + (i16 >> 2);                       // (k & 7)
+      const int k = ks * 16 + 8 * (g >> 1) + k7;
+      const unsigned char* ad = op_base + k * 512 + ((u ^ (k7 << 1)) * 16) + (i16 & 1) * 8;
+      h[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t*)ad);
+    }
+    const v8s_t v = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+struct V2Plan {
+  int tiles_m, tiles_n, full_tiles, tail_tiles, split;   // grid = full_tiles + tail_tiles * split
+};
+
+inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
+  V2Plan p;
+  p.tiles_m = (M + V2_B - 1) / V2_B;
+  p.tiles_n = (N + V2_B - 1) / V2_B;
+  const int tiles = p.tiles_m * p.tiles_n;
+  const int rem = tiles % V2_CUS;
+  const int nk = K / V2_BK;
+  int split = 1;
+  if (allow_split && rem != 0 && rem * 4 <= V2_CUS * 3) {
+    split = V2_CUS / rem;
+    if (split > 16) split = 16;
+    while (split > 1 && nk / split < 8) --split;     // keep at least 8 k-slices per piece
+  }
+  p.split = split;
+  p.tail_tiles = split > 1 ? rem : 0;
+  p.full_tiles = tiles - p.tail_tiles;
+  return p;
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan plan, float* splitk_ws) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+
+  // work item: a full tile, or one k-piece of a tail tile
+  int vt, piece = 0, npieces = 1;
+  const int pid = blockIdx.x;
+  if (pid < plan.full_tiles) {
+    vt = pid;
+  } else {
+    const int t = pid - plan.full_tiles;
+    vt = plan.full_tiles + t / plan.split;
+    piece = t % plan.split;
+    npieces = plan.split;
+  }
+  // Plain order, tile row fastest: the 256 concurrent tiles form 8 tile-columns of 32 tile-rows, and the ids that
+  // share an XCD (congruent mod 8) share tile rows, so each XCD's L2 sees few distinct operand panels.
+  const int tile_m = vt % plan.tiles_m, tile_n = vt / plan.tiles_m;
+  const int m0 = tile_m * V2_B, n0 = tile_n * V2_B;
+  const int nk_total = a.K / V2_BK;
+  const int kt_begin = (int)((long)nk_total * piece / npieces);
+  const int kt_end = (int)((long)nk_total * (piece + 1) / npieces);
+  const int nk = kt_end - kt_begin;
+
+  V2Src<A_KC> sa;
+  V2Src<B_KC> sb;
+  sa.init((const bf16*)a.A, a.lda, m0, a.M, kt_begin * V2_BK, wave, lane);
+  sb.init((const bf16*)a.B, a.ldb, n0, a.N, kt_begin * V2_BK, wave, lane);
+
+  floatx16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const uint32_t lds0 = lds_offset_of(lds_raw);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+  for (int s = 0; s < V2_STAGES - 1; ++s) {
+    if (s < nk) {
+      sa.issue(lds0 + s * V2_STAGE_BYTES, wave_u, s);
+      sb.issue(lds0 + s * V2_STAGE_BYTES + V2_OP_BYTES, wave_u, s);
+    }
+  }
+  for (int kt = 0; kt < nk; ++kt) {
+    // slices kt+1 and kt+2 may stay in flight (8 DMA instructions each per wave); slice kt must have landed
+    const int ahead = nk - 1 - kt;
+    if (ahead >= 2) wait_vmcnt<16>();
+    else if (ahead == 1) wait_vmcnt<8>();
+    else wait_vmcnt<0>();
+    // Bare s_barrier (no memory fence: a fence would wait for the slices still in flight).  After it everyone's
+    // part of slice kt is in LDS, and everyone has consumed (in MFMAs) every fragment it read from slice kt-1.
+    __builtin_amdgcn_s_barrier();
+    if (kt + V2_STAGES - 1 < nk) {
+      const uint32_t st = lds0 + ((kt + V2_STAGES - 1) & (V2_STAGES - 1)) * V2_STAGE_BYTES;
+      sa.issue(st, wave_u, kt + V2_STAGES - 1);
+      sb.issue(st + V2_OP_BYTES, wave_u, kt + V2_STAGES - 1);
+    }
+    const unsigned char* sA = lds_raw + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
+    const unsigned char* sB = sA + V2_OP_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 fa[4], fb[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) fa[j] = v2_frag<A_KC>(sA, wm0 + j * 32, ks, lane);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fb[i] = v2_frag<B_KC>(sB, wn0 + i * 32, ks, lane);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  __syncthreads();
+
+  if (npieces > 1) {
+    // fp32 partial tile: piece-major [tail tile][piece][256][256]
+    const int l32 = lane & 31, lh = lane >> 5;
+    float* dst = splitk_ws + ((size_t)(vt - plan.full_tiles) * plan.split + piece) * (V2_B * V2_B);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+          *reinterpret_cast<float4*>(dst + (wm0 + j * 32 + l32) * V2_B + wn0 + i * 32 + 8 * g + 4 * lh) = v;
+        }
+    return;
+  }
+  gemm_epilogue<V2_B, V2_B, 2, 2, EPI>(a, acc, lds_raw, m0, n0, tile_n);
+}
+
+// Sum the k-pieces of every tail tile in piece order, add the bias, round once to bf16.
+template <int UNUSED>
+__global__ __launch_bounds__(256) void gemm_v2_fixup_kernel(GemmArgs a, V2Plan plan, const float* __restrict__ ws) {
+  const int t = blockIdx.y;                          // tail tile
+  const int vt = plan.full_tiles + t;
+  const int m0 = (vt % plan.tiles_m) * V2_B, n0 = (vt / plan.tiles_m) * V2_B;
+  const int v = blockIdx.x * 256 + threadIdx.x;      // 4-column group inside the tile
+  const int r = v / (V2_B / 4), c4 = (v % (V2_B / 4)) * 4;
+  const int m = m0 + r, n = n0 + c4;
+  if (m >= a.M || n >= a.N) return;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p = 0; p < plan.split; ++p) {
+    const float4 x = *reinterpret_cast<const float4*>(ws + ((size_t)t * plan.split + p) * (V2_B * V2_B) + r * V2_B + c4);
+    s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
+  }
+  if (a.bias) {
+    const bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16*)a.bias + n);
+    s.x += (float)b[0]; s.y += (float)b[1]; s.z += (float)b[2]; s.w += (float)b[3];
+  }
+  bf16x4 o;
+  o[0] = (bf16)s.x; o[1] = (bf16)s.y; o[2] = (bf16)s.z; o[3] = (bf16)s.w;
+  *reinterpret_cast<bf16x4*>((bf16*)a.C + (size_t)m * a.ldc + n) = o;
+}
+
+inline size_t v2_splitk_ws_bytes() { return (size_t)V2_CUS * V2_B * V2_B * sizeof(float); }   // 64 MB upper bound
+
+template <bool A_KC, bool B_KC, int EPI>
+hipError_t launch_gemm_bf16_v2(const GemmArgs& a, float* splitk_ws, hipStream_t st) {
+  auto kern = gemm_bf16_v2_kernel<A_KC, B_KC, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)V2_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const V2Plan plan = v2_plan(a.M, a.N, a.K, EPI == EPI_STORE && splitk_ws != nullptr);
+  const int grid = plan.full_tiles + plan.tail_tiles * plan.split;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), V2_LDS_BYTES, st, a, plan, splitk_ws);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (plan.tail_tiles) {
+    hipLaunchKernelGGL((gemm_v2_fixup_kernel<0>), dim3(V2_B * V2_B / 4 / 256, plan.tail_tiles), dim3(256), 0, st, a, plan,
+                       splitk_ws);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace mlm

@@ -77,4 +77,4 @@ def test_workspace_sizes_are_positive_and_aligned():
     for which in range(8):
         nbytes = B.mlm_workspace_bytes(d, which)
         assert nbytes % 256 == 0
-    assert B.mlm_workspace_bytes(d, B.WS_VOCAB_CE_BWD) == 8192 * 6400 * 2
+    assert B.mlm_workspace_bytes(d, B.WS_VOCAB_CE_BWD) == 8192 * 6400 * 2 + 64 * 2 ** 20
