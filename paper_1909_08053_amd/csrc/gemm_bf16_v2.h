@@ -178,35 +178,58 @@ __global__ __launch_bounds__(256) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan pl
       sb.issue(lds0 + s * V2_STAGE_BYTES + V2_OP_BYTES, wave_u, s);
     }
   }
-  for (int kt = 0; kt < nk; ++kt) {
-    // slices kt+1 and kt+2 may stay in flight (8 DMA instructions each per wave); slice kt must have landed
-    const int ahead = nk - 1 - kt;
-    if (ahead >= 2) wait_vmcnt<16>();
-    else if (ahead == 1) wait_vmcnt<8>();
+  // Software pipeline over half-slices (16 k each = 16 MFMAs per wave).  The operand registers of the NEXT half are
+  // read from LDS while the matrix cores work on the current half, and the slice hand-over (wait for the DMA of
+  // slice kt+1, barrier, re-arm the freed stage) sits in the middle of slice kt, so LDS latency, barrier skew and
+  // DMA issue are all covered by 512 clocks of MFMA work.
+  bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
+  {
+    // slice 0 must have landed; slices 1 and 2 may stay in flight (8 DMA instructions each per wave)
+    if (nk >= 3) wait_vmcnt<16>();
+    else if (nk == 2) wait_vmcnt<8>();
     else wait_vmcnt<0>();
-    // Bare s_barrier (no memory fence: a fence would wait for the slices still in flight).  After it everyone's
-    // part of slice kt is in LDS, and everyone has consumed (in MFMAs) every fragment it read from slice kt-1.
     __builtin_amdgcn_s_barrier();
-    if (kt + V2_STAGES - 1 < nk) {
-      const uint32_t st = lds0 + ((kt + V2_STAGES - 1) & (V2_STAGES - 1)) * V2_STAGE_BYTES;
-      sa.issue(st, wave_u, kt + V2_STAGES - 1);
-      sb.issue(st + V2_OP_BYTES, wave_u, kt + V2_STAGES - 1);
-    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(lds_raw, wm0 + j * 32, 0, lane);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fb0[i] = v2_frag<B_KC>(lds_raw + V2_OP_BYTES, wn0 + i * 32, 0, lane);
+  }
+  for (int kt = 0; kt < nk; ++kt) {
     const unsigned char* sA = lds_raw + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
     const unsigned char* sB = sA + V2_OP_BYTES;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 fa[4], fb[4];
+    for (int j = 0; j < 4; ++j) fa1[j] = v2_frag<A_KC>(sA, wm0 + j * 32, 1, lane);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) fa[j] = v2_frag<A_KC>(sA, wm0 + j * 32, ks, lane);
+    for (int i = 0; i < 4; ++i) fb1[i] = v2_frag<B_KC>(sB, wn0 + i * 32, 1, lane);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) fb[i] = v2_frag<B_KC>(sB, wn0 + i * 32, ks, lane);
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[i], fa0[j], acc[i][j], 0, 0, 0);
+    if (kt + 1 < nk) {
+      // slice kt+1 must have landed; slice kt+2 may stay in flight
+      if (kt + 2 < nk) wait_vmcnt<8>();
+      else wait_vmcnt<0>();
+      // Bare s_barrier (no memory fence: a fence would also wait for the slice still in flight).  After it
+      // everyone's part of slice kt+1 is in LDS, and everyone has finished reading slice kt-1 (its last operand
+      // registers were consumed by MFMAs issued before this point), so that stage can be re-armed.
+      __builtin_amdgcn_s_barrier();
+      if (kt + V2_STAGES - 1 < nk) {
+        const uint32_t st = lds0 + ((kt + V2_STAGES - 1) & (V2_STAGES - 1)) * V2_STAGE_BYTES;
+        sa.issue(st, wave_u, kt + V2_STAGES - 1);
+        sb.issue(st + V2_OP_BYTES, wave_u, kt + V2_STAGES - 1);
+      }
+      const unsigned char* nA = lds_raw + ((kt + 1) & (V2_STAGES - 1)) * V2_STAGE_BYTES;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(nA, wm0 + j * 32, 0, lane);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fb0[i] = v2_frag<B_KC>(nA + V2_OP_BYTES, wn0 + i * 32, 0, lane);
     }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[i], fa1[j], acc[i][j], 0, 0, 0);
   }
   __syncthreads();
 

@@ -82,16 +82,17 @@ hipError_t launch_layernorm_fwd(int dtype, int T, int H, float eps, const void* 
 }
 
 // ------------------------------------------------------------------------------ layer norm backward
-// Block = 4 waves, kLnBwdRowsPerBlock rows; each lane keeps the dgamma/dbeta partial sums of the columns it
-// owns across its rows, the four waves are then summed in a fixed order through LDS (deterministic) and the
-// block partial goes to the workspace; ln_bwd_reduce_kernel sums the block partials.
+// Block = 4 waves, kLnBwdRowsPerBlock rows, one wave per row with the next row's vectors prefetched while the
+// current row is reduced.  Each lane keeps the dgamma/dbeta partial sums of the columns it owns; the four waves are
+// then summed in a fixed order (deterministic) through a conflict-free LDS layout [value][lane] and the block
+// partial goes to the workspace; reduce_cols_kernel sums the block partials.
 template <typename T, int NV>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy,
                                                      const T* __restrict__ x, const T* __restrict__ gamma,
                                                      const float* __restrict__ mean, const float* __restrict__ rstd,
                                                      const T* residual, T* dx, float* __restrict__ ws) {
   constexpr int VN = Vec16<T>::N;
-  extern __shared__ float red[];   // [2][H]
+  extern __shared__ float red[];   // [2 * NV * VN][64]
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nvec = H / VN;
@@ -105,18 +106,40 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int H, const T* _
     for (int e = 0; e < VN; ++e) { dg[i][e] = 0.f; db[i][e] = 0.f; }
   }
   const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
-  for (int rr = wave; rr < kLnBwdRowsPerBlock; rr += 4) {
-    const int row = row0 + rr;
-    if (row >= rows) break;
-    const float mu = mean[row], rs = rstd[row];
-    Vec16<T> vdy[NV], vx[NV];
-    float s1 = 0.f, s2 = 0.f;
+  const int row_end = min(rows, row0 + kLnBwdRowsPerBlock);
+  Vec16<T> vdy[NV], vx[NV], vres[NV], ndy[NV], nx[NV], nres[NV];
+  int row = row0 + wave;
+  if (row < row_end) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int idx = lane + 64 * i;
       if (idx < nvec) {
-        vdy[i].load(dy + (size_t)row * H + (size_t)idx * VN);
-        vx[i].load(x + (size_t)row * H + (size_t)idx * VN);
+        ndy[i].load(dy + (size_t)row * H + (size_t)idx * VN);
+        nx[i].load(x + (size_t)row * H + (size_t)idx * VN);
+        if (residual) nres[i].load(residual + (size_t)row * H + (size_t)idx * VN);
+      }
+    }
+  }
+  for (; row < row_end; row += 4) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) { vdy[i] = ndy[i]; vx[i] = nx[i]; vres[i] = nres[i]; }
+    const int nrow = row + 4;
+    if (nrow < row_end) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int idx = lane + 64 * i;
+        if (idx < nvec) {
+          ndy[i].load(dy + (size_t)nrow * H + (size_t)idx * VN);
+          nx[i].load(x + (size_t)nrow * H + (size_t)idx * VN);
+          if (residual) nres[i].load(residual + (size_t)nrow * H + (size_t)idx * VN);
+        }
+      }
+    }
+    const float mu = mean[row], rs = rstd[row];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      if (lane + 64 * i < nvec) {
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
           const float xh = (vx[i].get(e) - mu) * rs;
@@ -135,51 +158,62 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int H, const T* _
     for (int i = 0; i < NV; ++i) {
       const int idx = lane + 64 * i;
       if (idx < nvec) {
-        Vec16<T> res, o;
-        if (residual) res.load(residual + (size_t)row * H + (size_t)idx * VN);
+        Vec16<T> o;
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
           const float xh = (vx[i].get(e) - mu) * rs;
           const float g = vdy[i].get(e) * gam[i].get(e);
           float v = rs * (g - s1 - xh * s2);
-          if (residual) v += res.get(e);
+          if (residual) v += vres[i].get(e);
           o.set(e, v);
         }
         o.store(dx + (size_t)row * H + (size_t)idx * VN);
       }
     }
   }
-  // fixed-order sum of the four waves' column partials
+  // fixed-order sum of the four waves' column partials; LDS slot (i, e, lane) -> red[(i*VN+e)*64 + lane]
   for (int w = 0; w < 4; ++w) {
     if (wave == w) {
 #pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int idx = lane + 64 * i;
-        if (idx < nvec) {
+      for (int i = 0; i < NV; ++i)
 #pragma unroll
-          for (int e = 0; e < VN; ++e) {
-            const int c = idx * VN + e;
-            if (w == 0) { red[c] = dg[i][e]; red[H + c] = db[i][e]; }
-            else { red[c] += dg[i][e]; red[H + c] += db[i][e]; }
-          }
+        for (int e = 0; e < VN; ++e) {
+          const int slot = (i * VN + e) * 64 + lane;
+          if (w == 0) { red[slot] = dg[i][e]; red[NV * VN * 64 + slot] = db[i][e]; }
+          else { red[slot] += dg[i][e]; red[NV * VN * 64 + slot] += db[i][e]; }
         }
-      }
     }
     __syncthreads();
   }
+  // coalesced write-out: consecutive threads take consecutive columns
   float* out = ws + (size_t)blockIdx.x * 2 * H;
-  for (int c = threadIdx.x; c < 2 * H; c += 256) out[c] = red[c];
+  for (int col = threadIdx.x; col < H; col += 256) {
+    const int idx = col / VN, e = col % VN;
+    const int slot = ((idx >> 6) * VN + e) * 64 + (idx & 63);
+    out[col] = red[slot];
+    out[H + col] = red[NV * VN * 64 + slot];
+  }
 }
 
+// out[c] = sum_k ws[k][c] over nchunk row-chunks: 32 columns x 8 chunk-slices per block, slices summed in a fixed order.
 template <typename T>
-__global__ __launch_bounds__(256) void ln_bwd_reduce_kernel(int nblk, int H, const float* __restrict__ ws,
-                                                            T* __restrict__ dgamma, T* __restrict__ dbeta) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= 2 * H) return;
+__global__ __launch_bounds__(256) void reduce_cols_kernel(int nchunk, int ncols, const float* __restrict__ ws,
+                                                          T* __restrict__ out0, T* __restrict__ out1, int split) {
+  __shared__ float red[8][33];
+  const int cx = threadIdx.x & 31, sl = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cx;
   float acc = 0.f;
-  for (int k = 0; k < nblk; ++k) acc += ws[(size_t)k * 2 * H + c];
-  if (c < H) dgamma[c] = from_f32<T>(acc);
-  else dbeta[c - H] = from_f32<T>(acc);
+  if (c < ncols)
+    for (int k = sl; k < nchunk; k += 8) acc += ws[(size_t)k * ncols + c];
+  red[sl][cx] = acc;
+  __syncthreads();
+  if (sl == 0 && c < ncols) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += red[k][cx];
+    if (c < split) out0[c] = from_f32<T>(t);
+    else out1[c - split] = from_f32<T>(t);
+  }
 }
 
 template <typename T>
@@ -190,7 +224,7 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
   const int nv = (H / VN + 63) / 64;
   const int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
   dim3 grid(nblk), block(256);
-  const size_t lds = (size_t)2 * H * sizeof(float);
+  const size_t lds = (size_t)2 * nv * VN * 64 * sizeof(float);
 #define MLM_LN_BWD(NVV)                                                                                    \
   case NVV:                                                                                                \
     hipLaunchKernelGGL((ln_bwd_kernel<T, NVV>), grid, block, lds, st, rows, H, (const T*)dy, (const T*)x,  \
@@ -203,8 +237,8 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
 #undef MLM_LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((ln_bwd_reduce_kernel<T>), dim3((2 * H + 255) / 256), dim3(256), 0, st, nblk, H, ws,
-                     (T*)dgamma, (T*)dbeta);
+  hipLaunchKernelGGL((reduce_cols_kernel<T>), dim3((2 * H + 31) / 32), dim3(256), 0, st, nblk, 2 * H, ws,
+                     (T*)dgamma, (T*)dbeta, H);
   return hipGetLastError();
 }
 
@@ -269,49 +303,54 @@ hipError_t launch_combine(int dtype, int T, int H, const void* const* partials, 
 }
 
 // ------------------------------------------------------------------------------ column sums (bias gradients)
+// Block = 64 vector-columns x 4 row-slices over kColsumRowsPerBlock rows; slices are summed through LDS in a fixed
+// order, the chunk partial goes to the workspace and reduce_cols_kernel finishes.
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(int rows, int N, const T* __restrict__ dy,
                                                              float* __restrict__ ws) {
   constexpr int VN = Vec16<T>::N;
-  const int vcol = blockIdx.x * 256 + threadIdx.x;   // vector column
-  if (vcol * VN >= N) return;
+  __shared__ float red[4][64 * VN + 1];
+  const int vx = threadIdx.x & 63, sl = threadIdx.x >> 6;
+  const int vcol = blockIdx.x * 64 + vx;
+  const bool ok = vcol * VN < N;
   const int r0 = blockIdx.y * kColsumRowsPerBlock;
   const int r1 = min(rows, r0 + kColsumRowsPerBlock);
   float acc[VN];
 #pragma unroll
   for (int e = 0; e < VN; ++e) acc[e] = 0.f;
-  for (int r = r0; r < r1; ++r) {
-    Vec16<T> v;
-    v.load(dy + (size_t)r * N + (size_t)vcol * VN);
+  if (ok) {
+#pragma unroll 4
+    for (int r = r0 + sl; r < r1; r += 4) {
+      Vec16<T> v;
+      v.load(dy + (size_t)r * N + (size_t)vcol * VN);
 #pragma unroll
-    for (int e = 0; e < VN; ++e) acc[e] += v.get(e);
+      for (int e = 0; e < VN; ++e) acc[e] += v.get(e);
+    }
   }
 #pragma unroll
-  for (int e = 0; e < VN; ++e) ws[(size_t)blockIdx.y * N + (size_t)vcol * VN + e] = acc[e];
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void colsum_reduce_kernel(int nchunk, int N, const float* __restrict__ ws,
-                                                            T* __restrict__ out) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= N) return;
-  float acc = 0.f;
-  for (int k = 0; k < nchunk; ++k) acc += ws[(size_t)k * N + c];
-  out[c] = from_f32<T>(acc);
+  for (int e = 0; e < VN; ++e) red[sl][e * 64 + vx] = acc[e];
+  __syncthreads();
+  if (sl == 0 && ok) {
+#pragma unroll
+    for (int e = 0; e < VN; ++e) {
+      const float t = (red[0][e * 64 + vx] + red[1][e * 64 + vx]) + (red[2][e * 64 + vx] + red[3][e * 64 + vx]);
+      ws[(size_t)blockIdx.y * N + (size_t)vcol * VN + e] = t;
+    }
+  }
 }
 
 hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, float* ws, hipStream_t st) {
   const int nchunk = (T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
   if (dtype == MLM_BF16) {
-    dim3 grid((N / 8 + 255) / 256, nchunk);
+    dim3 grid((N / 8 + 63) / 64, nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<bf16>), grid, dim3(256), 0, st, T, N, (const bf16*)dy, ws);
-    hipLaunchKernelGGL((colsum_reduce_kernel<bf16>), dim3((N + 255) / 256), dim3(256), 0, st, nchunk, N, ws,
-                       (bf16*)dbias);
+    hipLaunchKernelGGL((reduce_cols_kernel<bf16>), dim3((N + 31) / 32), dim3(256), 0, st, nchunk, N, ws,
+                       (bf16*)dbias, (bf16*)dbias, N);
   } else {
-    dim3 grid((N / 4 + 255) / 256, nchunk);
+    dim3 grid((N / 4 + 63) / 64, nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(256), 0, st, T, N, (const float*)dy, ws);
-    hipLaunchKernelGGL((colsum_reduce_kernel<float>), dim3((N + 255) / 256), dim3(256), 0, st, nchunk, N, ws,
-                       (float*)dbias);
+    hipLaunchKernelGGL((reduce_cols_kernel<float>), dim3((N + 31) / 32), dim3(256), 0, st, nchunk, N, ws,
+                       (float*)dbias, (float*)dbias, N);
   }
   return hipGetLastError();
 }
@@ -323,22 +362,41 @@ __global__ __launch_bounds__(256) void ce_tile_merge_kernel(int T, int ntiles, c
                                                             const float* __restrict__ t_ws,
                                                             const int32_t* __restrict__ targets, int v0, int v1,
                                                             float* m_r, float* s_r, float* t_r) {
-  const int t = blockIdx.x * 256 + threadIdx.x;
-  if (t >= T) return;
-  float M = -INFINITY;
-  for (int k = 0; k < ntiles; ++k) M = fmaxf(M, part_m[(size_t)k * T + t]);
-  float S = 0.f;
-  for (int k = 0; k < ntiles; ++k) S += part_s[(size_t)k * T + t] * __expf(part_m[(size_t)k * T + t] - M);
-  m_r[t] = M;
-  s_r[t] = S;
-  const int tg = targets[t];
-  t_r[t] = (tg >= v0 && tg < v1) ? t_ws[t] : 0.f;
+  // 32 tokens x 8 tile-slices per block; each slice merges its tiles online, slices are merged in a fixed order.
+  __shared__ float sm[8][33], ss[8][33];
+  const int tx = threadIdx.x & 31, sl = threadIdx.x >> 5;
+  const int t = blockIdx.x * 32 + tx;
+  float M = -INFINITY, S = 0.f;
+  if (t < T) {
+    for (int k = sl; k < ntiles; k += 8) {
+      const float mk = part_m[(size_t)k * T + t], sk = part_s[(size_t)k * T + t];
+      const float Mn = fmaxf(M, mk);
+      if (Mn > -INFINITY) S = S * __expf(M - Mn) + sk * __expf(mk - Mn);
+      M = Mn;
+    }
+  }
+  sm[sl][tx] = M;
+  ss[sl][tx] = S;
+  __syncthreads();
+  if (sl == 0 && t < T) {
+    float Mt = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) Mt = fmaxf(Mt, sm[k][tx]);
+    float St = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (sm[k][tx] > -INFINITY) St += ss[k][tx] * __expf(sm[k][tx] - Mt);
+    m_r[t] = Mt;
+    s_r[t] = St;
+    const int tg = targets[t];
+    t_r[t] = (tg >= v0 && tg < v1) ? t_ws[t] : 0.f;
+  }
 }
 
 hipError_t launch_ce_tile_merge(int T, int ntiles, const float* part_m, const float* part_s, const float* t_ws,
                                 const int32_t* targets, int v0, int v1, float* m_r, float* s_r, float* t_r,
                                 hipStream_t st) {
-  hipLaunchKernelGGL(ce_tile_merge_kernel, dim3((T + 255) / 256), dim3(256), 0, st, T, ntiles, part_m, part_s, t_ws,
+  hipLaunchKernelGGL(ce_tile_merge_kernel, dim3((T + 31) / 32), dim3(256), 0, st, T, ntiles, part_m, part_s, t_ws,
                      targets, v0, v1, m_r, s_r, t_r);
   return hipGetLastError();
 }

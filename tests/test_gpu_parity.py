@@ -214,3 +214,15 @@ def test_attention_integer_work_bf16():
     o = L.fetch()["shards"][0]
     v_row0 = o["qkv"][0, 2 * cfg2.H:]
     assert np.array_equal(o["ctx"][0], v_row0)
+
+
+# ------------------------------------------------------------------ the benchmark workloads at full size
+@pytest.mark.parametrize("name", ["gpt2_8p3b", "bert_3p9b", "gpt2_2p5b", "gpt2_1p2b"])
+def test_full_size_configs_all_shards(name):
+    """Every shard of the paper-shaped layers (Table 1 / Table 4 sizes), run sequentially on the one GPU through the
+    same calls and launch configuration that bench.py times, combined in-device and compared tensor by tensor with
+    the fp64 oracle of the sharded method (whose combined results equal the unsharded layer)."""
+    cfg = synth.CONFIGS[name]
+    errs = run_layer_parity(cfg, nonzero_bias=False, random_ln=False)
+    worst = sorted(errs, key=lambda e: -e[1])[:6]
+    print(name, "worst max-norm relative errors:", worst)
