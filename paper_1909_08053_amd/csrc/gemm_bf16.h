@@ -120,9 +120,9 @@ struct GemmTile {
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   static constexpr int TM = WM / 32, TN = WN / 32;
   static constexpr int STAGE = (BM + BN) * GLS;                    // elements per pipeline stage
-  static constexpr int STRIP = 32 * (WN + 8);                      // elements of one wave's epilogue strip
+  static constexpr int STRIP = 32 * 68 * 2;                        // bf16-sized elements of one epilogue strip (32 x 68 floats)
   static constexpr size_t LDS_MAIN = (size_t)2 * STAGE * 2;
-  static constexpr size_t LDS_EPI = (size_t)WAVES_M * WAVES_N * STRIP * 2 + (size_t)2 * WAVES_N * BM * 4;
+  static constexpr size_t LDS_EPI = (size_t)2 * WAVES_M * WAVES_N * STRIP * 2 + (size_t)2 * WAVES_N * BM * 4;
   static constexpr size_t LDS_BYTES = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
 };
 
@@ -144,12 +144,59 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
   tn = in / gsz;
 }
 
-// Epilogue shared by the GEMM kernels.  acc[i][j][e] holds row m = m0 + wm0 + 32 j + l32 and column
-// n = n0 + wn0 + 32 i + 8 (e/4) + 4 lh + (e%4) of the output tile.  Must be entered after a workgroup barrier that
-// follows the last LDS read of the main loop (the LDS is reused for the staging strips).
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, floatx16 (&acc)[BN / WAVES_N / 32][BM / WAVES_M / 32],
-                                              unsigned char* lds_raw, int m0, int n0, int tile_n) {
+// ---------------------------------------------------------------------------------------------- epilogue
+// acc[i][j][e] holds row m = m0 + wm0 + 32 j + l32 and column n = n0 + wn0 + 32 i + 8 (e/4) + 4 lh + (e%4) of the
+// output tile.  Must be entered after a workgroup barrier that follows the last LDS read of the main loop (the LDS
+// is reused: two staging strips per wave, then the cross-wave reduction area of the cross-entropy partials).
+
+// Per-row softmax statistics of the logits tile (fused cross entropy): row max and sum of exp over the tile's
+// columns, plus the target logit if the target column lies in this tile.  RAGGED: the tile hangs over column N.
+template <int TN, int TM, int WN, bool RAGGED>
+__device__ __forceinline__ void ce_tile_stats(const GemmArgs& a, const floatx16 (&acc)[TN][TM], int m0w, int n0w,
+                                              int l32, int lh, float* red_m_w, float* red_s_w) {
+  const int nvalid = a.N - (n0w + 4 * lh);     // RAGGED: register column c (relative) is real iff c < nvalid
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int row = m0w + j * 32 + l32;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int c = i * 32 + 8 * (e >> 2) + (e & 3);
+        const float v = (RAGGED && c >= nvalid) ? -INFINITY : acc[i][j][e];
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // column of the target relative to this lane's registers (integer test), one select per value
+    const int loc = (row < a.M) ? a.targets[row] - a.v0 - (n0w + 4 * lh) : -1;
+    const float mxl = mx * 1.4426950408889634f;
+    float se = 0.f, tv = 0.f;
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int c = i * 32 + 8 * (e >> 2) + (e & 3);
+        const float v = acc[i][j][e];
+        const float p = __builtin_amdgcn_exp2f(fmaf(v, 1.4426950408889634f, -mxl));
+        se += (RAGGED && c >= nvalid) ? 0.f : p;
+        tv = (loc == c) ? v : tv;
+      }
+    se += __shfl_xor(se, 32, 64);
+    // the half that owns the column has bit 2 of (target - 4 lh) clear
+    if (loc >= 0 && loc < WN && (loc & 4) == 0 && (!RAGGED || loc < nvalid)) a.t_out[row] = tv;
+    if (lh == 0) {
+      red_m_w[j * 32 + l32] = mx;
+      red_s_w[j * 32 + l32] = se;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, bool GELU_TANH>
+__device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
+                                                   floatx16 (&acc)[BN / WAVES_N / 32][BM / WAVES_M / 32],
+                                                   unsigned char* lds_raw, int m0, int n0, int tile_n) {
   typedef GemmTile<BM, BN, WAVES_M, WAVES_N> Tcfg;
   constexpr int NT = Tcfg::NT, TM = Tcfg::TM, TN = Tcfg::TN, WM = Tcfg::WM, WN = Tcfg::WN;
   bf16* lds = reinterpret_cast<bf16*>(lds_raw);
@@ -157,52 +204,16 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, floatx16 (&acc)
   const int lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lh = lane >> 5;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
-  bf16* strip = lds + wave * Tcfg::STRIP;
   bf16* C = (bf16*)a.C;
   const bf16* bias = (const bf16*)a.bias;
 
   if (EPI == EPI_CE) {
-    float* red_m = reinterpret_cast<float*>(lds_raw + (size_t)WAVES_M * WAVES_N * Tcfg::STRIP * 2);
+    float* red_m = reinterpret_cast<float*>(lds_raw + (size_t)2 * WAVES_M * WAVES_N * Tcfg::STRIP * 2);
     float* red_s = red_m + WAVES_N * BM;
-    if (n0 + BN > a.N) {
-      // ragged last column tile: columns past N take no part in the statistics (exp(-inf) = 0)
-#pragma unroll
-      for (int j = 0; j < TM; ++j)
-#pragma unroll
-        for (int i = 0; i < TN; ++i)
-#pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (n0 + wn0 + i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3) >= a.N) acc[i][j][e] = -INFINITY;
-    }
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-      const int row = m0 + wm0 + j * 32 + l32;
-      float mx = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, acc[i][j][e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      // column of the target inside this lane's registers, or -1: integer test, then one select per value
-      const int loc = (row < a.M) ? a.targets[row] - a.v0 - (n0 + wn0 + 4 * lh) : -1;
-      const float mxl = mx * 1.4426950408889634f;
-      float se = 0.f, tv = 0.f;
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float v = acc[i][j][e];
-          se += __builtin_amdgcn_exp2f(fmaf(v, 1.4426950408889634f, -mxl));
-          tv = (loc == i * 32 + 8 * (e >> 2) + (e & 3)) ? v : tv;
-        }
-      se += __shfl_xor(se, 32, 64);
-      if (loc >= 0 && loc < WN && ((loc >> 2) & 1) == 0) a.t_out[row] = tv;   // (loc & 4) == 0: column owned by this half
-      if (lh == 0) {
-        red_m[(wave % WAVES_N) * BM + wm0 + j * 32 + l32] = mx;
-        red_s[(wave % WAVES_N) * BM + wm0 + j * 32 + l32] = se;
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    float* rm = red_m + (wave % WAVES_N) * BM + wm0;
+    float* rs = red_s + (wave % WAVES_N) * BM + wm0;
+    if (n0 + BN > a.N) ce_tile_stats<TN, TM, WN, true>(a, acc, m0 + wm0, n0 + wn0, l32, lh, rm, rs);
+    else ce_tile_stats<TN, TM, WN, false>(a, acc, m0 + wm0, n0 + wn0, l32, lh, rm, rs);
     __syncthreads();
     for (int rloc = tid; rloc < BM; rloc += NT) {
       const int row = m0 + rloc;
@@ -223,75 +234,102 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, floatx16 (&acc)
     if (C == nullptr) return;
   }
 
-  constexpr int NPASS = (EPI == EPI_BIAS_GELU) ? 2 : 1;
+  // ---- store passes.  The fp32 accumulators go through per-wave LDS strips of 32 rows x 64 columns (two strips,
+  // software-pipelined: strip s+1 is written while strip s is read back).  All element-wise work happens at
+  // read-back time, where a lane owns 8 consecutive columns of one row: bias, the saved pre-activation and the
+  // outputs are then 16-byte accesses with 128-byte contiguous row segments.
+  constexpr int NSTEP = TM * (TN / 2);
+  constexpr int SW = 64 + 4;                                   // strip row stride in floats (272 B)
+  static_assert(32 * SW * 4 <= Tcfg::STRIP * 2, "strip does not fit");
+  static_assert(TN % 2 == 0, "wave tile must be a multiple of 64 columns");
+  float* strip0 = reinterpret_cast<float*>(lds + (size_t)wave * 2 * Tcfg::STRIP);
+  const bool full = (m0 + BM <= a.M) && (n0 + BN <= a.N);
+  const int rb_r = lane >> 3, rb_c = (lane & 7) * 8;           // read-back: 8 rows x 8 column groups per iteration
+
 #pragma unroll
-  for (int j = 0; j < TM; ++j) {
-    const int row = m0 + wm0 + j * 32 + l32;
-    const int rowc = min(row, a.M - 1);
-    float coef = 0.f, Mr = 0.f, invS = 0.f;
-    int loc = -1;
-    if (EPI == EPI_DLOGITS) {
-      coef = (a.loss_w ? a.loss_w[rowc] : 1.0f) / a.loss_stats[1];
-      Mr = a.Mrow[rowc];
-      invS = coef / a.Srow[rowc];
-      loc = a.targets[rowc] - a.v0;
-    }
+  for (int step = 0; step <= NSTEP; ++step) {
+    if (step < NSTEP) {
+      const int j = step / (TN / 2), h = step % (TN / 2);
+      float* strip = strip0 + (step & 1) * (Tcfg::STRIP / 2);
 #pragma unroll
-    for (int pass = 0; pass < NPASS; ++pass) {
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
+      for (int il = 0; il < 2; ++il)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int nl = i * 32 + 8 * g + 4 * lh;            // column inside the wave tile
-          const int n = n0 + wn0 + nl;
-          const int nc = min(n, a.N - 4);
-          float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * g + e];
-          if (EPI == EPI_STORE || EPI == EPI_BIAS_GELU) {
-            if (bias) {
-              const bf16x4 bv = *reinterpret_cast<const bf16x4*>(bias + nc);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += (float)bv[e];
-            }
-            if (EPI == EPI_BIAS_GELU && pass == 1) {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] = gelu_fwd(v[e], a.gelu_tanh != 0);
-            }
-          } else if (EPI == EPI_DGELU) {
-            const bf16x4 gv = *reinterpret_cast<const bf16x4*>((const bf16*)a.aux + (size_t)rowc * a.ldaux + nc);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] *= gelu_bwd((float)gv[e], a.gelu_tanh != 0);
-          } else if (EPI == EPI_DLOGITS) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              v[e] = __expf(v[e] - Mr) * invS;
-              if (n + e == loc) v[e] -= coef;
-            }
-          }
-          bf16x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-          *reinterpret_cast<bf16x4*>(strip + l32 * (WN + 8) + nl) = o;
+          const floatx16& t = acc[2 * h + il][j];
+          const float4 v = make_float4(t[4 * g], t[4 * g + 1], t[4 * g + 2], t[4 * g + 3]);
+          *reinterpret_cast<float4*>(strip + l32 * SW + il * 32 + 8 * g + 4 * lh) = v;
         }
-      __builtin_amdgcn_sched_barrier(0);
-      __builtin_amdgcn_wave_barrier();
-      bf16* dst = (EPI == EPI_BIAS_GELU && pass == 0) ? (bf16*)a.aux : C;
-      const int ldd = (EPI == EPI_BIAS_GELU && pass == 0) ? a.ldaux : a.ldc;
-      constexpr int VPR = WN / 8;                              // 16-byte vectors per strip row
-#pragma unroll
-      for (int it = 0; it < (32 * VPR) / 64; ++it) {
-        const int v = lane + it * 64;
-        const int r = v / VPR, cv = v % VPR;
-        const int gm = m0 + wm0 + j * 32 + r;
-        const int gn = n0 + wn0 + cv * 8;
-        if (gm < a.M && gn < a.N)
-          *reinterpret_cast<uint4*>(dst + (size_t)gm * ldd + gn) =
-              *reinterpret_cast<const uint4*>(strip + r * (WN + 8) + cv * 8);
-      }
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_wave_barrier();
+    if (step > 0) {
+      const int ps = step - 1;
+      const int j = ps / (TN / 2), h = ps % (TN / 2);
+      const float* strip = strip0 + (ps & 1) * (Tcfg::STRIP / 2);
+      const int gn = n0 + wn0 + h * 64 + rb_c;                 // first of this lane's 8 columns
+      const int gnc = min(gn, a.N - 8);
+      float bvals[8];
+      if ((EPI == EPI_STORE || EPI == EPI_BIAS_GELU) && bias != nullptr) {
+        const bf16x8 b8 = *reinterpret_cast<const bf16x8*>(bias + gnc);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bvals[e] = (float)b8[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bvals[e] = 0.f;
+      }
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int r = rb_r + it * 8;
+        const int gm = m0 + wm0 + j * 32 + r;
+        const int gmc = min(gm, a.M - 1);
+        const float4 lo = *reinterpret_cast<const float4*>(strip + r * SW + rb_c);
+        const float4 hi = *reinterpret_cast<const float4*>(strip + r * SW + rb_c + 4);
+        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        const bool ok = full || (gm < a.M && gn < a.N);
+        bf16x8 o;
+        if (EPI == EPI_STORE || EPI == EPI_CE) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (bf16)(v[e] + bvals[e]);
+        } else if (EPI == EPI_BIAS_GELU) {
+          bf16x8 pre;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float x = v[e] + bvals[e];
+            pre[e] = (bf16)x;
+            o[e] = (bf16)gelu_fwd(x, GELU_TANH);
+          }
+          if (ok) *reinterpret_cast<bf16x8*>((bf16*)a.aux + (size_t)gm * a.ldaux + gn) = pre;
+        } else if (EPI == EPI_DGELU) {
+          const bf16x8 g8 = *reinterpret_cast<const bf16x8*>((const bf16*)a.aux + (size_t)gmc * a.ldaux + gnc);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (bf16)(v[e] * gelu_bwd((float)g8[e], GELU_TANH));
+        } else if (EPI == EPI_DLOGITS) {
+          const float coef = (a.loss_w ? a.loss_w[gmc] : 1.0f) / a.loss_stats[1];
+          const float Mrl = a.Mrow[gmc] * 1.4426950408889634f;
+          const float invS = coef / a.Srow[gmc];
+          const int loc = a.targets[gmc] - a.v0 - gn;           // target column relative to this lane's first column
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            float pz = __builtin_amdgcn_exp2f(fmaf(v[e], 1.4426950408889634f, -Mrl)) * invS;
+            if (loc == e) pz -= coef;
+            o[e] = (bf16)pz;
+          }
+        }
+        if (ok) *reinterpret_cast<bf16x8*>(C + (size_t)gm * a.ldc + gn) = o;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, floatx16 (&acc)[BN / WAVES_N / 32][BM / WAVES_M / 32],
+                                              unsigned char* lds_raw, int m0, int n0, int tile_n) {
+  if (EPI == EPI_BIAS_GELU || EPI == EPI_DGELU) {
+    // the GeLU form is a launch-wide constant: branch once, not per element
+    if (a.gelu_tanh) gemm_epilogue_impl<BM, BN, WAVES_M, WAVES_N, EPI, true>(a, acc, lds_raw, m0, n0, tile_n);
+    else gemm_epilogue_impl<BM, BN, WAVES_M, WAVES_N, EPI, false>(a, acc, lds_raw, m0, n0, tile_n);
+  } else {
+    gemm_epilogue_impl<BM, BN, WAVES_M, WAVES_N, EPI, true>(a, acc, lds_raw, m0, n0, tile_n);
   }
 }
 
