@@ -126,7 +126,7 @@ hipError_t launch_attn_fwd_f32(const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_bwd_f32(const AttnArgs& a, hipStream_t st);
 
 // ---- row / elementwise kernels (rowops.hip); dtype = MLM_F32 / MLM_BF16 ----------
-constexpr int kLnBwdRowsPerBlock = 16;
+constexpr int kLnBwdRowsPerBlock = 32;
 constexpr int kColsumRowsPerBlock = 64;
 constexpr int kMaxPartials = 16;
 

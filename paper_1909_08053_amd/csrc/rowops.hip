@@ -83,27 +83,36 @@ hipError_t launch_layernorm_fwd(int dtype, int T, int H, float eps, const void* 
 
 // ------------------------------------------------------------------------------ layer norm backward
 // Block = 4 waves, kLnBwdRowsPerBlock rows, one wave per row with the next row's vectors prefetched while the
-// current row is reduced.  Each lane keeps the dgamma/dbeta partial sums of the columns it owns; the four waves are
-// then summed in a fixed order (deterministic) through a conflict-free LDS layout [value][lane] and the block
-// partial goes to the workspace; reduce_cols_kernel sums the block partials.
+// current row is reduced.  Each lane keeps the dgamma/dbeta partial sums of the columns it owns; at the end the
+// waves' partials meet in LDS ([wave][value][lane], conflict-free) and are summed per column in wave order
+// (deterministic); the block partial goes to the workspace and reduce_cols_kernel sums the block partials.
+constexpr int kLnBwdWaves = 4;
+
 template <typename T, int NV>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy,
-                                                     const T* __restrict__ x, const T* __restrict__ gamma,
-                                                     const float* __restrict__ mean, const float* __restrict__ rstd,
-                                                     const T* residual, T* dx, float* __restrict__ ws) {
+__global__ __launch_bounds__(kLnBwdWaves * 64) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy,
+                                                                  const T* __restrict__ x, const T* __restrict__ gamma,
+                                                                  const float* __restrict__ mean,
+                                                                  const float* __restrict__ rstd, const T* residual,
+                                                                  T* dx, float* __restrict__ ws) {
   constexpr int VN = Vec16<T>::N;
-  extern __shared__ float red[];   // [2 * NV * VN][64]
+  constexpr int SLOTS = NV * VN * 64;
+  extern __shared__ float red[];   // [kLnBwdWaves][SLOTS]
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nvec = H / VN;
   const float invH = 1.0f / (float)H;
   float dg[NV][VN], db[NV][VN];
-  Vec16<T> gam[NV];
+  float gam[NV][VN];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    if (lane + 64 * i < nvec) gam[i].load(gamma + (size_t)(lane + 64 * i) * VN);
+    Vec16<T> g;
+    if (lane + 64 * i < nvec) g.load(gamma + (size_t)(lane + 64 * i) * VN);
 #pragma unroll
-    for (int e = 0; e < VN; ++e) { dg[i][e] = 0.f; db[i][e] = 0.f; }
+    for (int e = 0; e < VN; ++e) {
+      gam[i][e] = (lane + 64 * i < nvec) ? g.get(e) : 0.f;
+      dg[i][e] = 0.f;
+      db[i][e] = 0.f;
+    }
   }
   const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
   const int row_end = min(rows, row0 + kLnBwdRowsPerBlock);
@@ -120,10 +129,10 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int H, const T* _
       }
     }
   }
-  for (; row < row_end; row += 4) {
+  for (; row < row_end; row += kLnBwdWaves) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) { vdy[i] = ndy[i]; vx[i] = nx[i]; vres[i] = nres[i]; }
-    const int nrow = row + 4;
+    const int nrow = row + kLnBwdWaves;
     if (nrow < row_end) {
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
@@ -137,17 +146,18 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int H, const T* _
     }
     const float mu = mean[row], rs = rstd[row];
     float s1 = 0.f, s2 = 0.f;
+    float xh[NV][VN];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       if (lane + 64 * i < nvec) {
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
-          const float xh = (vx[i].get(e) - mu) * rs;
+          xh[i][e] = (vx[i].get(e) - mu) * rs;
           const float d = vdy[i].get(e);
-          const float g = d * gam[i].get(e);
+          const float g = d * gam[i][e];
           s1 += g;
-          s2 += g * xh;
-          dg[i][e] += d * xh;
+          s2 = fmaf(g, xh[i][e], s2);
+          dg[i][e] = fmaf(d, xh[i][e], dg[i][e]);
           db[i][e] += d;
         }
       }
@@ -161,9 +171,8 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int H, const T* _
         Vec16<T> o;
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
-          const float xh = (vx[i].get(e) - mu) * rs;
-          const float g = vdy[i].get(e) * gam[i].get(e);
-          float v = rs * (g - s1 - xh * s2);
+          const float g = vdy[i].get(e) * gam[i][e];
+          float v = rs * (g - s1 - xh[i][e] * s2);
           if (residual) v += vres[i].get(e);
           o.set(e, v);
         }
@@ -171,48 +180,55 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int H, const T* _
       }
     }
   }
-  // fixed-order sum of the four waves' column partials; LDS slot (i, e, lane) -> red[(i*VN+e)*64 + lane]
-  for (int w = 0; w < 4; ++w) {
-    if (wave == w) {
+  float* out = ws + (size_t)blockIdx.x * 2 * H;
 #pragma unroll
-      for (int i = 0; i < NV; ++i)
+  for (int part = 0; part < 2; ++part) {
+    float* mine = red + (size_t)wave * SLOTS;
 #pragma unroll
-        for (int e = 0; e < VN; ++e) {
-          const int slot = (i * VN + e) * 64 + lane;
-          if (w == 0) { red[slot] = dg[i][e]; red[NV * VN * 64 + slot] = db[i][e]; }
-          else { red[slot] += dg[i][e]; red[NV * VN * 64 + slot] += db[i][e]; }
-        }
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+      for (int e = 0; e < VN; ++e) mine[(i * VN + e) * 64 + lane] = part == 0 ? dg[i][e] : db[i][e];
+    __syncthreads();
+    for (int col = threadIdx.x; col < H; col += kLnBwdWaves * 64) {
+      const int idx = col / VN, e = col % VN;
+      const int slot = ((idx >> 6) * VN + e) * 64 + (idx & 63);
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < kLnBwdWaves; ++w) t += red[(size_t)w * SLOTS + slot];
+      out[part * H + col] = t;
     }
     __syncthreads();
   }
-  // coalesced write-out: consecutive threads take consecutive columns
-  float* out = ws + (size_t)blockIdx.x * 2 * H;
-  for (int col = threadIdx.x; col < H; col += 256) {
-    const int idx = col / VN, e = col % VN;
-    const int slot = ((idx >> 6) * VN + e) * 64 + (idx & 63);
-    out[col] = red[slot];
-    out[H + col] = red[NV * VN * 64 + slot];
-  }
 }
 
-// out[c] = sum_k ws[k][c] over nchunk row-chunks: 32 columns x 8 chunk-slices per block, slices summed in a fixed order.
+// out[c] = sum_k ws[k][c] over nchunk row-chunks: 16 float4 column groups x 16 chunk-slices per block; every slice
+// sums its chunks in order and the 16 slices are added in a fixed order (deterministic).
 template <typename T>
 __global__ __launch_bounds__(256) void reduce_cols_kernel(int nchunk, int ncols, const float* __restrict__ ws,
                                                           T* __restrict__ out0, T* __restrict__ out1, int split) {
-  __shared__ float red[8][33];
-  const int cx = threadIdx.x & 31, sl = threadIdx.x >> 5;
-  const int c = blockIdx.x * 32 + cx;
-  float acc = 0.f;
-  if (c < ncols)
-    for (int k = sl; k < nchunk; k += 8) acc += ws[(size_t)k * ncols + c];
+  __shared__ float4 red[16][17];
+  const int cx = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int c = (blockIdx.x * 16 + cx) * 4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (c < ncols) {
+#pragma unroll 4
+    for (int k = sl; k < nchunk; k += 16) {
+      const float4 v = *reinterpret_cast<const float4*>(ws + (size_t)k * ncols + c);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+  }
   red[sl][cx] = acc;
   __syncthreads();
   if (sl == 0 && c < ncols) {
-    float t = 0.f;
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t += red[k][cx];
-    if (c < split) out0[c] = from_f32<T>(t);
-    else out1[c - split] = from_f32<T>(t);
+    for (int k = 0; k < 16; ++k) { t.x += red[k][cx].x; t.y += red[k][cx].y; t.z += red[k][cx].z; t.w += red[k][cx].w; }
+    const float tv[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (c + e < split) out0[c + e] = from_f32<T>(tv[e]);
+      else out1[c + e - split] = from_f32<T>(tv[e]);
+    }
   }
 }
 
@@ -223,13 +239,18 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
   constexpr int VN = Vec16<T>::N;
   const int nv = (H / VN + 63) / 64;
   const int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
-  dim3 grid(nblk), block(256);
-  const size_t lds = (size_t)2 * nv * VN * 64 * sizeof(float);
+  dim3 grid(nblk), block(kLnBwdWaves * 64);
+  const size_t lds = (size_t)kLnBwdWaves * nv * VN * 64 * sizeof(float);
 #define MLM_LN_BWD(NVV)                                                                                    \
-  case NVV:                                                                                                \
+  case NVV: {                                                                                              \
+    if (lds > 64 * 1024) {                                                                                 \
+      hipError_t ea = hipFuncSetAttribute((const void*)ln_bwd_kernel<T, NVV>,                              \
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
+      if (ea != hipSuccess) return ea;                                                                     \
+    }                                                                                                      \
     hipLaunchKernelGGL((ln_bwd_kernel<T, NVV>), grid, block, lds, st, rows, H, (const T*)dy, (const T*)x,  \
                        (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws);                       \
-    break;
+  } break;
   switch (nv) {
     MLM_LN_BWD(1) MLM_LN_BWD(2) MLM_LN_BWD(3) MLM_LN_BWD(4) MLM_LN_BWD(5) MLM_LN_BWD(6) MLM_LN_BWD(7) MLM_LN_BWD(8)
     default: return hipErrorInvalidValue;
@@ -237,7 +258,7 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
 #undef MLM_LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((reduce_cols_kernel<T>), dim3((2 * H + 31) / 32), dim3(256), 0, st, nblk, 2 * H, ws,
+  hipLaunchKernelGGL((reduce_cols_kernel<T>), dim3((2 * H + 63) / 64), dim3(256), 0, st, nblk, 2 * H, ws,
                      (T*)dgamma, (T*)dbeta, H);
   return hipGetLastError();
 }
@@ -344,12 +365,12 @@ hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, f
   if (dtype == MLM_BF16) {
     dim3 grid((N / 8 + 63) / 64, nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<bf16>), grid, dim3(256), 0, st, T, N, (const bf16*)dy, ws);
-    hipLaunchKernelGGL((reduce_cols_kernel<bf16>), dim3((N + 31) / 32), dim3(256), 0, st, nchunk, N, ws,
+    hipLaunchKernelGGL((reduce_cols_kernel<bf16>), dim3((N + 63) / 64), dim3(256), 0, st, nchunk, N, ws,
                        (bf16*)dbias, (bf16*)dbias, N);
   } else {
     dim3 grid((N / 4 + 63) / 64, nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(256), 0, st, T, N, (const float*)dy, ws);
-    hipLaunchKernelGGL((reduce_cols_kernel<float>), dim3((N + 31) / 32), dim3(256), 0, st, nchunk, N, ws,
+    hipLaunchKernelGGL((reduce_cols_kernel<float>), dim3((N + 63) / 64), dim3(256), 0, st, nchunk, N, ws,
                        (float*)dbias, (float*)dbias, N);
   }
   return hipGetLastError();
