@@ -31,9 +31,9 @@
  *   - Errors: every call returns 0 (MLM_OK) or a negative mlm_status.  Arguments are
  *     validated on the host before anything is launched, so a failing call has
  *     launched nothing.  No exceptions cross the ABI and there is no global state.
- *   - MLM_BF16 requires H, H/p, F/p, V/p and the head size to be multiples of 8 and
- *     16-byte aligned pointers (MLM_E_ALIGN otherwise).  Supported head sizes:
- *     64, 96, 128 (MLM_BF16); any multiple of 4 up to 128 (MLM_F32).
+ *   - H, H/p, F/p, V/p and the head size must be multiples of 8 and pointers 16-byte
+ *     aligned (MLM_E_ALIGN otherwise).  Supported head sizes: 64, 96, 128 (MLM_BF16);
+ *     any multiple of 16 up to 128 (MLM_F32).  H <= 4096 (MLM_BF16) / 2048 (MLM_F32).
  */
 #ifndef MLM_SHARD_H
 #define MLM_SHARD_H
