@@ -41,6 +41,15 @@ bool gemm_use_v2(const GemmArgs& a) {
   return enabled && a.K % 32 == 0 && a.K >= 32;
 }
 
+int gemm_v2_waves() {
+  static int nw = -1;
+  if (nw < 0) {
+    const char* e = getenv("MLM_GEMM_WAVES");
+    nw = (e && atoi(e) == 4) ? 4 : 8;
+  }
+  return nw;
+}
+
 int gemm_bf16_ce_col_tiles(int M, int N, int K) {
   GemmArgs probe;
   probe.K = K;

@@ -52,16 +52,17 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // Per-lane source pointers of one operand's four 1-KB DMA instructions per stage.
-template <bool KC>
+// QPW = 16 / (waves per workgroup): 1-KB DMA instructions per wave, operand and slice.
+template <bool KC, int QPW>
 struct V2Src {
-  const bf16* p[4];
+  const bf16* p[QPW];
   size_t step;     // elements to advance per k-slice
   __device__ __forceinline__ void init(const bf16* P, int ld, int row0, int nrows, int k_begin, int wave, int lane) {
     if (KC) {
       // LDS layout [256 rows][32 k] (64 B rows, four 16-byte units); unit u of row r holds k-chunk u ^ ((r >> 2) & 3)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int row = (wave * 4 + q) * 16 + (lane >> 2);
+      for (int q = 0; q < QPW; ++q) {
+        const int row = (wave * QPW + q) * 16 + (lane >> 2);
         const int c = (lane & 3) ^ ((lane >> 4) & 3);
         p[q] = P + (size_t)min(row0 + row, nrows - 1) * ld + k_begin + c * 8;
       }
@@ -69,9 +70,9 @@ struct V2Src {
     } else {
       // LDS layout [32 k][256 rows] (512 B per k, 32 units); unit u of k-row holds row-chunk u ^ ((k & 7) << 1)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int k = 2 * (wave * 4 + q) + (lane >> 5);
-        const int u = (lane & 31) ^ (((2 * q + (lane >> 5)) & 7) << 1);
+      for (int q = 0; q < QPW; ++q) {
+        const int k = 2 * (wave * QPW + q) + (lane >> 5);
+        const int u = (lane & 31) ^ ((k & 7) << 1);
         p[q] = P + (size_t)(k_begin + k) * ld + min(row0 + u * 8, nrows - 8);
       }
       step = (size_t)V2_BK * ld;
@@ -80,7 +81,7 @@ struct V2Src {
   // op_lds: LDS byte address of this operand's stage buffer; wave_u: wave index as a uniform (SGPR) value
   __device__ __forceinline__ void issue(uint32_t op_lds, int wave_u, int kt_rel) const {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) dma16(p[q] + (size_t)kt_rel * step, op_lds + (wave_u * 4 + q) * 1024);
+    for (int q = 0; q < QPW; ++q) dma16(p[q] + (size_t)kt_rel * step, op_lds + (wave_u * QPW + q) * 1024);
   }
 };
 
@@ -130,11 +131,13 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
   return p;
 }
 
-template <bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan plan, float* splitk_ws) {
+// NW = waves per workgroup: 4 (2 x 2 waves of 128 x 128) or 8 (2 x 4 waves of 128 x 64, two waves per SIMD).
+template <bool A_KC, bool B_KC, int EPI, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan plan, float* splitk_ws) {
+  constexpr int WAVES_N = NW / 2, WN = V2_B / WAVES_N, TN = WN / 32, QPW = 16 / NW, LPS = 2 * QPW;  // LPS: DMA per slice per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+  const int wm0 = (wave / WAVES_N) * 128, wn0 = (wave % WAVES_N) * WN;
 
   // work item: a full tile, or one k-piece of a tail tile
   int vt, piece = 0, npieces = 1;
@@ -156,14 +159,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan pl
   const int kt_end = (int)((long)nk_total * (piece + 1) / npieces);
   const int nk = kt_end - kt_begin;
 
-  V2Src<A_KC> sa;
-  V2Src<B_KC> sb;
+  V2Src<A_KC, QPW> sa;
+  V2Src<B_KC, QPW> sb;
   sa.init((const bf16*)a.A, a.lda, m0, a.M, kt_begin * V2_BK, wave, lane);
   sb.init((const bf16*)a.B, a.ldb, n0, a.N, kt_begin * V2_BK, wave, lane);
 
-  floatx16 acc[4][4];
+  floatx16 acc[TN][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TN; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -182,17 +185,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan pl
   // read from LDS while the matrix cores work on the current half, and the slice hand-over (wait for the DMA of
   // slice kt+1, barrier, re-arm the freed stage) sits in the middle of slice kt, so LDS latency, barrier skew and
   // DMA issue are all covered by 512 clocks of MFMA work.
-  bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
+  bf16x8 fa0[4], fb0[TN], fa1[4], fb1[TN];
   {
     // slice 0 must have landed; slices 1 and 2 may stay in flight (8 DMA instructions each per wave)
-    if (nk >= 3) wait_vmcnt<16>();
-    else if (nk == 2) wait_vmcnt<8>();
+    if (nk >= 3) wait_vmcnt<2 * LPS>();
+    else if (nk == 2) wait_vmcnt<LPS>();
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(lds_raw, wm0 + j * 32, 0, lane);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fb0[i] = v2_frag<B_KC>(lds_raw + V2_OP_BYTES, wn0 + i * 32, 0, lane);
+    for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(lds_raw + V2_OP_BYTES, wn0 + i * 32, 0, lane);
   }
   for (int kt = 0; kt < nk; ++kt) {
     const unsigned char* sA = lds_raw + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
@@ -200,15 +203,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan pl
 #pragma unroll
     for (int j = 0; j < 4; ++j) fa1[j] = v2_frag<A_KC>(sA, wm0 + j * 32, 1, lane);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fb1[i] = v2_frag<B_KC>(sB, wn0 + i * 32, 1, lane);
+    for (int i = 0; i < TN; ++i) fb1[i] = v2_frag<B_KC>(sB, wn0 + i * 32, 1, lane);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[i], fa0[j], acc[i][j], 0, 0, 0);
     if (kt + 1 < nk) {
       // slice kt+1 must have landed; slice kt+2 may stay in flight
-      if (kt + 2 < nk) wait_vmcnt<8>();
+      if (kt + 2 < nk) wait_vmcnt<LPS>();
       else wait_vmcnt<0>();
       // Bare s_barrier (no memory fence: a fence would also wait for the slice still in flight).  After it
       // everyone's part of slice kt+1 is in LDS, and everyone has finished reading slice kt-1 (its last operand
@@ -223,10 +226,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan pl
 #pragma unroll
       for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(nA, wm0 + j * 32, 0, lane);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) fb0[i] = v2_frag<B_KC>(nA + V2_OP_BYTES, wn0 + i * 32, 0, lane);
+      for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(nA + V2_OP_BYTES, wn0 + i * 32, 0, lane);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[i], fa1[j], acc[i][j], 0, 0, 0);
@@ -240,7 +243,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan pl
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
@@ -248,7 +251,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan pl
         }
     return;
   }
-  gemm_epilogue<V2_B, V2_B, 2, 2, EPI>(a, acc, lds_raw, m0, n0, tile_n);
+  gemm_epilogue<V2_B, V2_B, 2, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
 }
 
 // Sum the k-pieces of every tail tile in piece order, add the bias, round once to bf16.
@@ -277,19 +280,25 @@ __global__ __launch_bounds__(256) void gemm_v2_fixup_kernel(GemmArgs a, V2Plan p
 
 inline size_t v2_splitk_ws_bytes() { return (size_t)V2_CUS * V2_B * V2_B * sizeof(float); }   // 64 MB upper bound
 
-template <bool A_KC, bool B_KC, int EPI>
-hipError_t launch_gemm_bf16_v2(const GemmArgs& a, float* splitk_ws, hipStream_t st) {
-  auto kern = gemm_bf16_v2_kernel<A_KC, B_KC, EPI>;
+int gemm_v2_waves();   // 8 by default; MLM_GEMM_WAVES=4 selects the 4-wave variant
+
+template <bool A_KC, bool B_KC, int EPI, int NW>
+hipError_t launch_gemm_bf16_v2_nw(const GemmArgs& a, float* splitk_ws, hipStream_t st) {
+  auto kern = gemm_bf16_v2_kernel<A_KC, B_KC, EPI, NW>;
+  // the ring (128 KB) or, with 8 waves, the epilogue's staging strips (2 per wave) + reduction area, whichever is larger
+  constexpr size_t kEpi = GemmTile<V2_B, V2_B, 2, NW / 2>::LDS_EPI;
+  constexpr size_t kLds = V2_LDS_BYTES > kEpi ? V2_LDS_BYTES : kEpi;
+  static_assert(kLds <= 160 * 1024, "LDS budget");
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)V2_LDS_BYTES);
+                                       (int)kLds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const V2Plan plan = v2_plan(a.M, a.N, a.K, EPI == EPI_STORE && splitk_ws != nullptr);
   const int grid = plan.full_tiles + plan.tail_tiles * plan.split;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), V2_LDS_BYTES, st, a, plan, splitk_ws);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), kLds, st, a, plan, splitk_ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (plan.tail_tiles) {
@@ -298,6 +307,12 @@ hipError_t launch_gemm_bf16_v2(const GemmArgs& a, float* splitk_ws, hipStream_t 
     e = hipGetLastError();
   }
   return e;
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+hipError_t launch_gemm_bf16_v2(const GemmArgs& a, float* splitk_ws, hipStream_t st) {
+  if (gemm_v2_waves() == 8) return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 8>(a, splitk_ws, st);
+  return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 4>(a, splitk_ws, st);
 }
 
 }  // namespace mlm
