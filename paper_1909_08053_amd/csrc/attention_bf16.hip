@@ -22,16 +22,19 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 // A [64][D] tile (row stride ld in HBM) fetched as 8x8 blocks: eight 16-byte row pieces per block.
+constexpr int ANW = 4;              // waves per workgroup: 32 owned rows each (2-wave blocks were measured slower: tile staging is re-done per block)
+constexpr int ANT = ANW * 64;
+
 template <int D>
 struct TileBlocks {
   static constexpr int BLKS = (ATILE / 8) * (D / 8);
-  static constexpr int PER = (BLKS + 255) / 256;
+  static constexpr int PER = (BLKS + ANT - 1) / ANT;
   uint4 reg[PER][8];
   // rows >= nvalid (relative to row0 = 0 of P) are zero-filled
   __device__ __forceinline__ void load(const bf16* __restrict__ P, int ld, int row0, int nrows, int tid) {
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      const int blk = tid + i * 256;
+      const int blk = tid + i * ANT;
       if (blk < BLKS) {
         const int rb = blk & 7, cb = blk >> 3;
 #pragma unroll
@@ -46,7 +49,7 @@ struct TileBlocks {
   __device__ __forceinline__ void store_rows(bf16* s, int tid) const {   // s: [64][D+8]
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      const int blk = tid + i * 256;
+      const int blk = tid + i * ANT;
       if (blk < BLKS) {
         const int rb = blk & 7, cb = blk >> 3;
 #pragma unroll
@@ -57,7 +60,7 @@ struct TileBlocks {
   __device__ __forceinline__ void store_transposed(bf16* s, int tid) const {   // s: [D][ATS]
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      const int blk = tid + i * 256;
+      const int blk = tid + i * ANT;
       if (blk < BLKS) {
         const int rb = blk & 7, cb = blk >> 3;
         uint4 o[8];
@@ -89,8 +92,8 @@ __device__ __forceinline__ bf16x8 pack8(const floatx16& v, int off) {
 
 // ------------------------------------------------------------------------------------------ forward
 template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnArgs a) {
-  constexpr int BQ = 128, KS = D + 8;
+__global__ __launch_bounds__(ANT) void attn_fwd_bf16_kernel(AttnArgs a) {
+  constexpr int BQ = 32 * ANW, KS = D + 8;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   bf16* sK = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
   bf16* sVt = sK + ATILE * KS;                    // [D][72]
@@ -206,8 +209,8 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnArgs a) {
 
 // ------------------------------------------------------------------------------------------ backward: dQ
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
-  constexpr int BQ = 128, KS = D + 8;
+__global__ __launch_bounds__(ANT) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
+  constexpr int BQ = 32 * ANW, KS = D + 8;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   bf16* sK = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
   bf16* sV = sK + ATILE * KS;                     // [64][D+8]
@@ -312,8 +315,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
 
 // ------------------------------------------------------------------------------------------ backward: dK, dV
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
-  constexpr int BKB = 128, KS = D + 8;
+__global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
+  constexpr int BKB = 32 * ANW, KS = D + 8;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   bf16* sQ = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
   bf16* sdO = sQ + ATILE * KS;                    // [64][D+8]
@@ -454,16 +457,16 @@ bool attn_bf16_supported(int d) { return d == 64 || d == 96 || d == 128; }
 template <int D>
 static hipError_t launch_fwd_d(const AttnArgs& a, hipStream_t st) {
   const size_t lds = ((size_t)ATILE * (D + 8) + (size_t)D * ATS) * 2;
-  dim3 grid((a.s + 127) / 128, a.hl, a.b);
-  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), grid, dim3(256), lds, st, a);
+  dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
+  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), grid, dim3(ANT), lds, st, a);
   return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_bwd_d(const AttnArgs& a, hipStream_t st) {
-  dim3 grid((a.s + 127) / 128, a.hl, a.b);
+  dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
   const size_t lds_q = ((size_t)2 * ATILE * (D + 8) + (size_t)D * ATS) * 2;
-  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), grid, dim3(256), lds_q, st, a);
+  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), grid, dim3(ANT), lds_q, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t lds_kv = ((size_t)2 * ATILE * (D + 8) + (size_t)2 * D * ATS) * 2 + 2 * ATILE * sizeof(float);
@@ -472,7 +475,7 @@ static hipError_t launch_bwd_d(const AttnArgs& a, hipStream_t st) {
                             (int)lds_kv);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D>), grid, dim3(256), lds_kv, st, a);
+  hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D>), grid, dim3(ANT), lds_kv, st, a);
   return hipGetLastError();
 }
 

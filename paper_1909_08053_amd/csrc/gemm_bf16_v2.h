@@ -8,9 +8,10 @@
 //     is transposed by the LDS read itself: 16 lanes read a 4(k) x 16(n) patch and each lane receives four
 //     consecutive k of one column.  Two such reads give the same 8-consecutive-k operand registers that a
 //     16-byte read of a k-contiguous tile gives, so both kinds of tiles feed the same MFMA loop.
-//   * 160 KB LDS: a 256 x 256 block tile (2 x 2 waves, 128 x 128 per wave: 64 B of LDS traffic per clock per
-//     CU for 16 MFMAs per k-step) with a FOUR-stage ring of 32-deep k-slices (128 KB): three slices are in
-//     flight while one is consumed, i.e. about 3000 MFMA clocks of prefetch distance, one barrier per slice.
+//   * 160 KB LDS: a 256 x 256 block tile with a FOUR-stage ring of 32-deep k-slices (128 KB).  The operands of a
+//     slice are pulled into registers half a slice ahead, so its stage is re-armed while it is still being
+//     multiplied: three slices are in flight and one is landed, about 3500 MFMA clocks of prefetch distance,
+//     one barrier per slice.
 // Requirements: K % 32 == 0 (the dispatcher falls back to the register-staged kernel otherwise).
 //
 // Tail split: when the tile count does not fill a whole number of rounds of the 256 CUs, the tiles of the last
@@ -77,6 +78,9 @@ struct V2Src {
       }
       step = (size_t)V2_BK * ld;
     }
+  }
+  __device__ __forceinline__ void issue_one(uint32_t op_lds, int wave_u, int kt_rel, int q) const {
+    dma16(p[q] + (size_t)kt_rel * step, op_lds + (wave_u * QPW + q) * 1024);
   }
   // op_lds: LDS byte address of this operand's stage buffer; wave_u: wave index as a uniform (SGPR) value
   __device__ __forceinline__ void issue(uint32_t op_lds, int wave_u, int kt_rel) const {
@@ -174,29 +178,28 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
 
   const uint32_t lds0 = lds_offset_of(lds_raw);
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  // Four slices are always in flight or landed; past the end of k the last slice is fetched again into a stage
+  // nobody reads (keeps the vmcnt bookkeeping and the instruction stream free of tail cases).
 #pragma unroll
-  for (int s = 0; s < V2_STAGES - 1; ++s) {
-    if (s < nk) {
-      sa.issue(lds0 + s * V2_STAGE_BYTES, wave_u, s);
-      sb.issue(lds0 + s * V2_STAGE_BYTES + V2_OP_BYTES, wave_u, s);
-    }
+  for (int s = 0; s < V2_STAGES; ++s) {
+    sa.issue(lds0 + s * V2_STAGE_BYTES, wave_u, min(s, nk - 1));
+    sb.issue(lds0 + s * V2_STAGE_BYTES + V2_OP_BYTES, wave_u, min(s, nk - 1));
   }
-  // Software pipeline over half-slices (16 k each = 16 MFMAs per wave).  The operand registers of the NEXT half are
-  // read from LDS while the matrix cores work on the current half, and the slice hand-over (wait for the DMA of
-  // slice kt+1, barrier, re-arm the freed stage) sits in the middle of slice kt, so LDS latency, barrier skew and
-  // DMA issue are all covered by 512 clocks of MFMA work.
+  // Software pipeline over half-slices (16 k each).  The operand registers of the NEXT half are read from LDS while
+  // the matrix cores work on the current half.  The slice hand-over sits in the middle of slice kt: wait for the
+  // DMA of slice kt+1, barrier, then re-arm slice kt's stage (its operands are all in registers by then) with
+  // slice kt+4.  The DMA instructions are ISSUED ONE AT A TIME BETWEEN MFMAs: eight back-to-back 1-KB copies fill
+  // the vector-memory queue and would stall the wave, and with it the matrix pipe, for hundreds of clocks.
   bf16x8 fa0[4], fb0[TN], fa1[4], fb1[TN];
-  {
-    // slice 0 must have landed; slices 1 and 2 may stay in flight (8 DMA instructions each per wave)
-    if (nk >= 3) wait_vmcnt<2 * LPS>();
-    else if (nk == 2) wait_vmcnt<LPS>();
-    else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
+  wait_vmcnt<3 * LPS>();                 // slice 0 landed; slices 1..3 may stay in flight (LPS copies each per wave)
+  __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(lds_raw, wm0 + j * 32, 0, lane);
+  for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(lds_raw, wm0 + j * 32, 0, lane);
 #pragma unroll
-    for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(lds_raw + V2_OP_BYTES, wn0 + i * 32, 0, lane);
-  }
+  for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(lds_raw + V2_OP_BYTES, wn0 + i * 32, 0, lane);
+  constexpr int NMF = TN * 4;            // MFMAs per half-slice per wave
+  constexpr int DSTRIDE = NMF / LPS;     // one copy every DSTRIDE MFMAs
+  static_assert(NMF % LPS == 0 && DSTRIDE >= 1, "copy interleave");
   for (int kt = 0; kt < nk; ++kt) {
     const unsigned char* sA = lds_raw + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
     const unsigned char* sB = sA + V2_OP_BYTES;
@@ -209,30 +212,34 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[i], fa0[j], acc[i][j], 0, 0, 0);
-    if (kt + 1 < nk) {
-      // slice kt+1 must have landed; slice kt+2 may stay in flight
-      if (kt + 2 < nk) wait_vmcnt<LPS>();
-      else wait_vmcnt<0>();
-      // Bare s_barrier (no memory fence: a fence would also wait for the slice still in flight).  After it
-      // everyone's part of slice kt+1 is in LDS, and everyone has finished reading slice kt-1 (its last operand
-      // registers were consumed by MFMAs issued before this point), so that stage can be re-armed.
-      __builtin_amdgcn_s_barrier();
-      if (kt + V2_STAGES - 1 < nk) {
-        const uint32_t st = lds0 + ((kt + V2_STAGES - 1) & (V2_STAGES - 1)) * V2_STAGE_BYTES;
-        sa.issue(st, wave_u, kt + V2_STAGES - 1);
-        sb.issue(st + V2_OP_BYTES, wave_u, kt + V2_STAGES - 1);
-      }
-      const unsigned char* nA = lds_raw + ((kt + 1) & (V2_STAGES - 1)) * V2_STAGE_BYTES;
+    // slice kt+1 must have landed; slices kt+2 and kt+3 stay in flight
+    wait_vmcnt<2 * LPS>();
+    // this wave's LDS reads of slice kt (second-half operands, issued above) have returned ...
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
+    // ... so after this bare s_barrier (no memory fence: a fence would also wait for the slices in flight)
+    // everyone's part of slice kt+1 is in LDS and nobody reads slice kt's stage any more.
+    __builtin_amdgcn_s_barrier();
+    const unsigned char* nA = lds_raw + ((kt + 1) & (V2_STAGES - 1)) * V2_STAGE_BYTES;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(nA, wm0 + j * 32, 0, lane);
+    for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(nA, wm0 + j * 32, 0, lane);
 #pragma unroll
-      for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(nA + V2_OP_BYTES, wn0 + i * 32, 0, lane);
-    }
+    for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(nA + V2_OP_BYTES, wn0 + i * 32, 0, lane);
+    const uint32_t st = lds0 + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
+    const int knext = min(kt + V2_STAGES, nk - 1);
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 4; ++j) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[i], fa1[j], acc[i][j], 0, 0, 0);
+        const int idx = i * 4 + j;
+        if (idx % DSTRIDE == DSTRIDE - 1) {
+          const int c = idx / DSTRIDE;   // copy number 0 .. LPS-1: first the A tile's, then the B tile's
+          __builtin_amdgcn_sched_barrier(0);   // pin the copy between these MFMAs (the scheduler would regroup them)
+          if (c < QPW) sa.issue_one(st, wave_u, knext, c);
+          else sb.issue_one(st + V2_OP_BYTES, wave_u, knext, c - QPW);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
   }
   __syncthreads();
 
