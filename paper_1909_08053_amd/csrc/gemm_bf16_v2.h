@@ -203,15 +203,23 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
   for (int kt = 0; kt < nk; ++kt) {
     const unsigned char* sA = lds_raw + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
     const unsigned char* sB = sA + V2_OP_BYTES;
+    // First half.  Order pinned with scheduling barriers: two MFMAs first (their operands were read half a slice
+    // ago, so the loop-top wait is free), THEN the LDS reads of the second half's operands, then the remaining
+    // MFMAs, which cover the latency of those reads.  (Left alone, the scheduler either hoists the reads above the
+    // loop-top wait or sinks them to the barrier; both expose their full LDS latency.)
+#pragma unroll
+    for (int idx = 0; idx < 2; ++idx)
+      acc[idx / 4][idx % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / 4], fa0[idx % 4], acc[idx / 4][idx % 4], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < 4; ++j) fa1[j] = v2_frag<A_KC>(sA, wm0 + j * 32, 1, lane);
 #pragma unroll
     for (int i = 0; i < TN; ++i) fb1[i] = v2_frag<B_KC>(sB, wn0 + i * 32, 1, lane);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[i], fa0[j], acc[i][j], 0, 0, 0);
+    for (int idx = 2; idx < NMF; ++idx)
+      acc[idx / 4][idx % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / 4], fa0[idx % 4], acc[idx / 4][idx % 4], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);     // ... and the MFMAs ahead of the hand-over
     // slice kt+1 must have landed; slices kt+2 and kt+3 stay in flight
     wait_vmcnt<2 * LPS>();
     // this wave's LDS reads of slice kt (second-half operands, issued above) have returned ...
