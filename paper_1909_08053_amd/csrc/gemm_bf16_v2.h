@@ -52,6 +52,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
+// Bank swizzle of the [k][row] tile layout (XOR on the 16-byte unit index of a k-row).  One transpose-read
+// instruction touches k-rows {b..b+3} (16-lane groups 0,1) and {b+8..b+11} (groups 2,3), 32 bytes per row and
+// group: bits 0-1 of k spread the four rows of a group over a 128-byte span, bit 3 of k sends the two row sets to
+// different 128-byte halves of the 256-byte bank row, so a 512-byte read completes in the minimum two passes.
+__device__ __forceinline__ int v2_mn_swizzle(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
+
 // Per-lane source pointers of one operand's four 1-KB DMA instructions per stage.
 // QPW = 16 / (waves per workgroup): 1-KB DMA instructions per wave, operand and slice.
 template <bool KC, int QPW>
@@ -69,11 +75,11 @@ struct V2Src {
       }
       step = V2_BK;
     } else {
-      // LDS layout [32 k][256 rows] (512 B per k, 32 units); unit u of k-row holds row-chunk u ^ ((k & 7) << 1)
+      // LDS layout [32 k][256 rows] (512 B per k, 32 units); unit u of k-row holds row-chunk u ^ v2_mn_swizzle(k)
 #pragma unroll
       for (int q = 0; q < QPW; ++q) {
         const int k = 2 * (wave * QPW + q) + (lane >> 5);
-        const int u = (lane & 31) ^ ((k & 7) << 1);
+        const int u = (lane & 31) ^ v2_mn_swizzle(k);
         p[q] = P + (size_t)(k_begin + k) * ld + min(row0 + u * 8, nrows - 8);
       }
       step = (size_t)V2_BK * ld;
@@ -102,9 +108,8 @@ __device__ __forceinline__ bf16x8 v2_frag(const unsigned char* op_base, int r0, 
     v4s_t h[2];
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
-      const int k7 = 4 * r + (i16 >> 2);                       // (k & 7)
-      const int k = ks * 16 + 8 * (g >> 1) + k7;
-      const unsigned char* ad = op_base + k * 512 + ((u ^ (k7 << 1)) * 16) + (i16 & 1) * 8;
+      const int k = ks * 16 + 8 * (g >> 1) + 4 * r + (i16 >> 2);
+      const unsigned char* ad = op_base + k * 512 + ((u ^ v2_mn_swizzle(k)) * 16) + (i16 & 1) * 8;
       h[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t*)ad);
     }
     const v8s_t v = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
