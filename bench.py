@@ -42,7 +42,7 @@ def shard_flops(cfg, causal_algorithmic=True):
     return 3.0 * fwd, gemm(T, H, Vl)
 
 
-def cpu_baseline(cfg, sample_b=1):
+def cpu_baseline(cfg, sample_b=4):
     """Time the fp64 oracle (as it stands) on the host cores on a bounded sample: the UNSHARDED layer + loss of the
     same model shape with batch `sample_b` (all p shards' work for that batch)."""
     import numpy as np
@@ -130,7 +130,7 @@ def main():
             traffic = None
     roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
-                "kernel": "gemm_bf16_kernel<...,EPI_CE> (logits GEMM + cross-entropy partials)",
+                "kernel": "gemm_bf16_v2_kernel<true,false,EPI_CE,8> (logits GEMM + cross-entropy partials)",
                 "kernel_ms": k_ms, "flops_per_launch": logits_flops}
 
     if args.breakdown:
