@@ -93,33 +93,37 @@ def main():
     L.load_random(seed=cfg.seed)
     torch.cuda.synchronize()
 
+    # The dominant kernel (logits GEMM fused with the cross-entropy partials) is timed live, inside the timed steps,
+    # with events recorded on the launch stream around the one call that enqueues it (the bracket also holds the
+    # few-microsecond partial-merge kernel of the same call).
+    from paper_1909_08053_amd import pipeline as P
+    ce_events = []
+    real_ce_fwd = B.mlm_vocab_ce_shard_fwd
+
+    def timed_ce_fwd(*a_, **k_):
+        e0_, e1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0_.record()
+        real_ce_fwd(*a_, **k_)
+        e1_.record()
+        ce_events.append((e0_, e1_))
+
     for _ in range(args.warmup):
         L.step()
     torch.cuda.synchronize()
+    P.B.mlm_vocab_ce_shard_fwd = timed_ce_fwd
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ev0.record()
     for _ in range(args.steps):
         L.step()
     ev1.record()
     torch.cuda.synchronize()
+    P.B.mlm_vocab_ce_shard_fwd = real_ce_fwd
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
     loss = float(L.act["loss"][0].item())
     flops, logits_flops = shard_flops(cfg)
     dense_flops, _ = shard_flops(cfg, causal_algorithmic=False)
     value = flops / (ms_per_step * 1e-3) / 1e12
-
-    # dominant kernel: the logits GEMM fused with the cross-entropy partials, timed with events on the launch stream
-    # (the bracket also contains the few-microsecond partial-merge kernel that the same call enqueues)
-    a, rep, w0, s0 = L.act, L.rep, L.w[0], L.sh[0]
-    hf = L._hf
-    reps = max(10, args.steps)
-    e = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps)]
-    for i in range(reps):
-        e[2 * i].record()
-        B.mlm_vocab_ce_shard_fwd(L.dims[0], hf, w0["E"], rep["tgt"], a["m"][0], a["s"][0], a["t"][0], s0["logits"], L.ws)
-        e[2 * i + 1].record()
-    torch.cuda.synchronize()
-    k_ms = sum(e[2 * i].elapsed_time(e[2 * i + 1]) for i in range(reps)) / reps
+    k_ms = sum(x.elapsed_time(y) for x, y in ce_events) / len(ce_events)
     achieved = logits_flops / (k_ms * 1e-3) / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")

@@ -121,6 +121,9 @@ struct V2Plan {
   int tiles_m, tiles_n, full_tiles, tail_tiles, split;   // grid = full_tiles + tail_tiles * split
 };
 
+// Decide whether to split the last partial round along k.  Cost model in microseconds, measured on MI355X with
+// in-kernel timestamps: a tile costs about 5.3 (fill + epilogue) + 0.78 per 32-deep k-slice; the fix-up kernel costs
+// about 6 (launch + drain) plus its fp32 traffic at ~5 TB/s.
 inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
   V2Plan p;
   p.tiles_m = (M + V2_B - 1) / V2_B;
@@ -133,6 +136,12 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
     split = V2_CUS / rem;
     if (split > 16) split = 16;
     while (split > 1 && nk / split < 8) --split;     // keep at least 8 k-slices per piece
+    if (split > 1) {
+      const double t_tile = 5.3 + 0.78 * nk;
+      const double t_piece = 5.3 + 0.78 * ((nk + split - 1) / split);
+      const double t_fix = 6.0 + (double)rem * split * (V2_B * V2_B * 4.0) / 5.0e6;
+      if (t_piece + t_fix >= t_tile) split = 1;
+    }
   }
   p.split = split;
   p.tail_tiles = split > 1 ? rem : 0;
