@@ -64,7 +64,7 @@ size_t ws_bytes_for(const mlm_dims* dm, const Local& L, int which) {
     case MLM_WS_VOCAB_CE_FWD:
       if (dm->dtype == MLM_BF16) {
         const size_t ntile = ((size_t)L.Vl + 127) / 128;   // upper bound over the tile configurations
-        return 2 * align256(ntile * T * 4) + align256(T * 4);
+        return 2 * align256(ntile * T * 4) + align256(T * 4) + sk;
       }
       return align256(T * L.Vl * 4);
     case MLM_WS_VOCAB_CE_BWD: return align256(T * L.Vl * L.esz) + sk;
@@ -289,7 +289,7 @@ MLM_API int mlm_mlp_shard_fwd(const mlm_dims* dims, const void* u2, const void* 
   g.bias = a_r;
   g.aux = g_r; g.ldaux = L.Fl;
   g.gelu_tanh = dims->gelu_tanh;
-  MLM_TRY_HIP(run_gemm(dt, g, st));
+  MLM_TRY_HIP(run_gemm(dt, g, st, sk));
   MLM_TRY_HIP(run_gemm(dt, gemm_fwd(L.T, dims->H, L.Fl, y_r, B_r, partial_r), st, sk));   // partial of Z = Y B
   return MLM_OK;
 }
@@ -318,7 +318,7 @@ MLM_API int mlm_mlp_shard_bwd(const mlm_dims* dims, const void* dx2, const void*
   g.epi = EPI_DGELU;
   g.aux = const_cast<void*>(g_r); g.ldaux = L.Fl;
   g.gelu_tanh = dims->gelu_tanh;
-  MLM_TRY_HIP(run_gemm(dt, g, st));
+  MLM_TRY_HIP(run_gemm(dt, g, st, sk));
   MLM_TRY_HIP(launch_colsum(dt, L.T, L.Fl, dg, da_r, csws, st));
   MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, L.Fl, L.T, u2, dg, dA_r), st, sk));
   MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, L.Fl, dg, A_r, du2_partial_r), st, sk));
@@ -341,8 +341,9 @@ MLM_API int mlm_vocab_ce_shard_fwd(const mlm_dims* dims, const void* hf, const v
     char* w = (char*)ws;
     float* part_m = (float*)w;    w += align256(ntile_max * T * 4);
     float* part_s = (float*)w;    w += align256(ntile_max * T * 4);
-    float* t_ws = (float*)w;
+    float* t_ws = (float*)w;      w += align256(T * 4);
     GemmArgs g = gemm_fwd(L.T, L.Vl, dims->H, hf, E_r, logits_r);
+    g.splitk_ws = (float*)w;
     g.epi = EPI_CE;
     g.targets = targets; g.v0 = v0;
     g.part_m = part_m; g.part_s = part_s; g.t_out = t_ws;
@@ -392,7 +393,7 @@ MLM_API int mlm_vocab_ce_shard_bwd(const mlm_dims* dims, const void* hf, const v
     g.epi = EPI_DLOGITS;
     g.targets = targets; g.v0 = v0;
     g.Mrow = M; g.Srow = S; g.loss_w = loss_w; g.loss_stats = loss_stats;
-    MLM_TRY_HIP(run_gemm(dt, g, st));
+    MLM_TRY_HIP(run_gemm(dt, g, st, sk));
   }
   MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, L.Vl, L.T, hf, dL, dE_r), st, sk));
   MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, L.Vl, dL, E_r, dhf_partial_r), st, sk));

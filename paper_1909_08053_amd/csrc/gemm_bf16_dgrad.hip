@@ -8,7 +8,7 @@ hipError_t launch_gemm_bf16_dgrad(const GemmArgs& a, hipStream_t st) {
   if (gemm_use_v2(a)) {
     switch (a.epi) {
       case EPI_STORE: return launch_gemm_bf16_v2<true, true, EPI_STORE>(a, a.splitk_ws, st);
-      case EPI_DGELU: return launch_gemm_bf16_v2<true, true, EPI_DGELU>(a, nullptr, st);
+      case EPI_DGELU: return launch_gemm_bf16_v2<true, true, EPI_DGELU>(a, a.splitk_ws, st);
       default: return hipErrorInvalidValue;
     }
   }

@@ -8,9 +8,9 @@ hipError_t launch_gemm_bf16_fwd(const GemmArgs& a, hipStream_t st) {
   if (gemm_use_v2(a)) {
     switch (a.epi) {
       case EPI_STORE: return launch_gemm_bf16_v2<true, false, EPI_STORE>(a, a.splitk_ws, st);
-      case EPI_BIAS_GELU: return launch_gemm_bf16_v2<true, false, EPI_BIAS_GELU>(a, nullptr, st);
-      case EPI_CE: return launch_gemm_bf16_v2<true, false, EPI_CE>(a, nullptr, st);
-      case EPI_DLOGITS: return launch_gemm_bf16_v2<true, false, EPI_DLOGITS>(a, nullptr, st);
+      case EPI_BIAS_GELU: return launch_gemm_bf16_v2<true, false, EPI_BIAS_GELU>(a, a.splitk_ws, st);
+      case EPI_CE: return launch_gemm_bf16_v2<true, false, EPI_CE>(a, a.splitk_ws, st);
+      case EPI_DLOGITS: return launch_gemm_bf16_v2<true, false, EPI_DLOGITS>(a, a.splitk_ws, st);
       default: return hipErrorInvalidValue;
     }
   }

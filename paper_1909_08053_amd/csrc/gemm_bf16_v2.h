@@ -121,9 +121,9 @@ struct V2Plan {
   int tiles_m, tiles_n, full_tiles, tail_tiles, split;   // grid = full_tiles + tail_tiles * split
 };
 
-// Decide whether to split the last partial round along k.  Cost model in microseconds, measured on MI355X with
-// in-kernel timestamps: a tile costs about 5.3 (fill + epilogue) + 0.78 per 32-deep k-slice; the fix-up kernel costs
-// about 6 (launch + drain) plus its fp32 traffic at ~5 TB/s.
+// Decide whether, and how far, to split the last partial round along k.  Cost model in microseconds, measured on
+// MI355X with in-kernel timestamps: a tile costs about 5.3 (fill + epilogue) + 0.78 per 32-deep k-slice; the pieces
+// write fp32 partial tiles and the fix-up kernel (about 6 for launch + drain) reads them back, both at ~5 TB/s.
 inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
   V2Plan p;
   p.tiles_m = (M + V2_B - 1) / V2_B;
@@ -132,15 +132,15 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
   const int rem = tiles % V2_CUS;
   const int nk = K / V2_BK;
   int split = 1;
-  if (allow_split && rem != 0 && rem * 4 <= V2_CUS * 3) {
-    split = V2_CUS / rem;
-    if (split > 16) split = 16;
-    while (split > 1 && nk / split < 8) --split;     // keep at least 8 k-slices per piece
-    if (split > 1) {
-      const double t_tile = 5.3 + 0.78 * nk;
-      const double t_piece = 5.3 + 0.78 * ((nk + split - 1) / split);
-      const double t_fix = 6.0 + (double)rem * split * (V2_B * V2_B * 4.0) / 5.0e6;
-      if (t_piece + t_fix >= t_tile) split = 1;
+  if (allow_split && rem != 0 && rem * 2 <= V2_CUS) {
+    int smax = V2_CUS / rem;
+    if (smax > 16) smax = 16;
+    double best = 5.3 + 0.78 * nk;                    // unsplit tail round
+    for (int sp = 2; sp <= smax; ++sp) {
+      if (nk / sp < 8) break;                         // keep at least 8 k-slices per piece
+      const double traffic = (double)rem * sp * (V2_B * V2_B * 4.0) / 5.0e6;
+      const double t = 5.3 + 0.78 * ((nk + sp - 1) / sp) + traffic + 6.0 + traffic;
+      if (t < best) { best = t; split = sp; }
     }
   }
   p.split = split;
@@ -263,6 +263,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
         }
       }
   }
+  // The ring is kept full to the end, so copies of the (clamped) last slice are still in flight here.  They were
+  // issued from inline assembly, which the compiler's wait-count tracking does not see: wait for them explicitly
+  // before the epilogue reuses the ring's memory for its staging strips.
+  wait_vmcnt<0>();
   __syncthreads();
 
   if (npieces > 1) {
@@ -283,28 +287,100 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
   gemm_epilogue<V2_B, V2_B, 2, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
 }
 
-// Sum the k-pieces of every tail tile in piece order, add the bias, round once to bf16.
-template <int UNUSED>
+// Tail tiles: sum the k-pieces in piece order (deterministic) and apply the epilogue to the fp32 sums.  A wave owns
+// whole 256-column tile rows (a lane: 4 consecutive columns), so the row statistics of the cross-entropy epilogue are
+// one wave reduction.  Grid: (256 / kFixRows row groups, tail tiles), 4 waves, kFixRows / 4 rows per wave.
+constexpr int kFixRows = 8;
+template <int EPI>
 __global__ __launch_bounds__(256) void gemm_v2_fixup_kernel(GemmArgs a, V2Plan plan, const float* __restrict__ ws) {
   const int t = blockIdx.y;                          // tail tile
   const int vt = plan.full_tiles + t;
-  const int m0 = (vt % plan.tiles_m) * V2_B, n0 = (vt / plan.tiles_m) * V2_B;
-  const int v = blockIdx.x * 256 + threadIdx.x;      // 4-column group inside the tile
-  const int r = v / (V2_B / 4), c4 = (v % (V2_B / 4)) * 4;
-  const int m = m0 + r, n = n0 + c4;
-  if (m >= a.M || n >= a.N) return;
-  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int p = 0; p < plan.split; ++p) {
-    const float4 x = *reinterpret_cast<const float4*>(ws + ((size_t)t * plan.split + p) * (V2_B * V2_B) + r * V2_B + c4);
-    s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
+  const int tile_n = vt / plan.tiles_m;
+  const int m0 = (vt % plan.tiles_m) * V2_B, n0 = tile_n * V2_B;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = n0 + lane * 4;
+  const bool col_ok = n < a.N;                        // N is a multiple of 8: a 4-column group is all in or all out
+  const int nc = col_ok ? n : 0;
+  const float* base = ws + (size_t)t * plan.split * (V2_B * V2_B) + lane * 4;
+  float bv[4] = {0.f, 0.f, 0.f, 0.f};
+  if ((EPI == EPI_STORE || EPI == EPI_BIAS_GELU) && a.bias != nullptr) {
+    const bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16*)a.bias + nc);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bv[e] = (float)b[e];
   }
-  if (a.bias) {
-    const bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16*)a.bias + n);
-    s.x += (float)b[0]; s.y += (float)b[1]; s.z += (float)b[2]; s.w += (float)b[3];
+  constexpr int RPW = kFixRows / 4;
+  float v[RPW][4];
+#pragma unroll
+  for (int i = 0; i < RPW; ++i) {
+    const int r = blockIdx.x * kFixRows + wave * RPW + i;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[i][e] = bv[e];
+    for (int p = 0; p < plan.split; ++p) {
+      const float4 x = *reinterpret_cast<const float4*>(base + (size_t)p * (V2_B * V2_B) + r * V2_B);
+      v[i][0] += x.x; v[i][1] += x.y; v[i][2] += x.z; v[i][3] += x.w;
+    }
   }
-  bf16x4 o;
-  o[0] = (bf16)s.x; o[1] = (bf16)s.y; o[2] = (bf16)s.z; o[3] = (bf16)s.w;
-  *reinterpret_cast<bf16x4*>((bf16*)a.C + (size_t)m * a.ldc + n) = o;
+#pragma unroll
+  for (int i = 0; i < RPW; ++i) {
+    const int r = blockIdx.x * kFixRows + wave * RPW + i;
+    const int m = m0 + r;
+    if (m >= a.M) break;                              // wave-uniform
+    const bool ok = col_ok;
+    bf16x4 o;
+    if (EPI == EPI_STORE) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16)v[i][e];
+    } else if (EPI == EPI_BIAS_GELU) {
+      bf16x4 pre;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        pre[e] = (bf16)v[i][e];
+        o[e] = (bf16)gelu_fwd(v[i][e], a.gelu_tanh != 0);
+      }
+      if (ok) *reinterpret_cast<bf16x4*>((bf16*)a.aux + (size_t)m * a.ldaux + n) = pre;
+    } else if (EPI == EPI_DGELU) {
+      const bf16x4 g4 = *reinterpret_cast<const bf16x4*>((const bf16*)a.aux + (size_t)m * a.ldaux + nc);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16)(v[i][e] * gelu_bwd((float)g4[e], a.gelu_tanh != 0));
+    } else if (EPI == EPI_CE) {
+      float mx = -INFINITY;
+      if (ok) mx = fmaxf(fmaxf(v[i][0], v[i][1]), fmaxf(v[i][2], v[i][3]));
+      mx = wave_max(mx);
+      const float mxl = mx * 1.4426950408889634f;
+      float se = 0.f;
+      if (ok) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) se += __builtin_amdgcn_exp2f(fmaf(v[i][e], 1.4426950408889634f, -mxl));
+      }
+      se = wave_sum(se);
+      const int loc = a.targets[m] - a.v0 - n0;       // target column inside this tile, if 0 <= loc < 256
+      if (ok && loc >= 0 && (loc >> 2) == lane) {
+        float tv = v[i][0];
+#pragma unroll
+        for (int e = 1; e < 4; ++e) tv = ((loc & 3) == e) ? v[i][e] : tv;
+        a.t_out[m] = tv;
+      }
+      if (lane == 0) {
+        a.part_m[(size_t)tile_n * a.M + m] = mx;
+        a.part_s[(size_t)tile_n * a.M + m] = se;
+      }
+      if (a.C == nullptr) continue;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16)v[i][e];
+    } else if (EPI == EPI_DLOGITS) {
+      const float coef = (a.loss_w ? a.loss_w[m] : 1.0f) / a.loss_stats[1];
+      const float Mrl = a.Mrow[m] * 1.4426950408889634f;
+      const float invS = coef / a.Srow[m];
+      const int loc = a.targets[m] - a.v0 - n;        // target column relative to this lane's first column
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float pz = __builtin_amdgcn_exp2f(fmaf(v[i][e], 1.4426950408889634f, -Mrl)) * invS;
+        if (loc == e) pz -= coef;
+        o[e] = (bf16)pz;
+      }
+    }
+    if (ok) *reinterpret_cast<bf16x4*>((bf16*)a.C + (size_t)m * a.ldc + n) = o;
+  }
 }
 
 inline size_t v2_splitk_ws_bytes() { return (size_t)V2_CUS * V2_B * V2_B * sizeof(float); }   // 64 MB upper bound
@@ -325,13 +401,13 @@ hipError_t launch_gemm_bf16_v2_nw(const GemmArgs& a, float* splitk_ws, hipStream
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const V2Plan plan = v2_plan(a.M, a.N, a.K, EPI == EPI_STORE && splitk_ws != nullptr);
+  const V2Plan plan = v2_plan(a.M, a.N, a.K, splitk_ws != nullptr);
   const int grid = plan.full_tiles + plan.tail_tiles * plan.split;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), kLds, st, a, plan, splitk_ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (plan.tail_tiles) {
-    hipLaunchKernelGGL((gemm_v2_fixup_kernel<0>), dim3(V2_B * V2_B / 4 / 256, plan.tail_tiles), dim3(256), 0, st, a, plan,
+    hipLaunchKernelGGL((gemm_v2_fixup_kernel<EPI>), dim3(V2_B / kFixRows, plan.tail_tiles), dim3(256), 0, st, a, plan,
                        splitk_ws);
     e = hipGetLastError();
   }
