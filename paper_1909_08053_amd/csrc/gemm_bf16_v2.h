@@ -217,22 +217,22 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
   for (int kt = 0; kt < nk; ++kt) {
     const unsigned char* sA = lds_raw + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
     const unsigned char* sB = sA + V2_OP_BYTES;
-    // First half.  Order pinned with scheduling barriers: two MFMAs first (their operands were read half a slice
-    // ago, so the loop-top wait is free), THEN the LDS reads of the second half's operands, then the remaining
-    // MFMAs, which cover the latency of those reads.  (Left alone, the scheduler either hoists the reads above the
-    // loop-top wait or sinks them to the barrier; both expose their full LDS latency.)
+    // First half.  Order pinned with scheduling barriers: one MFMA first (its operands were read half a slice ago,
+    // so the loop-top wait is free), then ONE fragment read of the second half's operands after each MFMA.  Spread
+    // like this the reads never queue up in the LDS pipe (all eight waves reach this point together after the
+    // barrier), and the MFMAs in between cover their latency.  (Left alone, the scheduler bunches the reads and
+    // either hoists them above the loop-top wait or sinks them to the barrier; both expose their full latency.)
 #pragma unroll
-    for (int idx = 0; idx < 2; ++idx)
+    for (int idx = 0; idx < NMF; ++idx) {
       acc[idx / 4][idx % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / 4], fa0[idx % 4], acc[idx / 4][idx % 4], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) fa1[j] = v2_frag<A_KC>(sA, wm0 + j * 32, 1, lane);
-#pragma unroll
-    for (int i = 0; i < TN; ++i) fb1[i] = v2_frag<B_KC>(sB, wn0 + i * 32, 1, lane);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int idx = 2; idx < NMF; ++idx)
-      acc[idx / 4][idx % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / 4], fa0[idx % 4], acc[idx / 4][idx % 4], 0, 0, 0);
+      if (idx >= 1 && idx - 1 < 4 + TN) {
+        const int q = idx - 1;
+        __builtin_amdgcn_sched_barrier(0);
+        if (q < 4) fa1[q] = v2_frag<A_KC>(sA, wm0 + q * 32, 1, lane);
+        else fb1[q - 4] = v2_frag<B_KC>(sB, wn0 + (q - 4) * 32, 1, lane);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
     __builtin_amdgcn_sched_barrier(0);     // ... and the MFMAs ahead of the hand-over
     // slice kt+1 must have landed; slices kt+2 and kt+3 stay in flight
     wait_vmcnt<2 * LPS>();
@@ -241,27 +241,29 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
     // ... so after this bare s_barrier (no memory fence: a fence would also wait for the slices in flight)
     // everyone's part of slice kt+1 is in LDS and nobody reads slice kt's stage any more.
     __builtin_amdgcn_s_barrier();
+    // Second half: after each MFMA one fragment read of slice kt+1's first-half operands, and every DSTRIDE MFMAs
+    // one copy of slice kt+4 into the stage slice kt just left.
     const unsigned char* nA = lds_raw + ((kt + 1) & (V2_STAGES - 1)) * V2_STAGE_BYTES;
+    {
+      const uint32_t st = lds0 + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
+      const int knext = min(kt + V2_STAGES, nk - 1);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(nA, wm0 + j * 32, 0, lane);
-#pragma unroll
-    for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(nA + V2_OP_BYTES, wn0 + i * 32, 0, lane);
-    const uint32_t st = lds0 + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
-    const int knext = min(kt + V2_STAGES, nk - 1);
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[i], fa1[j], acc[i][j], 0, 0, 0);
-        const int idx = i * 4 + j;
+      for (int idx = 0; idx < NMF; ++idx) {
+        acc[idx / 4][idx % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[idx / 4], fa1[idx % 4], acc[idx / 4][idx % 4], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (idx < 4 + TN) {
+          const int q = idx;
+          if (q < 4) fa0[q] = v2_frag<A_KC>(nA, wm0 + q * 32, 0, lane);
+          else fb0[q - 4] = v2_frag<B_KC>(nA + V2_OP_BYTES, wn0 + (q - 4) * 32, 0, lane);
+        }
         if (idx % DSTRIDE == DSTRIDE - 1) {
-          const int c = idx / DSTRIDE;   // copy number 0 .. LPS-1: first the A tile's, then the B tile's
-          __builtin_amdgcn_sched_barrier(0);   // pin the copy between these MFMAs (the scheduler would regroup them)
+          const int c = idx / DSTRIDE;
           if (c < QPW) sa.issue_one(st, wave_u, knext, c);
           else sb.issue_one(st + V2_OP_BYTES, wave_u, knext, c - QPW);
-          __builtin_amdgcn_sched_barrier(0);
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
+    }
   }
   // The ring is kept full to the end, so copies of the (clamped) last slice are still in flight here.  They were
   // issued from inline assembly, which the compiler's wait-count tracking does not see: wait for them explicitly
