@@ -166,7 +166,8 @@ def breakdown(L, B, cfg):
         evs.append(ev)
 
     orig = {}
-    calls = ["mlm_layernorm_fwd", "mlm_layernorm_bwd", "mlm_combine", "mlm_colsum", "mlm_attn_shard_fwd",
+    calls = ["mlm_layernorm_fwd", "mlm_layernorm_bwd", "mlm_combine", "mlm_colsum", "mlm_combine_layernorm_fwd",
+             "mlm_combine_layernorm_bwd", "mlm_attn_shard_fwd",
              "mlm_attn_shard_bwd", "mlm_mlp_shard_fwd", "mlm_mlp_shard_bwd", "mlm_vocab_ce_shard_fwd",
              "mlm_vocab_ce_merge", "mlm_vocab_ce_shard_bwd"]
     for c in calls:

@@ -132,6 +132,29 @@ MLM_API int mlm_layernorm_bwd(const mlm_dims* dims, const void* dy, const void* 
 MLM_API int mlm_combine(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
                 const void* bias, const void* residual, void* out, void* stream);
 
+/* mlm_combine fused with the layer norm that consumes its result (Section 3: the all-reduced
+ * block output plus bias and residual is normalised identically on every GPU):
+ *   x_out = sum_i partials[i] + bias + residual      (rounded once to dtype and stored)
+ *   y = layer norm of x_out with gamma, beta;  mean, rstd as in mlm_layernorm_fwd.
+ * Arguments as in mlm_combine and mlm_layernorm_fwd; x_out: [T,H] dtype, may alias residual
+ * or a partial; y must not alias an input. */
+MLM_API int mlm_combine_layernorm_fwd(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                              const void* bias, const void* residual, void* x_out, const void* gamma,
+                              const void* beta, void* y, float* mean, float* rstd, void* stream);
+
+/* mlm_combine (no bias, no residual) fused with mlm_layernorm_bwd: the layer-norm gradient reads
+ *   dy = sum_i partials[i]   (rounded once to dtype; also stored to dy_out unless dy_out is NULL)
+ * -- the stand-in for f's backward all-reduce feeding the replicated layer norm -- and produces
+ * dx, dgamma, dbeta as mlm_layernorm_bwd does.  If dx_colsum is not NULL it also receives
+ * dx_colsum[j] = sum_t dx[t,j] ([H] dtype): the gradient of the replicated bias that was added
+ * to form this layer norm's input (output-projection bias, second MLP bias), so no separate
+ * mlm_colsum pass over dx is needed.  dx may alias residual_grad; dy_out must not alias an
+ * input.  ws: MLM_WS_LAYERNORM_BWD bytes. */
+MLM_API int mlm_combine_layernorm_bwd(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                              const void* x, const void* gamma, const float* mean, const float* rstd,
+                              const void* residual_grad, void* dy_out, void* dx, void* dgamma, void* dbeta,
+                              void* dx_colsum, void* ws, size_t ws_bytes, void* stream);
+
 /* Column sums over tokens, dbias[j] = sum_t dy[t,j]: the gradient of a replicated bias
  * (output-projection bias, second MLP bias).  dy: [T,H] dtype; dbias: [H] dtype.
  * ws: MLM_WS_COLSUM bytes. */

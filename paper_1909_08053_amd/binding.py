@@ -19,7 +19,7 @@ MLM_F32, MLM_BF16 = 0, 1
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmlm_shard.so")
 
 EXPORTS = ("mlm_shard_range", "mlm_workspace_bytes", "mlm_status_string", "mlm_layernorm_fwd", "mlm_layernorm_bwd",
-           "mlm_combine", "mlm_colsum", "mlm_attn_shard_fwd", "mlm_attn_shard_bwd", "mlm_mlp_shard_fwd",
+           "mlm_combine", "mlm_combine_layernorm_fwd", "mlm_combine_layernorm_bwd", "mlm_colsum", "mlm_attn_shard_fwd", "mlm_attn_shard_bwd", "mlm_mlp_shard_fwd",
            "mlm_mlp_shard_bwd", "mlm_vocab_ce_shard_fwd", "mlm_vocab_ce_merge", "mlm_vocab_ce_shard_bwd", "mlm_gemm")
 
 
@@ -119,6 +119,29 @@ def mlm_combine(dims, partials: Sequence[torch.Tensor], bias, residual, out, str
         _p(t)
     _chk(lib().mlm_combine(ctypes.byref(dims), arr, ctypes.c_int32(n), _p(bias), _p(residual), _p(out), _st(stream)),
          "mlm_combine")
+
+
+def _partial_array(partials):
+    n = len(partials)
+    for t in partials:
+        _p(t)
+    return (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t in partials]), n
+
+
+def mlm_combine_layernorm_fwd(dims, partials: Sequence[torch.Tensor], bias, residual, x_out, gamma, beta, y, mean, rstd,
+                              stream=None):
+    arr, n = _partial_array(partials)
+    _chk(lib().mlm_combine_layernorm_fwd(ctypes.byref(dims), arr, ctypes.c_int32(n), _p(bias), _p(residual), _p(x_out),
+                                         _p(gamma), _p(beta), _p(y), _p(mean), _p(rstd), _st(stream)),
+         "mlm_combine_layernorm_fwd")
+
+
+def mlm_combine_layernorm_bwd(dims, partials: Sequence[torch.Tensor], x, gamma, mean, rstd, residual_grad, dy_out, dx,
+                              dgamma, dbeta, dx_colsum, ws, stream=None):
+    arr, n = _partial_array(partials)
+    _chk(lib().mlm_combine_layernorm_bwd(ctypes.byref(dims), arr, ctypes.c_int32(n), _p(x), _p(gamma), _p(mean),
+                                         _p(rstd), _p(residual_grad), _p(dy_out), _p(dx), _p(dgamma), _p(dbeta),
+                                         _p(dx_colsum), *_ws(ws), _st(stream)), "mlm_combine_layernorm_bwd")
 
 
 def mlm_colsum(dims, dy, dbias, ws, stream=None):

@@ -53,7 +53,7 @@ size_t ws_bytes_for(const mlm_dims* dm, const Local& L, int which) {
   const size_t sk = dm->dtype == MLM_BF16 ? kSplitKBytes : 0;
   switch (which) {
     case MLM_WS_LAYERNORM_BWD:
-      return align256(((T + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock) * 2 * (size_t)dm->H * 4);
+      return align256(((T + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock) * 3 * (size_t)dm->H * 4);
     case MLM_WS_ATTN_FWD: return sk;
     case MLM_WS_ATTN_BWD:
       return align256(T * L.Hl * L.esz) + align256(T * 3 * L.Hl * L.esz) +
@@ -189,6 +189,51 @@ MLM_API int mlm_combine(const mlm_dims* dims, const void* const* partials, int32
   if (!aligned16(out) || (bias && !aligned16(bias)) || (residual && !aligned16(residual))) return MLM_E_ALIGN;
   return hip_status(launch_combine(dims->dtype, L.T, dims->H, partials, n_partials, bias, residual, out,
                                    (hipStream_t)stream));
+}
+
+static int check_partials(const void* const* partials, int32_t n) {
+  if (!partials) return MLM_E_NULL;
+  if (n < 1 || n > kMaxPartials) return MLM_E_SHAPE;
+  for (int i = 0; i < n; ++i) {
+    if (!partials[i]) return MLM_E_NULL;
+    if (!aligned16(partials[i])) return MLM_E_ALIGN;
+  }
+  return MLM_OK;
+}
+
+MLM_API int mlm_combine_layernorm_fwd(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                      const void* bias, const void* residual, void* x_out, const void* gamma,
+                                      const void* beta, void* y, float* mean, float* rstd, void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if ((rc = check_partials(partials, n_partials))) return rc;
+  if (!x_out || !gamma || !beta || !y || !mean || !rstd) return MLM_E_NULL;
+  if (!aligned16(x_out) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y) || (bias && !aligned16(bias)) ||
+      (residual && !aligned16(residual)))
+    return MLM_E_ALIGN;
+  if ((rc = ln_supported(dims))) return rc;
+  return hip_status(launch_combine_layernorm_fwd(dims->dtype, L.T, dims->H, dims->ln_eps, partials, n_partials, bias,
+                                                 residual, x_out, gamma, beta, y, mean, rstd, (hipStream_t)stream));
+}
+
+MLM_API int mlm_combine_layernorm_bwd(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                      const void* x, const void* gamma, const float* mean, const float* rstd,
+                                      const void* residual_grad, void* dy_out, void* dx, void* dgamma, void* dbeta,
+                                      void* dx_colsum, void* ws, size_t ws_bytes, void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if ((rc = check_partials(partials, n_partials))) return rc;
+  if (!x || !gamma || !mean || !rstd || !dx || !dgamma || !dbeta || !ws) return MLM_E_NULL;
+  if (!aligned16(x) || !aligned16(gamma) || !aligned16(dx) || !aligned16(ws) ||
+      (residual_grad && !aligned16(residual_grad)) || (dy_out && !aligned16(dy_out)))
+    return MLM_E_ALIGN;
+  if ((rc = ln_supported(dims))) return rc;
+  if (ws_bytes < ws_bytes_for(dims, L, MLM_WS_LAYERNORM_BWD)) return MLM_E_WORKSPACE;
+  return hip_status(launch_combine_layernorm_bwd(dims->dtype, L.T, dims->H, partials, n_partials, x, gamma, mean, rstd,
+                                                 residual_grad, dy_out, dx, dgamma, dbeta, dx_colsum, (float*)ws,
+                                                 (hipStream_t)stream));
 }
 
 MLM_API int mlm_colsum(const mlm_dims* dims, const void* dy, void* dbias, void* ws, size_t ws_bytes, void* stream) {

@@ -132,10 +132,19 @@ constexpr int kMaxPartials = 16;
 
 hipError_t launch_layernorm_fwd(int dtype, int T, int H, float eps, const void* x, const void* gamma,
                                 const void* beta, void* y, float* mean, float* rstd, hipStream_t st);
-// ws: [ceil(T/kLnBwdRowsPerBlock)][2][H] float
+// ws: [ceil(T/kLnBwdRowsPerBlock)][2][H] float (the workspace query reserves 3 parts)
 hipError_t launch_layernorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
                                 const float* mean, const float* rstd, const void* residual_grad, void* dx,
                                 void* dgamma, void* dbeta, float* ws, hipStream_t st);
+// Fused forms: the layer norm reads sum(partials) (+ bias + residual) instead of a stored tensor.
+hipError_t launch_combine_layernorm_fwd(int dtype, int T, int H, float eps, const void* const* partials, int n,
+                                        const void* bias, const void* residual, void* x_out, const void* gamma,
+                                        const void* beta, void* y, float* mean, float* rstd, hipStream_t st);
+// ws: [ceil(T/kLnBwdRowsPerBlock)][3][H] float; dy_out and dx_colsum may be NULL
+hipError_t launch_combine_layernorm_bwd(int dtype, int T, int H, const void* const* partials, int n, const void* x,
+                                        const void* gamma, const float* mean, const float* rstd,
+                                        const void* residual_grad, void* dy_out, void* dx, void* dgamma, void* dbeta,
+                                        void* dx_colsum, float* ws, hipStream_t st);
 hipError_t launch_combine(int dtype, int T, int H, const void* const* partials, int n, const void* bias,
                           const void* residual, void* out, hipStream_t st);
 // ws: [ceil(T/kColsumRowsPerBlock)][N] float

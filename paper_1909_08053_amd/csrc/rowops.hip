@@ -7,12 +7,57 @@
 
 namespace mlm {
 
-// ------------------------------------------------------------------------------ layer norm forward
+struct PartialPtrs { const void* p[kMaxPartials]; };
+
+// One token row (a lane's NV 16-byte vectors) of sum_r partials[r] + bias + residual: partials are added in the fixed
+// order r = 0..n-1 (deterministic) in fp32 and the sum is rounded once to the storage type -- the value the separate
+// combine kernel would have stored.  All of a partial's vectors are loaded before they are added, so the loads of a
+// row overlap; a single partial with nothing to add is passed through untouched.
 template <typename T, int NV>
+__device__ __forceinline__ void combine_row(const PartialPtrs& ptrs, int n, const T* bias, const T* residual,
+                                            size_t row_off, int lane, int nvec, Vec16<T> (&out)[NV]) {
+  constexpr int VN = Vec16<T>::N;
+  if (n == 1 && bias == nullptr && residual == nullptr) {
+    const T* p = (const T*)ptrs.p[0] + row_off;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (lane + 64 * i < nvec) out[i].load(p + (size_t)(lane + 64 * i) * VN);
+    return;
+  }
+  float acc[NV][VN];
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int e = 0; e < VN; ++e) acc[i][e] = 0.f;
+  for (int k = 0; k < n + 2; ++k) {
+    const T* p = k < n ? (const T*)ptrs.p[k] + row_off : (k == n ? bias : (residual ? residual + row_off : nullptr));
+    if (p == nullptr) continue;                       // uniform
+    Vec16<T> t[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (lane + 64 * i < nvec) t[i].load(p + (size_t)(lane + 64 * i) * VN);
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (lane + 64 * i < nvec) {
+#pragma unroll
+        for (int e = 0; e < VN; ++e) acc[i][e] += t[i].get(e);
+      }
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int e = 0; e < VN; ++e) out[i].set(e, acc[i][e]);
+}
+
+// ------------------------------------------------------------------------------ layer norm forward
+// FUSED: the input row is first formed as sum of partials + bias + residual (the single-GPU stand-in for the
+// all-reduce followed by the bias/residual add), stored to x_out, and normalised from registers.
+template <typename T, int NV, bool FUSED>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int H, float eps, const T* __restrict__ x,
                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
                                                      T* __restrict__ y, float* __restrict__ mean,
-                                                     float* __restrict__ rstd) {
+                                                     float* __restrict__ rstd, PartialPtrs ptrs, int n,
+                                                     const T* __restrict__ bias, const T* residual, T* x_out) {
   constexpr int VN = Vec16<T>::N;
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -21,11 +66,13 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int H, float eps,
   const T* xr = x + (size_t)row * H;
   Vec16<T> v[NV];
   float sum = 0.f;
+  if (FUSED) combine_row<T, NV>(ptrs, n, bias, residual, (size_t)row * H, lane, nvec, v);
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int idx = lane + 64 * i;
     if (idx < nvec) {
-      v[i].load(xr + (size_t)idx * VN);
+      if (FUSED) v[i].store(x_out + (size_t)row * H + (size_t)idx * VN);
+      else v[i].load(xr + (size_t)idx * VN);
 #pragma unroll
       for (int e = 0; e < VN; ++e) sum += v[i].get(e);
     }
@@ -58,14 +105,23 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int H, float eps,
 
 template <typename T>
 static hipError_t ln_fwd_dispatch(int rows, int H, float eps, const void* x, const void* gamma, const void* beta,
-                                  void* y, float* mean, float* rstd, hipStream_t st) {
+                                  void* y, float* mean, float* rstd, const PartialPtrs* pp, int n, const void* bias,
+                                  const void* residual, void* x_out, hipStream_t st) {
   constexpr int VN = Vec16<T>::N;
   const int nv = (H / VN + 63) / 64;
   dim3 grid((rows + 3) / 4), block(256);
+  PartialPtrs none;
+  for (int k = 0; k < kMaxPartials; ++k) none.p[k] = nullptr;
 #define MLM_LN_FWD(NVV)                                                                                    \
   case NVV:                                                                                                \
-    hipLaunchKernelGGL((ln_fwd_kernel<T, NVV>), grid, block, 0, st, rows, H, eps, (const T*)x,             \
-                       (const T*)gamma, (const T*)beta, (T*)y, mean, rstd);                                \
+    if (pp)                                                                                                \
+      hipLaunchKernelGGL((ln_fwd_kernel<T, NVV, true>), grid, block, 0, st, rows, H, eps, (const T*)x,     \
+                         (const T*)gamma, (const T*)beta, (T*)y, mean, rstd, *pp, n, (const T*)bias,       \
+                         (const T*)residual, (T*)x_out);                                                   \
+    else                                                                                                   \
+      hipLaunchKernelGGL((ln_fwd_kernel<T, NVV, false>), grid, block, 0, st, rows, H, eps, (const T*)x,    \
+                         (const T*)gamma, (const T*)beta, (T*)y, mean, rstd, none, 0, (const T*)nullptr,   \
+                         (const T*)nullptr, (T*)nullptr);                                                  \
     break;
   switch (nv) {
     MLM_LN_FWD(1) MLM_LN_FWD(2) MLM_LN_FWD(3) MLM_LN_FWD(4) MLM_LN_FWD(5) MLM_LN_FWD(6) MLM_LN_FWD(7) MLM_LN_FWD(8)
@@ -77,8 +133,19 @@ static hipError_t ln_fwd_dispatch(int rows, int H, float eps, const void* x, con
 
 hipError_t launch_layernorm_fwd(int dtype, int T, int H, float eps, const void* x, const void* gamma,
                                 const void* beta, void* y, float* mean, float* rstd, hipStream_t st) {
-  return dtype == MLM_BF16 ? ln_fwd_dispatch<bf16>(T, H, eps, x, gamma, beta, y, mean, rstd, st)
-                           : ln_fwd_dispatch<float>(T, H, eps, x, gamma, beta, y, mean, rstd, st);
+  return dtype == MLM_BF16
+             ? ln_fwd_dispatch<bf16>(T, H, eps, x, gamma, beta, y, mean, rstd, nullptr, 0, nullptr, nullptr, nullptr, st)
+             : ln_fwd_dispatch<float>(T, H, eps, x, gamma, beta, y, mean, rstd, nullptr, 0, nullptr, nullptr, nullptr, st);
+}
+
+hipError_t launch_combine_layernorm_fwd(int dtype, int T, int H, float eps, const void* const* partials, int n,
+                                        const void* bias, const void* residual, void* x_out, const void* gamma,
+                                        const void* beta, void* y, float* mean, float* rstd, hipStream_t st) {
+  PartialPtrs pp;
+  for (int k = 0; k < kMaxPartials; ++k) pp.p[k] = k < n ? partials[k] : nullptr;
+  return dtype == MLM_BF16
+             ? ln_fwd_dispatch<bf16>(T, H, eps, nullptr, gamma, beta, y, mean, rstd, &pp, n, bias, residual, x_out, st)
+             : ln_fwd_dispatch<float>(T, H, eps, nullptr, gamma, beta, y, mean, rstd, &pp, n, bias, residual, x_out, st);
 }
 
 // ------------------------------------------------------------------------------ layer norm backward
@@ -88,12 +155,16 @@ hipError_t launch_layernorm_fwd(int dtype, int T, int H, float eps, const void* 
 // (deterministic); the block partial goes to the workspace and reduce_cols_kernel sums the block partials.
 constexpr int kLnBwdWaves = 4;
 
-template <typename T, int NV>
+// FUSED: dy is formed on the fly as the sum of n partial tensors (stored to dy_out if that is not NULL).
+// SUM: the column sums of dx (the bias gradient of the layer that produced this layer norm's input) are accumulated
+// as a third per-column partial next to dgamma / dbeta.
+template <typename T, int NV, bool FUSED, bool SUM>
 __global__ __launch_bounds__(kLnBwdWaves * 64) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy,
                                                                   const T* __restrict__ x, const T* __restrict__ gamma,
                                                                   const float* __restrict__ mean,
                                                                   const float* __restrict__ rstd, const T* residual,
-                                                                  T* dx, float* __restrict__ ws) {
+                                                                  T* dx, float* __restrict__ ws, PartialPtrs ptrs, int n,
+                                                                  T* dy_out) {
   constexpr int VN = Vec16<T>::N;
   constexpr int SLOTS = NV * VN * 64;
   extern __shared__ float red[];   // [kLnBwdWaves][SLOTS]
@@ -101,7 +172,8 @@ __global__ __launch_bounds__(kLnBwdWaves * 64) void ln_bwd_kernel(int rows, int 
   const int wave = threadIdx.x >> 6;
   const int nvec = H / VN;
   const float invH = 1.0f / (float)H;
-  float dg[NV][VN], db[NV][VN];
+  constexpr int NP = SUM ? 3 : 2;
+  float dg[NV][VN], db[NV][VN], dsum[SUM ? NV : 1][VN];
   float gam[NV][VN];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
@@ -112,6 +184,7 @@ __global__ __launch_bounds__(kLnBwdWaves * 64) void ln_bwd_kernel(int rows, int 
       gam[i][e] = (lane + 64 * i < nvec) ? g.get(e) : 0.f;
       dg[i][e] = 0.f;
       db[i][e] = 0.f;
+      if (SUM) dsum[i][e] = 0.f;
     }
   }
   const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
@@ -119,11 +192,16 @@ __global__ __launch_bounds__(kLnBwdWaves * 64) void ln_bwd_kernel(int rows, int 
   Vec16<T> vdy[NV], vx[NV], vres[NV], ndy[NV], nx[NV], nres[NV];
   int row = row0 + wave;
   if (row < row_end) {
+    if (FUSED) combine_row<T, NV>(ptrs, n, nullptr, nullptr, (size_t)row * H, lane, nvec, ndy);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int idx = lane + 64 * i;
       if (idx < nvec) {
-        ndy[i].load(dy + (size_t)row * H + (size_t)idx * VN);
+        if (FUSED) {
+          if (dy_out) ndy[i].store(dy_out + (size_t)row * H + (size_t)idx * VN);
+        } else {
+          ndy[i].load(dy + (size_t)row * H + (size_t)idx * VN);
+        }
         nx[i].load(x + (size_t)row * H + (size_t)idx * VN);
         if (residual) nres[i].load(residual + (size_t)row * H + (size_t)idx * VN);
       }
@@ -134,11 +212,16 @@ __global__ __launch_bounds__(kLnBwdWaves * 64) void ln_bwd_kernel(int rows, int 
     for (int i = 0; i < NV; ++i) { vdy[i] = ndy[i]; vx[i] = nx[i]; vres[i] = nres[i]; }
     const int nrow = row + kLnBwdWaves;
     if (nrow < row_end) {
+      if (FUSED) combine_row<T, NV>(ptrs, n, nullptr, nullptr, (size_t)nrow * H, lane, nvec, ndy);
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         const int idx = lane + 64 * i;
         if (idx < nvec) {
-          ndy[i].load(dy + (size_t)nrow * H + (size_t)idx * VN);
+          if (FUSED) {
+            if (dy_out) ndy[i].store(dy_out + (size_t)nrow * H + (size_t)idx * VN);
+          } else {
+            ndy[i].load(dy + (size_t)nrow * H + (size_t)idx * VN);
+          }
           nx[i].load(x + (size_t)nrow * H + (size_t)idx * VN);
           if (residual) nres[i].load(residual + (size_t)nrow * H + (size_t)idx * VN);
         }
@@ -175,19 +258,21 @@ __global__ __launch_bounds__(kLnBwdWaves * 64) void ln_bwd_kernel(int rows, int 
           float v = rs * (g - s1 - xh[i][e] * s2);
           if (residual) v += vres[i].get(e);
           o.set(e, v);
+          if (SUM) dsum[i][e] += o.get(e);     // the stored (rounded) value, as a separate column sum would read it
         }
         o.store(dx + (size_t)row * H + (size_t)idx * VN);
       }
     }
   }
-  float* out = ws + (size_t)blockIdx.x * 2 * H;
+  float* out = ws + (size_t)blockIdx.x * NP * H;
 #pragma unroll
-  for (int part = 0; part < 2; ++part) {
+  for (int part = 0; part < NP; ++part) {
     float* mine = red + (size_t)wave * SLOTS;
 #pragma unroll
     for (int i = 0; i < NV; ++i)
 #pragma unroll
-      for (int e = 0; e < VN; ++e) mine[(i * VN + e) * 64 + lane] = part == 0 ? dg[i][e] : db[i][e];
+      for (int e = 0; e < VN; ++e)
+        mine[(i * VN + e) * 64 + lane] = part == 0 ? dg[i][e] : (part == 1 ? db[i][e] : dsum[SUM ? i : 0][e]);
     __syncthreads();
     for (int col = threadIdx.x; col < H; col += kLnBwdWaves * 64) {
       const int idx = col / VN, e = col % VN;
@@ -201,11 +286,11 @@ __global__ __launch_bounds__(kLnBwdWaves * 64) void ln_bwd_kernel(int rows, int 
   }
 }
 
-// out[c] = sum_k ws[k][c] over nchunk row-chunks: 16 float4 column groups x 16 chunk-slices per block; every slice
+// out[c] = sum_k ws[k][c] over nchunk row-chunks (the columns are up to three output vectors of `seg` entries): 16 float4 column groups x 16 chunk-slices per block; every slice
 // sums its chunks in order and the 16 slices are added in a fixed order (deterministic).
 template <typename T>
 __global__ __launch_bounds__(256) void reduce_cols_kernel(int nchunk, int ncols, const float* __restrict__ ws,
-                                                          T* __restrict__ out0, T* __restrict__ out1, int split) {
+                                                          T* out0, T* out1, T* out2, int seg) {
   __shared__ float4 red[16][17];
   const int cx = threadIdx.x & 15, sl = threadIdx.x >> 4;
   const int c = (blockIdx.x * 16 + cx) * 4;
@@ -224,42 +309,53 @@ __global__ __launch_bounds__(256) void reduce_cols_kernel(int nchunk, int ncols,
 #pragma unroll
     for (int k = 0; k < 16; ++k) { t.x += red[k][cx].x; t.y += red[k][cx].y; t.z += red[k][cx].z; t.w += red[k][cx].w; }
     const float tv[4] = {t.x, t.y, t.z, t.w};
+    T* out = c < seg ? out0 : (c < 2 * seg ? out1 : out2);   // segments are multiples of 4 columns
+    const int cc = c % seg;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      if (c + e < split) out0[c + e] = from_f32<T>(tv[e]);
-      else out1[c + e - split] = from_f32<T>(tv[e]);
-    }
+    for (int e = 0; e < 4; ++e) out[cc + e] = from_f32<T>(tv[e]);
   }
 }
 
 template <typename T>
 static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x, const void* gamma,
                                   const float* mean, const float* rstd, const void* residual, void* dx,
-                                  void* dgamma, void* dbeta, float* ws, hipStream_t st) {
+                                  void* dgamma, void* dbeta, float* ws, const PartialPtrs* pp, int n, void* dy_out,
+                                  void* dx_colsum, hipStream_t st) {
   constexpr int VN = Vec16<T>::N;
   const int nv = (H / VN + 63) / 64;
   const int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
   dim3 grid(nblk), block(kLnBwdWaves * 64);
   const size_t lds = (size_t)kLnBwdWaves * nv * VN * 64 * sizeof(float);
-#define MLM_LN_BWD(NVV)                                                                                    \
-  case NVV: {                                                                                              \
+  PartialPtrs none;
+  for (int k = 0; k < kMaxPartials; ++k) none.p[k] = nullptr;
+  const int np = (pp && dx_colsum) ? 3 : 2;
+#define MLM_LN_BWD_GO(NVV, F, S)                                                                           \
+  {                                                                                                        \
     if (lds > 64 * 1024) {                                                                                 \
-      hipError_t ea = hipFuncSetAttribute((const void*)ln_bwd_kernel<T, NVV>,                              \
+      hipError_t ea = hipFuncSetAttribute((const void*)ln_bwd_kernel<T, NVV, F, S>,                        \
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
       if (ea != hipSuccess) return ea;                                                                     \
     }                                                                                                      \
-    hipLaunchKernelGGL((ln_bwd_kernel<T, NVV>), grid, block, lds, st, rows, H, (const T*)dy, (const T*)x,  \
-                       (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws);                       \
+    hipLaunchKernelGGL((ln_bwd_kernel<T, NVV, F, S>), grid, block, lds, st, rows, H, (const T*)dy,         \
+                       (const T*)x, (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws,           \
+                       pp ? *pp : none, n, (T*)dy_out);                                                    \
+  }
+#define MLM_LN_BWD(NVV)                                                                                    \
+  case NVV: {                                                                                              \
+    if (pp && dx_colsum) MLM_LN_BWD_GO(NVV, true, true)                                                    \
+    else if (pp) MLM_LN_BWD_GO(NVV, true, false)                                                           \
+    else MLM_LN_BWD_GO(NVV, false, false)                                                                  \
   } break;
   switch (nv) {
     MLM_LN_BWD(1) MLM_LN_BWD(2) MLM_LN_BWD(3) MLM_LN_BWD(4) MLM_LN_BWD(5) MLM_LN_BWD(6) MLM_LN_BWD(7) MLM_LN_BWD(8)
     default: return hipErrorInvalidValue;
   }
 #undef MLM_LN_BWD
+#undef MLM_LN_BWD_GO
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((reduce_cols_kernel<T>), dim3((2 * H + 63) / 64), dim3(256), 0, st, nblk, 2 * H, ws,
-                     (T*)dgamma, (T*)dbeta, H);
+  hipLaunchKernelGGL((reduce_cols_kernel<T>), dim3((np * H + 63) / 64), dim3(256), 0, st, nblk, np * H, ws,
+                     (T*)dgamma, (T*)dbeta, (T*)dx_colsum, H);
   return hipGetLastError();
 }
 
@@ -267,13 +363,27 @@ hipError_t launch_layernorm_bwd(int dtype, int T, int H, const void* dy, const v
                                 const float* mean, const float* rstd, const void* residual_grad, void* dx,
                                 void* dgamma, void* dbeta, float* ws, hipStream_t st) {
   return dtype == MLM_BF16
-             ? ln_bwd_dispatch<bf16>(T, H, dy, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, st)
-             : ln_bwd_dispatch<float>(T, H, dy, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, st);
+             ? ln_bwd_dispatch<bf16>(T, H, dy, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, nullptr, 0,
+                                     nullptr, nullptr, st)
+             : ln_bwd_dispatch<float>(T, H, dy, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, nullptr, 0,
+                                      nullptr, nullptr, st);
+}
+
+// ws: [ceil(T/kLnBwdRowsPerBlock)][3][H] float
+hipError_t launch_combine_layernorm_bwd(int dtype, int T, int H, const void* const* partials, int n, const void* x,
+                                        const void* gamma, const float* mean, const float* rstd,
+                                        const void* residual_grad, void* dy_out, void* dx, void* dgamma, void* dbeta,
+                                        void* dx_colsum, float* ws, hipStream_t st) {
+  PartialPtrs pp;
+  for (int k = 0; k < kMaxPartials; ++k) pp.p[k] = k < n ? partials[k] : nullptr;
+  return dtype == MLM_BF16
+             ? ln_bwd_dispatch<bf16>(T, H, nullptr, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, &pp, n,
+                                     dy_out, dx_colsum, st)
+             : ln_bwd_dispatch<float>(T, H, nullptr, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, &pp, n,
+                                      dy_out, dx_colsum, st);
 }
 
 // ------------------------------------------------------------------------------ combine (stand-in for g / f)
-struct PartialPtrs { const void* p[kMaxPartials]; };
-
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(size_t nvec, int hvec, PartialPtrs ptrs, int n,
                                                       const T* __restrict__ bias, const T* residual, T* out) {
@@ -366,12 +476,12 @@ hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, f
     dim3 grid((N / 8 + 63) / 64, nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<bf16>), grid, dim3(256), 0, st, T, N, (const bf16*)dy, ws);
     hipLaunchKernelGGL((reduce_cols_kernel<bf16>), dim3((N + 63) / 64), dim3(256), 0, st, nchunk, N, ws,
-                       (bf16*)dbias, (bf16*)dbias, N);
+                       (bf16*)dbias, (bf16*)dbias, (bf16*)dbias, N);
   } else {
     dim3 grid((N / 4 + 63) / 64, nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(256), 0, st, T, N, (const float*)dy, ws);
     hipLaunchKernelGGL((reduce_cols_kernel<float>), dim3((N + 63) / 64), dim3(256), 0, st, nchunk, N, ws,
-                       (float*)dbias, (float*)dbias, N);
+                       (float*)dbias, (float*)dbias, (float*)dbias, N);
   }
   return hipGetLastError();
 }

@@ -22,8 +22,13 @@ def _tdtype(cfg: LayerConfig):
 
 
 class LayerShards:
-    def __init__(self, cfg: LayerConfig, shards: Sequence[int], device: str = "cuda:0", store_logits: bool = True):
+    def __init__(self, cfg: LayerConfig, shards: Sequence[int], device: str = "cuda:0", store_logits: bool = True,
+                 fused: bool = True, store_combined: bool = False):
+        """fused: the combine that stands in for an all-reduce runs inside the layer-norm kernel that consumes it
+        (and the layer-norm backward also emits the row-parallel bias gradient); store_combined: in fused mode,
+        also store the combined gradients dHf / dU2 / dU (nothing in the path reads them)."""
         self.cfg, self.shards, self.dev = cfg, list(shards), torch.device(device)
+        self.fused, self.store_combined = fused, store_combined
         self.dt = _tdtype(cfg)
         self.code = B.MLM_BF16 if cfg.dtype == "bf16" else B.MLM_F32
         self.store_logits = store_logits
@@ -126,16 +131,26 @@ class LayerShards:
             w, s = self.w[r], self.sh[r]
             B.mlm_attn_shard_fwd(self.dims[r], a["U"], w["Wqkv"], w["bqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
                                  s["attn_partial"], ws)
-        B.mlm_combine(d0, [self.sh[r]["attn_partial"] for r in self.shards], rep["bo"], rep["X"], a["X1"])
-        B.mlm_layernorm_fwd(d0, a["X1"], rep["g2"], rep["b2"], a["U2"], a["mu2"], a["rstd2"])
+        if self.fused:
+            B.mlm_combine_layernorm_fwd(d0, [self.sh[r]["attn_partial"] for r in self.shards], rep["bo"], rep["X"],
+                                        a["X1"], rep["g2"], rep["b2"], a["U2"], a["mu2"], a["rstd2"])
+        else:
+            B.mlm_combine(d0, [self.sh[r]["attn_partial"] for r in self.shards], rep["bo"], rep["X"], a["X1"])
+            B.mlm_layernorm_fwd(d0, a["X1"], rep["g2"], rep["b2"], a["U2"], a["mu2"], a["rstd2"])
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
             B.mlm_mlp_shard_fwd(self.dims[r], a["U2"], w["A"], w["a"], w["B"], s["g"], s["y"], s["mlp_partial"], ws)
-        B.mlm_combine(d0, [self.sh[r]["mlp_partial"] for r in self.shards], rep["c"], a["X1"], a["X2"])
-        if cfg.final_ln:
+        mlp_partials = [self.sh[r]["mlp_partial"] for r in self.shards]
+        if cfg.final_ln and self.fused:
+            B.mlm_combine_layernorm_fwd(d0, mlp_partials, rep["c"], a["X1"], a["X2"], rep["gf"], rep["bf"], a["Hf"],
+                                        a["muf"], a["rstdf"])
+            hf = a["Hf"]
+        elif cfg.final_ln:
+            B.mlm_combine(d0, mlp_partials, rep["c"], a["X1"], a["X2"])
             B.mlm_layernorm_fwd(d0, a["X2"], rep["gf"], rep["bf"], a["Hf"], a["muf"], a["rstdf"])
             hf = a["Hf"]
         else:
+            B.mlm_combine(d0, mlp_partials, rep["c"], a["X1"], a["X2"])
             hf = a["X2"]
         self._hf = hf
         for i, r in enumerate(self.shards):
@@ -154,29 +169,47 @@ class LayerShards:
             w, s = self.w[r], self.sh[r]
             B.mlm_vocab_ce_shard_bwd(self.dims[r], hf, w["E"], rep["tgt"], rep["w"], a["M"], a["S"], a["loss"],
                                      s["logits"], s["dE"], s["dhf_partial"], ws)
-        B.mlm_combine(d0, [self.sh[r]["dhf_partial"] for r in self.shards], None, None, a["dHf"])
-        if cfg.final_ln:
-            B.mlm_layernorm_bwd(d0, a["dHf"], a["X2"], rep["gf"], a["muf"], a["rstdf"], None, a["dX2"], a["dgf"],
-                                a["dbf"], ws)
+        fused = self.fused
+        keep = (lambda k: a[k]) if self.store_combined else (lambda k: None)
+        dhf_partials = [self.sh[r]["dhf_partial"] for r in self.shards]
+        if cfg.final_ln and fused:
+            B.mlm_combine_layernorm_bwd(d0, dhf_partials, a["X2"], rep["gf"], a["muf"], a["rstdf"], None, keep("dHf"),
+                                        a["dX2"], a["dgf"], a["dbf"], a["dc"], ws)
             dx2 = a["dX2"]
         else:
-            dx2 = a["dHf"]
-        B.mlm_colsum(d0, dx2, a["dc"], ws)
+            B.mlm_combine(d0, dhf_partials, None, None, a["dHf"])
+            if cfg.final_ln:
+                B.mlm_layernorm_bwd(d0, a["dHf"], a["X2"], rep["gf"], a["muf"], a["rstdf"], None, a["dX2"], a["dgf"],
+                                    a["dbf"], ws)
+                dx2 = a["dX2"]
+            else:
+                dx2 = a["dHf"]
+            B.mlm_colsum(d0, dx2, a["dc"], ws)
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
             B.mlm_mlp_shard_bwd(self.dims[r], dx2, a["U2"], w["A"], w["B"], s["g"], s["y"], s["dA"], s["da"], s["dB"],
                                 s["du2_partial"], ws)
-        B.mlm_combine(d0, [self.sh[r]["du2_partial"] for r in self.shards], None, None, a["dU2"])
-        B.mlm_layernorm_bwd(d0, a["dU2"], a["X1"], rep["g2"], a["mu2"], a["rstd2"], dx2, a["dX1"], a["dg2"], a["db2"],
-                            ws)
-        B.mlm_colsum(d0, a["dX1"], a["dbo"], ws)
+        du2_partials = [self.sh[r]["du2_partial"] for r in self.shards]
+        if fused:
+            B.mlm_combine_layernorm_bwd(d0, du2_partials, a["X1"], rep["g2"], a["mu2"], a["rstd2"], dx2, keep("dU2"),
+                                        a["dX1"], a["dg2"], a["db2"], a["dbo"], ws)
+        else:
+            B.mlm_combine(d0, du2_partials, None, None, a["dU2"])
+            B.mlm_layernorm_bwd(d0, a["dU2"], a["X1"], rep["g2"], a["mu2"], a["rstd2"], dx2, a["dX1"], a["dg2"],
+                                a["db2"], ws)
+            B.mlm_colsum(d0, a["dX1"], a["dbo"], ws)
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
             B.mlm_attn_shard_bwd(self.dims[r], a["dX1"], a["U"], w["Wqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
                                  s["dWqkv"], s["dbqkv"], s["dWo"], s["du_partial"], ws)
-        B.mlm_combine(d0, [self.sh[r]["du_partial"] for r in self.shards], None, None, a["dU"])
-        B.mlm_layernorm_bwd(d0, a["dU"], rep["X"], rep["g1"], a["mu1"], a["rstd1"], a["dX1"], a["dX"], a["dg1"],
-                            a["db1"], ws)
+        du_partials = [self.sh[r]["du_partial"] for r in self.shards]
+        if fused:
+            B.mlm_combine_layernorm_bwd(d0, du_partials, rep["X"], rep["g1"], a["mu1"], a["rstd1"], a["dX1"],
+                                        keep("dU"), a["dX"], a["dg1"], a["db1"], None, ws)
+        else:
+            B.mlm_combine(d0, du_partials, None, None, a["dU"])
+            B.mlm_layernorm_bwd(d0, a["dU"], rep["X"], rep["g1"], a["mu1"], a["rstd1"], a["dX1"], a["dX"], a["dg1"],
+                                a["db1"], ws)
         self._dx2 = dx2
 
     def step(self):
@@ -188,6 +221,9 @@ class LayerShards:
         torch.cuda.synchronize(self.dev)
         cp = lambda t: t.detach().float().cpu().numpy().astype(np.float64)
         out: Dict[str, object] = {k: cp(v) for k, v in self.act.items()}
+        if self.fused and not self.store_combined:      # never written in this mode
+            for k in ("dU2", "dU") + (("dHf",) if self.cfg.final_ln else ()):
+                out.pop(k, None)
         if getattr(self, "_dx2", None) is not None:
             out["dX2"] = cp(self._dx2)
         if getattr(self, "_hf", None) is not None:

@@ -91,10 +91,30 @@ def test_layernorm_combine_colsum(dtype, H):
     cs = torch.empty(H, device=DEV, dtype=dt)
     B.mlm_colsum(cfg_dims, _up(dy, dt), cs, ws2)
     check("colsum", _dn(cs), dy.astype(np.float64).sum(0), tol, errs)
+    # fused forms: bit-identical to combine followed by the layer norm (same arithmetic on the same rounded sums);
+    # the fused column sum of dx adds in another order, so it is compared with the oracle's sum instead
+    dparts = [_up(p_, dt) for p_ in parts]
+    xo = torch.empty(T, H, device=DEV, dtype=dt); y2 = torch.empty_like(y); m2 = torch.empty_like(mean); r2 = torch.empty_like(rstd)
+    B.mlm_combine_layernorm_fwd(cfg_dims, dparts, _up(be, dt), _up(res, dt), xo, _up(g, dt), _up(be, dt), y2, m2, r2)
+    B.mlm_layernorm_fwd(cfg_dims, out.copy_(xo), _up(g, dt), _up(be, dt), y, mean, rstd)
+    B.mlm_combine(cfg_dims, dparts, _up(be, dt), _up(res, dt), out)
+    assert torch.equal(out, xo) and torch.equal(y, y2) and torch.equal(mean, m2) and torch.equal(rstd, r2)
+    check("fused.y", _dn(y2), O.layernorm_fwd(_dn(xo), g.astype(np.float64), be.astype(np.float64), 1e-5)[0], tol, errs)
+    dyo = torch.empty(T, H, device=DEV, dtype=dt); dx2 = torch.empty_like(dx); dg2 = torch.empty_like(dg); db2 = torch.empty_like(db)
+    dcs = torch.empty(H, device=DEV, dtype=dt)
+    B.mlm_combine_layernorm_bwd(cfg_dims, dparts, xo, _up(g, dt), m2, r2, _up(res, dt), dyo, dx2, dg2, db2, dcs, ws)
+    B.mlm_combine(cfg_dims, dparts, None, None, out)
+    B.mlm_layernorm_bwd(cfg_dims, out, xo, _up(g, dt), m2, r2, _up(res, dt), dx, dg, db, ws)
+    assert torch.equal(out, dyo) and torch.equal(dx, dx2) and torch.equal(dg, dg2) and torch.equal(db, db2)
+    check("fused.dx_colsum", _dn(dcs), _dn(dx2).sum(0), tol, errs)
+    dx3 = torch.empty_like(dx)
+    B.mlm_combine_layernorm_bwd(cfg_dims, dparts, xo, _up(g, dt), m2, r2, _up(res, dt), None, dx3, dg2, db2, None, ws)
+    assert torch.equal(dx3, dx) and torch.equal(dg, dg2) and torch.equal(db, db2)
 
 
 # ------------------------------------------------------------------ whole layer, all shards, every tensor
-def run_layer_parity(cfg, nonzero_bias=True, random_ln=True, store_logits=True, scale_w=1.0, shards=None):
+def run_layer_parity(cfg, nonzero_bias=True, random_ln=True, store_logits=True, scale_w=1.0, shards=None, fused=True,
+                     store_combined=True):
     inp = synth.make_inputs(cfg, nonzero_bias=nonzero_bias, random_ln=random_ln)
     if scale_w != 1.0:
         for k in ("Wq", "Wk", "Wv", "Wo", "A", "B", "E"):
@@ -105,7 +125,7 @@ def run_layer_parity(cfg, nonzero_bias=True, random_ln=True, store_logits=True, 
     ref = O.sharded_reference(inp, spec, cfg.p)
     shards = list(range(cfg.p)) if shards is None else shards
     assert shards == list(range(cfg.p)), "full-layer parity needs every shard"
-    L = LayerShards(cfg, shards, DEV, store_logits=store_logits)
+    L = LayerShards(cfg, shards, DEV, store_logits=store_logits, fused=fused, store_combined=store_combined)
     L.load_host_inputs(inp)
     L.forward()
     fwd = L.fetch()
@@ -135,6 +155,9 @@ def run_layer_parity(cfg, nonzero_bias=True, random_ln=True, store_logits=True, 
     for k in ("dHf", "dX2", "dU2", "dX1", "dU", "dX", "dgf", "dbf", "dg2", "db2", "dg1", "db1", "dc", "dbo"):
         if k in ("dgf", "dbf") and not cfg.final_ln:
             continue
+        if k not in out:      # combined gradients are not stored in the benchmark's fused configuration
+            assert k in ("dHf", "dU2", "dU") and fused and not store_combined
+            continue
         check(k, out[k], ref[k], tol, errs)
     for r in shards:
         g, rs = out["shards"][r], ref["shards"][r]
@@ -163,6 +186,13 @@ def test_small_fp32_variants(variant):
     elif variant == "p4_d32":
         kw.update(p=4, s=72)
     run_layer_parity(synth.small_config(**kw), store_logits=store, scale_w=4.0)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_unfused_entry_points_whole_layer(dtype):
+    """The same layer through the separate combine / layer-norm / column-sum calls."""
+    cfg = synth.small_config(dtype=dtype, b=2, s=96, H=128, h=2, F=512, V=512, p=2)
+    run_layer_parity(cfg, fused=False, scale_w=3.0)
 
 
 # ------------------------------------------------------------------ bf16 (MFMA) path: small layers spanning several tiles
@@ -227,7 +257,7 @@ def test_full_size_configs_all_shards(name):
     same calls and launch configuration that bench.py times, combined in-device and compared tensor by tensor with
     the fp64 oracle of the sharded method (whose combined results equal the unsharded layer)."""
     cfg = synth.CONFIGS[name]
-    errs = run_layer_parity(cfg, nonzero_bias=False, random_ln=False)
+    errs = run_layer_parity(cfg, nonzero_bias=False, random_ln=False, store_combined=False)
     worst = sorted(errs, key=lambda e: -e[1])[:6]
     print(name, "worst max-norm relative errors:", worst)
 
