@@ -13,6 +13,7 @@
 //
 // Mask: allowed(i, j) = (j < key_len[b]) && (!causal || j <= i); excluded entries get probability exactly 0.
 #include "gemm_bf16.h"   // transpose8x8
+#include "lds_dma.h"
 
 namespace mlm {
 
@@ -90,14 +91,81 @@ __device__ __forceinline__ bf16x8 pack8(const floatx16& v, int off) {
   return r;
 }
 
-// ------------------------------------------------------------------------------------------ forward
+// ---- streamed [64][D] bf16 tiles copied HBM -> LDS by the DMA path -------------------------------------------
+// A tile is 64 rows of U = D/8 16-byte units, stored densely (the copy writes 1 KB per wave instruction in lane
+// order) with the unit index XOR-swizzled per row, so that both kinds of operand read are bank-conflict free:
+//   * "kc" fragments (contraction along D: 16 lanes read one 16-byte unit of 16 consecutive rows), and
+//   * transposing reads (contraction along the tile's rows: 32 lanes read 64 bytes of 4 consecutive rows).
 template <int D>
-__global__ __launch_bounds__(ANT) void attn_fwd_bf16_kernel(AttnArgs a) {
-  constexpr int BQ = 32 * ANW, KS = D + 8;
+struct ATile {
+  static constexpr int U = D / 8;
+  static constexpr int BYTES = ATILE * D * 2;
+  static constexpr int QPW = U / ANW;              // 1-KB copies per wave and tile
+  static_assert(U % ANW == 0 && (U == 8 || U == 12 || U == 16), "head size");
+  __device__ static __forceinline__ int sw(int row) {
+    if (U == 16) return ((row & 3) << 2) | ((row >> 2) & 3);
+    if (U == 12) return (row >> 2) & 3;
+    return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+  }
+  // operand with k along D: 8 consecutive elements [16 ks + 8 lh, +8) of row r0 + l32
+  __device__ static __forceinline__ bf16x8 frag_kc(const unsigned char* tile, int r0, int ks, int lane) {
+    const int row = r0 + (lane & 31), c = 2 * ks + (lane >> 5);
+    return *reinterpret_cast<const bf16x8*>(tile + row * (U * 16) + ((c ^ sw(row)) << 4));
+  }
+  // operand with k along the tile's rows, for column d0 + l32: k-slot (lh, e) <-> row 16 c4 + 8 (e/4) + 4 lh + e%4,
+  // which is how a transposed score accumulator lays out its rows
+  __device__ static __forceinline__ bf16x8 frag_tr(const unsigned char* tile, int c4, int d0, int lane) {
+    const int g = lane >> 4, j = lane & 15;
+    const int col = d0 + 16 * (g & 1) + 4 * (j & 3);
+    const int cu = col >> 3, half = (col >> 2) & 1;
+    v4s_t h[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int row = 16 * c4 + 4 * (g >> 1) + 8 * r + (j >> 2);
+      h[r] = lds_read_tr16(tile + row * (U * 16) + ((cu ^ sw(row)) << 4) + half * 8);
+    }
+    const v8s_t v = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+
+// Which 16 bytes of a tile each lane copies (fixed per lane), and the copy of one tile.
+template <int D>
+struct ATileSrc {
+  typedef ATile<D> TL;
+  int row[TL::QPW], col[TL::QPW];
+  __device__ __forceinline__ void init(int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < TL::QPW; ++i) {
+      const int u = 64 * (wave * TL::QPW + i) + lane;
+      row[i] = u / TL::U;
+      col[i] = ((u % TL::U) ^ TL::sw(row[i])) * 8;
+    }
+  }
+  // P: element (0, 0) of the streamed matrix (row stride ld); rows beyond nrows - 1 re-read the last row (callers mask)
+  __device__ __forceinline__ void issue(const bf16* P, int ld, int row0, int nrows, uint32_t lds_tile, int wave_u) const {
+#pragma unroll
+    for (int i = 0; i < TL::QPW; ++i)
+      dma16(P + (size_t)min(row0 + row[i], nrows - 1) * ld + col[i], lds_tile + (wave_u * TL::QPW + i) * 1024);
+  }
+};
+
+// ------------------------------------------------------------------------------------------ forward
+// Workgroup = 128 queries of one (batch, head), 4 waves of 32 queries.  K and V tiles of 64 keys stream through a
+// three-stage LDS ring filled by DMA two tiles ahead; per tile: S^T = K Q^T (12 MFMAs at d = 96), online softmax in
+// registers, O^T += V^T P^T with V read through the transposing LDS loads (12 MFMAs).  One barrier per tile.
+constexpr int ANST = 3;
+
+// (two waves per SIMD requested: with at most 256 registers per lane the MFMA accumulators live in ordinary VGPRs, so
+// the softmax arithmetic needs no accumulator-register moves)
+template <int D>
+__global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void attn_fwd_bf16_kernel(AttnArgs a) {
+  typedef ATile<D> TL;
+  constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW;   // LPT: copies per tile and wave (K + V)
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16* sK = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
-  bf16* sVt = sK + ATILE * KS;                    // [D][72]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform values must be known as such: the mask test below is a scalar branch
+  const int wave_u = wave;
   const int nqb = (a.s + BQ - 1) / BQ;
   const int qb = nqb - 1 - blockIdx.x;            // longest (causal) blocks first
   const int hd = blockIdx.y, bi = blockIdx.z;
@@ -124,72 +192,91 @@ __global__ __launch_bounds__(ANT) void attn_fwd_bf16_kernel(AttnArgs a) {
   const float sc = kLog2e / sqrtf((float)D);
   const bf16* Kb = base + (a.hl + hd) * D;
   const bf16* Vb = base + (2 * a.hl + hd) * D;
-  TileBlocks<D> lk, lv;
-  lk.load(Kb, ld, 0, a.s, tid);
-  lv.load(Vb, ld, 0, a.s, tid);
+  ATileSrc<D> src;
+  src.init(wave, lane);
+  const uint32_t lds0 = lds_offset_of(lds_raw);
+  // The ring is always kept full: past the last tile the copies re-read tile nt - 1 into a stage nobody reads, so
+  // the outstanding-copy count is the same in every iteration.
+#pragma unroll
+  for (int t = 0; t < ANST - 1; ++t) {
+    const int tc = min(t, nt - 1) * ATILE;
+    src.issue(Kb, ld, tc, a.s, lds0 + t * STAGE, wave_u);
+    src.issue(Vb, ld, tc, a.s, lds0 + t * STAGE + TL::BYTES, wave_u);
+  }
+  int stage = 0;
   for (int t = 0; t < nt; ++t) {
     const int k0 = t * ATILE;
-    __syncthreads();
-    lk.store_rows(sK, tid);
-    lv.store_transposed(sVt, tid);
-    __syncthreads();
-    if (t + 1 < nt) {
-      lk.load(Kb, ld, k0 + ATILE, a.s, tid);
-      lv.load(Vb, ld, k0 + ATILE, a.s, tid);
+    wait_vmcnt<LPT*(ANST - 2)>();                  // this wave's copies of tile t have landed; tile t + 1 may be in flight
+    __builtin_amdgcn_s_barrier();                 // everyone's have; and everyone is done with tile t - 1
+    {
+      const int pst = stage == 0 ? ANST - 1 : stage - 1;          // stage of tile t - 1 = stage of tile t + 2
+      const int tc = min(t + ANST - 1, nt - 1) * ATILE;
+      src.issue(Kb, ld, tc, a.s, lds0 + pst * STAGE, wave_u);
+      src.issue(Vb, ld, tc, a.s, lds0 + pst * STAGE + TL::BYTES, wave_u);
     }
+    const unsigned char* sK = lds_raw + stage * STAGE;
+    const unsigned char* sV = sK + TL::BYTES;
+    stage = stage == ANST - 1 ? 0 : stage + 1;
     if (a.causal && k0 > qw0 + 31) continue;     // tile entirely above this wave's diagonal (wave-uniform)
     floatx16 sacc[2];
+    float lsum_t = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) sacc[kt][e] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (kt * 32 + l32) * KS + ks * 16 + lh * 8);
-        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kt], 0, 0, 0);
-      }
+      for (int ks = 0; ks < D / 16; ++ks)
+        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sK, kt * 32, ks, lane), qf[ks], sacc[kt], 0, 0, 0);
     }
-    const bool need_mask = (a.causal && k0 + ATILE - 1 > qw0) || (k0 + ATILE > klen);
+    // raw scores s; probabilities p = exp2(s * sc - max) with the scale folded into one fma per element
+    const bool need_mask = (a.causal && k0 + ATILE - 1 > qw0) || (k0 + ATILE > klen);   // wave-uniform
     float mt = -INFINITY;
+    if (need_mask) {
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float v = sacc[kt][e] * sc;
-        if (need_mask) {
+        for (int e = 0; e < 16; ++e) {
           const int key = k0 + kt * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-          if (key >= klen || (a.causal && key > qi)) v = -INFINITY;
+          const bool off = key >= klen || (a.causal && key > qi);
+          sacc[kt][e] = off ? -INFINITY : sacc[kt][e];
+          mt = fmaxf(mt, sacc[kt][e]);
         }
-        sacc[kt][e] = v;
-        mt = fmaxf(mt, v);
-      }
-    mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+    } else {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mt = fmaxf(mt, sacc[kt][e]);
+    }
+    mt = fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc;
     const float mn = fmaxf(m, mt);               // finite from the first tile on: key 0 is allowed for every query
-    const float corr = __builtin_amdgcn_exp2f(m - mn);
-    lsum *= corr;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float p = __builtin_amdgcn_exp2f(sacc[kt][e] - mn);
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kt][e], sc, -mn));
         sacc[kt][e] = p;
-        lsum += p;
+        lsum_t += p;
       }
-    m = mn;
+    // rescale the running sums only when some row's maximum moved (wave-uniform test)
+    if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
+      const float corr = __builtin_amdgcn_exp2f(m - mn);
+      lsum *= corr;
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+      for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) o[dt][e] *= corr;
+        for (int e = 0; e < 16; ++e) o[dt][e] *= corr;
+      m = mn;
+    }
+    lsum += lsum_t;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const bf16x8 pf = pack8(sacc[c >> 1], 8 * (c & 1));
 #pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt) {
-        const bf16x8 vf = read_tr_frag(sVt, dt * 32 + l32, c, lh);
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[dt], 0, 0, 0);
-      }
+      for (int dt = 0; dt < D / 32; ++dt)
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_tr(sV, c, dt * 32, lane), pf, o[dt], 0, 0, 0);
     }
   }
+  wait_vmcnt<0>();                                // copies still in flight target this workgroup's LDS
   lsum += __shfl_xor(lsum, 32, 64);
   if (qi < a.s) {
     const float inv = 1.0f / lsum;
@@ -215,7 +302,8 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   bf16* sK = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
   bf16* sV = sK + ATILE * KS;                     // [64][D+8]
   bf16* sKt = sV + ATILE * KS;                    // [D][72]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known wave-uniform: mask tests become scalar branches
   const int nqb = (a.s + BQ - 1) / BQ;
   const int qb = nqb - 1 - blockIdx.x;
   const int hd = blockIdx.y, bi = blockIdx.z;
@@ -324,7 +412,8 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   bf16* sdOt = sQt + D * ATS;                     // [D][72]
   float* sLse = reinterpret_cast<float*>(sdOt + D * ATS);   // [64] (log2 units; +inf for rows past s)
   float* sDl = sLse + ATILE;                                // [64]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known wave-uniform: mask tests become scalar branches
   const int kb = blockIdx.x;                       // key block; for causal, block 0 has the most queries: first
   const int hd = blockIdx.y, bi = blockIdx.z;
   const int ld = 3 * a.hl * D;
@@ -456,7 +545,12 @@ bool attn_bf16_supported(int d) { return d == 64 || d == 96 || d == 128; }
 
 template <int D>
 static hipError_t launch_fwd_d(const AttnArgs& a, hipStream_t st) {
-  const size_t lds = ((size_t)ATILE * (D + 8) + (size_t)D * ATS) * 2;
+  const size_t lds = (size_t)ANST * 2 * ATile<D>::BYTES;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess) return e;
+  }
   dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
   hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), grid, dim3(ANT), lds, st, a);
   return hipGetLastError();

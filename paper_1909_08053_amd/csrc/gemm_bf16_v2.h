@@ -20,6 +20,7 @@
 // the bias.  Only the plain-store epilogue takes part.
 #pragma once
 #include "gemm_bf16.h"
+#include "lds_dma.h"
 
 namespace mlm {
 
@@ -30,27 +31,6 @@ constexpr int V2_OP_BYTES = V2_B * V2_BK * 2;          // 16 KB per operand per 
 constexpr int V2_STAGE_BYTES = 2 * V2_OP_BYTES;
 constexpr size_t V2_LDS_BYTES = (size_t)V2_STAGES * V2_STAGE_BYTES;   // 128 KB
 constexpr int V2_CUS = 256;
-
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) void glb_void_t;
-typedef short v4s_t __attribute__((ext_vector_type(4)));
-typedef short v8s_t __attribute__((ext_vector_type(8)));
-
-// One wave-wide 16-byte-per-lane copy HBM -> LDS: lane t's 16 bytes land at lds_addr + 16 t (lds_addr is the
-// wave-uniform LDS byte address, passed in M0).  Written as inline assembly so that the compiler's conservative
-// "LDS DMA may alias any LDS read" rule does not turn every fragment read into s_waitcnt vmcnt(0); completion is
-// tracked by hand with wait_vmcnt<> below.
-__device__ __forceinline__ void dma16(const bf16* g, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
-}
-__device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
-  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)p;
-}
-
-// s_waitcnt vmcnt(N) only (lgkmcnt / expcnt left at "no wait"): gfx9 encoding vmcnt[3:0] | expcnt<<4 | lgkm<<8 | vmcnt[5:4]<<14
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
 
 // Bank swizzle of the [k][row] tile layout (XOR on the 16-byte unit index of a k-row).  One transpose-read
 // instruction touches k-rows {b..b+3} (16-lane groups 0,1) and {b+8..b+11} (groups 2,3), 32 bytes per row and
