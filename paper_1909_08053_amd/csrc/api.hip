@@ -57,7 +57,7 @@ size_t ws_bytes_for(const mlm_dims* dm, const Local& L, int which) {
     case MLM_WS_ATTN_FWD: return sk;
     case MLM_WS_ATTN_BWD:
       return align256(T * L.Hl * L.esz) + align256(T * 3 * L.Hl * L.esz) +
-             align256((size_t)dm->b * L.hl * dm->s * 4) + align256(cs_rows * 3 * L.Hl * 4) + sk;
+             align256((size_t)dm->b * L.hl * dm->s * 8) + align256(cs_rows * 3 * L.Hl * 4) + sk;
     case MLM_WS_MLP_FWD: return sk;
     case MLM_WS_MLP_BWD: return align256(T * L.Fl * L.esz) + align256(cs_rows * L.Fl * 4) + sk;
     case MLM_WS_COLSUM: return align256(cs_rows * (size_t)dm->H * 4);
@@ -294,14 +294,15 @@ MLM_API int mlm_attn_shard_bwd(const mlm_dims* dims, const void* dx1, const void
   char* w = (char*)ws;
   void* dctx = w;                 w += align256(T * L.Hl * L.esz);
   void* dqkv = w;                 w += align256(T * 3 * L.Hl * L.esz);
-  float* delta = (float*)w;       w += align256((size_t)dims->b * L.hl * dims->s * 4);
+  float* delta = (float*)w;       w += align256((size_t)dims->b * L.hl * dims->s * 8);   // delta, and lse in log2 units
   float* csws = (float*)w;        w += align256(((T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock) * 3 * L.Hl * 4);
   float* sk = dt == MLM_BF16 ? (float*)w : nullptr;
   // output projection: dWo_r = ctx^T dx1, dctx = dx1 Wo_r^T
   MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(L.Hl, dims->H, L.T, ctx_r, dx1, dWo_r), st, sk));
   MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, L.Hl, dims->H, dx1, Wo_r, dctx), st, sk));
   // attention core
-  MLM_TRY_HIP(launch_attn_delta(dt, L.T, L.hl, L.d, dims->b, dims->s, ctx_r, dctx, delta, st));
+  // bf16: the dQ kernel computes delta itself (and stores it for the dK/dV kernel)
+  if (dt != MLM_BF16) MLM_TRY_HIP(launch_attn_delta(dt, L.T, L.hl, L.d, dims->b, dims->s, ctx_r, dctx, delta, st));
   AttnArgs a;
   memset(&a, 0, sizeof(a));
   a.b = dims->b; a.s = dims->s; a.hl = L.hl; a.d = L.d; a.causal = dims->causal; a.key_len = key_len;

@@ -295,13 +295,15 @@ __global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void a
 }
 
 // ------------------------------------------------------------------------------------------ backward: dQ
+// Same streaming structure as the forward kernel.  Per tile: S^T = K Q^T and dP^T = V dO^T (contraction along D),
+// P = exp2(S sc - lse), dS = P o (dP - delta), dQ^T += K^T dS^T with K read a second time through the transposing
+// loads.  delta_i = sum_d dO_id O_id is computed here from the rows the lanes already hold and stored for the
+// dK/dV kernel, which runs after this one.
 template <int D>
-__global__ __launch_bounds__(ANT) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
-  constexpr int BQ = 32 * ANW, KS = D + 8;
+__global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
+  typedef ATile<D> TL;
+  constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16* sK = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
-  bf16* sV = sK + ATILE * KS;                     // [64][D+8]
-  bf16* sKt = sV + ATILE * KS;                    // [D][72]
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known wave-uniform: mask tests become scalar branches
   const int nqb = (a.s + BQ - 1) / BQ;
@@ -314,17 +316,26 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   const int qc = min(qi, a.s - 1);
 
   bf16x8 qf[D / 16], dof[D / 16];
+  float dl = 0.f;
   {
     const bf16* qrow = base + (size_t)qc * ld + hd * D;
     const bf16* drow = (const bf16*)a.dctx + ((size_t)bi * a.s + qc) * (a.hl * D) + hd * D;
+    const bf16* orow = (const bf16*)a.ctx + ((size_t)bi * a.s + qc) * (a.hl * D) + hd * D;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
       qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + lh * 8);
       dof[ks] = *reinterpret_cast<const bf16x8*>(drow + ks * 16 + lh * 8);
+      const bf16x8 of = *reinterpret_cast<const bf16x8*>(orow + ks * 16 + lh * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dl = fmaf((float)dof[ks][e], (float)of[e], dl);
     }
+    dl += __shfl_xor(dl, 32, 64);
   }
   const float lse2 = a.lse[((size_t)bi * a.hl + hd) * a.s + qc] * kLog2e;
-  const float dl = a.delta[((size_t)bi * a.hl + hd) * a.s + qc];
+  if (lh == 0 && qi < a.s) {                      // for the dK/dV kernel: [0] delta, [1] log-sum-exp in log2 units
+    a.delta[((size_t)bi * a.hl + hd) * a.s + qi] = dl;
+    a.delta[(size_t)a.b * a.hl * a.s + ((size_t)bi * a.hl + hd) * a.s + qi] = lse2;
+  }
   floatx16 dq[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
@@ -337,20 +348,29 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   const float sc = kLog2e * scale;
   const bf16* Kb = base + (a.hl + hd) * D;
   const bf16* Vb = base + (2 * a.hl + hd) * D;
-  TileBlocks<D> lk, lv;
-  lk.load(Kb, ld, 0, a.s, tid);
-  lv.load(Vb, ld, 0, a.s, tid);
+  ATileSrc<D> src;
+  src.init(wave, lane);
+  const uint32_t lds0 = lds_offset_of(lds_raw);
+#pragma unroll
+  for (int t = 0; t < ANST - 1; ++t) {
+    const int tc = min(t, nt - 1) * ATILE;
+    src.issue(Kb, ld, tc, a.s, lds0 + t * STAGE, wave);
+    src.issue(Vb, ld, tc, a.s, lds0 + t * STAGE + TL::BYTES, wave);
+  }
+  int stage = 0;
   for (int t = 0; t < nt; ++t) {
     const int k0 = t * ATILE;
-    __syncthreads();
-    lk.store_rows(sK, tid);
-    lk.store_transposed(sKt, tid);
-    lv.store_rows(sV, tid);
-    __syncthreads();
-    if (t + 1 < nt) {
-      lk.load(Kb, ld, k0 + ATILE, a.s, tid);
-      lv.load(Vb, ld, k0 + ATILE, a.s, tid);
+    wait_vmcnt<LPT*(ANST - 2)>();
+    __builtin_amdgcn_s_barrier();
+    {
+      const int pst = stage == 0 ? ANST - 1 : stage - 1;
+      const int tc = min(t + ANST - 1, nt - 1) * ATILE;
+      src.issue(Kb, ld, tc, a.s, lds0 + pst * STAGE, wave);
+      src.issue(Vb, ld, tc, a.s, lds0 + pst * STAGE + TL::BYTES, wave);
     }
+    const unsigned char* sK = lds_raw + stage * STAGE;
+    const unsigned char* sV = sK + TL::BYTES;
+    stage = stage == ANST - 1 ? 0 : stage + 1;
     if (a.causal && k0 > qw0 + 31) continue;
     floatx16 sacc[2], pacc[2];
 #pragma unroll
@@ -359,34 +379,37 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
       for (int e = 0; e < 16; ++e) { sacc[kt][e] = 0.f; pacc[kt][e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (kt * 32 + l32) * KS + ks * 16 + lh * 8);
-        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sV + (kt * 32 + l32) * KS + ks * 16 + lh * 8);
-        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kt], 0, 0, 0);    // S^T[key][query]
-        pacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], pacc[kt], 0, 0, 0);   // dP^T[key][query]
+        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sK, kt * 32, ks, lane), qf[ks], sacc[kt], 0, 0, 0);   // S^T[key][query]
+        pacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sV, kt * 32, ks, lane), dof[ks], pacc[kt], 0, 0, 0);  // dP^T[key][query]
       }
     }
-    const bool need_mask = (a.causal && k0 + ATILE - 1 > qw0) || (k0 + ATILE > klen);
+    const bool need_mask = (a.causal && k0 + ATILE - 1 > qw0) || (k0 + ATILE > klen);   // wave-uniform
+    if (need_mask) {
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float p = __builtin_amdgcn_exp2f(sacc[kt][e] * sc - lse2);
-        if (need_mask) {
+        for (int e = 0; e < 16; ++e) {
           const int key = k0 + kt * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-          if (key >= klen || (a.causal && key > qi)) p = 0.f;
+          const bool off = key >= klen || (a.causal && key > qi);
+          const float p = off ? 0.f : __builtin_amdgcn_exp2f(fmaf(sacc[kt][e], sc, -lse2));
+          sacc[kt][e] = p * (pacc[kt][e] - dl);     // dS^T
         }
-        sacc[kt][e] = p * (pacc[kt][e] - dl);     // dS^T
-      }
+    } else {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          sacc[kt][e] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][e], sc, -lse2)) * (pacc[kt][e] - dl);
+    }
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const bf16x8 dsf = pack8(sacc[c >> 1], 8 * (c & 1));
 #pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt) {
-        const bf16x8 ktf = read_tr_frag(sKt, dt * 32 + l32, c, lh);
-        dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf, dq[dt], 0, 0, 0);          // dQ^T[dcol][query]
-      }
+      for (int dt = 0; dt < D / 32; ++dt)
+        dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_tr(sK, c, dt * 32, lane), dsf, dq[dt], 0, 0, 0);   // dQ^T[dcol][query]
     }
   }
+  wait_vmcnt<0>();
   if (qi < a.s) {
     bf16* orow = (bf16*)a.dqkv + ((size_t)bi * a.s + qi) * ld + hd * D;
 #pragma unroll
@@ -402,16 +425,19 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ backward: dK, dV
+// Workgroup = 128 keys of one (batch, head), a wave owns 32 keys (K and V rows in registers).  Q and dO tiles of 64
+// queries stream through the DMA ring together with the tile's log-sum-exp (log2 units) and delta vectors, which
+// the dQ kernel left in the workspace.  Per 32-query half tile: S = Q K^T and dP = dO V^T (contraction along D),
+// P = exp2(S sc - lse), dS = P o (dP - delta), then dV^T += dO^T P and dK^T += Q^T dS with Q and dO read a second
+// time through the transposing loads.
+// (No two-waves-per-SIMD request here: with the 256-register cap the dK / dV accumulators spill, which was measured
+// twice as slow as letting them live in the accumulation registers.)
 template <int D>
 __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
-  constexpr int BKB = 32 * ANW, KS = D + 8;
+  typedef ATile<D> TL;
+  constexpr int BKB = 32 * ANW, VEC = 2 * ATILE * 4;          // VEC: bytes of the lse + delta vectors of a tile
+  constexpr int STAGE = 2 * TL::BYTES + VEC, LPT = 2 * TL::QPW + 1;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16* sQ = reinterpret_cast<bf16*>(lds_raw);    // [64][D+8]
-  bf16* sdO = sQ + ATILE * KS;                    // [64][D+8]
-  bf16* sQt = sdO + ATILE * KS;                   // [D][72]
-  bf16* sdOt = sQt + D * ATS;                     // [D][72]
-  float* sLse = reinterpret_cast<float*>(sdOt + D * ATS);   // [64] (log2 units; +inf for rows past s)
-  float* sDl = sLse + ATILE;                                // [64]
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known wave-uniform: mask tests become scalar branches
   const int kb = blockIdx.x;                       // key block; for causal, block 0 has the most queries: first
@@ -442,57 +468,51 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   const int nqt = (a.s + ATILE - 1) / ATILE;
   int qt0 = a.causal ? kb0 / ATILE : 0;
   if (kb0 >= klen) qt0 = nqt;                     // every key of the block is padding: gradients are zero
+  const int nt = nqt - qt0;                       // tiles to stream (block-uniform)
   const bf16* Qb = base + hd * D;
-  const bf16* dOb = (const bf16*)a.dctx + (size_t)bi * a.s * (a.hl * D) + hd * D;
-  const float* lse_b = a.lse + ((size_t)bi * a.hl + hd) * a.s;
-  const float* dl_b = a.delta + ((size_t)bi * a.hl + hd) * a.s;
-  TileBlocks<D> lq, ldo;
-  float lse_next = 0.f, dl_next = 0.f;
-  if (qt0 < nqt) {
-    lq.load(Qb, ld, qt0 * ATILE, a.s, tid);
-    ldo.load(dOb, a.hl * D, qt0 * ATILE, a.s, tid);
-    if (tid < ATILE) {
-      const int q = qt0 * ATILE + tid;
-      lse_next = q < a.s ? lse_b[q] * kLog2e : INFINITY;
-      dl_next = q < a.s ? dl_b[q] : 0.f;
-    }
+  const int ldo = a.hl * D;
+  const bf16* dOb = (const bf16*)a.dctx + (size_t)bi * a.s * ldo + hd * D;
+  // per-query vectors in the workspace: [0] delta, [1] log-sum-exp in log2 units (both written by the dQ kernel)
+  const size_t nrow_all = (size_t)a.b * a.hl * a.s;
+  const float* vec_b = ((wave & 1) ? a.delta + nrow_all : a.delta) + ((size_t)bi * a.hl + hd) * a.s;
+  ATileSrc<D> src;
+  src.init(wave, lane);
+  const uint32_t lds0 = lds_offset_of(lds_raw);
+  auto issue_tile = [&](int t, int st) {          // tile index relative to qt0 (clamped), ring stage
+    const int r0 = (qt0 + min(t, nt - 1)) * ATILE;
+    const uint32_t sb = lds0 + st * STAGE;
+    src.issue(Qb, ld, r0, a.s, sb, wave);
+    src.issue(dOb, ldo, r0, a.s, sb + TL::BYTES, wave);
+    // waves 0, 2 copy the delta vector, waves 1, 3 the log-sum-exp vector (same data twice: uniform copy counts)
+    dma4(vec_b + min(r0 + lane, a.s - 1), sb + 2 * TL::BYTES + (wave & 1) * (ATILE * 4));
+  };
+  if (nt > 0) {
+#pragma unroll
+    for (int t = 0; t < ANST - 1; ++t) issue_tile(t, t);
   }
-  for (int qt = qt0; qt < nqt; ++qt) {
-    const int q0 = qt * ATILE;
-    __syncthreads();
-    lq.store_rows(sQ, tid);
-    lq.store_transposed(sQt, tid);
-    ldo.store_rows(sdO, tid);
-    ldo.store_transposed(sdOt, tid);
-    if (tid < ATILE) { sLse[tid] = lse_next; sDl[tid] = dl_next; }
-    __syncthreads();
-    if (qt + 1 < nqt) {
-      lq.load(Qb, ld, q0 + ATILE, a.s, tid);
-      ldo.load(dOb, a.hl * D, q0 + ATILE, a.s, tid);
-      if (tid < ATILE) {
-        const int q = q0 + ATILE + tid;
-        lse_next = q < a.s ? lse_b[q] * kLog2e : INFINITY;
-        dl_next = q < a.s ? dl_b[q] : 0.f;
-      }
-    }
+  int stage = 0;
+  for (int t = 0; t < nt; ++t) {
+    const int q0 = (qt0 + t) * ATILE;
+    wait_vmcnt<LPT*(ANST - 2)>();
+    __builtin_amdgcn_s_barrier();
+    issue_tile(t + ANST - 1, stage == 0 ? ANST - 1 : stage - 1);
+    const unsigned char* sQ = lds_raw + stage * STAGE;
+    const unsigned char* sdO = sQ + TL::BYTES;
+    const float* sDl = reinterpret_cast<const float*>(sdO + TL::BYTES);
+    const float* sLse = sDl + ATILE;
+    stage = stage == ANST - 1 ? 0 : stage + 1;
     if (a.causal && q0 + ATILE - 1 < kw0) continue;   // every query of the tile precedes this wave's keys
-    floatx16 sacc[2], pacc[2];
+    const bool need_mask = (a.causal && q0 < kw0 + 31) || (kw0 + 32 > klen) || (q0 + ATILE > a.s);   // wave-uniform
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
+      floatx16 sacc, pacc;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { sacc[qs][e] = 0.f; pacc[qs][e] = 0.f; }
+      for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8 qfr = *reinterpret_cast<const bf16x8*>(sQ + (qs * 32 + l32) * KS + ks * 16 + lh * 8);
-        const bf16x8 dofr = *reinterpret_cast<const bf16x8*>(sdO + (qs * 32 + l32) * KS + ks * 16 + lh * 8);
-        sacc[qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr, kf[ks], sacc[qs], 0, 0, 0);    // S[query][key]
-        pacc[qs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dofr, vf[ks], pacc[qs], 0, 0, 0);   // dP[query][key]
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sQ, qs * 32, ks, lane), kf[ks], sacc, 0, 0, 0);    // S[query][key]
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sdO, qs * 32, ks, lane), vf[ks], pacc, 0, 0, 0);   // dP[query][key]
       }
-    }
-    const bool need_mask = a.causal && q0 < kw0 + 31;
-    const bool key_ok = kj < klen;
-#pragma unroll
-    for (int qs = 0; qs < 2; ++qs)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int qoff = qs * 32 + 8 * g + 4 * lh;
@@ -502,25 +522,29 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
         const float dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          float p = __builtin_amdgcn_exp2f(sacc[qs][4 * g + e] * sc - lv4[e]);
-          if (!key_ok || (need_mask && kj > q0 + qoff + e)) p = 0.f;
-          sacc[qs][4 * g + e] = p;                                   // P
-          pacc[qs][4 * g + e] = p * (pacc[qs][4 * g + e] - dv4[e]);  // dS
+          float p = __builtin_amdgcn_exp2f(fmaf(sacc[4 * g + e], sc, -lv4[e]));
+          if (need_mask) {
+            const int q = q0 + qoff + e;
+            p = (kj >= klen || q >= a.s || (a.causal && kj > q)) ? 0.f : p;
+          }
+          sacc[4 * g + e] = p;                                // P
+          pacc[4 * g + e] = p * (pacc[4 * g + e] - dv4[e]);   // dS
         }
       }
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const bf16x8 pf = pack8(sacc[c >> 1], 8 * (c & 1));
-      const bf16x8 dsf = pack8(pacc[c >> 1], 8 * (c & 1));
+      for (int cc = 0; cc < 2; ++cc) {
+        const int c = 2 * qs + cc;
+        const bf16x8 pf = pack8(sacc, 8 * cc);
+        const bf16x8 dsf = pack8(pacc, 8 * cc);
 #pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt) {
-        const bf16x8 dotf = read_tr_frag(sdOt, dt * 32 + l32, c, lh);
-        const bf16x8 qtf = read_tr_frag(sQt, dt * 32 + l32, c, lh);
-        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dotf, pf, dv[dt], 0, 0, 0);    // dV^T[dcol][key]
-        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, dsf, dk[dt], 0, 0, 0);    // dK^T[dcol][key]
+        for (int dt = 0; dt < D / 32; ++dt) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_tr(sdO, c, dt * 32, lane), pf, dv[dt], 0, 0, 0);    // dV^T[dcol][key]
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_tr(sQ, c, dt * 32, lane), dsf, dk[dt], 0, 0, 0);    // dK^T[dcol][key]
+        }
       }
     }
   }
+  wait_vmcnt<0>();
   if (kj < a.s) {
     bf16* krow = (bf16*)a.dqkv + ((size_t)bi * a.s + kj) * ld + (a.hl + hd) * D;
     bf16* vrow = (bf16*)a.dqkv + ((size_t)bi * a.s + kj) * ld + (2 * a.hl + hd) * D;
@@ -559,11 +583,17 @@ static hipError_t launch_fwd_d(const AttnArgs& a, hipStream_t st) {
 template <int D>
 static hipError_t launch_bwd_d(const AttnArgs& a, hipStream_t st) {
   dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
-  const size_t lds_q = ((size_t)2 * ATILE * (D + 8) + (size_t)D * ATS) * 2;
+  const size_t lds_q = (size_t)ANST * 2 * ATile<D>::BYTES;
+  hipError_t e;
+  if (lds_q > 64 * 1024) {
+    e = hipFuncSetAttribute((const void*)attn_bwd_dq_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_q);
+    if (e != hipSuccess) return e;
+  }
   hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), grid, dim3(ANT), lds_q, st, a);
-  hipError_t e = hipGetLastError();
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const size_t lds_kv = ((size_t)2 * ATILE * (D + 8) + (size_t)2 * D * ATS) * 2 + 2 * ATILE * sizeof(float);
+  const size_t lds_kv = (size_t)ANST * (2 * ATile<D>::BYTES + 2 * ATILE * 4);
   if (lds_kv > 64 * 1024) {
     e = hipFuncSetAttribute((const void*)attn_bwd_dkv_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds_kv);

@@ -16,6 +16,10 @@ typedef short v8s_t __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ void dma16(const bf16* g, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
 }
+// Same with 4 bytes per lane: lane t's dword lands at lds_addr + 4 t (one 256-byte vector per wave instruction).
+__device__ __forceinline__ void dma4(const float* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
 __device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)p;
 }
