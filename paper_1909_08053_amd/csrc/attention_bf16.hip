@@ -7,82 +7,21 @@
 // wave owns, so that v_mfma_f32_32x32x16_bf16 leaves, in every lane, 16 score values that all belong to ONE
 // owned row (a query in forward / dQ, a key in dK/dV).  Row statistics (max, sum, lse, delta) are then
 // per-lane scalars (plus one cross-half shuffle), and the probability registers are already in the operand
-// layout of the second MFMA (k index = the other sequence axis) -- P never goes through LDS.  The operand
-// that must be read with k along the sequence axis (V, K, Q, dO "transposed") is transposed in registers
-// (8x8 byte-permute blocks) on its way from HBM to LDS.
+// layout of the second MFMA (k index = the other sequence axis) -- P never goes through LDS.  The streamed
+// tiles (K, V, Q, dO) are copied HBM -> LDS asynchronously, several tiles ahead, and an operand that must be read
+// with k along the sequence axis is fetched from the same LDS tile with the transposing read instruction.
 //
 // Mask: allowed(i, j) = (j < key_len[b]) && (!causal || j <= i); excluded entries get probability exactly 0.
-#include "gemm_bf16.h"   // transpose8x8
 #include "lds_dma.h"
 
 namespace mlm {
 
 constexpr int ATILE = 64;           // rows of the streamed tile (keys in fwd/dQ, queries in dK/dV)
-constexpr int ATS = ATILE + 8;      // LDS stride of a transposed tile [D][ATILE]
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// A [64][D] tile (row stride ld in HBM) fetched as 8x8 blocks: eight 16-byte row pieces per block.
-constexpr int ANW = 4;              // waves per workgroup: 32 owned rows each (2-wave blocks were measured slower: tile staging is re-done per block)
+constexpr int ANW = 4;              // waves per workgroup: 32 owned rows each
 constexpr int ANT = ANW * 64;
-
-template <int D>
-struct TileBlocks {
-  static constexpr int BLKS = (ATILE / 8) * (D / 8);
-  static constexpr int PER = (BLKS + ANT - 1) / ANT;
-  uint4 reg[PER][8];
-  // rows >= nvalid (relative to row0 = 0 of P) are zero-filled
-  __device__ __forceinline__ void load(const bf16* __restrict__ P, int ld, int row0, int nrows, int tid) {
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int blk = tid + i * ANT;
-      if (blk < BLKS) {
-        const int rb = blk & 7, cb = blk >> 3;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int r = row0 + rb * 8 + j;
-          if (r < nrows) reg[i][j] = *reinterpret_cast<const uint4*>(P + (size_t)r * ld + cb * 8);
-          else reg[i][j] = make_uint4(0, 0, 0, 0);
-        }
-      }
-    }
-  }
-  __device__ __forceinline__ void store_rows(bf16* s, int tid) const {   // s: [64][D+8]
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int blk = tid + i * ANT;
-      if (blk < BLKS) {
-        const int rb = blk & 7, cb = blk >> 3;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) *reinterpret_cast<uint4*>(s + (rb * 8 + j) * (D + 8) + cb * 8) = reg[i][j];
-      }
-    }
-  }
-  __device__ __forceinline__ void store_transposed(bf16* s, int tid) const {   // s: [D][ATS]
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int blk = tid + i * ANT;
-      if (blk < BLKS) {
-        const int rb = blk & 7, cb = blk >> 3;
-        uint4 o[8];
-        transpose8x8(reg[i], o);
-#pragma unroll
-        for (int n = 0; n < 8; ++n) *reinterpret_cast<uint4*>(s + (cb * 8 + n) * ATS + rb * 8) = o[n];
-      }
-    }
-  }
-};
-
-// MFMA operand whose k index runs along the tile's 64 rows (transposed LDS tile [D][ATS]): 16-row chunk c,
-// k-slot (lh, e) <-> row 16c + 8 (e/4) + 4 lh + e%4, which is exactly how a score accumulator lays out its rows.
-__device__ __forceinline__ bf16x8 read_tr_frag(const bf16* st, int col, int c, int lh) {
-  const bf16x4 lo = *reinterpret_cast<const bf16x4*>(st + col * ATS + 16 * c + 4 * lh);
-  const bf16x4 hi = *reinterpret_cast<const bf16x4*>(st + col * ATS + 16 * c + 8 + 4 * lh);
-  bf16x8 r;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) { r[e] = lo[e]; r[4 + e] = hi[e]; }
-  return r;
-}
 
 __device__ __forceinline__ bf16x8 pack8(const floatx16& v, int off) {
   bf16x8 r;
@@ -154,7 +93,10 @@ struct ATileSrc {
 // Workgroup = 128 queries of one (batch, head), 4 waves of 32 queries.  K and V tiles of 64 keys stream through a
 // three-stage LDS ring filled by DMA two tiles ahead; per tile: S^T = K Q^T (12 MFMAs at d = 96), online softmax in
 // registers, O^T += V^T P^T with V read through the transposing LDS loads (12 MFMAs).  One barrier per tile.
-constexpr int ANST = 3;
+#ifndef MLM_ANST
+#define MLM_ANST 3
+#endif
+constexpr int ANST = MLM_ANST;
 
 // (two waves per SIMD requested: with at most 256 registers per lane the MFMA accumulators live in ordinary VGPRs, so
 // the softmax arithmetic needs no accumulator-register moves)
