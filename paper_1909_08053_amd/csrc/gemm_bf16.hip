@@ -38,7 +38,7 @@ bool gemm_use_v2(const GemmArgs& a) {
     const char* e = getenv("MLM_GEMM_V2");
     enabled = (e && atoi(e) == 0) ? 0 : 1;
   }
-  return enabled && a.K % 32 == 0 && a.K >= 32;
+  return enabled && a.K % 64 == 0 && a.K >= 64;
 }
 
 int gemm_v2_waves() {

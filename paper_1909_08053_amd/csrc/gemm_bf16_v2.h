@@ -12,7 +12,7 @@
 //     slice are pulled into registers half a slice ahead, so its stage is re-armed while it is still being
 //     multiplied: three slices are in flight and one is landed, about 3500 MFMA clocks of prefetch distance,
 //     one barrier per slice.
-// Requirements: K % 32 == 0 (the dispatcher falls back to the register-staged kernel otherwise).
+// Requirements: K % 64 == 0 (the dispatcher falls back to the register-staged kernel otherwise).
 //
 // Tail split: when the tile count does not fill a whole number of rounds of the 256 CUs, the tiles of the last
 // partial round are split along k into f pieces (f = floor(256 / remainder)); each piece writes an fp32 partial
@@ -21,6 +21,7 @@
 #pragma once
 #include "gemm_bf16.h"
 #include "lds_dma.h"
+#include <type_traits>
 
 namespace mlm {
 
@@ -28,8 +29,8 @@ constexpr int V2_B = 256;                   // block tile edge (M and N)
 constexpr int V2_BK = 32;                   // k per stage
 constexpr int V2_STAGES = 4;
 constexpr int V2_OP_BYTES = V2_B * V2_BK * 2;          // 16 KB per operand per stage
-constexpr int V2_STAGE_BYTES = 2 * V2_OP_BYTES;
-constexpr size_t V2_LDS_BYTES = (size_t)V2_STAGES * V2_STAGE_BYTES;   // 128 KB
+constexpr int V2_REGION_BYTES = V2_STAGES * V2_OP_BYTES;   // 64 KB ring per operand: A's ring, then B's ring
+constexpr size_t V2_LDS_BYTES = (size_t)2 * V2_REGION_BYTES;          // 128 KB
 constexpr int V2_CUS = 256;
 
 // Bank swizzle of the [k][row] tile layout (XOR on the 16-byte unit index of a k-row).  One transpose-read
@@ -38,26 +39,36 @@ constexpr int V2_CUS = 256;
 // different 128-byte halves of the 256-byte bank row, so a 512-byte read completes in the minimum two passes.
 __device__ __forceinline__ int v2_mn_swizzle(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
 
-// Per-lane source pointers of one operand's four 1-KB DMA instructions per stage.
-// QPW = 16 / (waves per workgroup): 1-KB DMA instructions per wave, operand and slice.
+// Bank swizzle of a k-contiguous operand's ring: rows of 128 bytes (two consecutive k-slices side by side, eight
+// 16-byte units), unit index XORed with this value; 16 consecutive rows reading the same logical unit then hit 16
+// different bank groups.
+__device__ __forceinline__ int v2_kc_swizzle(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
+
+// Per-lane source pointers of one operand's DMA copies.  QPW = 16 / (waves per workgroup): 1-KB copies per wave,
+// operand and k-slice.
+//  * k-contiguous operand (KC): the ring holds two PAIRS of slices; a pair is [256 rows][64 k] = 128 bytes per row,
+//    so one copy instruction fetches 8 rows x one full 128-byte line (fetching the two 64-byte halves separately,
+//    slice by slice, costs twice the cache-line requests and was measured 40 % slower on the copy side).  A pair
+//    takes 2 QPW copies per wave and is fetched once every two slices.
+//  * operand contiguous along m / n (MN): a slice is [32 k][256 rows] = 512 bytes per k, QPW copies per slice.
 template <bool KC, int QPW>
 struct V2Src {
-  const bf16* p[QPW];
-  size_t step;     // elements to advance per k-slice
+  static constexpr int NP = KC ? 2 * QPW : QPW;
+  const bf16* p[NP];
+  size_t step;     // elements to advance per pair (KC) / per slice (MN)
   __device__ __forceinline__ void init(const bf16* P, int ld, int row0, int nrows, int k_begin, int wave, int lane) {
     if (KC) {
-      // LDS layout [256 rows][32 k] (64 B rows, four 16-byte units); unit u of row r holds k-chunk u ^ ((r >> 2) & 3)
 #pragma unroll
-      for (int q = 0; q < QPW; ++q) {
-        const int row = (wave * QPW + q) * 16 + (lane >> 2);
-        const int c = (lane & 3) ^ ((lane >> 4) & 3);
-        p[q] = P + (size_t)min(row0 + row, nrows - 1) * ld + k_begin + c * 8;
+      for (int q = 0; q < NP; ++q) {
+        const int row = (wave * NP + q) * 8 + (lane >> 3);
+        const int u = (lane & 7) ^ v2_kc_swizzle(row);
+        p[q] = P + (size_t)min(row0 + row, nrows - 1) * ld + k_begin + u * 8;
       }
-      step = V2_BK;
+      step = 2 * V2_BK;
     } else {
-      // LDS layout [32 k][256 rows] (512 B per k, 32 units); unit u of k-row holds row-chunk u ^ v2_mn_swizzle(k)
+      // unit u of k-row holds row-chunk u ^ v2_mn_swizzle(k)
 #pragma unroll
-      for (int q = 0; q < QPW; ++q) {
+      for (int q = 0; q < NP; ++q) {
         const int k = 2 * (wave * QPW + q) + (lane >> 5);
         const int u = (lane & 31) ^ v2_mn_swizzle(k);
         p[q] = P + (size_t)(k_begin + k) * ld + min(row0 + u * 8, nrows - 8);
@@ -65,32 +76,36 @@ struct V2Src {
       step = (size_t)V2_BK * ld;
     }
   }
-  __device__ __forceinline__ void issue_one(uint32_t op_lds, int wave_u, int kt_rel, int q) const {
-    dma16(p[q] + (size_t)kt_rel * step, op_lds + (wave_u * QPW + q) * 1024);
+  // dst: LDS byte address of the pair's (KC) / slice's (MN) buffer; idx: pair / slice index relative to k_begin;
+  // wave_u: wave index as a uniform (SGPR) value
+  __device__ __forceinline__ void issue_one(uint32_t dst, int wave_u, int idx, int q) const {
+    dma16(p[q] + (size_t)idx * step, dst + (wave_u * NP + q) * 1024);
   }
-  // op_lds: LDS byte address of this operand's stage buffer; wave_u: wave index as a uniform (SGPR) value
-  __device__ __forceinline__ void issue(uint32_t op_lds, int wave_u, int kt_rel) const {
+  __device__ __forceinline__ void issue(uint32_t dst, int wave_u, int idx) const {
 #pragma unroll
-    for (int q = 0; q < QPW; ++q) dma16(p[q] + (size_t)kt_rel * step, op_lds + (wave_u * QPW + q) * 1024);
+    for (int q = 0; q < NP; ++q) issue_one(dst, wave_u, idx, q);
   }
 };
 
-// Operand registers (8 consecutive k of one row/column per lane) for the 32-row MFMA tile starting at row `r0`.
+// Operand registers (8 consecutive k of one row/column per lane) for the 32-row MFMA tile starting at row `r0`,
+// k-step ks (0 / 1) of the slice in ring stage `stage` of the operand ring at `ring`.
 template <bool KC>
-__device__ __forceinline__ bf16x8 v2_frag(const unsigned char* op_base, int r0, int ks, int lane) {
+__device__ __forceinline__ bf16x8 v2_frag(const unsigned char* ring, int stage, int r0, int ks, int lane) {
   const int l32 = lane & 31, lh = lane >> 5;
   if (KC) {
-    const int unit = (ks * 2 + lh) ^ ((l32 >> 2) & 3);
-    return *reinterpret_cast<const bf16x8*>(op_base + (r0 + l32) * 64 + unit * 16);
+    const int row = r0 + l32;
+    const int u = (stage & 1) * 4 + ks * 2 + lh;
+    return *reinterpret_cast<const bf16x8*>(ring + (stage >> 1) * (2 * V2_OP_BYTES) + row * 128 +
+                                            ((u ^ v2_kc_swizzle(row)) << 4));
   } else {
+    const unsigned char* op_base = ring + stage * V2_OP_BYTES;
     const int g = lane >> 4, i16 = lane & 15;
     const int u = (r0 >> 3) + 2 * (g & 1) + ((i16 & 3) >> 1);
     v4s_t h[2];
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
       const int k = ks * 16 + 8 * (g >> 1) + 4 * r + (i16 >> 2);
-      const unsigned char* ad = op_base + k * 512 + ((u ^ v2_mn_swizzle(k)) * 16) + (i16 & 1) * 8;
-      h[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s_t*)ad);
+      h[r] = lds_read_tr16(op_base + k * 512 + ((u ^ v2_mn_swizzle(k)) * 16) + (i16 & 1) * 8);
     }
     const v8s_t v = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
@@ -110,7 +125,7 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
   p.tiles_n = (N + V2_B - 1) / V2_B;
   const int tiles = p.tiles_m * p.tiles_n;
   const int rem = tiles % V2_CUS;
-  const int nk = K / V2_BK;
+  const int nk = K / V2_BK;                           // even: K is a multiple of 64
   int split = 1;
   if (allow_split && rem != 0 && rem * 2 <= V2_CUS) {
     int smax = V2_CUS / rem;
@@ -132,7 +147,7 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
 // NW = waves per workgroup: 4 (2 x 2 waves of 128 x 128) or 8 (2 x 4 waves of 128 x 64, two waves per SIMD).
 template <bool A_KC, bool B_KC, int EPI, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan plan, float* splitk_ws) {
-  constexpr int WAVES_N = NW / 2, WN = V2_B / WAVES_N, TN = WN / 32, QPW = 16 / NW, LPS = 2 * QPW;  // LPS: DMA per slice per wave
+  constexpr int WAVES_N = NW / 2, WN = V2_B / WAVES_N, TN = WN / 32, QPW = 16 / NW;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_N) * 128, wn0 = (wave % WAVES_N) * WN;
@@ -152,10 +167,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
   // share an XCD (congruent mod 8) share tile rows, so each XCD's L2 sees few distinct operand panels.
   const int tile_m = vt % plan.tiles_m, tile_n = vt / plan.tiles_m;
   const int m0 = tile_m * V2_B, n0 = tile_n * V2_B;
-  const int nk_total = a.K / V2_BK;
-  const int kt_begin = (int)((long)nk_total * piece / npieces);
-  const int kt_end = (int)((long)nk_total * (piece + 1) / npieces);
-  const int nk = kt_end - kt_begin;
+  const int np_total = a.K / (2 * V2_BK);            // k is walked in pairs of 32-deep slices
+  const int kt_begin = 2 * (int)((long)np_total * piece / npieces);
+  const int kt_end = 2 * (int)((long)np_total * (piece + 1) / npieces);
+  const int nk = kt_end - kt_begin;                  // even, >= 2
 
   V2Src<A_KC, QPW> sa;
   V2Src<B_KC, QPW> sb;
@@ -170,33 +185,51 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const uint32_t lds0 = lds_offset_of(lds_raw);
+  const uint32_t ldsA = lds_offset_of(lds_raw), ldsB = ldsA + V2_REGION_BYTES;
+  const unsigned char* ringA = lds_raw;
+  const unsigned char* ringB = lds_raw + V2_REGION_BYTES;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  // Four slices are always in flight or landed; past the end of k the last slice is fetched again into a stage
-  // nobody reads (keeps the vmcnt bookkeeping and the instruction stream free of tail cases).
+  constexpr int NKC = (A_KC ? 1 : 0) + (B_KC ? 1 : 0), NMN = 2 - NKC;
+  // Four slices are always in flight or landed; past the end of k the last pair / slice is fetched again into a
+  // stage nobody reads (keeps the vmcnt bookkeeping and the instruction stream free of tail cases).  Issue order of
+  // the initial fill = the order the steady state would have produced: pair 0, slices 0 1, pair 1, slices 2 3.
+  const int last_pair = nk / 2 - 1, last_slice = nk - 1;
 #pragma unroll
-  for (int s = 0; s < V2_STAGES; ++s) {
-    sa.issue(lds0 + s * V2_STAGE_BYTES, wave_u, min(s, nk - 1));
-    sb.issue(lds0 + s * V2_STAGE_BYTES + V2_OP_BYTES, wave_u, min(s, nk - 1));
+  for (int h = 0; h < 2; ++h) {
+    if (A_KC) sa.issue(ldsA + h * 2 * V2_OP_BYTES, wave_u, min(h, last_pair));
+    if (B_KC) sb.issue(ldsB + h * 2 * V2_OP_BYTES, wave_u, min(h, last_pair));
+#pragma unroll
+    for (int s = 2 * h; s < 2 * h + 2; ++s) {
+      if (!A_KC) sa.issue(ldsA + s * V2_OP_BYTES, wave_u, min(s, last_slice));
+      if (!B_KC) sb.issue(ldsB + s * V2_OP_BYTES, wave_u, min(s, last_slice));
+    }
   }
   // Software pipeline over half-slices (16 k each).  The operand registers of the NEXT half are read from LDS while
   // the matrix cores work on the current half.  The slice hand-over sits in the middle of slice kt: wait for the
-  // DMA of slice kt+1, barrier, then re-arm slice kt's stage (its operands are all in registers by then) with
-  // slice kt+4.  The DMA instructions are ISSUED ONE AT A TIME BETWEEN MFMAs: eight back-to-back 1-KB copies fill
+  // copies of slice kt+1, barrier, then re-arm what slice kt leaves behind (its operands are all in registers by
+  // then): an MN operand's stage gets slice kt+4; a KC operand's pair-stage is free after the ODD slice of the pair
+  // and then gets the pair two ahead.  Copies are ISSUED ONE AT A TIME BETWEEN MFMAs: back-to-back 1-KB copies fill
   // the vector-memory queue and would stall the wave, and with it the matrix pipe, for hundreds of clocks.
+  //
+  // Copies per wave issued at the hand-over of an even slice: EV = NMN QPW; of an odd slice: OD = NKC 2 QPW + NMN QPW
+  // (pairs first).  Copies return in order, so "slice kt+1 has landed" is a bound on the copies still outstanding:
+  //   even kt: everything up to the hand-over of kt-3 must be done           -> at most EV + OD = 4 QPW outstanding
+  //   odd kt:  the pair issued first at the hand-over of kt-2 must be done   -> at most 2 EV outstanding (if NKC > 0)
+  constexpr int EV = NMN * QPW, OD = NKC * 2 * QPW + NMN * QPW;
+  constexpr int W_INIT = 3 * NMN * QPW + 2 * NKC * QPW, W_EVEN = EV + OD, W_ODD = NKC > 0 ? 2 * EV : EV + OD;
+  constexpr int NMF = TN * 4;            // MFMAs per half-slice per wave
   bf16x8 fa0[4], fb0[TN], fa1[4], fb1[TN];
-  wait_vmcnt<3 * LPS>();                 // slice 0 landed; slices 1..3 may stay in flight (LPS copies each per wave)
+  wait_vmcnt<W_INIT>();                  // slice 0 landed
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(lds_raw, wm0 + j * 32, 0, lane);
+  for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(ringA, 0, wm0 + j * 32, 0, lane);
 #pragma unroll
-  for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(lds_raw + V2_OP_BYTES, wn0 + i * 32, 0, lane);
-  constexpr int NMF = TN * 4;            // MFMAs per half-slice per wave
-  constexpr int DSTRIDE = NMF / LPS;     // one copy every DSTRIDE MFMAs
-  static_assert(NMF % LPS == 0 && DSTRIDE >= 1, "copy interleave");
-  for (int kt = 0; kt < nk; ++kt) {
-    const unsigned char* sA = lds_raw + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
-    const unsigned char* sB = sA + V2_OP_BYTES;
+  for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(ringB, 0, wn0 + i * 32, 0, lane);
+
+  // one 32-deep slice; PAR = parity of kt (compile time: it fixes the ring stage bits and the copy schedule)
+  auto slice = [&](auto par_c, int kt) {
+    constexpr int PAR = decltype(par_c)::value;
+    const int stage = kt & (V2_STAGES - 1);
     // First half.  Order pinned with scheduling barriers: one MFMA first (its operands were read half a slice ago,
     // so the loop-top wait is free), then ONE fragment read of the second half's operands after each MFMA.  Spread
     // like this the reads never queue up in the LDS pipe (all eight waves reach this point together after the
@@ -208,42 +241,56 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
       if (idx >= 1 && idx - 1 < 4 + TN) {
         const int q = idx - 1;
         __builtin_amdgcn_sched_barrier(0);
-        if (q < 4) fa1[q] = v2_frag<A_KC>(sA, wm0 + q * 32, 1, lane);
-        else fb1[q - 4] = v2_frag<B_KC>(sB, wn0 + (q - 4) * 32, 1, lane);
+        if (q < 4) fa1[q] = v2_frag<A_KC>(ringA, stage, wm0 + q * 32, 1, lane);
+        else fb1[q - 4] = v2_frag<B_KC>(ringB, stage, wn0 + (q - 4) * 32, 1, lane);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     __builtin_amdgcn_sched_barrier(0);     // ... and the MFMAs ahead of the hand-over
-    // slice kt+1 must have landed; slices kt+2 and kt+3 stay in flight
-    wait_vmcnt<2 * LPS>();
+    wait_vmcnt<PAR == 0 ? W_EVEN : W_ODD>();   // this wave's copies of slice kt+1 have landed
     // this wave's LDS reads of slice kt (second-half operands, issued above) have returned ...
     __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
-    // ... so after this bare s_barrier (no memory fence: a fence would also wait for the slices in flight)
+    // ... so after this bare s_barrier (no memory fence: a fence would also wait for the copies in flight)
     // everyone's part of slice kt+1 is in LDS and nobody reads slice kt's stage any more.
     __builtin_amdgcn_s_barrier();
-    // Second half: after each MFMA one fragment read of slice kt+1's first-half operands, and every DSTRIDE MFMAs
-    // one copy of slice kt+4 into the stage slice kt just left.
-    const unsigned char* nA = lds_raw + ((kt + 1) & (V2_STAGES - 1)) * V2_STAGE_BYTES;
-    {
-      const uint32_t st = lds0 + (kt & (V2_STAGES - 1)) * V2_STAGE_BYTES;
-      const int knext = min(kt + V2_STAGES, nk - 1);
+    // Second half: after each MFMA one fragment read of slice kt+1's first-half operands, and the copies that
+    // re-arm the freed stage(s) spread evenly between the MFMAs.
+    const int nstage = (kt + 1) & (V2_STAGES - 1);
+    constexpr int NC = PAR == 0 ? EV : OD;                 // copies to issue in this half
+    const int pair_idx = min((kt + 3) >> 1, last_pair);    // PAR == 1: the pair two ahead of this slice's pair
+    const uint32_t pair_off = (uint32_t)(((kt + 3) >> 1) & 1) * (2 * V2_OP_BYTES);
+    const int slice_idx = min(kt + V2_STAGES, last_slice);
+    const uint32_t slice_off = (uint32_t)stage * V2_OP_BYTES;
 #pragma unroll
-      for (int idx = 0; idx < NMF; ++idx) {
-        acc[idx / 4][idx % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[idx / 4], fa1[idx % 4], acc[idx / 4][idx % 4], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (idx < 4 + TN) {
-          const int q = idx;
-          if (q < 4) fa0[q] = v2_frag<A_KC>(nA, wm0 + q * 32, 0, lane);
-          else fb0[q - 4] = v2_frag<B_KC>(nA + V2_OP_BYTES, wn0 + (q - 4) * 32, 0, lane);
-        }
-        if (idx % DSTRIDE == DSTRIDE - 1) {
-          const int c = idx / DSTRIDE;
-          if (c < QPW) sa.issue_one(st, wave_u, knext, c);
-          else sb.issue_one(st + V2_OP_BYTES, wave_u, knext, c - QPW);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+    for (int idx = 0; idx < NMF; ++idx) {
+      acc[idx / 4][idx % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[idx / 4], fa1[idx % 4], acc[idx / 4][idx % 4], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (idx < 4 + TN) {
+        const int q = idx;
+        if (q < 4) fa0[q] = v2_frag<A_KC>(ringA, nstage, wm0 + q * 32, 0, lane);
+        else fb0[q - 4] = v2_frag<B_KC>(ringB, nstage, wn0 + (q - 4) * 32, 0, lane);
       }
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        if ((c * NMF) / (NC > 0 ? NC : 1) != idx) continue;   // copy c goes after MFMA (c NMF) / NC
+        // order: A's pair, B's pair (odd slices only), then A's slice, B's slice
+        int r = c;
+        constexpr int KA = (PAR == 1 && A_KC) ? 2 * QPW : 0, KB = (PAR == 1 && B_KC) ? 2 * QPW : 0;
+        constexpr int MA = A_KC ? 0 : QPW;
+        if (r < KA) { sa.issue_one(ldsA + pair_off, wave_u, pair_idx, r); continue; }
+        r -= KA;
+        if (r < KB) { sb.issue_one(ldsB + pair_off, wave_u, pair_idx, r); continue; }
+        r -= KB;
+        if (r < MA) { sa.issue_one(ldsA + slice_off, wave_u, slice_idx, r); continue; }
+        r -= MA;
+        sb.issue_one(ldsB + slice_off, wave_u, slice_idx, r);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  for (int kt = 0; kt < nk; kt += 2) {
+    slice(std::integral_constant<int, 0>{}, kt);
+    slice(std::integral_constant<int, 1>{}, kt + 1);
   }
   // The ring is kept full to the end, so copies of the (clamped) last slice are still in flight here.  They were
   // issued from inline assembly, which the compiler's wait-count tracking does not see: wait for them explicitly
