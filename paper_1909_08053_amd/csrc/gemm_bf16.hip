@@ -41,13 +41,17 @@ bool gemm_use_v2(const GemmArgs& a) {
   return enabled && a.K % 64 == 0 && a.K >= 64;
 }
 
-int gemm_v2_waves() {
-  static int nw = -1;
-  if (nw < 0) {
+// Waves per workgroup of the 256 x 256 tile: 8 (two per SIMD) wherever a k-contiguous operand is involved; the
+// weight-gradient layout (both operands read through the transposing loads) measured ~3 % faster with 4 waves of
+// 128 x 128 (fewer LDS bytes per MFMA).  MLM_GEMM_WAVES=4|8 forces one variant.
+int gemm_v2_waves(bool a_kc, bool b_kc) {
+  static int forced = -1;
+  if (forced < 0) {
     const char* e = getenv("MLM_GEMM_WAVES");
-    nw = (e && atoi(e) == 4) ? 4 : 8;
+    forced = e ? (atoi(e) == 4 ? 4 : 8) : 0;
   }
-  return nw;
+  if (forced) return forced;
+  return (!a_kc && !b_kc) ? 4 : 8;
 }
 
 int gemm_bf16_ce_col_tiles(int M, int N, int K) {

@@ -414,7 +414,7 @@ __global__ __launch_bounds__(256) void gemm_v2_fixup_kernel(GemmArgs a, V2Plan p
 
 inline size_t v2_splitk_ws_bytes() { return (size_t)V2_CUS * V2_B * V2_B * sizeof(float); }   // 64 MB upper bound
 
-int gemm_v2_waves();   // 8 by default; MLM_GEMM_WAVES=4 selects the 4-wave variant
+int gemm_v2_waves(bool a_kc, bool b_kc);   // 4 or 8 waves per workgroup for this operand layout
 
 template <bool A_KC, bool B_KC, int EPI, int NW>
 hipError_t launch_gemm_bf16_v2_nw(const GemmArgs& a, float* splitk_ws, hipStream_t st) {
@@ -445,7 +445,7 @@ hipError_t launch_gemm_bf16_v2_nw(const GemmArgs& a, float* splitk_ws, hipStream
 
 template <bool A_KC, bool B_KC, int EPI>
 hipError_t launch_gemm_bf16_v2(const GemmArgs& a, float* splitk_ws, hipStream_t st) {
-  if (gemm_v2_waves() == 8) return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 8>(a, splitk_ws, st);
+  if (gemm_v2_waves(A_KC, B_KC) == 8) return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 8>(a, splitk_ws, st);
   return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 4>(a, splitk_ws, st);
 }
 
