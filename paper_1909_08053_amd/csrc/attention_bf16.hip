@@ -93,20 +93,27 @@ struct ATileSrc {
 // Workgroup = 128 queries of one (batch, head), 4 waves of 32 queries.  K and V tiles of 64 keys stream through a
 // three-stage LDS ring filled by DMA two tiles ahead; per tile: S^T = K Q^T (12 MFMAs at d = 96), online softmax in
 // registers, O^T += V^T P^T with V read through the transposing LDS loads (12 MFMAs).  One barrier per tile.
-#ifndef MLM_ANST
-#define MLM_ANST 3
-#endif
-constexpr int ANST = MLM_ANST;
+constexpr int ANST = 3;             // ring stages of the one-group kernel (dK/dV)
+// Forward and dQ run TWO wave groups (8 waves) per 128 owned rows: group g takes the streamed tiles 2j + g, each
+// group has its own DMA ring, and the groups' partial results are merged through LDS at the end.  That halves the
+// serial chain of the longest (causal) blocks and puts two waves on every SIMD, so one wave's exp2 / VALU work
+// overlaps the other's MFMAs.  Ring stages per group: 3, or 2 at d = 128 (LDS budget).
+constexpr int ANG = 2;
+constexpr int ANT2 = ANG * ANT;
+template <int D> constexpr int group_stages() { return D == 128 ? 2 : 3; }
 
 // (two waves per SIMD requested: with at most 256 registers per lane the MFMA accumulators live in ordinary VGPRs, so
 // the softmax arithmetic needs no accumulator-register moves)
 template <int D>
-__global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void attn_fwd_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(ANT2) void attn_fwd_bf16_kernel(AttnArgs a) {
   typedef ATile<D> TL;
   constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW;   // LPT: copies per tile and wave (K + V)
+  constexpr int NST = group_stages<D>();
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform values must be known as such: the mask test below is a scalar branch
+  // wave-uniform values must be known as such: the mask test below is a scalar branch
+  const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);    // wave group: 0 takes the even tiles, 1 the odd tiles
+  const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave inside its group: 32 queries
   const int wave_u = wave;
   const int nqb = (a.s + BQ - 1) / BQ;
   const int qb = nqb - 1 - blockIdx.x;            // longest (causal) blocks first
@@ -136,30 +143,33 @@ __global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void a
   const bf16* Vb = base + (2 * a.hl + hd) * D;
   ATileSrc<D> src;
   src.init(wave, lane);
-  const uint32_t lds0 = lds_offset_of(lds_raw);
+  unsigned char* ring = lds_raw + grp * (NST * STAGE);   // this group's ring
+  const uint32_t lds0 = lds_offset_of(ring);
+  const int njt = (nt + 1) / 2;                    // steps: group g handles tile 2 j + g in step j (if it exists)
   // The ring is always kept full: past the last tile the copies re-read tile nt - 1 into a stage nobody reads, so
   // the outstanding-copy count is the same in every iteration.
 #pragma unroll
-  for (int t = 0; t < ANST - 1; ++t) {
-    const int tc = min(t, nt - 1) * ATILE;
+  for (int t = 0; t < NST - 1; ++t) {
+    const int tc = min(2 * t + grp, nt - 1) * ATILE;
     src.issue(Kb, ld, tc, a.s, lds0 + t * STAGE, wave_u);
     src.issue(Vb, ld, tc, a.s, lds0 + t * STAGE + TL::BYTES, wave_u);
   }
   int stage = 0;
-  for (int t = 0; t < nt; ++t) {
+  for (int j = 0; j < njt; ++j) {
+    const int t = 2 * j + grp;
     const int k0 = t * ATILE;
-    wait_vmcnt<LPT*(ANST - 2)>();                  // this wave's copies of tile t have landed; tile t + 1 may be in flight
-    __builtin_amdgcn_s_barrier();                 // everyone's have; and everyone is done with tile t - 1
+    wait_vmcnt<LPT*(NST - 2)>();                   // this wave's copies of step j have landed; step j + 1 may be in flight
+    __builtin_amdgcn_s_barrier();                 // everyone's have; and everyone is done with step j - 1
     {
-      const int pst = stage == 0 ? ANST - 1 : stage - 1;          // stage of tile t - 1 = stage of tile t + 2
-      const int tc = min(t + ANST - 1, nt - 1) * ATILE;
+      const int pst = stage == 0 ? NST - 1 : stage - 1;           // stage of step j - 1 = stage of step j + NST - 1
+      const int tc = min(t + 2 * (NST - 1), nt - 1) * ATILE;
       src.issue(Kb, ld, tc, a.s, lds0 + pst * STAGE, wave_u);
       src.issue(Vb, ld, tc, a.s, lds0 + pst * STAGE + TL::BYTES, wave_u);
     }
-    const unsigned char* sK = lds_raw + stage * STAGE;
+    const unsigned char* sK = ring + stage * STAGE;
     const unsigned char* sV = sK + TL::BYTES;
-    stage = stage == ANST - 1 ? 0 : stage + 1;
-    if (a.causal && k0 > qw0 + 31) continue;     // tile entirely above this wave's diagonal (wave-uniform)
+    stage = stage == NST - 1 ? 0 : stage + 1;
+    if (t >= nt || (a.causal && k0 > qw0 + 31)) continue;   // no such tile / entirely above this wave's diagonal (wave-uniform)
     floatx16 sacc[2];
     float lsum_t = 0.f;
 #pragma unroll
@@ -219,6 +229,31 @@ __global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void a
     }
   }
   wait_vmcnt<0>();                                // copies still in flight target this workgroup's LDS
+  // merge the two groups' (m, l, O): group 1 parks its values in LDS ([wave][value][lane]: conflict-free)
+  __syncthreads();
+  {
+    constexpr int NR = D / 2 + 2;
+    float* park = reinterpret_cast<float*>(lds_raw) + (size_t)wave * NR * 64 + lane;
+    if (grp == 1) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) park[(dt * 16 + e) * 64] = o[dt][e];
+      park[(D / 2) * 64] = m;
+      park[(D / 2 + 1) * 64] = lsum;
+    }
+    __syncthreads();
+    if (grp == 1) return;
+    const float m1 = park[(D / 2) * 64], l1 = park[(D / 2 + 1) * 64];
+    const float mn = fmaxf(m, m1);                // group 0 always has tile 0: finite
+    const float c0 = __builtin_amdgcn_exp2f(m - mn), c1 = __builtin_amdgcn_exp2f(m1 - mn);
+    lsum = lsum * c0 + l1 * c1;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[dt][e] = o[dt][e] * c0 + park[(dt * 16 + e) * 64] * c1;
+    m = mn;
+  }
   lsum += __shfl_xor(lsum, 32, 64);
   if (qi < a.s) {
     const float inv = 1.0f / lsum;
@@ -242,12 +277,13 @@ __global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void a
 // loads.  delta_i = sum_d dO_id O_id is computed here from the rows the lanes already hold and stored for the
 // dK/dV kernel, which runs after this one.
 template <int D>
-__global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(ANT2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   typedef ATile<D> TL;
-  constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW;
+  constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW, NST = group_stages<D>();
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known wave-uniform: mask tests become scalar branches
+  const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);          // wave group: even / odd tiles
+  const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave inside its group (uniform: scalar mask branches)
   const int nqb = (a.s + BQ - 1) / BQ;
   const int qb = nqb - 1 - blockIdx.x;
   const int hd = blockIdx.y, bi = blockIdx.z;
@@ -274,7 +310,7 @@ __global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void a
     dl += __shfl_xor(dl, 32, 64);
   }
   const float lse2 = a.lse[((size_t)bi * a.hl + hd) * a.s + qc] * kLog2e;
-  if (lh == 0 && qi < a.s) {                      // for the dK/dV kernel: [0] delta, [1] log-sum-exp in log2 units
+  if (grp == 0 && lh == 0 && qi < a.s) {          // for the dK/dV kernel: [0] delta, [1] log-sum-exp in log2 units
     a.delta[((size_t)bi * a.hl + hd) * a.s + qi] = dl;
     a.delta[(size_t)a.b * a.hl * a.s + ((size_t)bi * a.hl + hd) * a.s + qi] = lse2;
   }
@@ -292,28 +328,31 @@ __global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void a
   const bf16* Vb = base + (2 * a.hl + hd) * D;
   ATileSrc<D> src;
   src.init(wave, lane);
-  const uint32_t lds0 = lds_offset_of(lds_raw);
+  unsigned char* ring = lds_raw + grp * (NST * STAGE);
+  const uint32_t lds0 = lds_offset_of(ring);
+  const int njt = (nt + 1) / 2;
 #pragma unroll
-  for (int t = 0; t < ANST - 1; ++t) {
-    const int tc = min(t, nt - 1) * ATILE;
+  for (int t = 0; t < NST - 1; ++t) {
+    const int tc = min(2 * t + grp, nt - 1) * ATILE;
     src.issue(Kb, ld, tc, a.s, lds0 + t * STAGE, wave);
     src.issue(Vb, ld, tc, a.s, lds0 + t * STAGE + TL::BYTES, wave);
   }
   int stage = 0;
-  for (int t = 0; t < nt; ++t) {
+  for (int j = 0; j < njt; ++j) {
+    const int t = 2 * j + grp;
     const int k0 = t * ATILE;
-    wait_vmcnt<LPT*(ANST - 2)>();
+    wait_vmcnt<LPT*(NST - 2)>();
     __builtin_amdgcn_s_barrier();
     {
-      const int pst = stage == 0 ? ANST - 1 : stage - 1;
-      const int tc = min(t + ANST - 1, nt - 1) * ATILE;
+      const int pst = stage == 0 ? NST - 1 : stage - 1;
+      const int tc = min(t + 2 * (NST - 1), nt - 1) * ATILE;
       src.issue(Kb, ld, tc, a.s, lds0 + pst * STAGE, wave);
       src.issue(Vb, ld, tc, a.s, lds0 + pst * STAGE + TL::BYTES, wave);
     }
-    const unsigned char* sK = lds_raw + stage * STAGE;
+    const unsigned char* sK = ring + stage * STAGE;
     const unsigned char* sV = sK + TL::BYTES;
-    stage = stage == ANST - 1 ? 0 : stage + 1;
-    if (a.causal && k0 > qw0 + 31) continue;
+    stage = stage == NST - 1 ? 0 : stage + 1;
+    if (t >= nt || (a.causal && k0 > qw0 + 31)) continue;
     floatx16 sacc[2], pacc[2];
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -352,6 +391,23 @@ __global__ __launch_bounds__(ANT) __attribute__((amdgpu_waves_per_eu(2))) void a
     }
   }
   wait_vmcnt<0>();
+  // dQ = group 0's sum + group 1's sum (group 1 parks its accumulators in LDS: [wave][value][lane])
+  __syncthreads();
+  {
+    float* park = reinterpret_cast<float*>(lds_raw) + (size_t)wave * (D / 2) * 64 + lane;
+    if (grp == 1) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) park[(dt * 16 + e) * 64] = dq[dt][e];
+    }
+    __syncthreads();
+    if (grp == 1) return;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dq[dt][e] += park[(dt * 16 + e) * 64];
+  }
   if (qi < a.s) {
     bf16* orow = (bf16*)a.dqkv + ((size_t)bi * a.s + qi) * ld + hd * D;
 #pragma unroll
@@ -511,28 +567,28 @@ bool attn_bf16_supported(int d) { return d == 64 || d == 96 || d == 128; }
 
 template <int D>
 static hipError_t launch_fwd_d(const AttnArgs& a, hipStream_t st) {
-  const size_t lds = (size_t)ANST * 2 * ATile<D>::BYTES;
+  const size_t lds = (size_t)ANG * group_stages<D>() * 2 * ATile<D>::BYTES;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds);
     if (e != hipSuccess) return e;
   }
   dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
-  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), grid, dim3(ANT), lds, st, a);
+  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), grid, dim3(ANT2), lds, st, a);
   return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_bwd_d(const AttnArgs& a, hipStream_t st) {
   dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
-  const size_t lds_q = (size_t)ANST * 2 * ATile<D>::BYTES;
+  const size_t lds_q = (size_t)ANG * group_stages<D>() * 2 * ATile<D>::BYTES;
   hipError_t e;
   if (lds_q > 64 * 1024) {
     e = hipFuncSetAttribute((const void*)attn_bwd_dq_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds_q);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), grid, dim3(ANT), lds_q, st, a);
+  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), grid, dim3(ANT2), lds_q, st, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t lds_kv = (size_t)ANST * (2 * ATile<D>::BYTES + 2 * ATILE * 4);
