@@ -32,7 +32,7 @@
  *     validated on the host before anything is launched, so a failing call has
  *     launched nothing.  No exceptions cross the ABI and there is no global state.
  *   - H, H/p, F/p, V/p and the head size must be multiples of 8 and pointers 16-byte
- *     aligned (MLM_E_ALIGN otherwise).  Supported head sizes: 64, 96, 128 (MLM_BF16);
+ *     aligned (MLM_E_ALIGN otherwise).  Supported head sizes: 64, 96, 128, 192 (MLM_BF16);
  *     any multiple of 16 up to 128 (MLM_F32).  H <= 4096 (MLM_BF16) / 2048 (MLM_F32).
  */
 #ifndef MLM_SHARD_H

@@ -40,11 +40,11 @@ struct ATile {
   static constexpr int U = D / 8;
   static constexpr int BYTES = ATILE * D * 2;
   static constexpr int QPW = U / ANW;              // 1-KB copies per wave and tile
-  static_assert(U % ANW == 0 && (U == 8 || U == 12 || U == 16), "head size");
+  static_assert(U % ANW == 0 && (U == 8 || U == 12 || U == 16 || U == 24), "head size");
   __device__ static __forceinline__ int sw(int row) {
     if (U == 16) return ((row & 3) << 2) | ((row >> 2) & 3);
     if (U == 12) return (row >> 2) & 3;
-    return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);   // U = 8 and U = 24: the row stride is 8 units mod 16
   }
   // operand with k along D: 8 consecutive elements [16 ks + 8 lh, +8) of row r0 + l32
   __device__ static __forceinline__ bf16x8 frag_kc(const unsigned char* tile, int r0, int ks, int lane) {
@@ -97,22 +97,23 @@ constexpr int ANST = 3;             // ring stages of the one-group kernel (dK/d
 // Forward and dQ run TWO wave groups (8 waves) per 128 owned rows: group g takes the streamed tiles 2j + g, each
 // group has its own DMA ring, and the groups' partial results are merged through LDS at the end.  That halves the
 // serial chain of the longest (causal) blocks and puts two waves on every SIMD, so one wave's exp2 / VALU work
-// overlaps the other's MFMAs.  Ring stages per group: 3, or 2 at d = 128 (LDS budget).
-constexpr int ANG = 2;
-constexpr int ANT2 = ANG * ANT;
+// overlaps the other's MFMAs.  Ring stages per group: 3, or 2 at d = 128 (LDS budget).  d = 192 keeps ONE group: its
+// 24-KB tiles leave no LDS for a second ring, and its accumulators need more than the 256 registers per lane that
+// two waves per SIMD allow.
+template <int D> constexpr int attn_groups() { return D > 128 ? 1 : 2; }
 template <int D> constexpr int group_stages() { return D == 128 ? 2 : 3; }
 
 // (two waves per SIMD requested: with at most 256 registers per lane the MFMA accumulators live in ordinary VGPRs, so
 // the softmax arithmetic needs no accumulator-register moves)
 template <int D>
-__global__ __launch_bounds__(ANT2) void attn_fwd_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(AttnArgs a) {
   typedef ATile<D> TL;
   constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW;   // LPT: copies per tile and wave (K + V)
-  constexpr int NST = group_stages<D>();
+  constexpr int NST = group_stages<D>(), NG = attn_groups<D>();
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
   // wave-uniform values must be known as such: the mask test below is a scalar branch
-  const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);    // wave group: 0 takes the even tiles, 1 the odd tiles
+  const int grp = NG == 1 ? 0 : __builtin_amdgcn_readfirstlane(tid >> 8);    // wave group: 0 takes the even tiles, 1 the odd tiles
   const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave inside its group: 32 queries
   const int wave_u = wave;
   const int nqb = (a.s + BQ - 1) / BQ;
@@ -145,24 +146,24 @@ __global__ __launch_bounds__(ANT2) void attn_fwd_bf16_kernel(AttnArgs a) {
   src.init(wave, lane);
   unsigned char* ring = lds_raw + grp * (NST * STAGE);   // this group's ring
   const uint32_t lds0 = lds_offset_of(ring);
-  const int njt = (nt + 1) / 2;                    // steps: group g handles tile 2 j + g in step j (if it exists)
+  const int njt = (nt + NG - 1) / NG;              // steps: group g handles tile NG j + g in step j (if it exists)
   // The ring is always kept full: past the last tile the copies re-read tile nt - 1 into a stage nobody reads, so
   // the outstanding-copy count is the same in every iteration.
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t) {
-    const int tc = min(2 * t + grp, nt - 1) * ATILE;
+    const int tc = min(NG * t + grp, nt - 1) * ATILE;
     src.issue(Kb, ld, tc, a.s, lds0 + t * STAGE, wave_u);
     src.issue(Vb, ld, tc, a.s, lds0 + t * STAGE + TL::BYTES, wave_u);
   }
   int stage = 0;
   for (int j = 0; j < njt; ++j) {
-    const int t = 2 * j + grp;
+    const int t = NG * j + grp;
     const int k0 = t * ATILE;
     wait_vmcnt<LPT*(NST - 2)>();                   // this wave's copies of step j have landed; step j + 1 may be in flight
     __builtin_amdgcn_s_barrier();                 // everyone's have; and everyone is done with step j - 1
     {
       const int pst = stage == 0 ? NST - 1 : stage - 1;           // stage of step j - 1 = stage of step j + NST - 1
-      const int tc = min(t + 2 * (NST - 1), nt - 1) * ATILE;
+      const int tc = min(t + NG * (NST - 1), nt - 1) * ATILE;
       src.issue(Kb, ld, tc, a.s, lds0 + pst * STAGE, wave_u);
       src.issue(Vb, ld, tc, a.s, lds0 + pst * STAGE + TL::BYTES, wave_u);
     }
@@ -230,8 +231,8 @@ __global__ __launch_bounds__(ANT2) void attn_fwd_bf16_kernel(AttnArgs a) {
   }
   wait_vmcnt<0>();                                // copies still in flight target this workgroup's LDS
   // merge the two groups' (m, l, O): group 1 parks its values in LDS ([wave][value][lane]: conflict-free)
-  __syncthreads();
-  {
+  if (NG == 2) {
+    __syncthreads();
     constexpr int NR = D / 2 + 2;
     float* park = reinterpret_cast<float*>(lds_raw) + (size_t)wave * NR * 64 + lane;
     if (grp == 1) {
@@ -277,12 +278,12 @@ __global__ __launch_bounds__(ANT2) void attn_fwd_bf16_kernel(AttnArgs a) {
 // loads.  delta_i = sum_d dO_id O_id is computed here from the rows the lanes already hold and stored for the
 // dK/dV kernel, which runs after this one.
 template <int D>
-__global__ __launch_bounds__(ANT2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   typedef ATile<D> TL;
-  constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW, NST = group_stages<D>();
+  constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW, NST = group_stages<D>(), NG = attn_groups<D>();
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
-  const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);          // wave group: even / odd tiles
+  const int grp = NG == 1 ? 0 : __builtin_amdgcn_readfirstlane(tid >> 8);   // wave group: even / odd tiles
   const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave inside its group (uniform: scalar mask branches)
   const int nqb = (a.s + BQ - 1) / BQ;
   const int qb = nqb - 1 - blockIdx.x;
@@ -330,22 +331,22 @@ __global__ __launch_bounds__(ANT2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   src.init(wave, lane);
   unsigned char* ring = lds_raw + grp * (NST * STAGE);
   const uint32_t lds0 = lds_offset_of(ring);
-  const int njt = (nt + 1) / 2;
+  const int njt = (nt + NG - 1) / NG;
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t) {
-    const int tc = min(2 * t + grp, nt - 1) * ATILE;
+    const int tc = min(NG * t + grp, nt - 1) * ATILE;
     src.issue(Kb, ld, tc, a.s, lds0 + t * STAGE, wave);
     src.issue(Vb, ld, tc, a.s, lds0 + t * STAGE + TL::BYTES, wave);
   }
   int stage = 0;
   for (int j = 0; j < njt; ++j) {
-    const int t = 2 * j + grp;
+    const int t = NG * j + grp;
     const int k0 = t * ATILE;
     wait_vmcnt<LPT*(NST - 2)>();
     __builtin_amdgcn_s_barrier();
     {
       const int pst = stage == 0 ? NST - 1 : stage - 1;
-      const int tc = min(t + 2 * (NST - 1), nt - 1) * ATILE;
+      const int tc = min(t + NG * (NST - 1), nt - 1) * ATILE;
       src.issue(Kb, ld, tc, a.s, lds0 + pst * STAGE, wave);
       src.issue(Vb, ld, tc, a.s, lds0 + pst * STAGE + TL::BYTES, wave);
     }
@@ -392,8 +393,8 @@ __global__ __launch_bounds__(ANT2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   }
   wait_vmcnt<0>();
   // dQ = group 0's sum + group 1's sum (group 1 parks its accumulators in LDS: [wave][value][lane])
-  __syncthreads();
-  {
+  if (NG == 2) {
+    __syncthreads();
     float* park = reinterpret_cast<float*>(lds_raw) + (size_t)wave * (D / 2) * 64 + lane;
     if (grp == 1) {
 #pragma unroll
@@ -563,32 +564,32 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ launchers
-bool attn_bf16_supported(int d) { return d == 64 || d == 96 || d == 128; }
+bool attn_bf16_supported(int d) { return d == 64 || d == 96 || d == 128 || d == 192; }
 
 template <int D>
 static hipError_t launch_fwd_d(const AttnArgs& a, hipStream_t st) {
-  const size_t lds = (size_t)ANG * group_stages<D>() * 2 * ATile<D>::BYTES;
+  const size_t lds = (size_t)attn_groups<D>() * group_stages<D>() * 2 * ATile<D>::BYTES;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds);
     if (e != hipSuccess) return e;
   }
   dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
-  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), grid, dim3(ANT2), lds, st, a);
+  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), grid, dim3(attn_groups<D>() * ANT), lds, st, a);
   return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_bwd_d(const AttnArgs& a, hipStream_t st) {
   dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
-  const size_t lds_q = (size_t)ANG * group_stages<D>() * 2 * ATile<D>::BYTES;
+  const size_t lds_q = (size_t)attn_groups<D>() * group_stages<D>() * 2 * ATile<D>::BYTES;
   hipError_t e;
   if (lds_q > 64 * 1024) {
     e = hipFuncSetAttribute((const void*)attn_bwd_dq_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds_q);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), grid, dim3(ANT2), lds_q, st, a);
+  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), grid, dim3(attn_groups<D>() * ANT), lds_q, st, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t lds_kv = (size_t)ANST * (2 * ATile<D>::BYTES + 2 * ATILE * 4);
@@ -606,6 +607,7 @@ hipError_t launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t st) {
     case 64: return launch_fwd_d<64>(a, st);
     case 96: return launch_fwd_d<96>(a, st);
     case 128: return launch_fwd_d<128>(a, st);
+    case 192: return launch_fwd_d<192>(a, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -615,6 +617,7 @@ hipError_t launch_attn_bwd_bf16(const AttnArgs& a, hipStream_t st) {
     case 64: return launch_bwd_d<64>(a, st);
     case 96: return launch_bwd_d<96>(a, st);
     case 128: return launch_bwd_d<128>(a, st);
+    case 192: return launch_bwd_d<192>(a, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -1,0 +1,81 @@
+#!/usr/bin/env python3
+"""Single-GPU shape sweeps of the layer-shard path (one shard, forward + backward, bf16).
+
+    python -m paper_1909_08053_amd.sweep [--sweep heads|strong_1p2b|all] [--steps K] [--warmup W]
+
+"heads" follows the paper's Table 7 (8.3B configuration, 8-way model parallel, 16 / 24 / 32 heads: head size
+192 / 128 / 96); "strong_1p2b" follows Table 8 (1.2B configuration split 1 / 2 / 4 / 8 ways at batch 8).  Both are
+run here as the per-GPU COMPUTE of one shard (shard 0) with synthetic inputs; the all-reduces the paper's numbers
+include are not part of this build, so the printed ratios are an upper bound on what those tables measure.
+Prints one line per configuration and a short ratio summary.
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+
+
+def shard_flops(cfg):
+    """Model FLOPs of one shard's forward + backward (GEMM = 2MKN, backward = 2 x forward, causal attention at its
+    algorithmic half)."""
+    T, H, d, p = cfg.T, cfg.H, cfg.H // cfg.h, cfg.p
+    hl, Fl, Vl = cfg.h // p, cfg.F // p, cfg.V // p
+    Hl = hl * d
+    gemm = lambda M, K, N: 2.0 * M * K * N
+    att = 2.0 * (2.0 * cfg.b * hl * cfg.s * cfg.s * d) * (0.5 if cfg.causal else 1.0)
+    return 3.0 * (gemm(T, H, 3 * Hl) + gemm(T, Hl, H) + gemm(T, H, Fl) + gemm(T, Fl, H) + gemm(T, H, Vl) + att)
+
+
+def time_config(cfg, steps, warmup, dev="cuda:0"):
+    import torch
+    from .pipeline import LayerShards
+    L = LayerShards(cfg, [0], dev, store_logits=True)
+    L.load_random(seed=cfg.seed)
+    for _ in range(warmup):
+        L.step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        L.step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    del L
+    torch.cuda.empty_cache()
+    return ms
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "all"])
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    args = ap.parse_args()
+    import torch
+    from . import binding as B
+    from . import synth
+    if not torch.cuda.is_available():
+        sys.exit("sweep: no GPU visible")
+    B.lib()
+    names = ["heads", "strong_1p2b"] if args.sweep == "all" else [args.sweep]
+    for sw in names:
+        print(f"# sweep {sw}")
+        rows = []
+        for cfg in synth.SWEEPS[sw]:
+            ms = time_config(cfg, args.steps, args.warmup)
+            fl = shard_flops(cfg)
+            rows.append((cfg, ms, fl))
+            print(f"{cfg.name:16s} p={cfg.p} heads={cfg.h:2d} d={cfg.H // cfg.h:3d} local_heads={cfg.h // cfg.p:2d}  "
+                  f"{ms * 1e3:9.1f} us/step  {fl / 1e12:6.3f} model TFLOP  {fl / (ms * 1e-3) / 1e12:7.1f} TFLOP/s", flush=True)
+        if sw == "heads":
+            ref = rows[0][1]
+            print("  step time relative to 16 heads: " + ", ".join(f"{c.h} heads {ms / ref:.3f}" for c, ms, _ in rows))
+        else:
+            ref = rows[0][1]
+            print("  compute-only speed-up of one shard over p = 1: " +
+                  ", ".join(f"p={c.p} {ref / ms:.2f}x" for c, ms, _ in rows))
+
+
+if __name__ == "__main__":
+    main()

@@ -13,7 +13,7 @@ E, targets, key lengths, loss mask) so that one seed always means one input.
 from __future__ import annotations
 
 from dataclasses import dataclass, replace
-from typing import Dict, Optional
+from typing import Dict, List, Optional
 
 import numpy as np
 
@@ -59,6 +59,23 @@ CONFIGS: Dict[str, LayerConfig] = {
     "bert_3p9b": LayerConfig("bert_3p9b", b=8, s=512, H=2560, h=40, F=10240, V=30592, p=4,
                              causal=False, dtype="bf16", seed=4, masked_lm=True),
 }
+
+
+def _variant(base: str, name: str, **kw) -> LayerConfig:
+    return replace(CONFIGS[base], name=name, **kw)
+
+
+# Shape sweeps of the paper's scaling studies, as single-GPU shard workloads:
+#  * "heads": the 8.3B configuration, 8-way model parallel, with 16 / 24 / 32 attention heads (Table 7): head sizes
+#    192 / 128 / 96, i.e. 2 / 3 / 4 local heads per GPU;
+#  * "strong_1p2b": the 1.2B configuration split 1 / 2 / 4 / 8 ways at fixed batch 8 (Table 8): the per-GPU share of
+#    the work shrinks with p.
+SWEEPS: Dict[str, List[LayerConfig]] = {
+    "heads": [_variant("gpt2_8p3b", "gpt2_8p3b_h16", h=16), _variant("gpt2_8p3b", "gpt2_8p3b_h24", h=24),
+              CONFIGS["gpt2_8p3b"]],
+    "strong_1p2b": [CONFIGS["gpt2_1p2b"]] + [_variant("gpt2_1p2b", f"gpt2_1p2b_p{p}", p=p) for p in (2, 4, 8)],
+}
+SWEEP_CONFIGS: Dict[str, LayerConfig] = {c.name: c for cs in SWEEPS.values() for c in cs}
 
 
 def small_config(name: str = "small", **kw) -> LayerConfig:

@@ -201,6 +201,8 @@ BF16_CASES = {
     "d64_causal": (dict(b=2, s=200, H=128, h=2, F=512, V=640, p=2), True, 3.0),
     "d96_causal": (dict(b=2, s=328, H=192, h=2, F=768, V=1088, p=2), True, 3.0),
     "d128_causal_p1": (dict(b=1, s=264, H=256, h=2, F=1024, V=520, p=1), True, 3.0),
+    "d192_causal": (dict(b=2, s=200, H=384, h=2, F=1536, V=640, p=2), True, 3.0),
+    "d192_bert": (dict(b=2, s=136, H=768, h=4, F=1536, V=512, p=2, causal=False, masked_lm=True), True, 3.0),
     "d64_bert": (dict(b=3, s=176, H=256, h=4, F=1024, V=960, p=4, causal=False, masked_lm=True), True, 3.0),
     "d96_bert_recompute": (dict(b=2, s=136, H=384, h=4, F=1536, V=512, p=2, causal=False, masked_lm=True), False, 3.0),
     "d64_noln_erf": (dict(b=2, s=128, H=128, h=2, F=512, V=256, p=1, final_ln=False, gelu_tanh=False), True, 3.0),
@@ -260,6 +262,15 @@ def test_full_size_configs_all_shards(name):
     errs = run_layer_parity(cfg, nonzero_bias=False, random_ln=False, store_combined=False)
     worst = sorted(errs, key=lambda e: -e[1])[:6]
     print(name, "worst max-norm relative errors:", worst)
+
+
+@pytest.mark.parametrize("name", ["gpt2_8p3b_h16", "gpt2_8p3b_h24", "gpt2_1p2b_p8"])
+def test_full_size_sweep_configs_all_shards(name):
+    """The shape-sweep workloads (head size 192 and 128 at the 8.3B shape; the 1.2B shape split 8 ways), all shards,
+    same launch configuration as the sweep runner, against the fp64 oracle."""
+    cfg = synth.SWEEP_CONFIGS[name]
+    errs = run_layer_parity(cfg, nonzero_bias=False, random_ln=False, store_combined=False)
+    print(name, "worst max-norm relative errors:", sorted(errs, key=lambda e: -e[1])[:6])
 
 
 def test_full_size_step_is_bit_reproducible():
