@@ -149,140 +149,146 @@ hipError_t launch_combine_layernorm_fwd(int dtype, int T, int H, float eps, cons
 }
 
 // ------------------------------------------------------------------------------ layer norm backward
-// Block = 4 waves, kLnBwdRowsPerBlock rows, one wave per row with the next row's vectors prefetched while the
-// current row is reduced.  Each lane keeps the dgamma/dbeta partial sums of the columns it owns; at the end the
-// waves' partials meet in LDS ([wave][value][lane], conflict-free) and are summed per column in wave order
-// (deterministic); the block partial goes to the workspace and reduce_cols_kernel sums the block partials.
-constexpr int kLnBwdWaves = 4;
-
+// Block = one wave per 64 vectors of a row (6 waves for 3072 bf16 columns), kLnBwdRowsPerBlock rows in batches of
+// kLnBwdBatch.  A lane owns ONE 16-byte vector of columns in every row, so its dgamma / dbeta (/ dx column-sum)
+// partials are a handful of registers and several waves fit on a SIMD (a wave-per-row layout needs the partials of
+// the whole row per lane: ~150 registers, one wave per SIMD, and ran at half the HBM rate).  The row statistics
+// s1 = mean(dy gamma), s2 = mean(dy gamma xhat) need the whole row: every wave reduces its slab, the per-wave
+// partials meet in LDS and are added in wave order (deterministic); one barrier per batch (the exchange buffer
+// alternates).  The next batch is prefetched while the current one is worked on.  The block's column partials go
+// to the workspace and reduce_cols_kernel sums them over the blocks.
+//
 // FUSED: dy is formed on the fly as the sum of n partial tensors (stored to dy_out if that is not NULL).
 // SUM: the column sums of dx (the bias gradient of the layer that produced this layer norm's input) are accumulated
 // as a third per-column partial next to dgamma / dbeta.
-template <typename T, int NV, bool FUSED, bool SUM>
-__global__ __launch_bounds__(kLnBwdWaves * 64) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy,
-                                                                  const T* __restrict__ x, const T* __restrict__ gamma,
-                                                                  const float* __restrict__ mean,
-                                                                  const float* __restrict__ rstd, const T* residual,
-                                                                  T* dx, float* __restrict__ ws, PartialPtrs ptrs, int n,
-                                                                  T* dy_out) {
-  constexpr int VN = Vec16<T>::N;
-  constexpr int SLOTS = NV * VN * 64;
-  extern __shared__ float red[];   // [kLnBwdWaves][SLOTS]
+constexpr int kLnBwdBatch = 4;
+
+template <typename T, bool FUSED, bool SUM>
+__global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy, const T* __restrict__ x,
+                                                     const T* __restrict__ gamma, const float* __restrict__ mean,
+                                                     const float* __restrict__ rstd, const T* residual, T* dx,
+                                                     float* __restrict__ ws, PartialPtrs ptrs, int n, T* dy_out) {
+  constexpr int VN = Vec16<T>::N, RB = kLnBwdBatch, NP = SUM ? 3 : 2;
+  __shared__ float red[2][RB][2][8];
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int nvec = H / VN;
+  const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  const int idx = threadIdx.x;                      // this lane's vector of every row
+  const bool active = idx < H / VN;
+  const size_t col0 = (size_t)idx * VN;
   const float invH = 1.0f / (float)H;
-  constexpr int NP = SUM ? 3 : 2;
-  float dg[NV][VN], db[NV][VN], dsum[SUM ? NV : 1][VN];
-  float gam[NV][VN];
-#pragma unroll
-  for (int i = 0; i < NV; ++i) {
+  float gam[VN], dg[VN], db[VN], dsum[VN];
+  {
     Vec16<T> g;
-    if (lane + 64 * i < nvec) g.load(gamma + (size_t)(lane + 64 * i) * VN);
+    if (active) g.load(gamma + col0);
 #pragma unroll
     for (int e = 0; e < VN; ++e) {
-      gam[i][e] = (lane + 64 * i < nvec) ? g.get(e) : 0.f;
-      dg[i][e] = 0.f;
-      db[i][e] = 0.f;
-      if (SUM) dsum[i][e] = 0.f;
+      gam[e] = active ? g.get(e) : 0.f;
+      dg[e] = 0.f; db[e] = 0.f; dsum[e] = 0.f;
     }
   }
   const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
   const int row_end = min(rows, row0 + kLnBwdRowsPerBlock);
-  Vec16<T> vdy[NV], vx[NV], vres[NV], ndy[NV], nx[NV], nres[NV];
-  int row = row0 + wave;
-  if (row < row_end) {
-    if (FUSED) combine_row<T, NV>(ptrs, n, nullptr, nullptr, (size_t)row * H, lane, nvec, ndy);
+  Vec16<T> vdy[RB], vx[RB], vres[RB], ndy[RB], nx[RB], nres[RB];
+  auto load_batch = [&](int r0) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int idx = lane + 64 * i;
-      if (idx < nvec) {
+    for (int j = 0; j < RB; ++j) {
+      const int r = r0 + j;
+      if (r < row_end && active) {
+        const size_t off = (size_t)r * H + col0;
         if (FUSED) {
-          if (dy_out) ndy[i].store(dy_out + (size_t)row * H + (size_t)idx * VN);
-        } else {
-          ndy[i].load(dy + (size_t)row * H + (size_t)idx * VN);
-        }
-        nx[i].load(x + (size_t)row * H + (size_t)idx * VN);
-        if (residual) nres[i].load(residual + (size_t)row * H + (size_t)idx * VN);
-      }
-    }
-  }
-  for (; row < row_end; row += kLnBwdWaves) {
+          if (n == 1) {
+            ndy[j].load((const T*)ptrs.p[0] + off);
+          } else {                                   // fixed order k = 0..n-1, fp32, rounded once
+            float acc[VN];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) { vdy[i] = ndy[i]; vx[i] = nx[i]; vres[i] = nres[i]; }
-    const int nrow = row + kLnBwdWaves;
-    if (nrow < row_end) {
-      if (FUSED) combine_row<T, NV>(ptrs, n, nullptr, nullptr, (size_t)nrow * H, lane, nvec, ndy);
+            for (int e = 0; e < VN; ++e) acc[e] = 0.f;
+            for (int k = 0; k < n; ++k) {
+              Vec16<T> t;
+              t.load((const T*)ptrs.p[k] + off);
 #pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int idx = lane + 64 * i;
-        if (idx < nvec) {
-          if (FUSED) {
-            if (dy_out) ndy[i].store(dy_out + (size_t)nrow * H + (size_t)idx * VN);
-          } else {
-            ndy[i].load(dy + (size_t)nrow * H + (size_t)idx * VN);
+              for (int e = 0; e < VN; ++e) acc[e] += t.get(e);
+            }
+#pragma unroll
+            for (int e = 0; e < VN; ++e) ndy[j].set(e, acc[e]);
           }
-          nx[i].load(x + (size_t)nrow * H + (size_t)idx * VN);
-          if (residual) nres[i].load(residual + (size_t)nrow * H + (size_t)idx * VN);
+          if (dy_out) ndy[j].store(dy_out + off);
+        } else {
+          ndy[j].load(dy + off);
         }
+        nx[j].load(x + off);
+        if (residual) nres[j].load(residual + off);
       }
     }
-    const float mu = mean[row], rs = rstd[row];
-    float s1 = 0.f, s2 = 0.f;
-    float xh[NV][VN];
+  };
+  load_batch(row0);
+  int it = 0;
+  for (int r0 = row0; r0 < row_end; r0 += RB, ++it) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      if (lane + 64 * i < nvec) {
+    for (int j = 0; j < RB; ++j) { vdy[j] = ndy[j]; vx[j] = nx[j]; vres[j] = nres[j]; }
+    if (r0 + RB < row_end) load_batch(r0 + RB);
+    float mu[RB], rs[RB], ps1[RB], ps2[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+      const int r = min(r0 + j, row_end - 1);
+      mu[j] = mean[r];
+      rs[j] = rstd[r];
+      ps1[j] = 0.f;
+      ps2[j] = 0.f;
+      if (r0 + j < row_end && active) {
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
-          xh[i][e] = (vx[i].get(e) - mu) * rs;
-          const float d = vdy[i].get(e);
-          const float g = d * gam[i][e];
-          s1 += g;
-          s2 = fmaf(g, xh[i][e], s2);
-          dg[i][e] = fmaf(d, xh[i][e], dg[i][e]);
-          db[i][e] += d;
+          const float xh = (vx[j].get(e) - mu[j]) * rs[j];
+          const float g = vdy[j].get(e) * gam[e];
+          ps1[j] += g;
+          ps2[j] = fmaf(g, xh, ps2[j]);
         }
       }
     }
-    s1 = wave_sum(s1) * invH;
-    s2 = wave_sum(s2) * invH;
+    // 2 RB independent butterflies: their shuffles overlap
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int idx = lane + 64 * i;
-      if (idx < nvec) {
+    for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+      for (int j = 0; j < RB; ++j) {
+        ps1[j] += __shfl_xor(ps1[j], o, 64);
+        ps2[j] += __shfl_xor(ps2[j], o, 64);
+      }
+    if (lane == 0) {
+#pragma unroll
+      for (int j = 0; j < RB; ++j) { red[it & 1][j][0][wave] = ps1[j]; red[it & 1][j][1][wave] = ps2[j]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+      if (r0 + j >= row_end) break;                  // block-uniform
+      float s1 = 0.f, s2 = 0.f;
+      for (int w = 0; w < nwaves; ++w) { s1 += red[it & 1][j][0][w]; s2 += red[it & 1][j][1][w]; }
+      s1 *= invH;
+      s2 *= invH;
+      if (active) {
         Vec16<T> o;
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
-          const float g = vdy[i].get(e) * gam[i][e];
-          float v = rs * (g - s1 - xh[i][e] * s2);
-          if (residual) v += vres[i].get(e);
+          const float xh = (vx[j].get(e) - mu[j]) * rs[j];
+          const float d = vdy[j].get(e);
+          dg[e] = fmaf(d, xh, dg[e]);
+          db[e] += d;
+          float v = rs[j] * (d * gam[e] - s1 - xh * s2);
+          if (residual) v += vres[j].get(e);
           o.set(e, v);
-          if (SUM) dsum[i][e] += o.get(e);     // the stored (rounded) value, as a separate column sum would read it
+          if (SUM) dsum[e] += o.get(e);              // the stored (rounded) value, as a separate column sum would read it
         }
-        o.store(dx + (size_t)row * H + (size_t)idx * VN);
+        o.store(dx + (size_t)(r0 + j) * H + col0);
       }
     }
   }
-  float* out = ws + (size_t)blockIdx.x * NP * H;
+  if (active) {
+    float* out = ws + (size_t)blockIdx.x * NP * H + col0;
 #pragma unroll
-  for (int part = 0; part < NP; ++part) {
-    float* mine = red + (size_t)wave * SLOTS;
-#pragma unroll
-    for (int i = 0; i < NV; ++i)
-#pragma unroll
-      for (int e = 0; e < VN; ++e)
-        mine[(i * VN + e) * 64 + lane] = part == 0 ? dg[i][e] : (part == 1 ? db[i][e] : dsum[SUM ? i : 0][e]);
-    __syncthreads();
-    for (int col = threadIdx.x; col < H; col += kLnBwdWaves * 64) {
-      const int idx = col / VN, e = col % VN;
-      const int slot = ((idx >> 6) * VN + e) * 64 + (idx & 63);
-      float t = 0.f;
-#pragma unroll
-      for (int w = 0; w < kLnBwdWaves; ++w) t += red[(size_t)w * SLOTS + slot];
-      out[part * H + col] = t;
+    for (int e = 0; e < VN; ++e) {
+      out[e] = dg[e];
+      out[H + e] = db[e];
+      if (SUM) out[2 * H + e] = dsum[e];
     }
-    __syncthreads();
   }
 }
 
@@ -322,35 +328,20 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
                                   void* dgamma, void* dbeta, float* ws, const PartialPtrs* pp, int n, void* dy_out,
                                   void* dx_colsum, hipStream_t st) {
   constexpr int VN = Vec16<T>::N;
-  const int nv = (H / VN + 63) / 64;
+  const int nwaves = (H / VN + 63) / 64;
+  if (nwaves < 1 || nwaves > 8) return hipErrorInvalidValue;
   const int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
-  dim3 grid(nblk), block(kLnBwdWaves * 64);
-  const size_t lds = (size_t)kLnBwdWaves * nv * VN * 64 * sizeof(float);
   PartialPtrs none;
   for (int k = 0; k < kMaxPartials; ++k) none.p[k] = nullptr;
   const int np = (pp && dx_colsum) ? 3 : 2;
-#define MLM_LN_BWD_GO(NVV, F, S)                                                                           \
-  {                                                                                                        \
-    if (lds > 64 * 1024) {                                                                                 \
-      hipError_t ea = hipFuncSetAttribute((const void*)ln_bwd_kernel<T, NVV, F, S>,                        \
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
-      if (ea != hipSuccess) return ea;                                                                     \
-    }                                                                                                      \
-    hipLaunchKernelGGL((ln_bwd_kernel<T, NVV, F, S>), grid, block, lds, st, rows, H, (const T*)dy,         \
-                       (const T*)x, (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws,           \
-                       pp ? *pp : none, n, (T*)dy_out);                                                    \
-  }
-#define MLM_LN_BWD(NVV)                                                                                    \
-  case NVV: {                                                                                              \
-    if (pp && dx_colsum) MLM_LN_BWD_GO(NVV, true, true)                                                    \
-    else if (pp) MLM_LN_BWD_GO(NVV, true, false)                                                           \
-    else MLM_LN_BWD_GO(NVV, false, false)                                                                  \
-  } break;
-  switch (nv) {
-    MLM_LN_BWD(1) MLM_LN_BWD(2) MLM_LN_BWD(3) MLM_LN_BWD(4) MLM_LN_BWD(5) MLM_LN_BWD(6) MLM_LN_BWD(7) MLM_LN_BWD(8)
-    default: return hipErrorInvalidValue;
-  }
-#undef MLM_LN_BWD
+  dim3 grid(nblk), block(nwaves * 64);
+#define MLM_LN_BWD_GO(F, S)                                                                                 \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, F, S>), grid, block, 0, st, rows, H, (const T*)dy, (const T*)x,      \
+                     (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws, pp ? *pp : none, n,       \
+                     (T*)dy_out)
+  if (pp && dx_colsum) MLM_LN_BWD_GO(true, true);
+  else if (pp) MLM_LN_BWD_GO(true, false);
+  else MLM_LN_BWD_GO(false, false);
 #undef MLM_LN_BWD_GO
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
