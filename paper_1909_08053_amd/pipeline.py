@@ -212,8 +212,40 @@ class LayerShards:
                                 a["db1"], ws)
         self._dx2 = dx2
 
-    def step(self):
+    # Activation recomputation (the paper checkpoints activations after every transformer layer, Section 5): only the
+    # layer input X is kept; everything the layer's backward reads is produced again by re-running the layer's forward
+    # calls (not the final layer norm / loss, which belong to the model's head) right before the backward.
+    LAYER_ACTIVATIONS = ("U", "mu1", "rstd1", "X1", "U2", "mu2", "rstd2")
+    SHARD_ACTIVATIONS = ("qkv", "ctx", "lse", "attn_partial", "g", "y", "mlp_partial")
+
+    def drop_layer_activations(self):
+        """Poison what a checkpointing run would not have kept (tests use it to prove the backward reads recomputed
+        values only)."""
+        for k in self.LAYER_ACTIVATIONS:
+            self.act[k].fill_(float("nan"))
+        for r in self.shards:
+            for k in self.SHARD_ACTIVATIONS:
+                self.sh[r][k].fill_(float("nan"))
+
+    def recompute_layer(self):
+        cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
+        d0 = self.dims[self.shards[0]]
+        kl = rep["key_len"] if cfg.masked_lm else None
+        B.mlm_layernorm_fwd(d0, rep["X"], rep["g1"], rep["b1"], a["U"], a["mu1"], a["rstd1"])
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_attn_shard_fwd(self.dims[r], a["U"], w["Wqkv"], w["bqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
+                                 s["attn_partial"], ws)
+        B.mlm_combine_layernorm_fwd(d0, [self.sh[r]["attn_partial"] for r in self.shards], rep["bo"], rep["X"],
+                                    a["X1"], rep["g2"], rep["b2"], a["U2"], a["mu2"], a["rstd2"])
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_mlp_shard_fwd(self.dims[r], a["U2"], w["A"], w["a"], w["B"], s["g"], s["y"], s["mlp_partial"], ws)
+
+    def step(self, recompute: bool = False):
         self.forward()
+        if recompute:
+            self.recompute_layer()
         self.backward()
 
     # ------------------------------------------------------------------ results (host copies, fp64)

@@ -3,7 +3,7 @@
 
     python -m paper_1909_08053_amd.sweep [--sweep heads|strong_1p2b|all] [--steps K] [--warmup W]
 
-"heads" follows the paper's Table 7 (8.3B configuration, 8-way model parallel, 16 / 24 / 32 heads: head size
+"table1" follows Table 1 (1.2B / 2.5B / 4.2B / 8.3B on 1 / 2 / 4 / 8 GPUs); "heads" follows the paper's Table 7 (8.3B configuration, 8-way model parallel, 16 / 24 / 32 heads: head size
 192 / 128 / 96); "strong_1p2b" follows Table 8 (1.2B configuration split 1 / 2 / 4 / 8 ways at batch 8).  Both are
 run here as the per-GPU COMPUTE of one shard (shard 0) with synthetic inputs; the all-reduces the paper's numbers
 include are not part of this build, so the printed ratios are an upper bound on what those tables measure.
@@ -26,18 +26,18 @@ def shard_flops(cfg):
     return 3.0 * (gemm(T, H, 3 * Hl) + gemm(T, Hl, H) + gemm(T, H, Fl) + gemm(T, Fl, H) + gemm(T, H, Vl) + att)
 
 
-def time_config(cfg, steps, warmup, dev="cuda:0"):
+def time_config(cfg, steps, warmup, dev="cuda:0", recompute=False):
     import torch
     from .pipeline import LayerShards
     L = LayerShards(cfg, [0], dev, store_logits=True)
     L.load_random(seed=cfg.seed)
     for _ in range(warmup):
-        L.step()
+        L.step(recompute)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(steps):
-        L.step()
+        L.step(recompute)
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
@@ -48,7 +48,9 @@ def time_config(cfg, steps, warmup, dev="cuda:0"):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "all"])
+    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "all"])
+    ap.add_argument("--recompute", action="store_true",
+                    help="checkpointed variant: re-run the layer's forward before its backward (activation recomputation)")
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     args = ap.parse_args()
@@ -58,12 +60,12 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("sweep: no GPU visible")
     B.lib()
-    names = ["heads", "strong_1p2b"] if args.sweep == "all" else [args.sweep]
+    names = ["heads", "strong_1p2b", "table1"] if args.sweep == "all" else [args.sweep]
     for sw in names:
-        print(f"# sweep {sw}")
+        print(f"# sweep {sw}" + (" (activation recomputation: layer forward run twice)" if args.recompute else ""))
         rows = []
         for cfg in synth.SWEEPS[sw]:
-            ms = time_config(cfg, args.steps, args.warmup)
+            ms = time_config(cfg, args.steps, args.warmup, recompute=args.recompute)
             fl = shard_flops(cfg)
             rows.append((cfg, ms, fl))
             print(f"{cfg.name:16s} p={cfg.p} heads={cfg.h:2d} d={cfg.H // cfg.h:3d} local_heads={cfg.h // cfg.p:2d}  "
@@ -71,6 +73,10 @@ def main():
         if sw == "heads":
             ref = rows[0][1]
             print("  step time relative to 16 heads: " + ", ".join(f"{c.h} heads {ms / ref:.3f}" for c, ms, _ in rows))
+        elif sw == "table1":
+            ref = rows[0][2] / rows[0][1]
+            print("  per-GPU model throughput relative to the 1-GPU row: " +
+                  ", ".join(f"p={c.p} {(fl / ms) / ref:.3f}" for c, ms, fl in rows))
         else:
             ref = rows[0][1]
             print("  compute-only speed-up of one shard over p = 1: " +

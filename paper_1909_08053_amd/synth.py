@@ -69,11 +69,15 @@ def _variant(base: str, name: str, **kw) -> LayerConfig:
 #  * "heads": the 8.3B configuration, 8-way model parallel, with 16 / 24 / 32 attention heads (Table 7): head sizes
 #    192 / 128 / 96, i.e. 2 / 3 / 4 local heads per GPU;
 #  * "strong_1p2b": the 1.2B configuration split 1 / 2 / 4 / 8 ways at fixed batch 8 (Table 8): the per-GPU share of
-#    the work shrinks with p.
+#    the work shrinks with p;
+#  * "table1": the four weak-scaling rows of Table 1 (1.2B on 1 GPU ... 8.3B on 8 GPUs): the per-GPU share stays about
+#    constant.
 SWEEPS: Dict[str, List[LayerConfig]] = {
     "heads": [_variant("gpt2_8p3b", "gpt2_8p3b_h16", h=16), _variant("gpt2_8p3b", "gpt2_8p3b_h24", h=24),
               CONFIGS["gpt2_8p3b"]],
     "strong_1p2b": [CONFIGS["gpt2_1p2b"]] + [_variant("gpt2_1p2b", f"gpt2_1p2b_p{p}", p=p) for p in (2, 4, 8)],
+    "table1": [CONFIGS["gpt2_1p2b"], CONFIGS["gpt2_2p5b"],
+               _variant("gpt2_8p3b", "gpt2_4p2b", H=2304, h=24, F=9216, p=4, seed=5), CONFIGS["gpt2_8p3b"]],
 }
 SWEEP_CONFIGS: Dict[str, LayerConfig] = {c.name: c for cs in SWEEPS.values() for c in cs}
 

@@ -264,7 +264,7 @@ def test_full_size_configs_all_shards(name):
     print(name, "worst max-norm relative errors:", worst)
 
 
-@pytest.mark.parametrize("name", ["gpt2_8p3b_h16", "gpt2_8p3b_h24", "gpt2_1p2b_p8"])
+@pytest.mark.parametrize("name", ["gpt2_8p3b_h16", "gpt2_8p3b_h24", "gpt2_1p2b_p8", "gpt2_4p2b"])
 def test_full_size_sweep_configs_all_shards(name):
     """The shape-sweep workloads (head size 192 and 128 at the 8.3B shape; the 1.2B shape split 8 ways), all shards,
     same launch configuration as the sweep runner, against the fp64 oracle."""
@@ -290,3 +290,29 @@ def test_full_size_step_is_bit_reproducible():
     for other in snaps[1:]:
         for k, v in snaps[0].items():
             assert torch.equal(v.view(torch.uint8), other[k].view(torch.uint8)), f"{k} differs between identical steps"
+
+
+def test_activation_recomputation_matches_stored_activations():
+    """Checkpointed variant: after the forward everything the layer saved is poisoned, the layer's forward calls are
+    re-run from the layer input, and the backward then gives bit-identical gradients to the stored-activation path
+    (which the tests above hold against the oracle)."""
+    cfg = synth.small_config(dtype="bf16", b=2, s=200, H=256, h=4, F=1024, V=1024, p=2)
+    inp = synth.make_inputs(cfg, nonzero_bias=True, random_ln=True)
+    grads = []
+    for recompute in (False, True):
+        L = LayerShards(cfg, [0, 1], DEV)
+        L.load_host_inputs(inp)
+        L.forward()
+        if recompute:
+            L.drop_layer_activations()
+            L.recompute_layer()
+        L.backward()
+        torch.cuda.synchronize()
+        g = {k: L.act[k].clone() for k in ("dX", "dX1", "dX2", "dg1", "db1", "dg2", "db2", "dbo", "dc")}
+        for r in (0, 1):
+            for k in ("dWqkv", "dbqkv", "dWo", "dA", "da", "dB", "dE"):
+                g[f"{r}.{k}"] = L.sh[r][k].clone()
+        grads.append(g)
+    for k, v in grads[0].items():
+        assert torch.isfinite(v.float()).all(), k
+        assert torch.equal(v, grads[1][k]), f"{k}: recomputed activations give a different gradient"
