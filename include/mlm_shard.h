@@ -242,6 +242,42 @@ MLM_API int mlm_vocab_ce_shard_bwd(const mlm_dims* dims, const void* hf, const v
                            void* logits_r, void* dE_r, void* dhf_partial_r,
                            void* ws, size_t ws_bytes, void* stream);
 
+/* ---- optimizer step of one model-parallel worker (Section 5: Adam with decoupled weight decay
+ *      0.01, global gradient-norm clipping at 1.0, mixed precision; Section 3: every worker
+ *      optimises its own parameters, no parameter values are communicated) ----------------- */
+
+/* sqnorm_out[0] = sum over the n_tensors gradient tensors of the sum of squares of their
+ * elements (fp32, fixed summation order), plus other_sqnorm[0] if that is not NULL -- the
+ * other workers' term of the GLOBAL norm, which on several GPUs is the one scalar all-reduce of
+ * the step.  grads: HOST array of n_tensors device pointers (1 <= n_tensors <= 64), counts:
+ * HOST array of their element counts (multiples of 8 for MLM_BF16, 4 for MLM_F32);
+ * other_sqnorm, sqnorm_out: device.  ws: n_tensors * 4096 bytes, 16-byte aligned. */
+MLM_API int mlm_grad_sqnorm(int32_t dtype, const void* const* grads, const int64_t* counts, int32_t n_tensors,
+                    const float* other_sqnorm, float* sqnorm_out, void* ws, size_t ws_bytes, void* stream);
+
+/* One AdamW update of one parameter tensor of `count` elements (step is 1-based):
+ *   g <- grad * min(1, max_norm / (sqrt(total_sqnorm[0]) + 1e-6))      (max_norm <= 0: no clipping,
+ *                                                                        total_sqnorm may be NULL)
+ *   m <- beta1 m + (1 - beta1) g;   v <- beta2 v + (1 - beta2) g^2
+ *   master <- master - lr ( (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ *                           + weight_decay * master )
+ *   weight_out <- master rounded to dtype        (NULL: not written)
+ * grad, weight_out: dtype; master, m, v: fp32, updated in place; total_sqnorm: device (from
+ * mlm_grad_sqnorm).  Everything 16-byte aligned; count a multiple of 8 (MLM_BF16) / 4 (MLM_F32). */
+MLM_API int mlm_adamw_step(int32_t dtype, int64_t count, const void* grad, float* master, float* m, float* v,
+                   void* weight_out, const float* total_sqnorm, float max_norm, float lr, float beta1,
+                   float beta2, float eps, float weight_decay, int32_t step, void* stream);
+
+/* mlm_adamw_step over n_tensors parameter tensors in ONE launch per 32 tensors (a worker owns many
+ * small tensors -- biases, layer-norm vectors -- whose separate launches would dominate the step).
+ * counts, grads, masters, ms, vs, weights_out, weight_decays: HOST arrays of n_tensors entries
+ * (1 <= n_tensors <= 64); the device buffers they name are as in mlm_adamw_step; weights_out[t] may
+ * be NULL; weight_decays[t] is tensor t's decay (0 for tensors that are not decayed). */
+MLM_API int mlm_adamw_step_multi(int32_t dtype, int32_t n_tensors, const int64_t* counts, const void* const* grads,
+                         float* const* masters, float* const* ms, float* const* vs, void* const* weights_out,
+                         const float* weight_decays, const float* total_sqnorm, float max_norm, float lr,
+                         float beta1, float beta2, float eps, int32_t step, void* stream);
+
 /* ---- the GEMM building block (Section 3: "XA", "YB", "XE") --------------------- */
 
 /* C = op(A) op(B) (+ bias per column), row-major, fp32 accumulation.

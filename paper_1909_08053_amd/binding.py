@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmlm_shar
 
 EXPORTS = ("mlm_shard_range", "mlm_workspace_bytes", "mlm_status_string", "mlm_layernorm_fwd", "mlm_layernorm_bwd",
            "mlm_combine", "mlm_combine_layernorm_fwd", "mlm_combine_layernorm_bwd", "mlm_colsum", "mlm_attn_shard_fwd", "mlm_attn_shard_bwd", "mlm_mlp_shard_fwd",
-           "mlm_mlp_shard_bwd", "mlm_vocab_ce_shard_fwd", "mlm_vocab_ce_merge", "mlm_vocab_ce_shard_bwd", "mlm_gemm")
+           "mlm_mlp_shard_bwd", "mlm_vocab_ce_shard_fwd", "mlm_vocab_ce_merge", "mlm_vocab_ce_shard_bwd", "mlm_gemm", "mlm_grad_sqnorm",
+           "mlm_adamw_step", "mlm_adamw_step_multi")
 
 
 class MlmError(RuntimeError):
@@ -190,3 +191,33 @@ def mlm_vocab_ce_shard_bwd(dims, hf, E_r, targets, loss_w, M, S, loss_stats, log
 def mlm_gemm(dtype, trans_a, trans_b, M, N, K, A, B, C, bias=None, stream=None):
     _chk(lib().mlm_gemm(ctypes.c_int32(dtype), ctypes.c_int32(trans_a), ctypes.c_int32(trans_b), ctypes.c_int64(M),
                         ctypes.c_int64(N), ctypes.c_int64(K), _p(A), _p(B), _p(C), _p(bias), _st(stream)), "mlm_gemm")
+
+
+def mlm_grad_sqnorm(dtype, grads: Sequence[torch.Tensor], other_sqnorm, sqnorm_out, ws, stream=None):
+    n = len(grads)
+    for t in grads:
+        _p(t)
+    arr = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t in grads])
+    cnt = (ctypes.c_int64 * max(n, 1))(*[t.numel() for t in grads])
+    _chk(lib().mlm_grad_sqnorm(ctypes.c_int32(dtype), arr, cnt, ctypes.c_int32(n), _p(other_sqnorm), _p(sqnorm_out),
+                               *_ws(ws), _st(stream)), "mlm_grad_sqnorm")
+
+
+def mlm_adamw_step(dtype, grad, master, m, v, weight_out, total_sqnorm, max_norm, lr, beta1, beta2, eps, weight_decay,
+                   step, stream=None):
+    f = ctypes.c_float
+    _chk(lib().mlm_adamw_step(ctypes.c_int32(dtype), ctypes.c_int64(grad.numel()), _p(grad), _p(master), _p(m), _p(v),
+                              _p(weight_out), _p(total_sqnorm), f(max_norm), f(lr), f(beta1), f(beta2), f(eps),
+                              f(weight_decay), ctypes.c_int32(step), _st(stream)), "mlm_adamw_step")
+
+
+def mlm_adamw_step_multi(dtype, grads, masters, ms, vs, weights_out, weight_decays, total_sqnorm, max_norm, lr, beta1,
+                         beta2, eps, step, stream=None):
+    n = len(grads)
+    ptrs = lambda ts: (ctypes.c_void_p * n)(*[(_p(t).value or 0) for t in ts])
+    cnt = (ctypes.c_int64 * n)(*[t.numel() for t in grads])
+    wds = (ctypes.c_float * n)(*[float(x) for x in weight_decays])
+    f = ctypes.c_float
+    _chk(lib().mlm_adamw_step_multi(ctypes.c_int32(dtype), ctypes.c_int32(n), cnt, ptrs(grads), ptrs(masters), ptrs(ms),
+                                    ptrs(vs), ptrs(weights_out), wds, _p(total_sqnorm), f(max_norm), f(lr), f(beta1),
+                                    f(beta2), f(eps), ctypes.c_int32(step), _st(stream)), "mlm_adamw_step_multi")

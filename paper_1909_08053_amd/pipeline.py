@@ -242,6 +242,39 @@ class LayerShards:
             w, s = self.w[r], self.sh[r]
             B.mlm_mlp_shard_fwd(self.dims[r], a["U2"], w["A"], w["a"], w["B"], s["g"], s["y"], s["mlp_partial"], ws)
 
+    # ------------------------------------------------------------------ optimizer (this worker's parameters)
+    def parameters(self):
+        """(name, weight tensor, gradient tensor) of everything this object owns: the shards' weights and, once, the
+        replicated layer-norm / bias parameters."""
+        out = []
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            for k, gk in (("Wqkv", "dWqkv"), ("bqkv", "dbqkv"), ("Wo", "dWo"), ("A", "dA"), ("a", "da"), ("B", "dB"),
+                          ("E", "dE")):
+                out.append((f"{r}.{k}", w[k], s[gk]))
+        rep, a = self.rep, self.act
+        pairs = [("g1", "dg1"), ("b1", "db1"), ("g2", "dg2"), ("b2", "db2"), ("bo", "dbo"), ("c", "dc")]
+        if self.cfg.final_ln:
+            pairs += [("gf", "dgf"), ("bf", "dbf")]
+        for k, gk in pairs:
+            out.append((k, rep[k], a[gk]))
+        return out
+
+    def optimizer_step(self, step: int, lr: float, max_norm: float = 1.0, beta1: float = 0.9, beta2: float = 0.999,
+                       eps: float = 1e-8, weight_decay: float = 0.01, other_sqnorm=None):
+        """Global-norm clip + AdamW on every parameter (fp32 master weights and moments are created on first use)."""
+        params = self.parameters()
+        if not hasattr(self, "opt"):
+            self.opt = {n: {"master": w.float().clone(), "m": torch.zeros_like(w, dtype=torch.float32),
+                            "v": torch.zeros_like(w, dtype=torch.float32)} for n, w, _ in params}
+            self.opt_ws = torch.empty(len(params) * 4096, device=self.dev, dtype=torch.uint8)
+            self.sqnorm = torch.zeros(1, device=self.dev, dtype=torch.float32)
+        B.mlm_grad_sqnorm(self.code, [g for _, _, g in params], other_sqnorm, self.sqnorm, self.opt_ws)
+        st = [self.opt[n] for n, _, _ in params]
+        B.mlm_adamw_step_multi(self.code, [g for _, _, g in params], [x["master"] for x in st], [x["m"] for x in st],
+                               [x["v"] for x in st], [w for _, w, _ in params], [weight_decay] * len(params),
+                               self.sqnorm, max_norm, lr, beta1, beta2, eps, step)
+
     def step(self, recompute: bool = False):
         self.forward()
         if recompute:

@@ -46,9 +46,36 @@ def time_config(cfg, steps, warmup, dev="cuda:0", recompute=False):
     return ms
 
 
+def optimizer_timing(steps, warmup, dev="cuda:0"):
+    """Global-norm clip + AdamW over one worker's parameters of the 8.3B-shape 1/8 shard (layer shard + vocabulary
+    shard + replicated vectors): bandwidth-bound, 2 + 28 bytes per bf16 parameter (norm pass, then update)."""
+    import torch
+    from . import synth
+    from .pipeline import LayerShards
+    cfg = synth.CONFIGS["gpt2_8p3b"]
+    L = LayerShards(cfg, [0], dev)
+    L.load_random(seed=cfg.seed)
+    L.step()
+    for i in range(warmup):
+        L.optimizer_step(i + 1, lr=1e-4)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        L.optimizer_step(warmup + i + 1, lr=1e-4)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    nparam = sum(w.numel() for _, w, _ in L.parameters())
+    nbytes = nparam * 30.0
+    print(f"# optimizer step, gpt2_8p3b shard 0 of 8: {nparam / 1e6:.2f} M parameters in {len(L.parameters())} tensors")
+    print(f"{ms * 1e3:9.1f} us/step  {nbytes / 1e6:8.1f} MB algorithmic  {nbytes / (ms * 1e-3) / 1e12:6.2f} TB/s "
+          f"({nbytes / (ms * 1e-3) / 8e12 * 100:.1f} % of the 8 TB/s HBM peak)")
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "all"])
+    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "optimizer", "all"])
     ap.add_argument("--recompute", action="store_true",
                     help="checkpointed variant: re-run the layer's forward before its backward (activation recomputation)")
     ap.add_argument("--steps", type=int, default=20)
@@ -61,6 +88,9 @@ def main():
         sys.exit("sweep: no GPU visible")
     B.lib()
     names = ["heads", "strong_1p2b", "table1"] if args.sweep == "all" else [args.sweep]
+    if args.sweep == "optimizer":
+        optimizer_timing(args.steps, args.warmup)
+        return
     for sw in names:
         print(f"# sweep {sw}" + (" (activation recomputation: layer forward run twice)" if args.recompute else ""))
         rows = []
