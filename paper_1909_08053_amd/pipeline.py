@@ -285,10 +285,10 @@ class LayerShards:
     def fetch(self) -> Dict[str, object]:
         torch.cuda.synchronize(self.dev)
         cp = lambda t: t.detach().float().cpu().numpy().astype(np.float64)
-        out: Dict[str, object] = {k: cp(v) for k, v in self.act.items()}
+        skip = ()
         if self.fused and not self.store_combined:      # never written in this mode
-            for k in ("dU2", "dU") + (("dHf",) if self.cfg.final_ln else ()):
-                out.pop(k, None)
+            skip = ("dU2", "dU") + (("dHf",) if self.cfg.final_ln else ())
+        out: Dict[str, object] = {k: cp(v) for k, v in self.act.items() if k not in skip}
         if getattr(self, "_dx2", None) is not None:
             out["dX2"] = cp(self._dx2)
         if getattr(self, "_hf", None) is not None:

@@ -54,7 +54,7 @@ def test_gemm_layouts_and_ragged_tiles(dtype, layout, shape):
 
 # ------------------------------------------------------------------ replicated row kernels
 @pytest.mark.parametrize("dtype,H", [("fp32", 256), ("bf16", 256), ("bf16", 3072), ("bf16", 1920), ("fp32", 136),
-                                     ("bf16", 2560)])
+                                     ("bf16", 2560), ("bf16", 4096), ("fp32", 2048), ("bf16", 8)])   # incl. the widest / narrowest rows supported
 def test_layernorm_combine_colsum(dtype, H):
     T = 2 * 37                     # ragged against the 4-rows-per-block / 32-rows-per-block groupings
     cfg_dims = B.make_dims(2, 37, H, 1, 4 * H, 8, 1, 0, B.MLM_BF16 if dtype == "bf16" else B.MLM_F32)
@@ -202,6 +202,10 @@ BF16_CASES = {
     "d96_causal": (dict(b=2, s=328, H=192, h=2, F=768, V=1088, p=2), True, 3.0),
     "d128_causal_p1": (dict(b=1, s=264, H=256, h=2, F=1024, V=520, p=1), True, 3.0),
     "d192_causal": (dict(b=2, s=200, H=384, h=2, F=1536, V=640, p=2), True, 3.0),
+    # sequences shorter than one 64-key tile (the second wave group of the attention kernels gets no tile at all) and
+    # of exactly one query block
+    "d64_short_seq": (dict(b=3, s=40, H=128, h=2, F=512, V=256, p=2), True, 3.0),
+    "d96_one_block_bert": (dict(b=2, s=128, H=192, h=2, F=768, V=512, p=1, causal=False, masked_lm=True), True, 3.0),
     "d192_bert": (dict(b=2, s=136, H=768, h=4, F=1536, V=512, p=2, causal=False, masked_lm=True), True, 3.0),
     "d64_bert": (dict(b=3, s=176, H=256, h=4, F=1024, V=960, p=4, causal=False, masked_lm=True), True, 3.0),
     "d96_bert_recompute": (dict(b=2, s=136, H=384, h=4, F=1536, V=512, p=2, causal=False, masked_lm=True), False, 3.0),
