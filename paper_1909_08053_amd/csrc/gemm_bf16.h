@@ -239,12 +239,52 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
   // read-back time, where a lane owns 8 consecutive columns of one row: bias, the saved pre-activation and the
   // outputs are then 16-byte accesses with 128-byte contiguous row segments.
   constexpr int NSTEP = TM * (TN / 2);
+  const int rb_r = lane >> 3, rb_c = (lane & 7) * 8;           // read-back: 8 rows x 8 column groups per iteration
+  const bool full = (m0 + BM <= a.M) && (n0 + BN <= a.N);
+  if ((EPI == EPI_STORE || EPI == EPI_CE) && bias == nullptr) {
+    // Nothing but the rounding happens between accumulator and memory: round first and stage bf16 strips (half the
+    // LDS traffic of the fp32 strips, no conversion at read-back).  Row stride 72 elements keeps rows 16-byte aligned.
+    constexpr int SWB = 72;
+    static_assert(2 * 32 * SWB <= Tcfg::STRIP * 2, "bf16 strips fit in the wave's staging area");
+    bf16* bstrip0 = lds + (size_t)wave * 2 * Tcfg::STRIP;
+#pragma unroll
+    for (int step = 0; step <= NSTEP; ++step) {
+      if (step < NSTEP) {
+        const int j = step / (TN / 2), h = step % (TN / 2);
+        bf16* strip = bstrip0 + (step & 1) * (32 * SWB);
+#pragma unroll
+        for (int il = 0; il < 2; ++il)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const floatx16& t = acc[2 * h + il][j];
+            bf16x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (bf16)t[4 * g + e];
+            *reinterpret_cast<bf16x4*>(strip + l32 * SWB + il * 32 + 8 * g + 4 * lh) = v;
+          }
+      }
+      __builtin_amdgcn_wave_barrier();
+      if (step > 0) {
+        const int ps = step - 1;
+        const int j = ps / (TN / 2), h = ps % (TN / 2);
+        const bf16* strip = bstrip0 + (ps & 1) * (32 * SWB);
+        const int gn = n0 + wn0 + h * 64 + rb_c;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int r = rb_r + it * 8;
+          const int gm = m0 + wm0 + j * 32 + r;
+          const bf16x8 o = *reinterpret_cast<const bf16x8*>(strip + r * SWB + rb_c);
+          if (full || (gm < a.M && gn < a.N)) *reinterpret_cast<bf16x8*>(C + (size_t)gm * a.ldc + gn) = o;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+    return;
+  }
   constexpr int SW = 64 + 4;                                   // strip row stride in floats (272 B)
   static_assert(32 * SW * 4 <= Tcfg::STRIP * 2, "strip does not fit");
   static_assert(TN % 2 == 0, "wave tile must be a multiple of 64 columns");
   float* strip0 = reinterpret_cast<float*>(lds + (size_t)wave * 2 * Tcfg::STRIP);
-  const bool full = (m0 + BM <= a.M) && (n0 + BN <= a.N);
-  const int rb_r = lane >> 3, rb_c = (lane & 7) * 8;           // read-back: 8 rows x 8 column groups per iteration
 
 #pragma unroll
   for (int step = 0; step <= NSTEP; ++step) {
