@@ -33,11 +33,12 @@ constexpr int V2_REGION_BYTES = V2_STAGES * V2_OP_BYTES;   // 64 KB ring per ope
 constexpr size_t V2_LDS_BYTES = (size_t)2 * V2_REGION_BYTES;          // 128 KB
 constexpr int V2_CUS = 256;
 
-// Bank swizzle of the [k][row] tile layout (XOR on the 16-byte unit index of a k-row).  One transpose-read
-// instruction touches k-rows {b..b+3} (16-lane groups 0,1) and {b+8..b+11} (groups 2,3), 32 bytes per row and
-// group: bits 0-1 of k spread the four rows of a group over a 128-byte span, bit 3 of k sends the two row sets to
-// different 128-byte halves of the 256-byte bank row, so a 512-byte read completes in the minimum two passes.
-__device__ __forceinline__ int v2_mn_swizzle(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
+// Bank swizzle of the [k][row] tile layout (XOR on the 16-byte unit index of a 512-byte k-row).  A transposing read
+// is served in two passes of 32 lanes; a pass reads 64 contiguous bytes (four units) of each of four consecutive
+// k-rows, and every k-row starts at bank 0.  XORing the unit index with 4 (k & 3) sends the four rows to four different
+// 64-byte slots of the 256-byte bank row, so a pass touches every bank once (checked by simulation and with the
+// LDS bank-conflict counter: an earlier swizzle that only spread the rows over 128 bytes showed 50 % conflict cycles).
+__device__ __forceinline__ int v2_mn_swizzle(int k) { return (k & 3) << 2; }
 
 // Bank swizzle of a k-contiguous operand's ring: rows of 128 bytes (two consecutive k-slices side by side, eight
 // 16-byte units), unit index XORed with this value; 16 consecutive rows reading the same logical unit then hit 16
