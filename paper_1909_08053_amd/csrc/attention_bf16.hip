@@ -174,13 +174,16 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(A
     floatx16 sacc[2];
     float lsum_t = 0.f;
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) sacc[kt][e] = 0.f;
+    // the two 32-key halves are independent accumulation chains: alternate them so that a dependent MFMA never
+    // follows its predecessor directly
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks)
+    for (int ks = 0; ks < D / 16; ++ks)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
         sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sK, kt * 32, ks, lane), qf[ks], sacc[kt], 0, 0, 0);
-    }
     // raw scores s; probabilities p = exp2(s * sc - max) with the scale folded into one fma per element
     const bool need_mask = (a.causal && k0 + ATILE - 1 > qw0) || (k0 + ATILE > klen);   // wave-uniform
     float mt = -INFINITY;
@@ -356,15 +359,17 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
     if (t >= nt || (a.causal && k0 > qw0 + 31)) continue;
     floatx16 sacc[2], pacc[2];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) { sacc[kt][e] = 0.f; pacc[kt][e] = 0.f; }
+    // four independent accumulation chains, interleaved
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
+    for (int ks = 0; ks < D / 16; ++ks)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
         sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sK, kt * 32, ks, lane), qf[ks], sacc[kt], 0, 0, 0);   // S^T[key][query]
         pacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sV, kt * 32, ks, lane), dof[ks], pacc[kt], 0, 0, 0);  // dP^T[key][query]
       }
-    }
     const bool need_mask = (a.causal && k0 + ATILE - 1 > qw0) || (k0 + ATILE > klen);   // wave-uniform
     if (need_mask) {
 #pragma unroll
