@@ -78,3 +78,39 @@ def test_workspace_sizes_are_positive_and_aligned():
         nbytes = B.mlm_workspace_bytes(d, which)
         assert nbytes % 256 == 0
     assert B.mlm_workspace_bytes(d, B.WS_VOCAB_CE_BWD) == 8192 * 6400 * 2 + 64 * 2 ** 20
+
+
+def test_validation_of_fused_and_optimizer_entry_points():
+    """Bad arguments of the fused layer-norm calls and of the optimizer calls are refused on the host, before any
+    launch (no GPU is touched: the pointers below are never dereferenced)."""
+    L = B.lib()
+    d = _dims()
+    P = ctypes.c_void_p
+    ok = P(4096)                                   # an aligned, non-NULL address that is never used
+    one = (P * 1)(4096)
+    f = ctypes.c_float
+    # fused combine + layer norm: NULL partial list, n out of range, NULL / misaligned partial
+    assert L.mlm_combine_layernorm_fwd(ctypes.byref(d), None, 1, None, None, ok, ok, ok, ok, ok, ok, None) == -1
+    assert L.mlm_combine_layernorm_fwd(ctypes.byref(d), one, 0, None, None, ok, ok, ok, ok, ok, ok, None) == -2
+    assert L.mlm_combine_layernorm_fwd(ctypes.byref(d), one, 17, None, None, ok, ok, ok, ok, ok, ok, None) == -2
+    assert L.mlm_combine_layernorm_fwd(ctypes.byref(d), (P * 1)(None), 1, None, None, ok, ok, ok, ok, ok, ok, None) == -1
+    assert L.mlm_combine_layernorm_fwd(ctypes.byref(d), (P * 1)(4100), 1, None, None, ok, ok, ok, ok, ok, ok, None) == -5
+    assert L.mlm_combine_layernorm_fwd(ctypes.byref(d), one, 1, None, None, None, ok, ok, ok, ok, ok, None) == -1
+    # backward: a workspace that is too small
+    assert L.mlm_combine_layernorm_bwd(ctypes.byref(d), one, 1, ok, ok, ok, ok, None, None, ok, ok, ok, None, ok,
+                                       ctypes.c_size_t(16), None) == -4
+    assert L.mlm_combine_layernorm_bwd(ctypes.byref(d), one, 1, ok, ok, ok, ok, None, None, None, ok, ok, None, ok,
+                                       ctypes.c_size_t(1 << 30), None) == -1
+    # optimizer
+    cnt = (ctypes.c_int64 * 1)(64)
+    assert L.mlm_grad_sqnorm(7, one, cnt, 1, None, ok, ok, ctypes.c_size_t(4096), None) == -3
+    assert L.mlm_grad_sqnorm(0, one, cnt, 0, None, ok, ok, ctypes.c_size_t(4096), None) == -2
+    assert L.mlm_grad_sqnorm(0, one, cnt, 1, None, ok, ok, ctypes.c_size_t(100), None) == -4
+    assert L.mlm_grad_sqnorm(1, one, (ctypes.c_int64 * 1)(60), 1, None, ok, ok, ctypes.c_size_t(4096), None) == -5
+    step = lambda count, st, clip, sq: L.mlm_adamw_step(0, ctypes.c_int64(count), ok, ok, ok, ok, None, sq, f(clip),
+                                                        f(1e-3), f(0.9), f(0.999), f(1e-8), f(0.0), st, None)
+    assert step(6, 1, 0.0, None) == -5             # count not a multiple of 4 (fp32)
+    assert step(64, 0, 0.0, None) == -2            # step is 1-based
+    assert step(64, 1, 1.0, None) == -1            # clipping asked for without a norm
+    assert L.mlm_adamw_step(0, ctypes.c_int64(64), ok, ok, ok, ok, None, None, f(0.0), f(1e-3), f(1.0), f(0.999),
+                            f(1e-8), f(0.0), 1, None) == -2          # beta1 must be < 1
