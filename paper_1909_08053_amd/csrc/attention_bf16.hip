@@ -102,6 +102,7 @@ constexpr int ANST = 3;             // ring stages of the one-group kernel (dK/d
 // two waves per SIMD allow.
 template <int D> constexpr int attn_groups() { return D > 128 ? 1 : 2; }
 template <int D> constexpr int group_stages() { return D == 128 ? 2 : 3; }
+template <int D> constexpr int dkv_dsplit() { return D >= 128 ? 2 : 1; }
 
 // (two waves per SIMD requested: with at most 256 registers per lane the MFMA accumulators live in ordinary VGPRs, so
 // the softmax arithmetic needs no accumulator-register moves)
@@ -441,10 +442,16 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   typedef ATile<D> TL;
   constexpr int BKB = 32 * ANW, VEC = 2 * ATILE * 4;          // VEC: bytes of the lse + delta vectors of a tile
   constexpr int STAGE = 2 * TL::BYTES + VEC, LPT = 2 * TL::QPW + 1;
+  // Large heads: the dK / dV accumulators of all D columns plus the owned K / V rows do not fit the register file
+  // (they spilled: 2.3x / 5.6x the d = 96 time at d = 128 / 192).  Two workgroups then share a key block, each
+  // accumulating one half of the D columns of dK and dV (the scores are computed by both); this also doubles the
+  // number of workgroups where a shard has few heads.
+  constexpr int DS = dkv_dsplit<D>(), DH = D / DS;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known wave-uniform: mask tests become scalar branches
-  const int kb = blockIdx.x;                       // key block; for causal, block 0 has the most queries: first
+  const int kb = blockIdx.x / DS;                  // key block; for causal, block 0 has the most queries: first
+  const int dh0 = (blockIdx.x % DS) * DH;          // first of this workgroup's dK / dV columns
   const int hd = blockIdx.y, bi = blockIdx.z;
   const int ld = 3 * a.hl * D;
   const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
@@ -462,9 +469,9 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
       vf[ks] = *reinterpret_cast<const bf16x8*>(vrow + ks * 16 + lh * 8);
     }
   }
-  floatx16 dk[D / 32], dv[D / 32];
+  floatx16 dk[DH / 32], dv[DH / 32];
 #pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt)
+  for (int dt = 0; dt < DH / 32; ++dt)
 #pragma unroll
     for (int e = 0; e < 16; ++e) { dk[dt][e] = 0.f; dv[dt][e] = 0.f; }
   const float scale = 1.0f / sqrtf((float)D);
@@ -541,9 +548,9 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
         const bf16x8 pf = pack8(sacc, 8 * cc);
         const bf16x8 dsf = pack8(pacc, 8 * cc);
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) {
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_tr(sdO, c, dt * 32, lane), pf, dv[dt], 0, 0, 0);    // dV^T[dcol][key]
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_tr(sQ, c, dt * 32, lane), dsf, dk[dt], 0, 0, 0);    // dK^T[dcol][key]
+        for (int dt = 0; dt < DH / 32; ++dt) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_tr(sdO, c, dh0 + dt * 32, lane), pf, dv[dt], 0, 0, 0);    // dV^T[dcol][key]
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_tr(sQ, c, dh0 + dt * 32, lane), dsf, dk[dt], 0, 0, 0);    // dK^T[dcol][key]
         }
       }
     }
@@ -553,7 +560,7 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
     bf16* krow = (bf16*)a.dqkv + ((size_t)bi * a.s + kj) * ld + (a.hl + hd) * D;
     bf16* vrow = (bf16*)a.dqkv + ((size_t)bi * a.s + kj) * ld + (2 * a.hl + hd) * D;
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+    for (int dt = 0; dt < DH / 32; ++dt)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         bf16x4 ok, ov;
@@ -562,8 +569,8 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
           ok[e] = (bf16)(dk[dt][4 * g + e] * scale);
           ov[e] = (bf16)dv[dt][4 * g + e];
         }
-        *reinterpret_cast<bf16x4*>(krow + dt * 32 + 8 * g + 4 * lh) = ok;
-        *reinterpret_cast<bf16x4*>(vrow + dt * 32 + 8 * g + 4 * lh) = ov;
+        *reinterpret_cast<bf16x4*>(krow + dh0 + dt * 32 + 8 * g + 4 * lh) = ok;
+        *reinterpret_cast<bf16x4*>(vrow + dh0 + dt * 32 + 8 * g + 4 * lh) = ov;
       }
   }
 }
@@ -603,7 +610,8 @@ static hipError_t launch_bwd_d(const AttnArgs& a, hipStream_t st) {
                             (int)lds_kv);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D>), grid, dim3(ANT), lds_kv, st, a);
+  dim3 grid_kv(grid.x * dkv_dsplit<D>(), grid.y, grid.z);
+  hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D>), grid_kv, dim3(ANT), lds_kv, st, a);
   return hipGetLastError();
 }
 
