@@ -23,8 +23,10 @@ Readings taken where the paper is silent (each is also listed in the design
 notes): tanh-form GeLU by default (erf form available), biases exist and the
 row-parallel bias is added once after the reduction, F = 4H, LN eps 1e-5 with
 the biased variance, score scale 1/sqrt(d), masked probabilities exactly 0,
-final LN before the output embedding (switchable), dropout = identity, loss =
-mean over positions with weight 1, targets are given per position (no shift).
+final LN before the output embedding (switchable), loss = mean over positions
+with weight 1, targets are given per position (no shift).  Dropout is the
+identity unless keep masks are handed in (``inp["drop"]``): the masks are
+inputs here, the generator that draws them is oracle/rng_embed_oracle.py.
 
 Pins (tests/test_oracle_*.py, all CPU): closed forms and identities for GeLU,
 LN, softmax/attention and cross entropy; library routines (torch fp64
@@ -147,10 +149,12 @@ def allowed_mask(s: int, causal: bool, key_len: int) -> np.ndarray:
     return ok
 
 
-def attention_fwd(Q, K, Vv, spec: Spec, key_len: np.ndarray):
+def attention_fwd(Q, K, Vv, spec: Spec, key_len: np.ndarray, keep=None, p_drop: float = 0.0):
     """softmax(mask(Q K^T / sqrt(d))) V per head (Section 3: each head's matmuls are local).
 
     Q, K, Vv: [b, s, H] with head k in columns [k d, (k+1) d).
+    keep: optional boolean [b, h, s, s] dropout mask of the attention probabilities (the dropout inside the
+    model-parallel region, Appendix B.2): C = (keep * P / (1 - p_drop)) V.  P and LSE are returned undropped.
     Returns C [b, s, H], P [b, h, s, s], LSE [b, h, s] (natural log of the masked row sum of exp(S))."""
     b, s, H, h, d = spec.b, spec.s, spec.H, spec.h, spec.d
     C = np.zeros((b, s, H), F64)
@@ -169,12 +173,17 @@ def attention_fwd(Q, K, Vv, spec: Spec, key_len: np.ndarray):
             p = e / den
             P[bi, k] = p
             LSE[bi, k] = (mx + np.log(den))[:, 0]
+            if keep is not None:
+                p = np.where(keep[bi, k], p, 0.0) / (1.0 - p_drop)
             C[bi, :, sl] = p @ Vv[bi, :, sl]
     return C, P, LSE
 
 
-def attention_bwd(dC, Q, K, Vv, P, spec: Spec):
-    """Gradients of attention_fwd w.r.t. Q, K, V given dC (masked entries have P = 0, so dS = 0 there)."""
+def attention_bwd(dC, Q, K, Vv, P, spec: Spec, keep=None, p_drop: float = 0.0):
+    """Gradients of attention_fwd w.r.t. Q, K, V given dC (masked entries have P = 0, so dS = 0 there).
+
+    With a dropout mask: C = Pd V with Pd = keep * P / (1 - p_drop), so dV = Pd^T dC and
+    dP = keep * (dC V^T) / (1 - p_drop); the softmax gradient then acts on the undropped P."""
     b, s, H, h, d = spec.b, spec.s, spec.H, spec.h, spec.d
     dQ = np.zeros_like(Q)
     dK = np.zeros_like(K)
@@ -184,8 +193,13 @@ def attention_bwd(dC, Q, K, Vv, P, spec: Spec):
         for k in range(h):
             sl = slice(k * d, (k + 1) * d)
             p = P[bi, k]
-            dV[bi, :, sl] = p.T @ dC[bi, :, sl]
-            dP = dC[bi, :, sl] @ Vv[bi, :, sl].T
+            if keep is None:
+                dV[bi, :, sl] = p.T @ dC[bi, :, sl]
+                dP = dC[bi, :, sl] @ Vv[bi, :, sl].T
+            else:
+                pd = np.where(keep[bi, k], p, 0.0) / (1.0 - p_drop)
+                dV[bi, :, sl] = pd.T @ dC[bi, :, sl]
+                dP = np.where(keep[bi, k], dC[bi, :, sl] @ Vv[bi, :, sl].T, 0.0) / (1.0 - p_drop)
             dS = p * (dP - (dP * p).sum(axis=-1, keepdims=True))
             dQ[bi, :, sl] = (dS @ K[bi, :, sl]) * scale
             dK[bi, :, sl] = (dS.T @ Q[bi, :, sl]) * scale
@@ -214,17 +228,39 @@ def cross_entropy_bwd(L, tgt, w, mx, se):
     return dL
 
 
+# --------------------------------------------------------------------------- dropout (masks are INPUTS)
+def apply_keep(x, keep, p_drop: float):
+    """Inverted dropout with a given boolean keep mask: keep * x / (1 - p_drop); identity if keep is None.
+
+    The same function is its own gradient map (d out = keep * d in / (1 - p_drop))."""
+    if keep is None:
+        return x
+    return np.where(np.asarray(keep, bool).reshape(x.shape), x, 0.0) / (1.0 - p_drop)
+
+
+def _drop_of(inp):
+    """(keep_attn [b,h,s,s], keep1 [T,H], keep2 [T,H], p_attn, p_hidden) from the optional ``drop`` entry of the
+    inputs; all None / 0 when the layer runs dropout-free (the default)."""
+    d = inp.get("drop")
+    if d is None:
+        return None, None, None, 0.0, 0.0
+    return d.get("keep_attn"), d.get("keep1"), d.get("keep2"), float(d.get("p_attn", 0.0)), float(d.get("p_hidden", 0.0))
+
+
 # --------------------------------------------------------------------------- unsharded layer
 def _f64(P: Dict[str, np.ndarray]) -> Dict[str, np.ndarray]:
-    return {k: (np.asarray(v, F64) if np.asarray(v).dtype.kind == "f" else np.asarray(v)) for k, v in P.items()}
+    return {k: (np.asarray(v, F64) if np.asarray(v).dtype.kind == "f" else np.asarray(v)) for k, v in P.items()
+            if k != "drop"}
 
 
 def forward(inp: Dict[str, np.ndarray], spec: Spec) -> Dict[str, np.ndarray]:
     """Unsharded pre-LN layer + output embedding + mean cross entropy; returns every intermediate.
 
     inp holds X [b,s,H], the parameters (g1,b1,Wq,Wk,Wv,bq,bk,bv,Wo,bo,g2,b2,A,a,B,c,gf,bf,E),
-    tgt [b,s] int, w [b,s] loss weights in {0,1}, key_len [b]."""
+    tgt [b,s] int, w [b,s] loss weights in {0,1}, key_len [b]; optionally ``drop``: the dropout keep masks of the
+    attention probabilities and of the two block outputs before their residual adds (Section 3 / Appendix B.2)."""
     p = _f64(inp)
+    keep_attn, keep1, keep2, p_attn, p_hidden = _drop_of(inp)
     b, s, H, T = spec.b, spec.s, spec.H, spec.T
     X = p["X"].reshape(T, H)
     c: Dict[str, np.ndarray] = {}
@@ -234,14 +270,14 @@ def forward(inp: Dict[str, np.ndarray], spec: Spec) -> Dict[str, np.ndarray]:
     c["K"] = c["U"] @ p["Wk"] + p["bk"]
     c["Vv"] = c["U"] @ p["Wv"] + p["bv"]
     C, Pm, LSE = attention_fwd(c["Q"].reshape(b, s, H), c["K"].reshape(b, s, H),
-                               c["Vv"].reshape(b, s, H), spec, p["key_len"])
+                               c["Vv"].reshape(b, s, H), spec, p["key_len"], keep_attn, p_attn)
     c["C"], c["P"], c["LSE"] = C.reshape(T, H), Pm, LSE
-    c["X1"] = X + c["C"] @ p["Wo"] + p["bo"]
+    c["X1"] = X + apply_keep(c["C"] @ p["Wo"] + p["bo"], keep1, p_hidden)
     # MLP block (Section 3, Eq. 1: Y = GeLU(X A); then Z = Y B, residual)
     c["U2"], c["mu2"], c["rstd2"] = layernorm_fwd(c["X1"], p["g2"], p["b2"], spec.ln_eps)
     c["G"] = c["U2"] @ p["A"] + p["a"]
     c["Y"] = gelu(c["G"], spec.gelu_tanh)
-    c["X2"] = c["X1"] + c["Y"] @ p["B"] + p["c"]
+    c["X2"] = c["X1"] + apply_keep(c["Y"] @ p["B"] + p["c"], keep2, p_hidden)
     # final LN (switch) and the output embedding fused with the loss (Section 3)
     if spec.final_ln:
         c["Hf"], c["muf"], c["rstdf"] = layernorm_fwd(c["X2"], p["gf"], p["bf"], spec.ln_eps)
@@ -261,6 +297,7 @@ def backward(inp: Dict[str, np.ndarray], c: Dict[str, np.ndarray], spec: Spec) -
     X = p["X"].reshape(T, H)
     tgt = p["tgt"].reshape(T).astype(np.int64)
     w = np.asarray(p["w"], F64).reshape(T)
+    keep_attn, keep1, keep2, p_attn, p_hidden = _drop_of(inp)
     g: Dict[str, np.ndarray] = {}
     g["dL"] = cross_entropy_bwd(c["L"], tgt, w, c["M"], c["S"])
     g["dE"] = c["Hf"].T @ g["dL"]
@@ -272,9 +309,10 @@ def backward(inp: Dict[str, np.ndarray], c: Dict[str, np.ndarray], spec: Spec) -
         g["dgf"] = np.zeros(H, F64)
         g["dbf"] = np.zeros(H, F64)
     # MLP block
-    g["dc"] = g["dX2"].sum(axis=0)
-    g["dB"] = c["Y"].T @ g["dX2"]
-    g["dY"] = g["dX2"] @ p["B"].T
+    g["dZ2"] = apply_keep(g["dX2"], keep2, p_hidden)       # gradient of the MLP block output before dropout
+    g["dc"] = g["dZ2"].sum(axis=0)
+    g["dB"] = c["Y"].T @ g["dZ2"]
+    g["dY"] = g["dZ2"] @ p["B"].T
     g["dG"] = g["dY"] * gelu_grad(c["G"], spec.gelu_tanh)
     g["da"] = g["dG"].sum(axis=0)
     g["dA"] = c["U2"].T @ g["dG"]
@@ -282,11 +320,12 @@ def backward(inp: Dict[str, np.ndarray], c: Dict[str, np.ndarray], spec: Spec) -
     dx1_ln, g["dg2"], g["db2"] = layernorm_bwd(g["dU2"], c["X1"], p["g2"], c["mu2"], c["rstd2"])
     g["dX1"] = g["dX2"] + dx1_ln
     # attention block
-    g["dbo"] = g["dX1"].sum(axis=0)
-    g["dWo"] = c["C"].T @ g["dX1"]
-    g["dC"] = g["dX1"] @ p["Wo"].T
+    g["dZ1"] = apply_keep(g["dX1"], keep1, p_hidden)
+    g["dbo"] = g["dZ1"].sum(axis=0)
+    g["dWo"] = c["C"].T @ g["dZ1"]
+    g["dC"] = g["dZ1"] @ p["Wo"].T
     dQ, dK, dV = attention_bwd(g["dC"].reshape(b, s, H), c["Q"].reshape(b, s, H), c["K"].reshape(b, s, H),
-                               c["Vv"].reshape(b, s, H), c["P"], spec)
+                               c["Vv"].reshape(b, s, H), c["P"], spec, keep_attn, p_attn)
     g["dQ"], g["dK"], g["dVv"] = dQ.reshape(T, H), dK.reshape(T, H), dV.reshape(T, H)
     g["dWq"], g["dWk"], g["dWv"] = c["U"].T @ g["dQ"], c["U"].T @ g["dK"], c["U"].T @ g["dVv"]
     g["dbq"], g["dbk"], g["dbv"] = g["dQ"].sum(axis=0), g["dK"].sum(axis=0), g["dVv"].sum(axis=0)
@@ -350,6 +389,8 @@ def sharded_reference(inp: Dict[str, np.ndarray], spec: Spec, p: int) -> Dict[st
     tgt = q["tgt"].reshape(T).astype(np.int64)
     w = np.asarray(q["w"], F64).reshape(T)
     sh = [shard_params(inp, spec, p, r) for r in range(p)]
+    keep_attn, keep1, keep2, p_attn, p_hidden = _drop_of(inp)
+    ka = lambda r: None if keep_attn is None else keep_attn[:, r * hl:(r + 1) * hl]   # local heads' masks
     out: Dict[str, object] = {}
     # ---- forward
     U, mu1, rstd1 = layernorm_fwd(X, q["g1"], q["b1"], spec.ln_eps)
@@ -358,17 +399,18 @@ def sharded_reference(inp: Dict[str, np.ndarray], spec: Spec, p: int) -> Dict[st
         S["qkv"] = U @ S["Wqkv"] + S["bqkv"]
         Qr, Kr, Vr = S["qkv"][:, :Hl], S["qkv"][:, Hl:2 * Hl], S["qkv"][:, 2 * Hl:]
         C, Pm, LSE = attention_fwd(Qr.reshape(b, s, Hl), Kr.reshape(b, s, Hl), Vr.reshape(b, s, Hl),
-                                   lspec, q["key_len"])
+                                   lspec, q["key_len"], ka(r), p_attn)
         S["ctx"], S["P"], S["lse"] = C.reshape(T, Hl), Pm, LSE
         S["attn_partial"] = S["ctx"] @ S["Wo"]
-    X1 = X + q["bo"] + sum(S["attn_partial"] for S in sh)          # g: all-reduce, then bias once + residual
+    # g: all-reduce, then (replicated) bias once, dropout, residual
+    X1 = X + apply_keep(q["bo"] + sum(S["attn_partial"] for S in sh), keep1, p_hidden)
     U2, mu2, rstd2 = layernorm_fwd(X1, q["g2"], q["b2"], spec.ln_eps)
     for r in range(p):
         S = sh[r]
         S["g"] = U2 @ S["A"] + S["a"]
         S["y"] = gelu(S["g"], spec.gelu_tanh)
         S["mlp_partial"] = S["y"] @ S["B"]
-    X2 = X1 + q["c"] + sum(S["mlp_partial"] for S in sh)
+    X2 = X1 + apply_keep(q["c"] + sum(S["mlp_partial"] for S in sh), keep2, p_hidden)
     if spec.final_ln:
         Hf, muf, rstdf = layernorm_fwd(X2, q["gf"], q["bf"], spec.ln_eps)
     else:
@@ -402,11 +444,12 @@ def sharded_reference(inp: Dict[str, np.ndarray], spec: Spec, p: int) -> Dict[st
         dX2, dgf, dbf = layernorm_bwd(dHf, X2, q["gf"], muf, rstdf)
     else:
         dX2, dgf, dbf = dHf, np.zeros(H), np.zeros(H)
-    dc = dX2.sum(axis=0)
+    dZ2 = apply_keep(dX2, keep2, p_hidden)
+    dc = dZ2.sum(axis=0)
     for r in range(p):
         S = sh[r]
-        S["dB"] = S["y"].T @ dX2
-        S["dy"] = dX2 @ S["B"].T
+        S["dB"] = S["y"].T @ dZ2
+        S["dy"] = dZ2 @ S["B"].T
         S["dg"] = S["dy"] * gelu_grad(S["g"], spec.gelu_tanh)
         S["da"] = S["dg"].sum(axis=0)
         S["dA"] = U2.T @ S["dg"]
@@ -414,14 +457,15 @@ def sharded_reference(inp: Dict[str, np.ndarray], spec: Spec, p: int) -> Dict[st
     dU2 = sum(S["du2_partial"] for S in sh)
     dx1_ln, dg2, db2 = layernorm_bwd(dU2, X1, q["g2"], mu2, rstd2)
     dX1 = dX2 + dx1_ln
-    dbo = dX1.sum(axis=0)
+    dZ1 = apply_keep(dX1, keep1, p_hidden)
+    dbo = dZ1.sum(axis=0)
     for r in range(p):
         S = sh[r]
-        S["dWo"] = S["ctx"].T @ dX1
-        S["dctx"] = dX1 @ S["Wo"].T
+        S["dWo"] = S["ctx"].T @ dZ1
+        S["dctx"] = dZ1 @ S["Wo"].T
         Qr, Kr, Vr = S["qkv"][:, :Hl], S["qkv"][:, Hl:2 * Hl], S["qkv"][:, 2 * Hl:]
         dQ, dK, dV = attention_bwd(S["dctx"].reshape(b, s, Hl), Qr.reshape(b, s, Hl), Kr.reshape(b, s, Hl),
-                                   Vr.reshape(b, s, Hl), S["P"], lspec)
+                                   Vr.reshape(b, s, Hl), S["P"], lspec, ka(r), p_attn)
         S["dqkv"] = np.concatenate([dQ.reshape(T, Hl), dK.reshape(T, Hl), dV.reshape(T, Hl)], axis=1)
         S["dWqkv"] = U.T @ S["dqkv"]
         S["dbqkv"] = S["dqkv"].sum(axis=0)
@@ -431,7 +475,7 @@ def sharded_reference(inp: Dict[str, np.ndarray], spec: Spec, p: int) -> Dict[st
     dX = dX1 + dx_ln
     out.update(U=U, mu1=mu1, rstd1=rstd1, X1=X1, U2=U2, mu2=mu2, rstd2=rstd2, X2=X2, Hf=Hf,
                M=M, S=Ssum, tsum=tsum, ce=ce, loss=loss, dHf=dHf, dX2=dX2, dgf=dgf, dbf=dbf, dc=dc,
-               dU2=dU2, dg2=dg2, db2=db2, dX1=dX1, dbo=dbo, dU=dU, dg1=dg1, db1=db1, dX=dX, shards=sh)
+               dU2=dU2, dg2=dg2, db2=db2, dX1=dX1, dZ1=dZ1, dZ2=dZ2, dbo=dbo, dU=dU, dg1=dg1, db1=db1, dX=dX, shards=sh)
     if spec.final_ln:
         out.update(muf=muf, rstdf=rstdf)
     return out
