@@ -278,6 +278,107 @@ MLM_API int mlm_adamw_step_multi(int32_t dtype, int32_t n_tensors, const int64_t
                          const float* weight_decays, const float* total_sqnorm, float max_norm, float lr,
                          float beta1, float beta2, float eps, int32_t step, void* stream);
 
+/* ---- dropout with the two model-parallel random streams (Appendix B.2; Section 5: "a dropout of
+ *      0.1 is used") and the variants of the calls above that apply it ---------------------- */
+
+/* One dropout site.  The paper asks for two random streams: one seeded identically on every
+ * model-parallel worker for the dropouts OUTSIDE the model-parallel regions (embedding output, the two
+ * block outputs before their residual adds), so that the replicated tensors stay identical, and one
+ * seeded uniquely per worker for the dropout INSIDE the attention block.  It fixes neither the
+ * generator nor the seed rule; this library uses the counter-based Philox4x32-10 generator:
+ * element e (row-major index in the tensor this worker holds) reads 32-bit word e mod 4 of the block
+ * with counter (lo32(e/4), hi32(e/4), lo32(offset), hi32(offset)) under key (lo32(seed), hi32(seed)),
+ * and is kept iff that word >= floor(p 2^32); kept values are scaled by 1/(1-p).  The decision is
+ * integer work and reproducible from (seed, offset, e) alone. */
+typedef struct mlm_dropout {
+  float p;         /* drop probability, 0 <= p < 1 (MLM_E_SHAPE otherwise); 0 = identity            */
+  uint64_t seed;   /* stream seed, see mlm_rng_stream_seed                                          */
+  uint64_t offset; /* names the site (layer, call, training step); the caller keeps sites distinct  */
+} mlm_dropout;
+
+enum { MLM_STREAM_REPLICATED = 0, MLM_STREAM_MODEL_PARALLEL = 1 };
+
+/* Seed of a stream on worker r (host, integer): the replicated stream's seed is base_seed on every
+ * worker; worker r's model-parallel seed is base_seed + 1 + r (mod 2^64), distinct from the replicated
+ * one and from every other worker's.  seed: host pointer.  MLM_E_SHAPE for an unknown stream or r < 0. */
+MLM_API int mlm_rng_stream_seed(uint64_t base_seed, int32_t stream, int32_t r, uint64_t* seed);
+
+/* mlm_combine with dropout on the reduced block output (Section 3: "run dropout and residual connection
+ * on these tensors"):  out = residual + dropout(sum_i partials[i] + bias).  bias is [bias_rows, H]
+ * (row t uses bias row t mod bias_rows; bias_rows = 1 is the ordinary bias vector, bias_rows = s adds a
+ * position embedding) or NULL.  drop NULL or p = 0: no dropout.  Element index of the site: t H + column. */
+MLM_API int mlm_combine_dropout(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                        const void* bias, int32_t bias_rows, const mlm_dropout* drop, const void* residual,
+                        void* out, void* stream);
+
+/* mlm_combine_layernorm_fwd with dropout:  x_out = residual + dropout(sum_i partials[i] + bias), then the
+ * layer norm of x_out.  Other arguments as in mlm_combine_layernorm_fwd. */
+MLM_API int mlm_combine_layernorm_fwd_dropout(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                      const void* bias, const mlm_dropout* drop, const void* residual,
+                                      void* x_out, const void* gamma, const void* beta, void* y, float* mean,
+                                      float* rstd, void* stream);
+
+/* mlm_combine_layernorm_bwd for a layer norm whose input was formed WITH dropout
+ * (x = residual + dropout(z)): besides dx it emits dz_out = dropout-mask(dx) / (1-p), the gradient of the
+ * block output z before dropout ([T,H] dtype) -- the tensor the row-parallel GEMM's backward consumes --
+ * and dx_colsum becomes the column sums of dz_out (the gradient of the bias inside z).  drop must name
+ * the same site as the forward call (NULL or p = 0: dz_out = dx).  dz_out must not alias dx. */
+MLM_API int mlm_combine_layernorm_bwd_dropout(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                      const void* x, const void* gamma, const float* mean, const float* rstd,
+                                      const void* residual_grad, const mlm_dropout* drop, void* dy_out, void* dx,
+                                      void* dz_out, void* dgamma, void* dbeta, void* dx_colsum, void* ws,
+                                      size_t ws_bytes, void* stream);
+
+/* Number of 32-bit words of the keep-bit tensor mlm_attn_shard_fwd_dropout saves: [b, h_l, s, pitch] with
+ * pitch = 4 ceil(s / 128) words per query row (bit j mod 32 of word j / 32 = key j kept).  words: host. */
+MLM_API int mlm_attn_keep_words(const mlm_dims* dims, size_t* words);
+
+/* mlm_attn_shard_fwd with dropout on the attention probabilities (the dropout inside the model-parallel
+ * region; drop->seed is this worker's model-parallel stream):
+ *   ctx_r = (keep o softmax(...) / (1-p)) V;  lse_r is the log-sum-exp of the UNdropped scores.
+ * Element index of the site: ((batch h_l + local head) s + query) s + key; s must be a multiple of 4
+ * (MLM_E_ALIGN).  keep_bits_r: uint32 output of mlm_attn_keep_words words, saved for the backward call;
+ * only bits of allowed (query, key) pairs are defined. */
+MLM_API int mlm_attn_shard_fwd_dropout(const mlm_dims* dims, const void* u, const void* Wqkv_r, const void* bqkv_r,
+                               const void* Wo_r, const int32_t* key_len, const mlm_dropout* drop,
+                               void* qkv_r, void* ctx_r, float* lse_r, uint32_t* keep_bits_r, void* partial_r,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of mlm_attn_shard_fwd_dropout: as mlm_attn_shard_bwd, with the saved keep bits and the same
+ * drop->p (the generator is not run again). */
+MLM_API int mlm_attn_shard_bwd_dropout(const mlm_dims* dims, const void* dx1, const void* u, const void* Wqkv_r,
+                               const void* Wo_r, const int32_t* key_len, const mlm_dropout* drop,
+                               const void* qkv_r, const void* ctx_r, const float* lse_r,
+                               const uint32_t* keep_bits_r, void* dWqkv_r, void* dbqkv_r, void* dWo_r,
+                               void* du_partial_r, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- vocabulary-parallel input embedding (Section 3: the input embedding shares its weights with the
+ *      output embedding E [H, v] and is split along the vocabulary like it; "an all-reduce (g operator)
+ *      is required after the input embedding") ------------------------------------------------------ */
+
+/* Forward of shard r:  partial_r[t, :] = E_r[:, ids[t] - r V_l] if the id lies in the shard's range,
+ * else 0.  ids: [T] int32 GLOBAL ids in [0, V); E_r: [H, V_l] (the matrix of mlm_vocab_ce_shard_fwd);
+ * partial_r: [T,H] dtype; perm_r: [T] int32 output saved for the backward call -- the tokens in stable
+ * order of their local id (ids outside the shard last); integer work, exact.  The sort is a brute-force
+ * rank computation, O(T^2) comparisons: meant for T = b s of a few thousand to a few ten thousand.
+ * The partials are reduced with mlm_combine_dropout (bias = position embedding [s,H], bias_rows = s,
+ * drop = the replicated stream's embedding site). */
+MLM_API int mlm_embed_shard_fwd(const mlm_dims* dims, const int32_t* ids, const void* E_r, int32_t* perm_r,
+                        void* partial_r, void* stream);
+
+/* Replicated part of the embedding backward:  dz0 = dropout-mask(dx0) / (1-p)  (drop NULL: dz0 = dx0) and
+ * dpos[i, :] = sum over the batch of dz0[batch s + i, :]  ([s,H] dtype; NULL: not computed).
+ * dx0, dz0: [T,H] dtype; dz0 may alias dx0. */
+MLM_API int mlm_embed_bwd_replicated(const mlm_dims* dims, const void* dx0, const mlm_dropout* drop, void* dz0,
+                             void* dpos, void* stream);
+
+/* Backward of shard r:  dE_r[:, c] += sum over the tokens t with ids[t] - r V_l == c of dz0[t, :], added
+ * in token order (deterministic) ON TOP of what dE_r holds -- the output embedding's gradient from
+ * mlm_vocab_ce_shard_bwd, since the two embeddings are one parameter.  Columns no token names are left
+ * untouched.  perm_r: from mlm_embed_shard_fwd for the same ids. */
+MLM_API int mlm_embed_shard_bwd(const mlm_dims* dims, const int32_t* ids, const int32_t* perm_r, const void* dz0,
+                        void* dE_r, void* stream);
+
 /* ---- the GEMM building block (Section 3: "XA", "YB", "XE") --------------------- */
 
 /* C = op(A) op(B) (+ bias per column), row-major, fp32 accumulation.

@@ -21,7 +21,11 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmlm_shar
 EXPORTS = ("mlm_shard_range", "mlm_workspace_bytes", "mlm_status_string", "mlm_layernorm_fwd", "mlm_layernorm_bwd",
            "mlm_combine", "mlm_combine_layernorm_fwd", "mlm_combine_layernorm_bwd", "mlm_colsum", "mlm_attn_shard_fwd", "mlm_attn_shard_bwd", "mlm_mlp_shard_fwd",
            "mlm_mlp_shard_bwd", "mlm_vocab_ce_shard_fwd", "mlm_vocab_ce_merge", "mlm_vocab_ce_shard_bwd", "mlm_gemm", "mlm_grad_sqnorm",
-           "mlm_adamw_step", "mlm_adamw_step_multi")
+           "mlm_adamw_step", "mlm_adamw_step_multi", "mlm_rng_stream_seed", "mlm_combine_dropout",
+           "mlm_combine_layernorm_fwd_dropout", "mlm_combine_layernorm_bwd_dropout", "mlm_attn_keep_words",
+           "mlm_attn_shard_fwd_dropout", "mlm_attn_shard_bwd_dropout", "mlm_embed_shard_fwd", "mlm_embed_bwd_replicated",
+           "mlm_embed_shard_bwd")
+STREAM_REPLICATED, STREAM_MODEL_PARALLEL = 0, 1
 
 
 class MlmError(RuntimeError):
@@ -35,6 +39,19 @@ class Dims(ctypes.Structure):
                 ("F", ctypes.c_int32), ("V", ctypes.c_int32), ("p", ctypes.c_int32), ("r", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32), ("gelu_tanh", ctypes.c_int32),
                 ("ln_eps", ctypes.c_float)]
+
+
+class Dropout(ctypes.Structure):
+    """One dropout site: probability, stream seed (mlm_rng_stream_seed) and the 64-bit offset that names the site."""
+    _fields_ = [("p", ctypes.c_float), ("seed", ctypes.c_uint64), ("offset", ctypes.c_uint64)]
+
+
+def make_dropout(p: float, seed: int, offset: int) -> Dropout:
+    return Dropout(float(p), int(seed) & 0xFFFFFFFFFFFFFFFF, int(offset) & 0xFFFFFFFFFFFFFFFF)
+
+
+def _d(drop: Optional[Dropout]):
+    return ctypes.byref(drop) if drop is not None else ctypes.c_void_p(0)
 
 
 _lib = None
@@ -221,3 +238,70 @@ def mlm_adamw_step_multi(dtype, grads, masters, ms, vs, weights_out, weight_deca
     _chk(lib().mlm_adamw_step_multi(ctypes.c_int32(dtype), ctypes.c_int32(n), cnt, ptrs(grads), ptrs(masters), ptrs(ms),
                                     ptrs(vs), ptrs(weights_out), wds, _p(total_sqnorm), f(max_norm), f(lr), f(beta1),
                                     f(beta2), f(eps), ctypes.c_int32(step), _st(stream)), "mlm_adamw_step_multi")
+
+
+# ---- dropout (two random streams) and the input embedding -------------------------------------------------------
+def mlm_rng_stream_seed(base_seed: int, stream: int, r: int) -> int:
+    out = ctypes.c_uint64(0)
+    _chk(lib().mlm_rng_stream_seed(ctypes.c_uint64(base_seed & 0xFFFFFFFFFFFFFFFF), ctypes.c_int32(stream),
+                                   ctypes.c_int32(r), ctypes.byref(out)), "mlm_rng_stream_seed")
+    return out.value
+
+
+def mlm_combine_dropout(dims, partials, bias, bias_rows, drop, residual, out, stream=None):
+    arr, n = _partial_array(partials)
+    _chk(lib().mlm_combine_dropout(ctypes.byref(dims), arr, ctypes.c_int32(n), _p(bias), ctypes.c_int32(bias_rows),
+                                   _d(drop), _p(residual), _p(out), _st(stream)), "mlm_combine_dropout")
+
+
+def mlm_combine_layernorm_fwd_dropout(dims, partials, bias, drop, residual, x_out, gamma, beta, y, mean, rstd,
+                                      stream=None):
+    arr, n = _partial_array(partials)
+    _chk(lib().mlm_combine_layernorm_fwd_dropout(ctypes.byref(dims), arr, ctypes.c_int32(n), _p(bias), _d(drop),
+                                                 _p(residual), _p(x_out), _p(gamma), _p(beta), _p(y), _p(mean),
+                                                 _p(rstd), _st(stream)), "mlm_combine_layernorm_fwd_dropout")
+
+
+def mlm_combine_layernorm_bwd_dropout(dims, partials, x, gamma, mean, rstd, residual_grad, drop, dy_out, dx, dz_out,
+                                      dgamma, dbeta, dx_colsum, ws, stream=None):
+    arr, n = _partial_array(partials)
+    _chk(lib().mlm_combine_layernorm_bwd_dropout(ctypes.byref(dims), arr, ctypes.c_int32(n), _p(x), _p(gamma),
+                                                 _p(mean), _p(rstd), _p(residual_grad), _d(drop), _p(dy_out), _p(dx),
+                                                 _p(dz_out), _p(dgamma), _p(dbeta), _p(dx_colsum), *_ws(ws),
+                                                 _st(stream)), "mlm_combine_layernorm_bwd_dropout")
+
+
+def mlm_attn_keep_words(dims) -> int:
+    n = ctypes.c_size_t(0)
+    _chk(lib().mlm_attn_keep_words(ctypes.byref(dims), ctypes.byref(n)), "mlm_attn_keep_words")
+    return n.value
+
+
+def mlm_attn_shard_fwd_dropout(dims, u, Wqkv_r, bqkv_r, Wo_r, key_len, drop, qkv_r, ctx_r, lse_r, keep_bits_r,
+                               partial_r, ws=None, stream=None):
+    _chk(lib().mlm_attn_shard_fwd_dropout(ctypes.byref(dims), _p(u), _p(Wqkv_r), _p(bqkv_r), _p(Wo_r), _p(key_len),
+                                          _d(drop), _p(qkv_r), _p(ctx_r), _p(lse_r), _p(keep_bits_r), _p(partial_r),
+                                          *_ws(ws), _st(stream)), "mlm_attn_shard_fwd_dropout")
+
+
+def mlm_attn_shard_bwd_dropout(dims, dx1, u, Wqkv_r, Wo_r, key_len, drop, qkv_r, ctx_r, lse_r, keep_bits_r, dWqkv_r,
+                               dbqkv_r, dWo_r, du_partial_r, ws, stream=None):
+    _chk(lib().mlm_attn_shard_bwd_dropout(ctypes.byref(dims), _p(dx1), _p(u), _p(Wqkv_r), _p(Wo_r), _p(key_len),
+                                          _d(drop), _p(qkv_r), _p(ctx_r), _p(lse_r), _p(keep_bits_r), _p(dWqkv_r),
+                                          _p(dbqkv_r), _p(dWo_r), _p(du_partial_r), *_ws(ws), _st(stream)),
+         "mlm_attn_shard_bwd_dropout")
+
+
+def mlm_embed_shard_fwd(dims, ids, E_r, perm_r, partial_r, stream=None):
+    _chk(lib().mlm_embed_shard_fwd(ctypes.byref(dims), _p(ids), _p(E_r), _p(perm_r), _p(partial_r), _st(stream)),
+         "mlm_embed_shard_fwd")
+
+
+def mlm_embed_bwd_replicated(dims, dx0, drop, dz0, dpos, stream=None):
+    _chk(lib().mlm_embed_bwd_replicated(ctypes.byref(dims), _p(dx0), _d(drop), _p(dz0), _p(dpos), _st(stream)),
+         "mlm_embed_bwd_replicated")
+
+
+def mlm_embed_shard_bwd(dims, ids, perm_r, dz0, dE_r, stream=None):
+    _chk(lib().mlm_embed_shard_bwd(ctypes.byref(dims), _p(ids), _p(perm_r), _p(dz0), _p(dE_r), _st(stream)),
+         "mlm_embed_shard_bwd")

@@ -18,7 +18,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmlm_shard.so")
 
 SOURCES = ["api.hip", "rowops.hip", "gemm_f32.hip", "attention_f32.hip", "gemm_bf16.hip",
-           "gemm_bf16_fwd.hip", "gemm_bf16_dgrad.hip", "gemm_bf16_wgrad.hip", "attention_bf16.hip", "optimizer.hip"]
+           "gemm_bf16_fwd.hip", "gemm_bf16_dgrad.hip", "gemm_bf16_wgrad.hip", "attention_bf16.hip", "optimizer.hip", "embed.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

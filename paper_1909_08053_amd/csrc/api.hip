@@ -2,6 +2,7 @@
 // per-block kernel sequences.  Every device step runs in this library's own kernels.
 #include <string.h>
 #include "common.h"
+#include "rng.h"
 
 using namespace mlm;
 
@@ -187,7 +188,7 @@ MLM_API int mlm_combine(const mlm_dims* dims, const void* const* partials, int32
     if (!aligned16(partials[i])) return MLM_E_ALIGN;
   }
   if (!aligned16(out) || (bias && !aligned16(bias)) || (residual && !aligned16(residual))) return MLM_E_ALIGN;
-  return hip_status(launch_combine(dims->dtype, L.T, dims->H, partials, n_partials, bias, residual, out,
+  return hip_status(launch_combine(dims->dtype, L.T, dims->H, partials, n_partials, bias, 1, residual, out, nullptr,
                                    (hipStream_t)stream));
 }
 
@@ -201,30 +202,72 @@ static int check_partials(const void* const* partials, int32_t n) {
   return MLM_OK;
 }
 
-MLM_API int mlm_combine_layernorm_fwd(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
-                                      const void* bias, const void* residual, void* x_out, const void* gamma,
-                                      const void* beta, void* y, float* mean, float* rstd, void* stream) {
+static int check_drop(const mlm_dropout* drop) {
+  if (drop && !(drop->p >= 0.0f && drop->p < 1.0f)) return MLM_E_SHAPE;
+  return MLM_OK;
+}
+
+static int combine_layernorm_fwd_impl(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                      const void* bias, const mlm_dropout* drop, const void* residual, void* x_out,
+                                      const void* gamma, const void* beta, void* y, float* mean, float* rstd,
+                                      void* stream) {
   Local L;
   int rc = check_dims(dims, &L);
   if (rc) return rc;
   if ((rc = check_partials(partials, n_partials))) return rc;
+  if ((rc = check_drop(drop))) return rc;
   if (!x_out || !gamma || !beta || !y || !mean || !rstd) return MLM_E_NULL;
   if (!aligned16(x_out) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y) || (bias && !aligned16(bias)) ||
       (residual && !aligned16(residual)))
     return MLM_E_ALIGN;
   if ((rc = ln_supported(dims))) return rc;
   return hip_status(launch_combine_layernorm_fwd(dims->dtype, L.T, dims->H, dims->ln_eps, partials, n_partials, bias,
-                                                 residual, x_out, gamma, beta, y, mean, rstd, (hipStream_t)stream));
+                                                 residual, x_out, gamma, beta, y, mean, rstd, drop,
+                                                 (hipStream_t)stream));
 }
 
-MLM_API int mlm_combine_layernorm_bwd(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
-                                      const void* x, const void* gamma, const float* mean, const float* rstd,
-                                      const void* residual_grad, void* dy_out, void* dx, void* dgamma, void* dbeta,
-                                      void* dx_colsum, void* ws, size_t ws_bytes, void* stream) {
+MLM_API int mlm_combine_layernorm_fwd(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                      const void* bias, const void* residual, void* x_out, const void* gamma,
+                                      const void* beta, void* y, float* mean, float* rstd, void* stream) {
+  return combine_layernorm_fwd_impl(dims, partials, n_partials, bias, nullptr, residual, x_out, gamma, beta, y, mean,
+                                    rstd, stream);
+}
+
+MLM_API int mlm_combine_layernorm_fwd_dropout(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                              const void* bias, const mlm_dropout* drop, const void* residual,
+                                              void* x_out, const void* gamma, const void* beta, void* y, float* mean,
+                                              float* rstd, void* stream) {
+  return combine_layernorm_fwd_impl(dims, partials, n_partials, bias, drop, residual, x_out, gamma, beta, y, mean, rstd,
+                                    stream);
+}
+
+MLM_API int mlm_combine_dropout(const mlm_dims* dims, const void* const* partials, int32_t n_partials, const void* bias,
+                                int32_t bias_rows, const mlm_dropout* drop, const void* residual, void* out,
+                                void* stream) {
   Local L;
   int rc = check_dims(dims, &L);
   if (rc) return rc;
   if ((rc = check_partials(partials, n_partials))) return rc;
+  if ((rc = check_drop(drop))) return rc;
+  if (!out) return MLM_E_NULL;
+  if (bias && (bias_rows < 1 || bias_rows > L.T)) return MLM_E_SHAPE;
+  if (!aligned16(out) || (bias && !aligned16(bias)) || (residual && !aligned16(residual))) return MLM_E_ALIGN;
+  return hip_status(launch_combine(dims->dtype, L.T, dims->H, partials, n_partials, bias, bias ? bias_rows : 1,
+                                   residual, out, drop, (hipStream_t)stream));
+}
+
+static int combine_layernorm_bwd_impl(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                      const void* x, const void* gamma, const float* mean, const float* rstd,
+                                      const void* residual_grad, const mlm_dropout* drop, void* dy_out, void* dx,
+                                      void* dz_out, void* dgamma, void* dbeta, void* dx_colsum, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if ((rc = check_partials(partials, n_partials))) return rc;
+  if ((rc = check_drop(drop))) return rc;
+  if ((drop && drop->p > 0.0f && !dz_out) || (dz_out && dz_out == dx)) return MLM_E_NULL;
+  if (dz_out && !aligned16(dz_out)) return MLM_E_ALIGN;
   if (!x || !gamma || !mean || !rstd || !dx || !dgamma || !dbeta || !ws) return MLM_E_NULL;
   if (!aligned16(x) || !aligned16(gamma) || !aligned16(dx) || !aligned16(ws) ||
       (residual_grad && !aligned16(residual_grad)) || (dy_out && !aligned16(dy_out)))
@@ -233,7 +276,24 @@ MLM_API int mlm_combine_layernorm_bwd(const mlm_dims* dims, const void* const* p
   if (ws_bytes < ws_bytes_for(dims, L, MLM_WS_LAYERNORM_BWD)) return MLM_E_WORKSPACE;
   return hip_status(launch_combine_layernorm_bwd(dims->dtype, L.T, dims->H, partials, n_partials, x, gamma, mean, rstd,
                                                  residual_grad, dy_out, dx, dgamma, dbeta, dx_colsum, (float*)ws,
-                                                 (hipStream_t)stream));
+                                                 drop, dz_out, (hipStream_t)stream));
+}
+
+MLM_API int mlm_combine_layernorm_bwd(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                      const void* x, const void* gamma, const float* mean, const float* rstd,
+                                      const void* residual_grad, void* dy_out, void* dx, void* dgamma, void* dbeta,
+                                      void* dx_colsum, void* ws, size_t ws_bytes, void* stream) {
+  return combine_layernorm_bwd_impl(dims, partials, n_partials, x, gamma, mean, rstd, residual_grad, nullptr, dy_out, dx,
+                                    nullptr, dgamma, dbeta, dx_colsum, ws, ws_bytes, stream);
+}
+
+MLM_API int mlm_combine_layernorm_bwd_dropout(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
+                                              const void* x, const void* gamma, const float* mean, const float* rstd,
+                                              const void* residual_grad, const mlm_dropout* drop, void* dy_out,
+                                              void* dx, void* dz_out, void* dgamma, void* dbeta, void* dx_colsum,
+                                              void* ws, size_t ws_bytes, void* stream) {
+  return combine_layernorm_bwd_impl(dims, partials, n_partials, x, gamma, mean, rstd, residual_grad, drop, dy_out, dx,
+                                    dz_out, dgamma, dbeta, dx_colsum, ws, ws_bytes, stream);
 }
 
 MLM_API int mlm_colsum(const mlm_dims* dims, const void* dy, void* dbias, void* ws, size_t ws_bytes, void* stream) {
@@ -246,12 +306,29 @@ MLM_API int mlm_colsum(const mlm_dims* dims, const void* dy, void* dbias, void* 
   return hip_status(launch_colsum(dims->dtype, L.T, dims->H, dy, dbias, (float*)ws, (hipStream_t)stream));
 }
 
-MLM_API int mlm_attn_shard_fwd(const mlm_dims* dims, const void* u, const void* Wqkv_r, const void* bqkv_r, const void* Wo_r,
-                       const int32_t* key_len, void* qkv_r, void* ctx_r, float* lse_r, void* partial_r, void* ws,
-                       size_t ws_bytes, void* stream) {
+static int keep_pitch_words(int s) { return 4 * ((s + 127) / 128); }
+
+// dropout of the attention probabilities requested and active (p > 0)?  Validates the extra arguments.
+static int check_attn_drop(const mlm_dims* dims, const mlm_dropout* drop, const void* keep_bits, bool* active) {
+  *active = false;
+  int rc = check_drop(drop);
+  if (rc) return rc;
+  if (!drop || drop->p <= 0.0f) return MLM_OK;
+  if (!keep_bits) return MLM_E_NULL;
+  if (dims->s % 4 != 0 || !aligned16(keep_bits)) return MLM_E_ALIGN;
+  *active = true;
+  return MLM_OK;
+}
+
+static int attn_shard_fwd_impl(const mlm_dims* dims, const void* u, const void* Wqkv_r, const void* bqkv_r,
+                               const void* Wo_r, const int32_t* key_len, const mlm_dropout* drop, void* qkv_r,
+                               void* ctx_r, float* lse_r, uint32_t* keep_bits_r, void* partial_r, void* ws,
+                               size_t ws_bytes, void* stream) {
   Local L;
   int rc = check_dims(dims, &L);
   if (rc) return rc;
+  bool dropping;
+  if ((rc = check_attn_drop(dims, drop, keep_bits_r, &dropping))) return rc;
   if (!u || !Wqkv_r || !Wo_r || !qkv_r || !ctx_r || !lse_r || !partial_r) return MLM_E_NULL;
   if (!aligned16(u) || !aligned16(Wqkv_r) || !aligned16(Wo_r) || !aligned16(qkv_r) || !aligned16(ctx_r) ||
       !aligned16(partial_r) || (bqkv_r && !aligned16(bqkv_r)))
@@ -269,17 +346,55 @@ MLM_API int mlm_attn_shard_fwd(const mlm_dims* dims, const void* u, const void* 
   memset(&a, 0, sizeof(a));
   a.b = dims->b; a.s = dims->s; a.hl = L.hl; a.d = L.d; a.causal = dims->causal; a.key_len = key_len;
   a.qkv = qkv_r; a.ctx = ctx_r; a.lse = lse_r;
+  a.drop = make_drop_args(dropping ? drop : nullptr);
+  a.keep_bits = keep_bits_r; a.keep_pitch = keep_pitch_words(dims->s);
   MLM_TRY_HIP(dt == MLM_BF16 ? launch_attn_fwd_bf16(a, st) : launch_attn_fwd_f32(a, st));
   MLM_TRY_HIP(run_gemm(dt, gemm_fwd(L.T, dims->H, L.Hl, ctx_r, Wo_r, partial_r), st, sk));
   return MLM_OK;
 }
 
-MLM_API int mlm_attn_shard_bwd(const mlm_dims* dims, const void* dx1, const void* u, const void* Wqkv_r, const void* Wo_r,
-                       const int32_t* key_len, const void* qkv_r, const void* ctx_r, const float* lse_r, void* dWqkv_r,
-                       void* dbqkv_r, void* dWo_r, void* du_partial_r, void* ws, size_t ws_bytes, void* stream) {
+MLM_API int mlm_attn_shard_fwd(const mlm_dims* dims, const void* u, const void* Wqkv_r, const void* bqkv_r, const void* Wo_r,
+                       const int32_t* key_len, void* qkv_r, void* ctx_r, float* lse_r, void* partial_r, void* ws,
+                       size_t ws_bytes, void* stream) {
+  return attn_shard_fwd_impl(dims, u, Wqkv_r, bqkv_r, Wo_r, key_len, nullptr, qkv_r, ctx_r, lse_r, nullptr, partial_r, ws,
+                             ws_bytes, stream);
+}
+
+MLM_API int mlm_attn_shard_fwd_dropout(const mlm_dims* dims, const void* u, const void* Wqkv_r, const void* bqkv_r,
+                                       const void* Wo_r, const int32_t* key_len, const mlm_dropout* drop, void* qkv_r,
+                                       void* ctx_r, float* lse_r, uint32_t* keep_bits_r, void* partial_r, void* ws,
+                                       size_t ws_bytes, void* stream) {
+  return attn_shard_fwd_impl(dims, u, Wqkv_r, bqkv_r, Wo_r, key_len, drop, qkv_r, ctx_r, lse_r, keep_bits_r, partial_r,
+                             ws, ws_bytes, stream);
+}
+
+MLM_API int mlm_attn_keep_words(const mlm_dims* dims, size_t* words) {
+  if (!words) return MLM_E_NULL;
   Local L;
   int rc = check_dims(dims, &L);
   if (rc) return rc;
+  *words = (size_t)dims->b * L.hl * dims->s * keep_pitch_words(dims->s);
+  return MLM_OK;
+}
+
+MLM_API int mlm_rng_stream_seed(uint64_t base_seed, int32_t stream, int32_t r, uint64_t* seed) {
+  if (!seed) return MLM_E_NULL;
+  if (r < 0) return MLM_E_SHAPE;
+  if (stream == MLM_STREAM_REPLICATED) { *seed = base_seed; return MLM_OK; }
+  if (stream == MLM_STREAM_MODEL_PARALLEL) { *seed = base_seed + 1ull + (uint64_t)r; return MLM_OK; }
+  return MLM_E_SHAPE;
+}
+
+static int attn_shard_bwd_impl(const mlm_dims* dims, const void* dx1, const void* u, const void* Wqkv_r,
+                               const void* Wo_r, const int32_t* key_len, const mlm_dropout* drop, const void* qkv_r,
+                               const void* ctx_r, const float* lse_r, const uint32_t* keep_bits_r, void* dWqkv_r,
+                               void* dbqkv_r, void* dWo_r, void* du_partial_r, void* ws, size_t ws_bytes,
+                               void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  bool dropping;
+  if ((rc = check_attn_drop(dims, drop, keep_bits_r, &dropping))) return rc;
   if (!dx1 || !u || !Wqkv_r || !Wo_r || !qkv_r || !ctx_r || !lse_r || !dWqkv_r || !dbqkv_r || !dWo_r ||
       !du_partial_r || !ws)
     return MLM_E_NULL;
@@ -308,12 +423,30 @@ MLM_API int mlm_attn_shard_bwd(const mlm_dims* dims, const void* dx1, const void
   a.b = dims->b; a.s = dims->s; a.hl = L.hl; a.d = L.d; a.causal = dims->causal; a.key_len = key_len;
   a.qkv = qkv_r; a.ctx = const_cast<void*>(ctx_r); a.lse = const_cast<float*>(lse_r);
   a.dctx = dctx; a.dqkv = dqkv; a.delta = delta;
+  a.drop = make_drop_args(dropping ? drop : nullptr);
+  a.keep_bits = const_cast<uint32_t*>(keep_bits_r); a.keep_pitch = keep_pitch_words(dims->s);
   MLM_TRY_HIP(dt == MLM_BF16 ? launch_attn_bwd_bf16(a, st) : launch_attn_bwd_f32(a, st));
   // QKV projection: dWqkv_r = u^T dqkv, dbqkv_r = column sums, du_partial_r = dqkv Wqkv_r^T
   MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, 3 * L.Hl, L.T, u, dqkv, dWqkv_r), st, sk));
   MLM_TRY_HIP(launch_colsum(dt, L.T, 3 * L.Hl, dqkv, dbqkv_r, csws, st));
   MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, 3 * L.Hl, dqkv, Wqkv_r, du_partial_r), st, sk));
   return MLM_OK;
+}
+
+MLM_API int mlm_attn_shard_bwd(const mlm_dims* dims, const void* dx1, const void* u, const void* Wqkv_r, const void* Wo_r,
+                       const int32_t* key_len, const void* qkv_r, const void* ctx_r, const float* lse_r, void* dWqkv_r,
+                       void* dbqkv_r, void* dWo_r, void* du_partial_r, void* ws, size_t ws_bytes, void* stream) {
+  return attn_shard_bwd_impl(dims, dx1, u, Wqkv_r, Wo_r, key_len, nullptr, qkv_r, ctx_r, lse_r, nullptr, dWqkv_r, dbqkv_r,
+                             dWo_r, du_partial_r, ws, ws_bytes, stream);
+}
+
+MLM_API int mlm_attn_shard_bwd_dropout(const mlm_dims* dims, const void* dx1, const void* u, const void* Wqkv_r,
+                                       const void* Wo_r, const int32_t* key_len, const mlm_dropout* drop,
+                                       const void* qkv_r, const void* ctx_r, const float* lse_r,
+                                       const uint32_t* keep_bits_r, void* dWqkv_r, void* dbqkv_r, void* dWo_r,
+                                       void* du_partial_r, void* ws, size_t ws_bytes, void* stream) {
+  return attn_shard_bwd_impl(dims, dx1, u, Wqkv_r, Wo_r, key_len, drop, qkv_r, ctx_r, lse_r, keep_bits_r, dWqkv_r,
+                             dbqkv_r, dWo_r, du_partial_r, ws, ws_bytes, stream);
 }
 
 MLM_API int mlm_mlp_shard_fwd(const mlm_dims* dims, const void* u2, const void* A_r, const void* a_r, const void* B_r,
@@ -444,6 +577,42 @@ MLM_API int mlm_vocab_ce_shard_bwd(const mlm_dims* dims, const void* hf, const v
   MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, L.Vl, L.T, hf, dL, dE_r), st, sk));
   MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, L.Vl, dL, E_r, dhf_partial_r), st, sk));
   return MLM_OK;
+}
+
+MLM_API int mlm_embed_shard_fwd(const mlm_dims* dims, const int32_t* ids, const void* E_r, int32_t* perm_r,
+                                void* partial_r, void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if (!ids || !E_r || !perm_r || !partial_r) return MLM_E_NULL;
+  if (!aligned16(E_r) || !aligned16(partial_r)) return MLM_E_ALIGN;
+  return hip_status(launch_embed_fwd(dims->dtype, L.T, dims->H, L.Vl, dims->r * L.Vl, ids, E_r, perm_r, partial_r,
+                                     (hipStream_t)stream));
+}
+
+MLM_API int mlm_embed_bwd_replicated(const mlm_dims* dims, const void* dx0, const mlm_dropout* drop, void* dz0,
+                                     void* dpos, void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if ((rc = check_drop(drop))) return rc;
+  if (!dx0 || (!dz0 && !dpos)) return MLM_E_NULL;
+  if (drop && drop->p > 0.0f && !dz0) return MLM_E_NULL;
+  if (!aligned16(dx0) || (dz0 && !aligned16(dz0)) || (dpos && !aligned16(dpos))) return MLM_E_ALIGN;
+  return hip_status(launch_embed_bwd_replicated(dims->dtype, dims->b, dims->s, dims->H, dx0, dz0, dpos, drop,
+                                                (hipStream_t)stream));
+}
+
+MLM_API int mlm_embed_shard_bwd(const mlm_dims* dims, const int32_t* ids, const int32_t* perm_r, const void* dz0,
+                                void* dE_r, void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if (!ids || !perm_r || !dz0 || !dE_r) return MLM_E_NULL;
+  if (!aligned16(dz0) || !aligned16(dE_r)) return MLM_E_ALIGN;
+  if ((rc = ln_supported(dims))) return rc;          // same row-width limit as the layer-norm kernels
+  return hip_status(launch_embed_bwd(dims->dtype, L.T, dims->H, L.Vl, dims->r * L.Vl, ids, perm_r, dz0, dE_r,
+                                     (hipStream_t)stream));
 }
 
 MLM_API int mlm_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K, const void* A,

@@ -12,7 +12,16 @@
 // with k along the sequence axis is fetched from the same LDS tile with the transposing read instruction.
 //
 // Mask: allowed(i, j) = (j < key_len[b]) && (!causal || j <= i); excluded entries get probability exactly 0.
+//
+// Dropout of the probabilities (DROP instantiations): the forward kernel draws the keep decision of element
+// ((batch, head, i), j) from the counter-based generator -- a lane's 16 scores of a 32-key half tile are four runs of
+// four consecutive keys, i.e. four generator blocks -- zeroes the dropped probabilities before the second MFMA, folds
+// 1 / (1 - p) into the final normalisation and saves the decisions as one bit per key.  The row sum and the
+// log-sum-exp stay those of the undropped scores.  The backward kernels read the saved bits instead of running the
+// generator again: dQ loads its query row's two words per tile, dK/dV gets the tile's 64 x 128-bit block through the
+// DMA ring.  delta = rowsum(dO o O) needs no change: O already contains the dropout.
 #include "lds_dma.h"
+#include "rng.h"
 
 namespace mlm {
 
@@ -106,7 +115,7 @@ template <int D> constexpr int dkv_dsplit() { return D >= 128 ? 2 : 1; }
 
 // (two waves per SIMD requested: with at most 256 registers per lane the MFMA accumulators live in ordinary VGPRs, so
 // the softmax arithmetic needs no accumulator-register moves)
-template <int D>
+template <int D, bool DROP>
 __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(AttnArgs a) {
   typedef ATile<D> TL;
   constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW;   // LPT: copies per tile and wave (K + V)
@@ -137,6 +146,7 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(A
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
   float m = -INFINITY, lsum = 0.f;
+  const size_t prow = ((size_t)bi * a.hl + hd) * a.s + min(qi, a.s - 1);   // row of the [b, hl, s, s] probabilities
   int kv_end = klen;
   if (a.causal) kv_end = min(kv_end, q0 + BQ);
   const int nt = (kv_end + ATILE - 1) / ATILE;
@@ -225,6 +235,21 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(A
       m = mn;
     }
     lsum += lsum_t;
+    if (DROP) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        uint32_t word = 0;                       // this lane's 16 of the 32 keep bits of keys k0 + 32 kt ..
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint32_t k4 = drop_keep4(a.drop, (prow * a.s + k0 + kt * 32 + 8 * g + 4 * lh) >> 2);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sacc[kt][4 * g + e] = ((k4 >> e) & 1u) ? sacc[kt][4 * g + e] : 0.f;
+          word |= k4 << (8 * g + 4 * lh);
+        }
+        word |= __shfl_xor(word, 32, 64);        // the other half-wave holds the other 16 bits
+        if (lh == kt && qi < a.s) a.keep_bits[prow * a.keep_pitch + (k0 >> 5) + kt] = word;
+      }
+    }
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const bf16x8 pf = pack8(sacc[c >> 1], 8 * (c & 1));
@@ -261,7 +286,7 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(A
   }
   lsum += __shfl_xor(lsum, 32, 64);
   if (qi < a.s) {
-    const float inv = 1.0f / lsum;
+    const float inv = (DROP ? a.drop.scale : 1.0f) / lsum;
     bf16* crow = (bf16*)a.ctx + ((size_t)bi * a.s + qi) * (a.hl * D) + hd * D;
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
@@ -281,7 +306,7 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(A
 // P = exp2(S sc - lse), dS = P o (dP - delta), dQ^T += K^T dS^T with K read a second time through the transposing
 // loads.  delta_i = sum_d dO_id O_id is computed here from the rows the lanes already hold and stored for the
 // dK/dV kernel, which runs after this one.
-template <int D>
+template <int D, bool DROP>
 __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   typedef ATile<D> TL;
   constexpr int BQ = 32 * ANW, STAGE = 2 * TL::BYTES, LPT = 2 * TL::QPW, NST = group_stages<D>(), NG = attn_groups<D>();
@@ -315,6 +340,7 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
     dl += __shfl_xor(dl, 32, 64);
   }
   const float lse2 = a.lse[((size_t)bi * a.hl + hd) * a.s + qc] * kLog2e;
+  const uint32_t* kbrow = DROP ? a.keep_bits + (((size_t)bi * a.hl + hd) * a.s + qc) * a.keep_pitch : nullptr;
   if (grp == 0 && lh == 0 && qi < a.s) {          // for the dK/dV kernel: [0] delta, [1] log-sum-exp in log2 units
     a.delta[((size_t)bi * a.hl + hd) * a.s + qi] = dl;
     a.delta[(size_t)a.b * a.hl * a.s + ((size_t)bi * a.hl + hd) * a.s + qi] = lse2;
@@ -358,6 +384,8 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
     const unsigned char* sV = sK + TL::BYTES;
     stage = stage == NST - 1 ? 0 : stage + 1;
     if (t >= nt || (a.causal && k0 > qw0 + 31)) continue;
+    uint2 kw = make_uint2(0xFFFFFFFFu, 0xFFFFFFFFu);          // keep bits of this query row, keys k0 .. k0 + 63
+    if (DROP) kw = *reinterpret_cast<const uint2*>(kbrow + (k0 >> 5));
     floatx16 sacc[2], pacc[2];
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
@@ -372,6 +400,16 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
         pacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sV, kt * 32, ks, lane), dof[ks], pacc[kt], 0, 0, 0);  // dP^T[key][query]
       }
     const bool need_mask = (a.causal && k0 + ATILE - 1 > qw0) || (k0 + ATILE > klen);   // wave-uniform
+    if (DROP) {
+      // gradient w.r.t. the undropped probability: keep o dP / (1 - p)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        const uint32_t w = (kt == 0 ? kw.x : kw.y) >> (4 * lh);
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          pacc[kt][e] = ((w >> (8 * (e >> 2) + (e & 3))) & 1u) ? pacc[kt][e] * a.drop.scale : 0.f;
+      }
+    }
     if (need_mask) {
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
@@ -437,11 +475,12 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
 // time through the transposing loads.
 // (No two-waves-per-SIMD request here: with the 256-register cap the dK / dV accumulators spill, which was measured
 // twice as slow as letting them live in the accumulation registers.)
-template <int D>
+template <int D, bool DROP>
 __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   typedef ATile<D> TL;
   constexpr int BKB = 32 * ANW, VEC = 2 * ATILE * 4;          // VEC: bytes of the lse + delta vectors of a tile
-  constexpr int STAGE = 2 * TL::BYTES + VEC, LPT = 2 * TL::QPW + 1;
+  constexpr int KBB = DROP ? ATILE * 16 : 0;                  // keep bits of the tile: 64 queries x 128 keys
+  constexpr int STAGE = 2 * TL::BYTES + VEC + KBB, LPT = 2 * TL::QPW + 1 + (DROP ? 1 : 0);
   // Large heads: the dK / dV accumulators of all D columns plus the owned K / V rows do not fit the register file
   // (they spilled: 2.3x / 5.6x the d = 96 time at d = 128 / 192).  Two workgroups then share a key block, each
   // accumulating one half of the D columns of dK and dV (the scores are computed by both); this also doubles the
@@ -496,6 +535,13 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
     src.issue(dOb, ldo, r0, a.s, sb + TL::BYTES, wave);
     // waves 0, 2 copy the delta vector, waves 1, 3 the log-sum-exp vector (same data twice: uniform copy counts)
     dma4(vec_b + min(r0 + lane, a.s - 1), sb + 2 * TL::BYTES + (wave & 1) * (ATILE * 4));
+    if (DROP) {
+      // lane t copies the four words of query r0 + t that cover this block's 128 keys (every wave copies the same
+      // kilobyte: uniform copy counts)
+      const uint32_t* src_bits = a.keep_bits + (((size_t)bi * a.hl + hd) * a.s + min(r0 + lane, a.s - 1)) * a.keep_pitch +
+                                 (kb0 >> 5);
+      dma16(reinterpret_cast<const bf16*>(src_bits), sb + 2 * TL::BYTES + VEC);
+    }
   };
   if (nt > 0) {
 #pragma unroll
@@ -511,6 +557,7 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
     const unsigned char* sdO = sQ + TL::BYTES;
     const float* sDl = reinterpret_cast<const float*>(sdO + TL::BYTES);
     const float* sLse = sDl + ATILE;
+    const uint32_t* sBits = reinterpret_cast<const uint32_t*>(sLse + ATILE);   // [64 queries][4 words]
     stage = stage == ANST - 1 ? 0 : stage + 1;
     if (a.causal && q0 + ATILE - 1 < kw0) continue;   // every query of the tile precedes this wave's keys
     const bool need_mask = (a.causal && q0 < kw0 + 31) || (kw0 + 32 > klen) || (q0 + ATILE > a.s);   // wave-uniform
@@ -538,8 +585,14 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
             const int q = q0 + qoff + e;
             p = (kj >= klen || q >= a.s || (a.causal && kj > q)) ? 0.f : p;
           }
-          sacc[4 * g + e] = p;                                // P
-          pacc[4 * g + e] = p * (pacc[4 * g + e] - dv4[e]);   // dS
+          if (DROP) {
+            const bool keep = (sBits[(qoff + e) * 4 + wave] >> l32) & 1u;
+            sacc[4 * g + e] = keep ? p * a.drop.scale : 0.f;                                       // dropped P (for dV)
+            pacc[4 * g + e] = p * ((keep ? pacc[4 * g + e] * a.drop.scale : 0.f) - dv4[e]);        // dS
+          } else {
+            sacc[4 * g + e] = p;                                // P
+            pacc[4 * g + e] = p * (pacc[4 * g + e] - dv4[e]);   // dS
+          }
         }
       }
 #pragma unroll
@@ -578,41 +631,52 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
 // ------------------------------------------------------------------------------------------ launchers
 bool attn_bf16_supported(int d) { return d == 64 || d == 96 || d == 128 || d == 192; }
 
-template <int D>
-static hipError_t launch_fwd_d(const AttnArgs& a, hipStream_t st) {
+template <int D, bool DROP>
+static hipError_t launch_fwd_dd(const AttnArgs& a, hipStream_t st) {
   const size_t lds = (size_t)attn_groups<D>() * group_stages<D>() * 2 * ATile<D>::BYTES;
   if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds);
+    hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_bf16_kernel<D, DROP>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
   dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
-  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D>), grid, dim3(attn_groups<D>() * ANT), lds, st, a);
+  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, DROP>), grid, dim3(attn_groups<D>() * ANT), lds, st, a);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_fwd_d(const AttnArgs& a, hipStream_t st) {
+  return a.drop.enabled ? launch_fwd_dd<D, true>(a, st) : launch_fwd_dd<D, false>(a, st);
+}
+
+template <int D, bool DROP>
+static hipError_t launch_bwd_dd(const AttnArgs& a, hipStream_t st) {
+  dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
+  const size_t lds_q = (size_t)attn_groups<D>() * group_stages<D>() * 2 * ATile<D>::BYTES;
+  hipError_t e;
+  if (lds_q > 64 * 1024) {
+    e = hipFuncSetAttribute((const void*)attn_bwd_dq_bf16_kernel<D, DROP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_q);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D, DROP>), grid, dim3(attn_groups<D>() * ANT), lds_q, st, a);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t lds_kv = (size_t)ANST * (2 * ATile<D>::BYTES + 2 * ATILE * 4 + (DROP ? ATILE * 16 : 0));
+  static_assert((size_t)ANST * (2 * ATile<D>::BYTES + 2 * ATILE * 4 + ATILE * 16) <= 160 * 1024, "LDS budget");
+  if (lds_kv > 64 * 1024) {
+    e = hipFuncSetAttribute((const void*)attn_bwd_dkv_bf16_kernel<D, DROP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_kv);
+    if (e != hipSuccess) return e;
+  }
+  dim3 grid_kv(grid.x * dkv_dsplit<D>(), grid.y, grid.z);
+  hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D, DROP>), grid_kv, dim3(ANT), lds_kv, st, a);
   return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_bwd_d(const AttnArgs& a, hipStream_t st) {
-  dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
-  const size_t lds_q = (size_t)attn_groups<D>() * group_stages<D>() * 2 * ATile<D>::BYTES;
-  hipError_t e;
-  if (lds_q > 64 * 1024) {
-    e = hipFuncSetAttribute((const void*)attn_bwd_dq_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_q);
-    if (e != hipSuccess) return e;
-  }
-  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D>), grid, dim3(attn_groups<D>() * ANT), lds_q, st, a);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const size_t lds_kv = (size_t)ANST * (2 * ATile<D>::BYTES + 2 * ATILE * 4);
-  if (lds_kv > 64 * 1024) {
-    e = hipFuncSetAttribute((const void*)attn_bwd_dkv_bf16_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_kv);
-    if (e != hipSuccess) return e;
-  }
-  dim3 grid_kv(grid.x * dkv_dsplit<D>(), grid.y, grid.z);
-  hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D>), grid_kv, dim3(ANT), lds_kv, st, a);
-  return hipGetLastError();
+  return a.drop.enabled ? launch_bwd_dd<D, true>(a, st) : launch_bwd_dd<D, false>(a, st);
 }
 
 hipError_t launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t st) {

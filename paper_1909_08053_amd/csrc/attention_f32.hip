@@ -5,7 +5,11 @@
 // tiles are staged through LDS and read as broadcasts.
 // Masking follows the integer predicate allowed(i,j) = (j < key_len[b]) && (!causal || j <= i);
 // excluded keys contribute exactly zero.
+// Dropout of the probabilities (a.drop.enabled): the forward kernel draws the keep decision of element
+// ((batch, head, i), j) from the counter-based generator, saves it as one bit per key and uses p_ij keep / (1 - p) in
+// C = P V; the row sum and the log-sum-exp stay those of the undropped scores.  The backward kernels read the bits.
 #include "common.h"
+#include "rng.h"
 
 namespace mlm {
 
@@ -34,6 +38,7 @@ __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(AttnArgs a) {
   float m = -INFINITY, l = 0.f;
   int kend = klen;
   if (a.causal) kend = min(kend, min(a.s, blockIdx.x * 64 + 64));
+  const size_t row = ((size_t)bi * a.hl + hd) * a.s + (active ? i : 0);   // row of the [b, hl, s, s] probability tensor
   for (int k0 = 0; k0 < kend; k0 += AF_TILE) {
     for (int e = lane; e < AF_TILE * D; e += 64) {
       const int j = e / D, c = e % D;
@@ -43,6 +48,13 @@ __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(AttnArgs a) {
     }
     __syncthreads();
     if (active) {
+      uint32_t bits = 0xFFFFFFFFu;                  // keep bits of keys k0 .. k0 + 31
+      if (a.drop.enabled) {
+        bits = 0;
+#pragma unroll
+        for (int g = 0; g < AF_TILE / 4; ++g) bits |= drop_keep4(a.drop, (row * a.s + k0 + 4 * g) >> 2) << (4 * g);
+        a.keep_bits[row * a.keep_pitch + k0 / 32] = bits;
+      }
       for (int j = 0; j < AF_TILE; ++j) {
         const int key = k0 + j;
         if (key >= klen || (a.causal && key > i)) continue;
@@ -54,15 +66,16 @@ __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(AttnArgs a) {
         const float corr = expf(m - mn);
         const float p = expf(sc - mn);
         l = l * corr + p;
+        const float pd = ((bits >> j) & 1u) ? p : 0.f;
 #pragma unroll
-        for (int c = 0; c < D; ++c) o[c] = o[c] * corr + p * sV[j * D + c];
+        for (int c = 0; c < D; ++c) o[c] = o[c] * corr + pd * sV[j * D + c];
         m = mn;
       }
     }
     __syncthreads();
   }
   if (active) {
-    const float inv = 1.0f / l;
+    const float inv = a.drop.scale / l;
     float* ctx = (float*)a.ctx;
 #pragma unroll
     for (int c = 0; c < D; ++c) ctx[(tok0 + i) * (a.hl * D) + hd * D + c] = o[c] * inv;
@@ -96,6 +109,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_f32_kernel(AttnArgs a) {
   }
   const float lse = active ? a.lse[((size_t)bi * a.hl + hd) * a.s + i] : 0.f;
   const float dl = active ? a.delta[((size_t)bi * a.hl + hd) * a.s + i] : 0.f;
+  const size_t row = ((size_t)bi * a.hl + hd) * a.s + (active ? i : 0);
   int kend = klen;
   if (a.causal) kend = min(kend, min(a.s, blockIdx.x * 64 + 64));
   for (int k0 = 0; k0 < kend; k0 += AF_TILE) {
@@ -107,6 +121,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_f32_kernel(AttnArgs a) {
     }
     __syncthreads();
     if (active) {
+      const uint32_t bits = a.drop.enabled ? a.keep_bits[row * a.keep_pitch + k0 / 32] : 0xFFFFFFFFu;
       for (int j = 0; j < AF_TILE; ++j) {
         const int key = k0 + j;
         if (key >= klen || (a.causal && key > i)) continue;
@@ -116,6 +131,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_f32_kernel(AttnArgs a) {
           sc = fmaf(q[c], sK[j * D + c], sc);
           dp = fmaf(sdO[lane * (D + 1) + c], sV[j * D + c], dp);
         }
+        dp = ((bits >> j) & 1u) ? dp * a.drop.scale : 0.f;     // gradient w.r.t. the undropped probability
         const float p = expf(sc * scale - lse);
         const float ds = p * (dp - dl);
 #pragma unroll
@@ -185,10 +201,17 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_f32_kernel(AttnArgs a) {
           dp = fmaf(sdO[ii * D + c], sVj[lane * (D + 1) + c], dp);
         }
         const float p = expf(sc * scale - sLse[ii]);
+        float keep = 1.0f;
+        if (a.drop.enabled) {
+          const size_t row = ((size_t)bi * a.hl + hd) * a.s + i;
+          keep = ((a.keep_bits[row * a.keep_pitch + (j >> 5)] >> (j & 31)) & 1u) ? a.drop.scale : 0.f;
+        }
+        dp *= keep;
         const float ds = p * (dp - sDl[ii]);
+        const float pd = p * keep;
 #pragma unroll
         for (int c = 0; c < D; ++c) {
-          dv[c] = fmaf(p, sdO[ii * D + c], dv[c]);
+          dv[c] = fmaf(pd, sdO[ii * D + c], dv[c]);
           dk[c] = fmaf(ds, sQ[ii * D + c], dk[c]);
         }
       }

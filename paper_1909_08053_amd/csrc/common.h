@@ -106,6 +106,15 @@ int gemm_bf16_ce_col_tiles(int M, int N, int K);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t st);
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t st);
 
+// ---- dropout site as the kernels see it (rng.h holds the generator) ---------------
+struct DropArgs {
+  uint32_t k0, k1;          // key: the stream seed
+  uint32_t off_lo, off_hi;  // site offset: counter words 2 and 3
+  uint32_t thr;             // keep iff word >= thr = floor(p 2^32)
+  float scale;              // 1 / (1 - p)
+  int enabled;              // 0: identity (p == 0 or no dropout requested)
+};
+
 // ---- attention ------------------------------------------------------------------
 struct AttnArgs {
   int b, s, hl, d;          // batch, sequence, local heads, head size
@@ -117,6 +126,10 @@ struct AttnArgs {
   const void* dctx;         // bwd: [T, hl*d]
   void* dqkv;               // bwd out: [T, 3*hl*d]
   float* delta;             // bwd scratch: [b, hl, s]
+  // dropout of the probabilities: forward draws the mask and saves it as bits, backward reads the bits
+  DropArgs drop;            // enabled = 0: no dropout
+  uint32_t* keep_bits;      // [b, hl, s, keep_pitch] words; bit (j % 32) of word j / 32 of row (b, head, i): key j kept
+  int keep_pitch;           // words per query row: 4 ceil(s / 128)
 };
 bool attn_bf16_supported(int d);
 hipError_t launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t st);
@@ -139,14 +152,18 @@ hipError_t launch_layernorm_bwd(int dtype, int T, int H, const void* dy, const v
 // Fused forms: the layer norm reads sum(partials) (+ bias + residual) instead of a stored tensor.
 hipError_t launch_combine_layernorm_fwd(int dtype, int T, int H, float eps, const void* const* partials, int n,
                                         const void* bias, const void* residual, void* x_out, const void* gamma,
-                                        const void* beta, void* y, float* mean, float* rstd, hipStream_t st);
-// ws: [ceil(T/kLnBwdRowsPerBlock)][3][H] float; dy_out and dx_colsum may be NULL
+                                        const void* beta, void* y, float* mean, float* rstd, const mlm_dropout* drop,
+                                        hipStream_t st);
+// ws: [ceil(T/kLnBwdRowsPerBlock)][3][H] float; dy_out and dx_colsum may be NULL.  With drop and dz_out the kernel
+// also emits dz_out = dropout-mask(dx) / (1 - p) and dx_colsum sums dz_out's columns instead of dx's.
 hipError_t launch_combine_layernorm_bwd(int dtype, int T, int H, const void* const* partials, int n, const void* x,
                                         const void* gamma, const float* mean, const float* rstd,
                                         const void* residual_grad, void* dy_out, void* dx, void* dgamma, void* dbeta,
-                                        void* dx_colsum, float* ws, hipStream_t st);
+                                        void* dx_colsum, float* ws, const mlm_dropout* drop, void* dz_out,
+                                        hipStream_t st);
+// out = residual + dropout(sum partials + bias[t mod bias_rows])
 hipError_t launch_combine(int dtype, int T, int H, const void* const* partials, int n, const void* bias,
-                          const void* residual, void* out, hipStream_t st);
+                          int bias_rows, const void* residual, void* out, const mlm_dropout* drop, hipStream_t st);
 // ws: [ceil(T/kColsumRowsPerBlock)][N] float
 hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, float* ws, hipStream_t st);
 hipError_t launch_ce_tile_merge(int T, int ntiles, const float* part_m, const float* part_s, const float* t_ws,
@@ -159,6 +176,12 @@ hipError_t launch_ce_merge(int T, int n_shards, const float* m, const float* s, 
 hipError_t launch_dlogits_inplace(int dtype, int T, int Vl, void* logits, const int32_t* targets, int v0,
                                   const float* M, const float* S, const float* loss_w, const float* loss_stats,
                                   hipStream_t st);
+hipError_t launch_embed_fwd(int dtype, int T, int H, int Vl, int v0, const int32_t* ids, const void* E, int32_t* perm,
+                            void* partial, hipStream_t st);
+hipError_t launch_embed_bwd(int dtype, int T, int H, int Vl, int v0, const int32_t* ids, const int32_t* perm,
+                            const void* dz, void* dE, hipStream_t st);
+hipError_t launch_embed_bwd_replicated(int dtype, int b, int s, int H, const void* dx0, void* dz0, void* dpos,
+                                       const mlm_dropout* drop, hipStream_t st);
 hipError_t launch_attn_delta(int dtype, int T, int hl, int d, int b, int s, const void* ctx, const void* dctx,
                              float* delta, hipStream_t st);
 

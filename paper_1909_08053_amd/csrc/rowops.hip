@@ -4,6 +4,7 @@
 // with the vocabulary-parallel logits).  One wavefront (64 lanes) owns one token row; row
 // statistics are wave-level shuffles, HBM access is 16-byte vectors, coalesced along H.
 #include "common.h"
+#include "rng.h"
 
 namespace mlm {
 
@@ -12,12 +13,14 @@ struct PartialPtrs { const void* p[kMaxPartials]; };
 // One token row (a lane's NV 16-byte vectors) of sum_r partials[r] + bias + residual: partials are added in the fixed
 // order r = 0..n-1 (deterministic) in fp32 and the sum is rounded once to the storage type -- the value the separate
 // combine kernel would have stored.  All of a partial's vectors are loaded before they are added, so the loads of a
-// row overlap; a single partial with nothing to add is passed through untouched.
+// row overlap; a single partial with nothing to add is passed through untouched.  With dropout the row is
+// residual + dropout(sum partials + bias): the mask of element row_off + column comes from the counter-based generator.
 template <typename T, int NV>
 __device__ __forceinline__ void combine_row(const PartialPtrs& ptrs, int n, const T* bias, const T* residual,
-                                            size_t row_off, int lane, int nvec, Vec16<T> (&out)[NV]) {
+                                            size_t row_off, int lane, int nvec, Vec16<T> (&out)[NV],
+                                            const DropArgs& drop) {
   constexpr int VN = Vec16<T>::N;
-  if (n == 1 && bias == nullptr && residual == nullptr) {
+  if (n == 1 && bias == nullptr && residual == nullptr && !drop.enabled) {
     const T* p = (const T*)ptrs.p[0] + row_off;
 #pragma unroll
     for (int i = 0; i < NV; ++i)
@@ -30,6 +33,11 @@ __device__ __forceinline__ void combine_row(const PartialPtrs& ptrs, int n, cons
 #pragma unroll
     for (int e = 0; e < VN; ++e) acc[i][e] = 0.f;
   for (int k = 0; k < n + 2; ++k) {
+    if (k == n + 1 && drop.enabled) {                 // uniform: everything but the residual is in, drop it out
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+        if (lane + 64 * i < nvec) drop_apply<VN>(drop, row_off + (size_t)(lane + 64 * i) * VN, acc[i]);
+    }
     const T* p = k < n ? (const T*)ptrs.p[k] + row_off : (k == n ? bias : (residual ? residual + row_off : nullptr));
     if (p == nullptr) continue;                       // uniform
     Vec16<T> t[NV];
@@ -57,7 +65,8 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int H, float eps,
                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
                                                      T* __restrict__ y, float* __restrict__ mean,
                                                      float* __restrict__ rstd, PartialPtrs ptrs, int n,
-                                                     const T* __restrict__ bias, const T* residual, T* x_out) {
+                                                     const T* __restrict__ bias, const T* residual, T* x_out,
+                                                     DropArgs drop) {
   constexpr int VN = Vec16<T>::N;
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -66,7 +75,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int H, float eps,
   const T* xr = x + (size_t)row * H;
   Vec16<T> v[NV];
   float sum = 0.f;
-  if (FUSED) combine_row<T, NV>(ptrs, n, bias, residual, (size_t)row * H, lane, nvec, v);
+  if (FUSED) combine_row<T, NV>(ptrs, n, bias, residual, (size_t)row * H, lane, nvec, v, drop);
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int idx = lane + 64 * i;
@@ -106,7 +115,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int H, float eps,
 template <typename T>
 static hipError_t ln_fwd_dispatch(int rows, int H, float eps, const void* x, const void* gamma, const void* beta,
                                   void* y, float* mean, float* rstd, const PartialPtrs* pp, int n, const void* bias,
-                                  const void* residual, void* x_out, hipStream_t st) {
+                                  const void* residual, void* x_out, const DropArgs& drop, hipStream_t st) {
   constexpr int VN = Vec16<T>::N;
   const int nv = (H / VN + 63) / 64;
   dim3 grid((rows + 3) / 4), block(256);
@@ -117,11 +126,11 @@ static hipError_t ln_fwd_dispatch(int rows, int H, float eps, const void* x, con
     if (pp)                                                                                                \
       hipLaunchKernelGGL((ln_fwd_kernel<T, NVV, true>), grid, block, 0, st, rows, H, eps, (const T*)x,     \
                          (const T*)gamma, (const T*)beta, (T*)y, mean, rstd, *pp, n, (const T*)bias,       \
-                         (const T*)residual, (T*)x_out);                                                   \
+                         (const T*)residual, (T*)x_out, drop);                                             \
     else                                                                                                   \
       hipLaunchKernelGGL((ln_fwd_kernel<T, NVV, false>), grid, block, 0, st, rows, H, eps, (const T*)x,    \
                          (const T*)gamma, (const T*)beta, (T*)y, mean, rstd, none, 0, (const T*)nullptr,   \
-                         (const T*)nullptr, (T*)nullptr);                                                  \
+                         (const T*)nullptr, (T*)nullptr, drop);                                            \
     break;
   switch (nv) {
     MLM_LN_FWD(1) MLM_LN_FWD(2) MLM_LN_FWD(3) MLM_LN_FWD(4) MLM_LN_FWD(5) MLM_LN_FWD(6) MLM_LN_FWD(7) MLM_LN_FWD(8)
@@ -133,19 +142,22 @@ static hipError_t ln_fwd_dispatch(int rows, int H, float eps, const void* x, con
 
 hipError_t launch_layernorm_fwd(int dtype, int T, int H, float eps, const void* x, const void* gamma,
                                 const void* beta, void* y, float* mean, float* rstd, hipStream_t st) {
+  const DropArgs nd = make_drop_args(nullptr);
   return dtype == MLM_BF16
-             ? ln_fwd_dispatch<bf16>(T, H, eps, x, gamma, beta, y, mean, rstd, nullptr, 0, nullptr, nullptr, nullptr, st)
-             : ln_fwd_dispatch<float>(T, H, eps, x, gamma, beta, y, mean, rstd, nullptr, 0, nullptr, nullptr, nullptr, st);
+             ? ln_fwd_dispatch<bf16>(T, H, eps, x, gamma, beta, y, mean, rstd, nullptr, 0, nullptr, nullptr, nullptr, nd, st)
+             : ln_fwd_dispatch<float>(T, H, eps, x, gamma, beta, y, mean, rstd, nullptr, 0, nullptr, nullptr, nullptr, nd, st);
 }
 
 hipError_t launch_combine_layernorm_fwd(int dtype, int T, int H, float eps, const void* const* partials, int n,
                                         const void* bias, const void* residual, void* x_out, const void* gamma,
-                                        const void* beta, void* y, float* mean, float* rstd, hipStream_t st) {
+                                        const void* beta, void* y, float* mean, float* rstd, const mlm_dropout* drop,
+                                        hipStream_t st) {
   PartialPtrs pp;
   for (int k = 0; k < kMaxPartials; ++k) pp.p[k] = k < n ? partials[k] : nullptr;
+  const DropArgs da = make_drop_args(drop);
   return dtype == MLM_BF16
-             ? ln_fwd_dispatch<bf16>(T, H, eps, nullptr, gamma, beta, y, mean, rstd, &pp, n, bias, residual, x_out, st)
-             : ln_fwd_dispatch<float>(T, H, eps, nullptr, gamma, beta, y, mean, rstd, &pp, n, bias, residual, x_out, st);
+             ? ln_fwd_dispatch<bf16>(T, H, eps, nullptr, gamma, beta, y, mean, rstd, &pp, n, bias, residual, x_out, da, st)
+             : ln_fwd_dispatch<float>(T, H, eps, nullptr, gamma, beta, y, mean, rstd, &pp, n, bias, residual, x_out, da, st);
 }
 
 // ------------------------------------------------------------------------------ layer norm backward
@@ -167,7 +179,8 @@ template <typename T, bool FUSED, bool SUM>
 __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy, const T* __restrict__ x,
                                                      const T* __restrict__ gamma, const float* __restrict__ mean,
                                                      const float* __restrict__ rstd, const T* residual, T* dx,
-                                                     float* __restrict__ ws, PartialPtrs ptrs, int n, T* dy_out) {
+                                                     float* __restrict__ ws, PartialPtrs ptrs, int n, T* dy_out,
+                                                     DropArgs drop, T* dz_out) {
   constexpr int VN = Vec16<T>::N, RB = kLnBwdBatch, NP = SUM ? 3 : 2;
   __shared__ float red[2][RB][2][8];
   const int lane = threadIdx.x & 63;
@@ -275,9 +288,23 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
           float v = rs[j] * (d * gam[e] - s1 - xh * s2);
           if (residual) v += vres[j].get(e);
           o.set(e, v);
-          if (SUM) dsum[e] += o.get(e);              // the stored (rounded) value, as a separate column sum would read it
+          if (SUM && dz_out == nullptr) dsum[e] += o.get(e);   // the stored (rounded) value, as a separate column sum would read it
         }
         o.store(dx + (size_t)(r0 + j) * H + col0);
+        if (dz_out != nullptr) {
+          // this layer norm's input was residual + dropout(z): emit dz = mask o dx / (1 - p) and sum ITS columns
+          float z[VN];
+#pragma unroll
+          for (int e = 0; e < VN; ++e) z[e] = o.get(e);
+          if (drop.enabled) drop_apply<VN>(drop, (size_t)(r0 + j) * H + col0, z);
+          Vec16<T> oz;
+#pragma unroll
+          for (int e = 0; e < VN; ++e) {
+            oz.set(e, z[e]);
+            if (SUM) dsum[e] += oz.get(e);
+          }
+          oz.store(dz_out + (size_t)(r0 + j) * H + col0);
+        }
       }
     }
   }
@@ -326,7 +353,7 @@ template <typename T>
 static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x, const void* gamma,
                                   const float* mean, const float* rstd, const void* residual, void* dx,
                                   void* dgamma, void* dbeta, float* ws, const PartialPtrs* pp, int n, void* dy_out,
-                                  void* dx_colsum, hipStream_t st) {
+                                  void* dx_colsum, const DropArgs& drop, void* dz_out, hipStream_t st) {
   constexpr int VN = Vec16<T>::N;
   const int nwaves = (H / VN + 63) / 64;
   if (nwaves < 1 || nwaves > 8) return hipErrorInvalidValue;
@@ -338,7 +365,7 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
 #define MLM_LN_BWD_GO(F, S)                                                                                 \
   hipLaunchKernelGGL((ln_bwd_kernel<T, F, S>), grid, block, 0, st, rows, H, (const T*)dy, (const T*)x,      \
                      (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws, pp ? *pp : none, n,       \
-                     (T*)dy_out)
+                     (T*)dy_out, drop, (T*)dz_out)
   if (pp && dx_colsum) MLM_LN_BWD_GO(true, true);
   else if (pp) MLM_LN_BWD_GO(true, false);
   else MLM_LN_BWD_GO(false, false);
@@ -353,31 +380,35 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
 hipError_t launch_layernorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
                                 const float* mean, const float* rstd, const void* residual_grad, void* dx,
                                 void* dgamma, void* dbeta, float* ws, hipStream_t st) {
+  const DropArgs nd = make_drop_args(nullptr);
   return dtype == MLM_BF16
              ? ln_bwd_dispatch<bf16>(T, H, dy, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, nullptr, 0,
-                                     nullptr, nullptr, st)
+                                     nullptr, nullptr, nd, nullptr, st)
              : ln_bwd_dispatch<float>(T, H, dy, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, nullptr, 0,
-                                      nullptr, nullptr, st);
+                                      nullptr, nullptr, nd, nullptr, st);
 }
 
 // ws: [ceil(T/kLnBwdRowsPerBlock)][3][H] float
 hipError_t launch_combine_layernorm_bwd(int dtype, int T, int H, const void* const* partials, int n, const void* x,
                                         const void* gamma, const float* mean, const float* rstd,
                                         const void* residual_grad, void* dy_out, void* dx, void* dgamma, void* dbeta,
-                                        void* dx_colsum, float* ws, hipStream_t st) {
+                                        void* dx_colsum, float* ws, const mlm_dropout* drop, void* dz_out,
+                                        hipStream_t st) {
   PartialPtrs pp;
   for (int k = 0; k < kMaxPartials; ++k) pp.p[k] = k < n ? partials[k] : nullptr;
+  const DropArgs da = make_drop_args(drop);
   return dtype == MLM_BF16
              ? ln_bwd_dispatch<bf16>(T, H, nullptr, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, &pp, n,
-                                     dy_out, dx_colsum, st)
+                                     dy_out, dx_colsum, da, dz_out, st)
              : ln_bwd_dispatch<float>(T, H, nullptr, x, gamma, mean, rstd, residual_grad, dx, dgamma, dbeta, ws, &pp, n,
-                                      dy_out, dx_colsum, st);
+                                      dy_out, dx_colsum, da, dz_out, st);
 }
 
 // ------------------------------------------------------------------------------ combine (stand-in for g / f)
 template <typename T>
-__global__ __launch_bounds__(256) void combine_kernel(size_t nvec, int hvec, PartialPtrs ptrs, int n,
-                                                      const T* __restrict__ bias, const T* residual, T* out) {
+__global__ __launch_bounds__(256) void combine_kernel(size_t nvec, size_t bias_vecs, PartialPtrs ptrs, int n,
+                                                      const T* __restrict__ bias, const T* residual, T* out,
+                                                      DropArgs drop) {
   constexpr int VN = Vec16<T>::N;
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= nvec) return;
@@ -392,10 +423,11 @@ __global__ __launch_bounds__(256) void combine_kernel(size_t nvec, int hvec, Par
   }
   if (bias) {
     Vec16<T> v;
-    v.load(bias + (size_t)(i % hvec) * VN);
+    v.load(bias + (i % bias_vecs) * VN);             // bias_vecs = vectors of the [bias_rows, H] bias block
 #pragma unroll
     for (int e = 0; e < VN; ++e) acc[e] += v.get(e);
   }
+  if (drop.enabled) drop_apply<VN>(drop, i * VN, acc);
   if (residual) {
     Vec16<T> v;
     v.load(residual + i * VN);
@@ -409,17 +441,18 @@ __global__ __launch_bounds__(256) void combine_kernel(size_t nvec, int hvec, Par
 }
 
 hipError_t launch_combine(int dtype, int T, int H, const void* const* partials, int n, const void* bias,
-                          const void* residual, void* out, hipStream_t st) {
+                          int bias_rows, const void* residual, void* out, const mlm_dropout* drop, hipStream_t st) {
   PartialPtrs pp;
   for (int k = 0; k < kMaxPartials; ++k) pp.p[k] = k < n ? partials[k] : nullptr;
+  const DropArgs da = make_drop_args(drop);
   if (dtype == MLM_BF16) {
     const size_t nvec = (size_t)T * H / 8;
-    hipLaunchKernelGGL((combine_kernel<bf16>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, nvec, H / 8,
-                       pp, n, (const bf16*)bias, (const bf16*)residual, (bf16*)out);
+    hipLaunchKernelGGL((combine_kernel<bf16>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, nvec,
+                       (size_t)bias_rows * H / 8, pp, n, (const bf16*)bias, (const bf16*)residual, (bf16*)out, da);
   } else {
     const size_t nvec = (size_t)T * H / 4;
-    hipLaunchKernelGGL((combine_kernel<float>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, nvec, H / 4,
-                       pp, n, (const float*)bias, (const float*)residual, (float*)out);
+    hipLaunchKernelGGL((combine_kernel<float>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, nvec,
+                       (size_t)bias_rows * H / 4, pp, n, (const float*)bias, (const float*)residual, (float*)out, da);
   }
   return hipGetLastError();
 }

@@ -23,12 +23,21 @@ def _tdtype(cfg: LayerConfig):
 
 class LayerShards:
     def __init__(self, cfg: LayerConfig, shards: Sequence[int], device: str = "cuda:0", store_logits: bool = True,
-                 fused: bool = True, store_combined: bool = False):
+                 fused: bool = True, store_combined: bool = False, dropout: Optional[Dict[str, object]] = None,
+                 embed: bool = False):
         """fused: the combine that stands in for an all-reduce runs inside the layer-norm kernel that consumes it
         (and the layer-norm backward also emits the row-parallel bias gradient); store_combined: in fused mode,
-        also store the combined gradients dHf / dU2 / dU (nothing in the path reads them)."""
+        also store the combined gradients dHf / dU2 / dU (nothing in the path reads them).
+        dropout: None, or {"p_attn", "p_hidden", "base_seed", "offsets": {"attn", "hidden1", "hidden2", "embed"}} --
+        the two-stream dropout of Appendix B.2 (fused mode only): the attention-probability site of shard r draws
+        from worker r's model-parallel stream, the hidden sites from the replicated stream.
+        embed: the layer input is produced by the vocabulary-parallel input embedding (token ids + position
+        embedding) instead of being given, and its backward adds into the tied dE."""
         self.cfg, self.shards, self.dev = cfg, list(shards), torch.device(device)
         self.fused, self.store_combined = fused, store_combined
+        self.dropout, self.embed = dropout, embed
+        if dropout is not None and not fused:
+            raise ValueError("dropout is wired into the fused combine + layer-norm calls only")
         self.dt = _tdtype(cfg)
         self.code = B.MLM_BF16 if cfg.dtype == "bf16" else B.MLM_F32
         self.store_logits = store_logits
@@ -39,6 +48,14 @@ class LayerShards:
         self.hl = cfg.h // p
         self.dims = {r: B.make_dims(cfg.b, cfg.s, cfg.H, cfg.h, cfg.F, cfg.V, p, r, self.code, cfg.causal,
                                     cfg.gelu_tanh, cfg.ln_eps) for r in range(p)}
+        self.drop: Dict[str, object] = {}
+        if dropout is not None:
+            off, base = dropout["offsets"], int(dropout["base_seed"])
+            rep_seed = B.mlm_rng_stream_seed(base, B.STREAM_REPLICATED, 0)
+            for site in ("hidden1", "hidden2", "embed"):
+                self.drop[site] = B.make_dropout(dropout["p_hidden"], rep_seed, off[site])
+            self.drop["attn"] = {r: B.make_dropout(dropout["p_attn"], B.mlm_rng_stream_seed(base, B.STREAM_MODEL_PARALLEL, r),
+                                                   off["attn"]) for r in range(p)}
         self.rep: Dict[str, torch.Tensor] = {}       # replicated parameters and inputs
         self.w: Dict[int, Dict[str, torch.Tensor]] = {}   # per-shard parameters
         self.act: Dict[str, torch.Tensor] = {}       # replicated activations / gradients
@@ -52,7 +69,12 @@ class LayerShards:
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev).to(self.dt).contiguous()
         for k in ("g1", "b1", "bo", "g2", "b2", "c", "gf", "bf"):
             self.rep[k] = up(inp[k])
-        self.rep["X"] = up(inp["X"].reshape(cfg.T, cfg.H))
+        if self.embed:
+            self.rep["ids"] = torch.from_numpy(inp["ids"].reshape(-1).astype(np.int32)).to(self.dev)
+            self.rep["pos"] = up(inp["pos"])
+            self.rep["X"] = torch.empty(cfg.T, cfg.H, device=self.dev, dtype=self.dt)
+        else:
+            self.rep["X"] = up(inp["X"].reshape(cfg.T, cfg.H))
         self.rep["tgt"] = torch.from_numpy(inp["tgt"].reshape(-1).astype(np.int32)).to(self.dev)
         self.rep["w"] = torch.from_numpy(inp["w"].reshape(-1).astype(np.float32)).to(self.dev)
         self.rep["key_len"] = torch.from_numpy(inp["key_len"].astype(np.int32)).to(self.dev)
@@ -80,6 +102,9 @@ class LayerShards:
         self.rep.update(X=rn(cfg.T, H, std=1.0), g1=ones(H), b1=zeros(H), g2=ones(H), b2=zeros(H), gf=ones(H),
                         bf=zeros(H), bo=zeros(H), c=zeros(H))
         self.rep["tgt"] = torch.randint(0, cfg.V, (cfg.T,), generator=g, device=self.dev, dtype=torch.int32)
+        if self.embed:
+            self.rep["ids"] = torch.randint(0, cfg.V, (cfg.T,), generator=g, device=self.dev, dtype=torch.int32)
+            self.rep["pos"] = rn(cfg.s, H)
         if cfg.masked_lm:
             kl = torch.randint(max(1, cfg.s // 2), cfg.s + 1, (cfg.b,), generator=g, device=self.dev, dtype=torch.int32)
             pos = torch.arange(cfg.s, device=self.dev)[None, :]
@@ -111,6 +136,10 @@ class LayerShards:
         d0 = self.dims[self.shards[0]]
         wsb = max(B.mlm_workspace_bytes(d0, k) for k in range(8))
         self.ws = torch.empty(max(wsb, 256), device=dev, dtype=torch.uint8)
+        if self.dropout is not None:
+            a["dZ1"], a["dZ2"] = e(T, H), e(T, H)
+        if self.embed:
+            a["dZ0"], a["dpos"] = e(T, H), e(cfg.s, H)
         for r in self.shards:
             self.sh[r] = {
                 "qkv": e(T, 3 * self.Hl), "ctx": e(T, self.Hl), "lse": e(cfg.b, self.hl, cfg.s, dtype=f32),
@@ -120,28 +149,65 @@ class LayerShards:
                 "dA": e(H, self.Fl), "da": e(self.Fl), "dB": e(self.Fl, H), "du2_partial": e(T, H),
                 "dWqkv": e(H, 3 * self.Hl), "dbqkv": e(3 * self.Hl), "dWo": e(self.Hl, H), "du_partial": e(T, H),
             }
+            if self.dropout is not None:
+                self.sh[r]["keep_bits"] = torch.zeros(B.mlm_attn_keep_words(self.dims[r]), device=dev, dtype=torch.int32)
+            if self.embed:
+                self.sh[r]["perm"] = e(T, dtype=torch.int32)
+                self.sh[r]["embed_partial"] = e(T, H)
 
     # ------------------------------------------------------------------ the path
-    def forward(self):
+    def _embed_forward(self):
+        """X = dropout(sum_r E_r[:, id] + position embedding): per-shard lookups, then the stand-in for g."""
+        d0, rep = self.dims[self.shards[0]], self.rep
+        for r in self.shards:
+            B.mlm_embed_shard_fwd(self.dims[r], rep["ids"], self.w[r]["E"], self.sh[r]["perm"],
+                                  self.sh[r]["embed_partial"])
+        B.mlm_combine_dropout(d0, [self.sh[r]["embed_partial"] for r in self.shards], rep["pos"], self.cfg.s,
+                              self.drop.get("embed"), None, rep["X"])
+
+    def _layer_forward(self):
+        """LN1, attention shards, combine (+dropout) + LN2, MLP shards: everything up to the MLP partial sums."""
         cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
         d0 = self.dims[self.shards[0]]
         kl = rep["key_len"] if cfg.masked_lm else None
         B.mlm_layernorm_fwd(d0, rep["X"], rep["g1"], rep["b1"], a["U"], a["mu1"], a["rstd1"])
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
-            B.mlm_attn_shard_fwd(self.dims[r], a["U"], w["Wqkv"], w["bqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
-                                 s["attn_partial"], ws)
-        if self.fused:
-            B.mlm_combine_layernorm_fwd(d0, [self.sh[r]["attn_partial"] for r in self.shards], rep["bo"], rep["X"],
-                                        a["X1"], rep["g2"], rep["b2"], a["U2"], a["mu2"], a["rstd2"])
+            if self.dropout is not None:
+                B.mlm_attn_shard_fwd_dropout(self.dims[r], a["U"], w["Wqkv"], w["bqkv"], w["Wo"], kl, self.drop["attn"][r],
+                                             s["qkv"], s["ctx"], s["lse"], s["keep_bits"], s["attn_partial"], ws)
+            else:
+                B.mlm_attn_shard_fwd(self.dims[r], a["U"], w["Wqkv"], w["bqkv"], w["Wo"], kl, s["qkv"], s["ctx"],
+                                     s["lse"], s["attn_partial"], ws)
+        attn_partials = [self.sh[r]["attn_partial"] for r in self.shards]
+        if self.dropout is not None:
+            B.mlm_combine_layernorm_fwd_dropout(d0, attn_partials, rep["bo"], self.drop["hidden1"], rep["X"], a["X1"],
+                                                rep["g2"], rep["b2"], a["U2"], a["mu2"], a["rstd2"])
+        elif self.fused:
+            B.mlm_combine_layernorm_fwd(d0, attn_partials, rep["bo"], rep["X"], a["X1"], rep["g2"], rep["b2"], a["U2"],
+                                        a["mu2"], a["rstd2"])
         else:
-            B.mlm_combine(d0, [self.sh[r]["attn_partial"] for r in self.shards], rep["bo"], rep["X"], a["X1"])
+            B.mlm_combine(d0, attn_partials, rep["bo"], rep["X"], a["X1"])
             B.mlm_layernorm_fwd(d0, a["X1"], rep["g2"], rep["b2"], a["U2"], a["mu2"], a["rstd2"])
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
             B.mlm_mlp_shard_fwd(self.dims[r], a["U2"], w["A"], w["a"], w["B"], s["g"], s["y"], s["mlp_partial"], ws)
+
+    def forward(self):
+        cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
+        d0 = self.dims[self.shards[0]]
+        if self.embed:
+            self._embed_forward()
+        self._layer_forward()
         mlp_partials = [self.sh[r]["mlp_partial"] for r in self.shards]
-        if cfg.final_ln and self.fused:
+        if self.dropout is not None and cfg.final_ln:
+            B.mlm_combine_layernorm_fwd_dropout(d0, mlp_partials, rep["c"], self.drop["hidden2"], a["X1"], a["X2"],
+                                                rep["gf"], rep["bf"], a["Hf"], a["muf"], a["rstdf"])
+            hf = a["Hf"]
+        elif self.dropout is not None:
+            B.mlm_combine_dropout(d0, mlp_partials, rep["c"], 1, self.drop["hidden2"], a["X1"], a["X2"])
+            hf = a["X2"]
+        elif cfg.final_ln and self.fused:
             B.mlm_combine_layernorm_fwd(d0, mlp_partials, rep["c"], a["X1"], a["X2"], rep["gf"], rep["bf"], a["Hf"],
                                         a["muf"], a["rstdf"])
             hf = a["Hf"]
@@ -172,7 +238,19 @@ class LayerShards:
         fused = self.fused
         keep = (lambda k: a[k]) if self.store_combined else (lambda k: None)
         dhf_partials = [self.sh[r]["dhf_partial"] for r in self.shards]
-        if cfg.final_ln and fused:
+        drop = self.dropout is not None
+        dz2 = dz1 = None          # gradients of the block outputs BEFORE their dropout (what the shards' backward reads)
+        if drop and cfg.final_ln:
+            B.mlm_combine_layernorm_bwd_dropout(d0, dhf_partials, a["X2"], rep["gf"], a["muf"], a["rstdf"], None,
+                                                self.drop["hidden2"], keep("dHf"), a["dX2"], a["dZ2"], a["dgf"],
+                                                a["dbf"], a["dc"], ws)
+            dx2, dz2 = a["dX2"], a["dZ2"]
+        elif drop:
+            B.mlm_combine(d0, dhf_partials, None, None, a["dHf"])
+            B.mlm_combine_dropout(d0, dhf_partials, None, 1, self.drop["hidden2"], None, a["dZ2"])
+            B.mlm_colsum(d0, a["dZ2"], a["dc"], ws)
+            dx2, dz2 = a["dHf"], a["dZ2"]
+        elif cfg.final_ln and fused:
             B.mlm_combine_layernorm_bwd(d0, dhf_partials, a["X2"], rep["gf"], a["muf"], a["rstdf"], None, keep("dHf"),
                                         a["dX2"], a["dgf"], a["dbf"], a["dc"], ws)
             dx2 = a["dX2"]
@@ -187,10 +265,15 @@ class LayerShards:
             B.mlm_colsum(d0, dx2, a["dc"], ws)
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
-            B.mlm_mlp_shard_bwd(self.dims[r], dx2, a["U2"], w["A"], w["B"], s["g"], s["y"], s["dA"], s["da"], s["dB"],
-                                s["du2_partial"], ws)
+            B.mlm_mlp_shard_bwd(self.dims[r], dz2 if drop else dx2, a["U2"], w["A"], w["B"], s["g"], s["y"], s["dA"],
+                                s["da"], s["dB"], s["du2_partial"], ws)
         du2_partials = [self.sh[r]["du2_partial"] for r in self.shards]
-        if fused:
+        if drop:
+            B.mlm_combine_layernorm_bwd_dropout(d0, du2_partials, a["X1"], rep["g2"], a["mu2"], a["rstd2"], dx2,
+                                                self.drop["hidden1"], keep("dU2"), a["dX1"], a["dZ1"], a["dg2"],
+                                                a["db2"], a["dbo"], ws)
+            dz1 = a["dZ1"]
+        elif fused:
             B.mlm_combine_layernorm_bwd(d0, du2_partials, a["X1"], rep["g2"], a["mu2"], a["rstd2"], dx2, keep("dU2"),
                                         a["dX1"], a["dg2"], a["db2"], a["dbo"], ws)
         else:
@@ -200,8 +283,13 @@ class LayerShards:
             B.mlm_colsum(d0, a["dX1"], a["dbo"], ws)
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
-            B.mlm_attn_shard_bwd(self.dims[r], a["dX1"], a["U"], w["Wqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
-                                 s["dWqkv"], s["dbqkv"], s["dWo"], s["du_partial"], ws)
+            if drop:
+                B.mlm_attn_shard_bwd_dropout(self.dims[r], dz1, a["U"], w["Wqkv"], w["Wo"], kl, self.drop["attn"][r],
+                                             s["qkv"], s["ctx"], s["lse"], s["keep_bits"], s["dWqkv"], s["dbqkv"],
+                                             s["dWo"], s["du_partial"], ws)
+            else:
+                B.mlm_attn_shard_bwd(self.dims[r], a["dX1"], a["U"], w["Wqkv"], w["Wo"], kl, s["qkv"], s["ctx"],
+                                     s["lse"], s["dWqkv"], s["dbqkv"], s["dWo"], s["du_partial"], ws)
         du_partials = [self.sh[r]["du_partial"] for r in self.shards]
         if fused:
             B.mlm_combine_layernorm_bwd(d0, du_partials, rep["X"], rep["g1"], a["mu1"], a["rstd1"], a["dX1"],
@@ -211,6 +299,11 @@ class LayerShards:
             B.mlm_layernorm_bwd(d0, a["dU"], rep["X"], rep["g1"], a["mu1"], a["rstd1"], a["dX1"], a["dX"], a["dg1"],
                                 a["db1"], ws)
         self._dx2 = dx2
+        if self.embed:
+            # replicated part (dropout mask, position-embedding gradient), then each shard's columns of the tied dE
+            B.mlm_embed_bwd_replicated(d0, a["dX"], self.drop.get("embed"), a["dZ0"], a["dpos"])
+            for r in self.shards:
+                B.mlm_embed_shard_bwd(self.dims[r], rep["ids"], self.sh[r]["perm"], a["dZ0"], self.sh[r]["dE"])
 
     # Activation recomputation (the paper checkpoints activations after every transformer layer, Section 5): only the
     # layer input X is kept; everything the layer's backward reads is produced again by re-running the layer's forward
@@ -228,19 +321,7 @@ class LayerShards:
                 self.sh[r][k].fill_(float("nan"))
 
     def recompute_layer(self):
-        cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
-        d0 = self.dims[self.shards[0]]
-        kl = rep["key_len"] if cfg.masked_lm else None
-        B.mlm_layernorm_fwd(d0, rep["X"], rep["g1"], rep["b1"], a["U"], a["mu1"], a["rstd1"])
-        for r in self.shards:
-            w, s = self.w[r], self.sh[r]
-            B.mlm_attn_shard_fwd(self.dims[r], a["U"], w["Wqkv"], w["bqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
-                                 s["attn_partial"], ws)
-        B.mlm_combine_layernorm_fwd(d0, [self.sh[r]["attn_partial"] for r in self.shards], rep["bo"], rep["X"],
-                                    a["X1"], rep["g2"], rep["b2"], a["U2"], a["mu2"], a["rstd2"])
-        for r in self.shards:
-            w, s = self.w[r], self.sh[r]
-            B.mlm_mlp_shard_fwd(self.dims[r], a["U2"], w["A"], w["a"], w["B"], s["g"], s["y"], s["mlp_partial"], ws)
+        self._layer_forward()
 
     # ------------------------------------------------------------------ optimizer (this worker's parameters)
     def parameters(self):
