@@ -610,7 +610,6 @@ MLM_API int mlm_embed_shard_bwd(const mlm_dims* dims, const int32_t* ids, const 
   if (rc) return rc;
   if (!ids || !perm_r || !dz0 || !dE_r) return MLM_E_NULL;
   if (!aligned16(dz0) || !aligned16(dE_r)) return MLM_E_ALIGN;
-  if ((rc = ln_supported(dims))) return rc;          // same row-width limit as the layer-norm kernels
   return hip_status(launch_embed_bwd(dims->dtype, L.T, dims->H, L.Vl, dims->r * L.Vl, ids, perm_r, dz0, dE_r,
                                      (hipStream_t)stream));
 }

@@ -12,94 +12,92 @@ namespace mlm {
 
 // key[t] = local id if the token's id is in [v0, v0 + Vl), else Vl (sorts last); perm[rank(t)] = t with
 // rank(t) = #{t' : key[t'] < key[t]} + #{t' < t : key[t'] == key[t]}.
-__global__ __launch_bounds__(256) void embed_rank_kernel(int T, const int32_t* __restrict__ ids, int v0, int Vl,
-                                                         int32_t* __restrict__ perm) {
-  __shared__ int32_t sk[1024];
-  const int t = blockIdx.x * 256 + threadIdx.x;
-  auto key_of = [&](int i) {
-    const int loc = ids[i] - v0;
-    return (loc >= 0 && loc < Vl) ? loc : Vl;
-  };
-  const int my = t < T ? key_of(t) : 0;
-  int rank = 0;
-  for (int c0 = 0; c0 < T; c0 += 1024) {
-    __syncthreads();
-    for (int i = threadIdx.x; i < 1024; i += 256) sk[i] = c0 + i < T ? key_of(c0 + i) : 0x7FFFFFFF;
-    __syncthreads();
-    const int n = min(1024, T - c0);
-    for (int i = 0; i < n; ++i) {
-      const int k = sk[i];
-      rank += (k < my || (k == my && c0 + i < t)) ? 1 : 0;
-    }
-  }
-  if (t < T) perm[rank] = t;
+// The T x T comparisons are split over blockIdx.y: block (x, y) counts, for its 256 tokens, the tokens t' of slice y
+// that precede them, and writes the partial count; embed_scatter_kernel adds the slices' counts (integers: exact in
+// any order) and scatters.  Keys are staged through LDS and compared four per LDS read.
+constexpr int kRankChunk = 1024;
+
+__device__ __forceinline__ int embed_key(const int32_t* ids, int i, int v0, int Vl) {
+  const int loc = ids[i] - v0;
+  return (loc >= 0 && loc < Vl) ? loc : Vl;
 }
 
-// One wave per sorted position: the token's row of the partial = column (id - v0) of E_r, or zeros.
+__global__ __launch_bounds__(256) void embed_rank_kernel(int T, int nslice, const int32_t* __restrict__ ids, int v0,
+                                                         int Vl, int32_t* __restrict__ partial) {
+  __shared__ __attribute__((aligned(16))) int32_t sk[kRankChunk];
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  const int my = t < T ? embed_key(ids, t, v0, Vl) : 0;
+  // slice y covers chunks y, y + nslice, ... of kRankChunk tokens
+  int rank = 0;
+  for (int c0 = blockIdx.y * kRankChunk; c0 < T; c0 += nslice * kRankChunk) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < kRankChunk; i += 256)
+      sk[i] = c0 + i < T ? embed_key(ids, c0 + i, v0, Vl) : 0x7FFFFFFF;      // padding sorts after everything
+    __syncthreads();
+    // tokens before t in index order win ties: in this chunk those are the first (t - c0) entries
+    const int before = min(max(t - c0, 0), kRankChunk);
+#pragma unroll 4
+    for (int i = 0; i < kRankChunk; i += 4) {
+      const int4 k = *reinterpret_cast<const int4*>(&sk[i]);
+      rank += (k.x < my || (k.x == my && i + 0 < before)) ? 1 : 0;
+      rank += (k.y < my || (k.y == my && i + 1 < before)) ? 1 : 0;
+      rank += (k.z < my || (k.z == my && i + 2 < before)) ? 1 : 0;
+      rank += (k.w < my || (k.w == my && i + 3 < before)) ? 1 : 0;
+    }
+  }
+  if (t < T) partial[(size_t)blockIdx.y * T + t] = rank;
+}
+
+__global__ __launch_bounds__(256) void embed_scatter_kernel(int T, int nslice, const int32_t* __restrict__ partial,
+                                                            int32_t* __restrict__ perm) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  int rank = 0;
+  for (int y = 0; y < nslice; ++y) rank += partial[(size_t)y * T + t];
+  perm[rank] = t;
+}
+
+// One wave per (sorted position, group of 64 rows of E_r): lane h reads E_r[h0 + h, loc] and the wave writes 64
+// consecutive elements of the token's row of the partial (zeros for a token outside the shard).  blockIdx.x (the
+// sorted positions) varies fastest, so the blocks in flight together share a row group -- 64 rows of E_r, which
+// stay in the L2 -- and walk its columns in increasing order.
 template <typename T>
 __global__ __launch_bounds__(256) void embed_fwd_kernel(int Tn, int H, int Vl, int v0, const int32_t* __restrict__ ids,
                                                         const int32_t* __restrict__ perm, const T* __restrict__ E,
                                                         T* __restrict__ out) {
-  constexpr int VN = Vec16<T>::N;
   const int lane = threadIdx.x & 63;
   const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (k >= Tn) return;
+  const int h = blockIdx.y * 64 + lane;
+  if (k >= Tn || h >= H) return;
   const int t = perm[k];
   const int loc = ids[t] - v0;
   const bool inside = loc >= 0 && loc < Vl;           // wave-uniform
-  T* row = out + (size_t)t * H;
-  for (int v = lane; v < H / VN; v += 64) {
-    Vec16<T> o;
-#pragma unroll
-    for (int e = 0; e < VN; ++e) o.set(e, inside ? to_f32(E[(size_t)(v * VN + e) * Vl + loc]) : 0.f);
-    o.store(row + (size_t)v * VN);
-  }
+  out[(size_t)t * H + h] = inside ? E[(size_t)h * Vl + loc] : from_f32<T>(0.f);
 }
 
-// One wave per sorted position; the wave at the head of a run of equal local ids sums the run's rows of dz0 in token
-// order (fp32) and adds the sum to column `loc` of dE_r.  Two-byte (or four-byte) accesses: neighbouring columns
-// belong to other waves.
-template <typename T, int NV>
+// One wave per (sorted position, group of 64 rows of dE_r); the wave at the head of a run of equal local ids sums the
+// run's rows of dz0 in token order (fp32) and adds the sum to column `loc` of dE_r.  Element-sized accesses:
+// neighbouring columns belong to other waves.
+template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_kernel(int Tn, int H, int Vl, int v0, const int32_t* __restrict__ ids,
                                                         const int32_t* __restrict__ perm, const T* __restrict__ dz,
                                                         T* __restrict__ dE) {
-  constexpr int VN = Vec16<T>::N;
   const int lane = threadIdx.x & 63;
   const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int h = blockIdx.y * 64 + lane;
   if (k >= Tn) return;
   const int loc = ids[perm[k]] - v0;
   if (loc < 0 || loc >= Vl) return;                   // outside the shard (wave-uniform)
   if (k > 0 && ids[perm[k - 1]] - v0 == loc) return;  // not the head of its run
-  float acc[NV][VN];
-#pragma unroll
-  for (int i = 0; i < NV; ++i)
-#pragma unroll
-    for (int e = 0; e < VN; ++e) acc[i][e] = 0.f;
-  const int nvec = H / VN;
+  float acc = 0.f;
   for (int kk = k; kk < Tn; ++kk) {
     const int t = perm[kk];
     if (ids[t] - v0 != loc) break;                    // end of the run (wave-uniform)
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int v = lane + 64 * i;
-      if (v < nvec) {
-        Vec16<T> x;
-        x.load(dz + (size_t)t * H + (size_t)v * VN);
-#pragma unroll
-        for (int e = 0; e < VN; ++e) acc[i][e] += x.get(e);
-      }
-    }
+    if (h < H) acc += to_f32(dz[(size_t)t * H + h]);
   }
-#pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const int v = lane + 64 * i;
-    if (v < nvec) {
-#pragma unroll
-      for (int e = 0; e < VN; ++e) {
-        T* p = dE + (size_t)(v * VN + e) * Vl + loc;
-        *p = from_f32<T>(to_f32(*p) + acc[i][e]);
-      }
-    }
+  if (h < H) {
+    T* p = dE + (size_t)h * Vl + loc;
+    *p = from_f32<T>(to_f32(*p) + acc);
   }
 }
 
@@ -138,43 +136,42 @@ __global__ __launch_bounds__(256) void embed_bwd_replicated_kernel(int b, int s,
   }
 }
 
+// The rank partials ([nslice][T] int32) live in the partial output buffer until the gather overwrites it: a row of
+// the partial has H elements, so up to H * sizeof(element) / 4 slices fit.
 hipError_t launch_embed_fwd(int dtype, int T, int H, int Vl, int v0, const int32_t* ids, const void* E, int32_t* perm,
                             void* partial, hipStream_t st) {
-  hipLaunchKernelGGL(embed_rank_kernel, dim3((T + 255) / 256), dim3(256), 0, st, T, ids, v0, Vl, perm);
+  const int esz = dtype == MLM_BF16 ? 2 : 4;
+  int nslice = (T + kRankChunk - 1) / kRankChunk;
+  nslice = nslice < 1 ? 1 : (nslice > 16 ? 16 : nslice);
+  if (nslice > H * esz / 4) nslice = H * esz / 4;
+  hipLaunchKernelGGL(embed_rank_kernel, dim3((T + 255) / 256, nslice), dim3(256), 0, st, T, nslice, ids, v0, Vl,
+                     (int32_t*)partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(embed_scatter_kernel, dim3((T + 255) / 256), dim3(256), 0, st, T, nslice, (const int32_t*)partial,
+                     perm);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dim3 grid((T + 3) / 4, (H + 63) / 64);
   if (dtype == MLM_BF16)
-    hipLaunchKernelGGL((embed_fwd_kernel<bf16>), dim3((T + 3) / 4), dim3(256), 0, st, T, H, Vl, v0, ids, perm,
-                       (const bf16*)E, (bf16*)partial);
+    hipLaunchKernelGGL((embed_fwd_kernel<bf16>), grid, dim3(256), 0, st, T, H, Vl, v0, ids, perm, (const bf16*)E,
+                       (bf16*)partial);
   else
-    hipLaunchKernelGGL((embed_fwd_kernel<float>), dim3((T + 3) / 4), dim3(256), 0, st, T, H, Vl, v0, ids, perm,
-                       (const float*)E, (float*)partial);
-  return hipGetLastError();
-}
-
-template <typename T>
-static hipError_t embed_bwd_dispatch(int Tn, int H, int Vl, int v0, const int32_t* ids, const int32_t* perm,
-                                     const void* dz, void* dE, hipStream_t st) {
-  constexpr int VN = Vec16<T>::N;
-  const int nv = (H / VN + 63) / 64;
-  dim3 grid((Tn + 3) / 4), block(256);
-#define MLM_EB(NVV)                                                                                         \
-  case NVV:                                                                                                 \
-    hipLaunchKernelGGL((embed_bwd_kernel<T, NVV>), grid, block, 0, st, Tn, H, Vl, v0, ids, perm, (const T*)dz, \
-                       (T*)dE);                                                                             \
-    break;
-  switch (nv) {
-    MLM_EB(1) MLM_EB(2) MLM_EB(3) MLM_EB(4) MLM_EB(5) MLM_EB(6) MLM_EB(7) MLM_EB(8)
-    default: return hipErrorInvalidValue;
-  }
-#undef MLM_EB
+    hipLaunchKernelGGL((embed_fwd_kernel<float>), grid, dim3(256), 0, st, T, H, Vl, v0, ids, perm, (const float*)E,
+                       (float*)partial);
   return hipGetLastError();
 }
 
 hipError_t launch_embed_bwd(int dtype, int T, int H, int Vl, int v0, const int32_t* ids, const int32_t* perm,
                             const void* dz, void* dE, hipStream_t st) {
-  return dtype == MLM_BF16 ? embed_bwd_dispatch<bf16>(T, H, Vl, v0, ids, perm, dz, dE, st)
-                           : embed_bwd_dispatch<float>(T, H, Vl, v0, ids, perm, dz, dE, st);
+  dim3 grid((T + 3) / 4, (H + 63) / 64);
+  if (dtype == MLM_BF16)
+    hipLaunchKernelGGL((embed_bwd_kernel<bf16>), grid, dim3(256), 0, st, T, H, Vl, v0, ids, perm, (const bf16*)dz,
+                       (bf16*)dE);
+  else
+    hipLaunchKernelGGL((embed_bwd_kernel<float>), grid, dim3(256), 0, st, T, H, Vl, v0, ids, perm, (const float*)dz,
+                       (float*)dE);
+  return hipGetLastError();
 }
 
 hipError_t launch_embed_bwd_replicated(int dtype, int b, int s, int H, const void* dx0, void* dz0, void* dpos,

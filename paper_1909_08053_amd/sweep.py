@@ -73,6 +73,61 @@ def optimizer_timing(steps, warmup, dev="cuda:0"):
           f"({nbytes / (ms * 1e-3) / 8e12 * 100:.1f} % of the 8 TB/s HBM peak)")
 
 
+def dropout_embed_timing(steps, warmup, dev="cuda:0"):
+    """Cost of the training-time extras on the 8.3B-shape 1/8 shard: dropout 0.1 at every site (attention
+    probabilities from the worker's own stream, hidden sites from the replicated stream) and the vocabulary-parallel
+    input embedding in front of the layer, against the dropout-free step the benchmark times."""
+    import torch
+    from . import binding as B
+    from . import synth
+    from .pipeline import LayerShards
+    cfg = synth.CONFIGS["gpt2_8p3b"]
+    drop = dict(p_attn=0.1, p_hidden=0.1, base_seed=1234, offsets={"attn": 1, "hidden1": 2, "hidden2": 3, "embed": 4})
+    print(f"# {cfg.name} shard 0 of {cfg.p}, forward + backward, bf16")
+    base = None
+    for label, kw in (("dropout-free (benchmark step)", {}), ("dropout 0.1, all sites", dict(dropout=drop)),
+                      ("dropout 0.1 + input embedding", dict(dropout=drop, embed=True))):
+        L = LayerShards(cfg, [0], dev, store_logits=True, **kw)
+        L.load_random(seed=cfg.seed)
+        for _ in range(warmup):
+            L.step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            L.step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        base = base or ms
+        print(f"{label:34s} {ms * 1e3:9.1f} us/step  ({ms / base:.3f} x)", flush=True)
+        if kw.get("embed"):
+            # the embedding calls on their own (event-timed, one at a time)
+            d0, rep, s0, a = L.dims[0], L.rep, L.sh[0], L.act
+            calls = {
+                "mlm_embed_shard_fwd (rank sort + column gather)":
+                    lambda: B.mlm_embed_shard_fwd(d0, rep["ids"], L.w[0]["E"], s0["perm"], s0["embed_partial"]),
+                "mlm_combine_dropout (+ position embedding)":
+                    lambda: B.mlm_combine_dropout(d0, [s0["embed_partial"]], rep["pos"], cfg.s, L.drop["embed"], None, rep["X"]),
+                "mlm_embed_bwd_replicated":
+                    lambda: B.mlm_embed_bwd_replicated(d0, a["dX"], L.drop["embed"], a["dZ0"], a["dpos"]),
+                "mlm_embed_shard_bwd (run sums into dE columns)":
+                    lambda: B.mlm_embed_shard_bwd(d0, rep["ids"], s0["perm"], a["dZ0"], s0["dE"]),
+            }
+            for name, fn in calls.items():
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(steps):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                print(f"    {name:48s} {e0.elapsed_time(e1) / steps * 1e3:8.1f} us", flush=True)
+        del L
+        torch.cuda.empty_cache()
+
+
 def gemm_data_dependence(steps, warmup, dev="cuda:0"):
     """The same 8192^3 bf16 GEMM launches on operands of different bit activity.  The instruction stream is identical;
     what changes is the power drawn per MFMA, and with it the clock the chip sustains."""
@@ -106,7 +161,7 @@ def gemm_data_dependence(steps, warmup, dev="cuda:0"):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "optimizer", "gemm_data", "all"])
+    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "optimizer", "gemm_data", "dropout", "all"])
     ap.add_argument("--recompute", action="store_true",
                     help="checkpointed variant: re-run the layer's forward before its backward (activation recomputation)")
     ap.add_argument("--steps", type=int, default=20)
@@ -124,6 +179,9 @@ def main():
         return
     if args.sweep == "gemm_data":
         gemm_data_dependence(args.steps, args.warmup)
+        return
+    if args.sweep == "dropout":
+        dropout_embed_timing(args.steps, args.warmup)
         return
     for sw in names:
         print(f"# sweep {sw}" + (" (activation recomputation: layer forward run twice)" if args.recompute else ""))

@@ -179,6 +179,15 @@ def test_small_bf16_dropout_layers(case):
     print(case, "worst:", sorted(errs, key=lambda e: -e[1])[:4])
 
 
+def test_full_size_8p3b_shape_dropout_and_embedding_all_shards():
+    """The 8.3B-shaped layer (s = 1024, H = 3072, 32 heads of 96, vocabulary 51,200, 8 shards: the launch
+    configuration of the benchmark, batch 2 of 8 to bound the oracle's s x s mask and probability tensors) with
+    dropout 0.1 at every site (Section 5) and the input embedding, all shards, against the oracle."""
+    cfg = synth.with_batch(synth.CONFIGS["gpt2_8p3b"], 2)
+    errs = run_dropout_layer(cfg, 0.1, 0.1, scale_w=1.0, embed=True)
+    print("worst max-norm relative errors:", sorted(errs, key=lambda e: -e[1])[:6])
+
+
 # ------------------------------------------------------------------ input embedding on its own
 @pytest.mark.parametrize("dtype,H,V,p", [("fp32", 80, 96, 2), ("bf16", 288, 1024, 4), ("bf16", 3072, 512, 1)])
 def test_embedding_entry_points(dtype, H, V, p):
