@@ -3,38 +3,11 @@ import numpy as np
 import torch
 import torch.nn.functional as TF
 
-from helpers import spec_of
+from helpers import make_stack_model as make_model, spec_of
 from oracle import layer_oracle as O
 from oracle import rng_embed_oracle as R
 from oracle import stack_oracle as S
 from paper_1909_08053_amd import synth
-
-
-def make_model(cfg, n_layers, scale=8.0, dropout=None, seed=0):
-    rng = np.random.default_rng(1000 + seed)
-    layers = []
-    first = None
-    for l in range(n_layers):
-        inp = synth.make_inputs(cfg, nonzero_bias=True, random_ln=True, seed=cfg.seed + 17 * l)
-        first = first or inp
-        P = {k: inp[k].astype(np.float64) for k in S.LAYER_PARAMS}
-        for k in ("Wq", "Wk", "Wv", "Wo", "A", "B"):
-            P[k] = P[k] * scale
-        layers.append(P)
-    model = {"layers": layers, "E": first["E"].astype(np.float64) * scale, "gf": first["gf"].astype(np.float64),
-             "bf": first["bf"].astype(np.float64), "tgt": first["tgt"], "w": first["w"], "key_len": first["key_len"],
-             "ids": rng.integers(0, cfg.V, size=(cfg.b, cfg.s)).astype(np.int32),
-             "pos": rng.standard_normal((cfg.s, cfg.H)) * 0.5}
-    model["ids"][0, :3] = model["ids"][0, 0]
-    if dropout:
-        p_attn, p_hidden = dropout
-        model["drop"] = {
-            "layers": [R.layer_dropout_masks(cfg.b, cfg.s, cfg.H, cfg.h, cfg.p, 5, {"attn": 10 * l + 1, "hidden1": 10 * l + 2,
-                                                                                      "hidden2": 10 * l + 3}, p_attn, p_hidden)
-                       for l in range(n_layers)],
-            "keep0": R.keep_mask(R.stream_seed(5, R.STREAM_REPLICATED, 0), 999, (cfg.T, cfg.H), p_hidden),
-            "p_hidden": float(np.float32(p_hidden))}
-    return model
 
 
 def test_one_layer_stack_equals_the_single_layer_oracle():
