@@ -128,6 +128,53 @@ def dropout_embed_timing(steps, warmup, dev="cuda:0"):
         torch.cuda.empty_cache()
 
 
+def stack_timing(steps, warmup, n_layers=4, dev="cuda:0"):
+    """One worker's training iteration at the 8.3B shape, 1/8 shard, on a stack of `n_layers` layers: embedding,
+    layers, loss, backward, global-norm clip + AdamW.  Four variants: stored activations or checkpointing after every
+    layer (the paper's setting), without and with dropout 0.1 on every site."""
+    import torch
+    from . import synth
+    from .stack import ModelShards
+    cfg = synth.CONFIGS["gpt2_8p3b"]
+    per_layer = shard_flops(cfg)
+    T, H, Vl = cfg.T, cfg.H, cfg.V // cfg.p
+    logits = 3.0 * 2.0 * T * H * Vl
+    layer = per_layer - logits
+    model_flops = n_layers * layer + logits
+    print(f"# {cfg.name} shard 0 of {cfg.p}, {n_layers} layers + embedding + loss + optimizer, bf16; "
+          f"{model_flops / 1e12:.3f} model TFLOP per iteration (recomputation not counted)")
+    drop = dict(p_attn=0.1, p_hidden=0.1, base_seed=99, step=1)
+    for label, kw in (("stored activations, no dropout", dict(checkpoint=False)),
+                      ("checkpoint every layer, no dropout", dict(checkpoint=True)),
+                      ("stored activations, dropout 0.1", dict(checkpoint=False, dropout=drop)),
+                      ("checkpoint every layer, dropout 0.1", dict(checkpoint=True, dropout=drop))):
+        M = ModelShards(cfg, n_layers, [0], dev, **kw)
+        M.load_random(seed=cfg.seed)
+        for i in range(warmup):
+            M.step()
+            M.optimizer_step(i + 1, lr=1e-4)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        t_fb = t_opt = 0.0
+        for i in range(steps):
+            ev[0].record()
+            M.step()
+            ev[1].record()
+            M.optimizer_step(warmup + i + 1, lr=1e-4)
+            ev[2].record()
+            torch.cuda.synchronize()
+            t_fb += ev[0].elapsed_time(ev[1])
+            t_opt += ev[1].elapsed_time(ev[2])
+        t_fb /= steps
+        t_opt /= steps
+        mem = torch.cuda.max_memory_allocated() / 2 ** 30
+        print(f"{label:38s} fwd+bwd {t_fb * 1e3:9.1f} us  optimizer {t_opt * 1e3:7.1f} us  "
+              f"{model_flops / ((t_fb + t_opt) * 1e-3) / 1e12:7.1f} model TFLOP/s  peak memory {mem:5.2f} GiB", flush=True)
+        del M
+        torch.cuda.empty_cache()
+        torch.cuda.reset_peak_memory_stats()
+
+
 def gemm_data_dependence(steps, warmup, dev="cuda:0"):
     """The same 8192^3 bf16 GEMM launches on operands of different bit activity.  The instruction stream is identical;
     what changes is the power drawn per MFMA, and with it the clock the chip sustains."""
@@ -161,7 +208,7 @@ def gemm_data_dependence(steps, warmup, dev="cuda:0"):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "optimizer", "gemm_data", "dropout", "all"])
+    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "optimizer", "gemm_data", "dropout", "stack", "all"])
     ap.add_argument("--recompute", action="store_true",
                     help="checkpointed variant: re-run the layer's forward before its backward (activation recomputation)")
     ap.add_argument("--steps", type=int, default=20)
@@ -179,6 +226,9 @@ def main():
         return
     if args.sweep == "gemm_data":
         gemm_data_dependence(args.steps, args.warmup)
+        return
+    if args.sweep == "stack":
+        stack_timing(args.steps, args.warmup)
         return
     if args.sweep == "dropout":
         dropout_embed_timing(args.steps, args.warmup)
