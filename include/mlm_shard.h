@@ -242,7 +242,7 @@ MLM_API int mlm_vocab_ce_shard_bwd(const mlm_dims* dims, const void* hf, const v
                            void* logits_r, void* dE_r, void* dhf_partial_r,
                            void* ws, size_t ws_bytes, void* stream);
 
-/* ---- optimizer step of one model-parallel worker (Section 5: Adam with decoupled weight decay
+/* ---- optimizer step of one model-parallel worker (Section 4.2: Adam with decoupled weight decay
  *      0.01, global gradient-norm clipping at 1.0, mixed precision; Section 3: every worker
  *      optimises its own parameters, no parameter values are communicated) ----------------- */
 
@@ -278,7 +278,7 @@ MLM_API int mlm_adamw_step_multi(int32_t dtype, int32_t n_tensors, const int64_t
                          const float* weight_decays, const float* total_sqnorm, float max_norm, float lr,
                          float beta1, float beta2, float eps, int32_t step, void* stream);
 
-/* ---- dropout with the two model-parallel random streams (Appendix B.2; Section 5: "a dropout of
+/* ---- dropout with the two model-parallel random streams (Appendix B.2; Section 4.2: "a dropout of
  *      0.1 is used") and the variants of the calls above that apply it ---------------------- */
 
 /* One dropout site.  The paper asks for two random streams: one seeded identically on every
@@ -378,6 +378,21 @@ MLM_API int mlm_embed_bwd_replicated(const mlm_dims* dims, const void* dx0, cons
  * untouched.  perm_r: from mlm_embed_shard_fwd for the same ids. */
 MLM_API int mlm_embed_shard_bwd(const mlm_dims* dims, const int32_t* ids, const int32_t* perm_r, const void* dz0,
                         void* dE_r, void* stream);
+
+/* ---- loss rows only (Section 4: BERT is trained by language-model masking, so the loss sits on a subset of the
+ *      positions; the vocabulary-parallel logits GEMM, the dominant cost, is needed for those rows only) */
+
+/* out[k, :] = x[row_idx[k], :] for k < n and zeros for n <= k < n_out.  x: [T,H] dtype; row_idx: [n] int32
+ * DEVICE array of token rows, strictly increasing, each in [0, T) (not checked on the device: the caller
+ * builds it from the loss mask); out: [n_out, H] dtype.  The compact tensor is then passed to the
+ * mlm_vocab_ce_* calls with dims whose b * s equals n_out (padding rows carry loss weight 0). */
+MLM_API int mlm_rows_gather(const mlm_dims* dims, const void* x, const int32_t* row_idx, int32_t n, int32_t n_out,
+                    void* out, void* stream);
+
+/* Inverse of mlm_rows_gather for the gradient: out[row_idx[k], :] = y[k, :] for k < n, every other row of
+ * out [T,H] is set to zero.  y: [>= n, H] dtype. */
+MLM_API int mlm_rows_scatter(const mlm_dims* dims, const void* y, const int32_t* row_idx, int32_t n, void* out,
+                     void* stream);
 
 /* ---- the GEMM building block (Section 3: "XA", "YB", "XE") --------------------- */
 

@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE ONLY.  This file is the checker, not the product: only ``tes
 ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import it.  It shares
 no code with the HIP path and imports nothing from it.
 
-What it computes.  Section 5 of the paper ("Training Optimization and Hyperparameters"): Adam with
+What it computes.  Section 4.2 of the paper ("Training Optimization and Hyperparameters"): Adam with
 decoupled weight decay (lambda = 0.01), global gradient-norm clipping at 1.0, mixed precision (the
 weights used by the GEMMs are a low-precision copy of fp32 master weights).  Section 3: every
 model-parallel worker optimises its own parameters, no parameter communication -- the only number

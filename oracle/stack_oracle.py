@@ -1,6 +1,6 @@
 """fp64 CPU oracle of an N-layer stack: token + position embedding, N pre-LN transformer layers, final layer norm,
 output embedding tied to the input embedding, mean cross entropy -- the model whose per-GPU share the paper trains
-with activation checkpointing after every layer (Section 5).
+with activation checkpointing after every layer (Section 4.2).
 
 TEST INFRASTRUCTURE ONLY (see oracle/layer_oracle.py): only tests/, the smoke test and the benchmark's cpu_baseline leg
 may import it; it shares no code with the HIP path.

@@ -24,7 +24,7 @@ EXPORTS = ("mlm_shard_range", "mlm_workspace_bytes", "mlm_status_string", "mlm_l
            "mlm_adamw_step", "mlm_adamw_step_multi", "mlm_rng_stream_seed", "mlm_combine_dropout",
            "mlm_combine_layernorm_fwd_dropout", "mlm_combine_layernorm_bwd_dropout", "mlm_attn_keep_words",
            "mlm_attn_shard_fwd_dropout", "mlm_attn_shard_bwd_dropout", "mlm_embed_shard_fwd", "mlm_embed_bwd_replicated",
-           "mlm_embed_shard_bwd")
+           "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter")
 STREAM_REPLICATED, STREAM_MODEL_PARALLEL = 0, 1
 
 
@@ -304,4 +304,14 @@ def mlm_embed_bwd_replicated(dims, dx0, drop, dz0, dpos, stream=None):
 
 def mlm_embed_shard_bwd(dims, ids, perm_r, dz0, dE_r, stream=None):
     _chk(lib().mlm_embed_shard_bwd(ctypes.byref(dims), _p(ids), _p(perm_r), _p(dz0), _p(dE_r), _st(stream)),
-         "mlm_embed_shard_bwd")
+         "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter")
+
+
+def mlm_rows_gather(dims, x, row_idx, n, n_out, out, stream=None):
+    _chk(lib().mlm_rows_gather(ctypes.byref(dims), _p(x), _p(row_idx), ctypes.c_int32(n), ctypes.c_int32(n_out), _p(out),
+                               _st(stream)), "mlm_rows_gather")
+
+
+def mlm_rows_scatter(dims, y, row_idx, n, out, stream=None):
+    _chk(lib().mlm_rows_scatter(ctypes.byref(dims), _p(y), _p(row_idx), ctypes.c_int32(n), _p(out), _st(stream)),
+         "mlm_rows_scatter")

@@ -614,6 +614,28 @@ MLM_API int mlm_embed_shard_bwd(const mlm_dims* dims, const int32_t* ids, const 
                                      (hipStream_t)stream));
 }
 
+MLM_API int mlm_rows_gather(const mlm_dims* dims, const void* x, const int32_t* row_idx, int32_t n, int32_t n_out,
+                            void* out, void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if (!x || !row_idx || !out) return MLM_E_NULL;
+  if (n < 0 || n > L.T || n_out < n || n_out < 1) return MLM_E_SHAPE;
+  if (!aligned16(x) || !aligned16(out)) return MLM_E_ALIGN;
+  return hip_status(launch_rows_gather(dims->dtype, n, n_out, dims->H, row_idx, x, out, (hipStream_t)stream));
+}
+
+MLM_API int mlm_rows_scatter(const mlm_dims* dims, const void* y, const int32_t* row_idx, int32_t n, void* out,
+                             void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if (!y || !row_idx || !out) return MLM_E_NULL;
+  if (n < 0 || n > L.T) return MLM_E_SHAPE;
+  if (!aligned16(y) || !aligned16(out)) return MLM_E_ALIGN;
+  return hip_status(launch_rows_scatter(dims->dtype, n, L.T, dims->H, row_idx, y, out, (hipStream_t)stream));
+}
+
 MLM_API int mlm_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K, const void* A,
              const void* B, void* C, const void* bias, void* stream) {
   if (dtype != MLM_F32 && dtype != MLM_BF16) return MLM_E_DTYPE;

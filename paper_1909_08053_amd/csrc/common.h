@@ -176,6 +176,10 @@ hipError_t launch_ce_merge(int T, int n_shards, const float* m, const float* s, 
 hipError_t launch_dlogits_inplace(int dtype, int T, int Vl, void* logits, const int32_t* targets, int v0,
                                   const float* M, const float* S, const float* loss_w, const float* loss_stats,
                                   hipStream_t st);
+hipError_t launch_rows_gather(int dtype, int n, int n_out, int H, const int32_t* idx, const void* x, void* out,
+                              hipStream_t st);
+hipError_t launch_rows_scatter(int dtype, int n, int rows, int H, const int32_t* idx, const void* y, void* out,
+                               hipStream_t st);
 hipError_t launch_embed_fwd(int dtype, int T, int H, int Vl, int v0, const int32_t* ids, const void* E, int32_t* perm,
                             void* partial, hipStream_t st);
 hipError_t launch_embed_bwd(int dtype, int T, int H, int Vl, int v0, const int32_t* ids, const int32_t* perm,

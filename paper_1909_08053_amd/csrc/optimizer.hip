@@ -1,4 +1,4 @@
-// One model-parallel worker's optimizer step (Section 5 of the paper: Adam with decoupled weight decay, global
+// One model-parallel worker's optimizer step (Section 4.2 of the paper: Adam with decoupled weight decay, global
 // gradient-norm clipping, fp32 master weights behind the low-precision weights the GEMMs read; Section 3: every
 // worker updates its own parameters, only the squared gradient norm crosses workers).  Bandwidth-bound: 28 bytes
 // per bf16 parameter (gradient 2, master / m / v read and written 24, weight 2).

@@ -673,6 +673,72 @@ hipError_t launch_dlogits_inplace(int dtype, int T, int Vl, void* logits, const 
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------ row gather / scatter
+// out[k, :] = x[idx[k], :] for k < n, zeros for n <= k < n_out (gather); out[idx[k], :] = y[k, :] and zeros in every
+// other row (scatter; idx strictly increasing, so each output row has at most one source: found by binary search).
+template <typename T>
+__global__ __launch_bounds__(256) void rows_gather_kernel(int n, int n_out, int H, const int32_t* __restrict__ idx,
+                                                          const T* __restrict__ x, T* __restrict__ out) {
+  constexpr int VN = Vec16<T>::N;
+  const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (k >= n_out) return;
+  const int lane = threadIdx.x & 63;
+  const T* src = k < n ? x + (size_t)idx[k] * H : nullptr;
+  for (int v = lane; v < H / VN; v += 64) {
+    Vec16<T> t;
+    if (src) t.load(src + (size_t)v * VN);
+    else {
+#pragma unroll
+      for (int e = 0; e < VN; ++e) t.set(e, 0.f);
+    }
+    t.store(out + (size_t)k * H + (size_t)v * VN);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rows_scatter_kernel(int n, int rows, int H, const int32_t* __restrict__ idx,
+                                                           const T* __restrict__ y, T* __restrict__ out) {
+  constexpr int VN = Vec16<T>::N;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int lane = threadIdx.x & 63;
+  int lo = 0, hi = n;                                  // first k with idx[k] >= r (wave-uniform search)
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (idx[mid] < r) lo = mid + 1; else hi = mid;
+  }
+  const T* src = (lo < n && idx[lo] == r) ? y + (size_t)lo * H : nullptr;
+  for (int v = lane; v < H / VN; v += 64) {
+    Vec16<T> t;
+    if (src) t.load(src + (size_t)v * VN);
+    else {
+#pragma unroll
+      for (int e = 0; e < VN; ++e) t.set(e, 0.f);
+    }
+    t.store(out + (size_t)r * H + (size_t)v * VN);
+  }
+}
+
+hipError_t launch_rows_gather(int dtype, int n, int n_out, int H, const int32_t* idx, const void* x, void* out,
+                              hipStream_t st) {
+  dim3 grid((n_out + 3) / 4), block(256);
+  if (dtype == MLM_BF16)
+    hipLaunchKernelGGL((rows_gather_kernel<bf16>), grid, block, 0, st, n, n_out, H, idx, (const bf16*)x, (bf16*)out);
+  else
+    hipLaunchKernelGGL((rows_gather_kernel<float>), grid, block, 0, st, n, n_out, H, idx, (const float*)x, (float*)out);
+  return hipGetLastError();
+}
+
+hipError_t launch_rows_scatter(int dtype, int n, int rows, int H, const int32_t* idx, const void* y, void* out,
+                               hipStream_t st) {
+  dim3 grid((rows + 3) / 4), block(256);
+  if (dtype == MLM_BF16)
+    hipLaunchKernelGGL((rows_scatter_kernel<bf16>), grid, block, 0, st, n, rows, H, idx, (const bf16*)y, (bf16*)out);
+  else
+    hipLaunchKernelGGL((rows_scatter_kernel<float>), grid, block, 0, st, n, rows, H, idx, (const float*)y, (float*)out);
+  return hipGetLastError();
+}
+
 // delta[b, head, i] = sum_c dctx[t, head*d + c] * ctx[t, head*d + c]  (row sum of dP o P in the softmax gradient)
 template <typename T>
 __global__ __launch_bounds__(256) void attn_delta_kernel(int Tn, int hl, int d, int s, const T* __restrict__ ctx,

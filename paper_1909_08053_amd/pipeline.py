@@ -24,7 +24,7 @@ def _tdtype(cfg: LayerConfig):
 class LayerShards:
     def __init__(self, cfg: LayerConfig, shards: Sequence[int], device: str = "cuda:0", store_logits: bool = True,
                  fused: bool = True, store_combined: bool = False, dropout: Optional[Dict[str, object]] = None,
-                 embed: bool = False):
+                 embed: bool = False, loss_rows: bool = False):
         """fused: the combine that stands in for an all-reduce runs inside the layer-norm kernel that consumes it
         (and the layer-norm backward also emits the row-parallel bias gradient); store_combined: in fused mode,
         also store the combined gradients dHf / dU2 / dU (nothing in the path reads them).
@@ -32,10 +32,13 @@ class LayerShards:
         the two-stream dropout of Appendix B.2 (fused mode only): the attention-probability site of shard r draws
         from worker r's model-parallel stream, the hidden sites from the replicated stream.
         embed: the layer input is produced by the vocabulary-parallel input embedding (token ids + position
-        embedding) instead of being given, and its backward adds into the tied dE."""
+        embedding) instead of being given, and its backward adds into the tied dE.
+        loss_rows: the rows of the final hidden state that carry loss weight are gathered first and the vocabulary-
+        parallel logits / loss / gradient calls run on that compact tensor only (BERT-style masked-LM loss: ~15 % of
+        the positions); the input gradient is scattered back with zeros elsewhere.  Same loss and gradients."""
         self.cfg, self.shards, self.dev = cfg, list(shards), torch.device(device)
         self.fused, self.store_combined = fused, store_combined
-        self.dropout, self.embed = dropout, embed
+        self.dropout, self.embed, self.loss_rows = dropout, embed, loss_rows
         if dropout is not None and not fused:
             raise ValueError("dropout is wired into the fused combine + layer-norm calls only")
         self.dt = _tdtype(cfg)
@@ -89,6 +92,34 @@ class LayerShards:
                 "A": up(inp["A"][:, f0:f1]), "a": up(inp["a"][f0:f1]), "B": up(inp["B"][f0:f1, :]),
                 "E": up(inp["E"][:, v0:v1]),
             }
+        self._prepare_loss_rows()
+
+    def _prepare_loss_rows(self):
+        """Row list of the positions with loss weight 1 and the compact targets / weights / buffers (input plumbing:
+        an index list built from the given loss mask)."""
+        if not self.loss_rows:
+            return
+        cfg, dev, dt, f32 = self.cfg, self.dev, self.dt, torch.float32
+        idx = torch.nonzero(self.rep["w"] > 0).reshape(-1).to(torch.int32)
+        n = int(idx.numel())
+        n_pad = max(8, (n + 7) // 8 * 8)
+        self.n_rows, self.n_pad = n, n_pad
+        self.rep["row_idx"] = idx.contiguous()
+        tgt_c = torch.zeros(n_pad, device=dev, dtype=torch.int32)
+        tgt_c[:n] = self.rep["tgt"][idx.long()]
+        w_c = torch.zeros(n_pad, device=dev, dtype=f32)
+        w_c[:n] = 1.0
+        self.rep["tgt_c"], self.rep["w_c"] = tgt_c, w_c
+        self.dims_c = {r: B.make_dims(1, n_pad, cfg.H, cfg.h, cfg.F, cfg.V, cfg.p, r, self.code, cfg.causal,
+                                      cfg.gelu_tanh, cfg.ln_eps) for r in range(cfg.p)}
+        e = lambda *shape, dtype=dt: torch.empty(*shape, device=dev, dtype=dtype)
+        a, ns = self.act, len(self.shards)
+        a["Hf_c"], a["dHf_c"] = e(n_pad, cfg.H), e(n_pad, cfg.H)
+        a["m"], a["s"], a["t"] = e(ns, n_pad, dtype=f32), e(ns, n_pad, dtype=f32), e(ns, n_pad, dtype=f32)
+        a["ce"], a["M"], a["S"] = e(n_pad, dtype=f32), e(n_pad, dtype=f32), e(n_pad, dtype=f32)
+        for r in self.shards:
+            self.sh[r]["logits"] = e(n_pad, self.Vl) if self.store_logits else None
+            self.sh[r]["dhf_partial"] = e(n_pad, cfg.H)
 
     def load_random(self, seed: int = 0):
         """Synthetic inputs drawn on the device (benchmark use: same shapes and distributions as synth.make_inputs)."""
@@ -117,6 +148,7 @@ class LayerShards:
         for r in self.shards:
             self.w[r] = {"Wqkv": rn(H, 3 * self.Hl), "bqkv": zeros(3 * self.Hl), "Wo": rn(self.Hl, H),
                          "A": rn(H, self.Fl), "a": zeros(self.Fl), "B": rn(self.Fl, H), "E": rn(H, self.Vl)}
+        self._prepare_loss_rows()
 
     # ------------------------------------------------------------------ buffers
     def _alloc(self):
@@ -219,25 +251,37 @@ class LayerShards:
             B.mlm_combine(d0, mlp_partials, rep["c"], a["X1"], a["X2"])
             hf = a["X2"]
         self._hf = hf
+        cdims, tgt, lw, dc0 = self.dims, rep["tgt"], rep["w"], d0
+        if self.loss_rows:
+            B.mlm_rows_gather(d0, hf, rep["row_idx"], self.n_rows, self.n_pad, a["Hf_c"])
+            hf, cdims, tgt, lw = a["Hf_c"], self.dims_c, rep["tgt_c"], rep["w_c"]
+            dc0 = cdims[self.shards[0]]
         for i, r in enumerate(self.shards):
             w, s = self.w[r], self.sh[r]
-            B.mlm_vocab_ce_shard_fwd(self.dims[r], hf, w["E"], rep["tgt"], a["m"][i], a["s"][i], a["t"][i], s["logits"],
-                                     ws)
-        B.mlm_vocab_ce_merge(d0, a["m"], a["s"], a["t"], len(self.shards), rep["w"], a["ce"], a["M"], a["S"],
-                             a["loss"])
+            B.mlm_vocab_ce_shard_fwd(cdims[r], hf, w["E"], tgt, a["m"][i], a["s"][i], a["t"][i], s["logits"], ws)
+        B.mlm_vocab_ce_merge(dc0, a["m"], a["s"], a["t"], len(self.shards), lw, a["ce"], a["M"], a["S"], a["loss"])
 
     def backward(self):
         cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
         d0 = self.dims[self.shards[0]]
         kl = rep["key_len"] if cfg.masked_lm else None
         hf = self._hf
+        cdims, tgt, lw = self.dims, rep["tgt"], rep["w"]
+        if self.loss_rows:
+            hf, cdims, tgt, lw = a["Hf_c"], self.dims_c, rep["tgt_c"], rep["w_c"]
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
-            B.mlm_vocab_ce_shard_bwd(self.dims[r], hf, w["E"], rep["tgt"], rep["w"], a["M"], a["S"], a["loss"],
-                                     s["logits"], s["dE"], s["dhf_partial"], ws)
+            B.mlm_vocab_ce_shard_bwd(cdims[r], hf, w["E"], tgt, lw, a["M"], a["S"], a["loss"], s["logits"], s["dE"],
+                                     s["dhf_partial"], ws)
         fused = self.fused
-        keep = (lambda k: a[k]) if self.store_combined else (lambda k: None)
+        # (with loss_rows the combined dHf IS the one partial: it must not also be the kernel's dy_out)
+        keep = (lambda k: None if (k == "dHf" and self.loss_rows) else a[k]) if self.store_combined else (lambda k: None)
         dhf_partials = [self.sh[r]["dhf_partial"] for r in self.shards]
+        if self.loss_rows:
+            # reduce the compact partials, then put the rows back (zeros elsewhere): one [T,H] "partial" for what follows
+            B.mlm_combine(cdims[self.shards[0]], dhf_partials, None, None, a["dHf_c"])
+            B.mlm_rows_scatter(d0, a["dHf_c"], rep["row_idx"], self.n_rows, a["dHf"])
+            dhf_partials = [a["dHf"]]
         drop = self.dropout is not None
         dz2 = dz1 = None          # gradients of the block outputs BEFORE their dropout (what the shards' backward reads)
         if drop and cfg.final_ln:
@@ -305,7 +349,7 @@ class LayerShards:
             for r in self.shards:
                 B.mlm_embed_shard_bwd(self.dims[r], rep["ids"], self.sh[r]["perm"], a["dZ0"], self.sh[r]["dE"])
 
-    # Activation recomputation (the paper checkpoints activations after every transformer layer, Section 5): only the
+    # Activation recomputation (the paper checkpoints activations after every transformer layer, Section 4.2): only the
     # layer input X is kept; everything the layer's backward reads is produced again by re-running the layer's forward
     # calls (not the final layer norm / loss, which belong to the model's head) right before the backward.
     LAYER_ACTIVATIONS = ("U", "mu1", "rstd1", "X1", "U2", "mu2", "rstd2")

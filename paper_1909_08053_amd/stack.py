@@ -2,7 +2,7 @@
 N transformer layers, final layer norm, vocabulary-parallel loss, backward, optimizer (allocation and call order only;
 all arithmetic is in the HIP library).
 
-The paper trains with activation checkpointing after every transformer layer (Section 5): with ``checkpoint=True``
+The paper trains with activation checkpointing after every transformer layer (Section 4.2): with ``checkpoint=True``
 only the layer INPUTS are kept by the forward pass, all layers share one set of activation buffers, and the backward
 pass re-runs layer l's forward calls from its saved input right before layer l's backward calls.  Dropout masks come
 from the counter-based generator, so the recomputed forward reproduces them exactly (Appendix B.2 needs the same:
@@ -86,7 +86,7 @@ class ModelShards:
             self.E[r] = up(np.asarray(model["E"])[:, v0:v1])
 
     def load_random(self, seed: int = 0):
-        """Synthetic parameters and inputs drawn on the device (weights N(0, std 0.02), Section 5)."""
+        """Synthetic parameters and inputs drawn on the device (weights N(0, std 0.02), Section 4.2)."""
         cfg, H = self.cfg, self.cfg.H
         g = torch.Generator(device=self.dev)
         g.manual_seed(seed)

@@ -175,6 +175,35 @@ def stack_timing(steps, warmup, n_layers=4, dev="cuda:0"):
         torch.cuda.reset_peak_memory_stats()
 
 
+def bert_loss_rows_timing(steps, warmup, dev="cuda:0"):
+    """The BERT-shaped shard (3.9B shape, shard 0 of 4, masked-LM loss on ~15 % of the valid positions): logits for
+    every row versus logits for the loss rows only."""
+    import torch
+    from . import synth
+    from .pipeline import LayerShards
+    cfg = synth.CONFIGS["bert_3p9b"]
+    print(f"# {cfg.name} shard 0 of {cfg.p}, forward + backward, bf16")
+    base = None
+    for label, kw in (("logits for all rows", {}), ("logits for the loss rows only", dict(loss_rows=True))):
+        L = LayerShards(cfg, [0], dev, store_logits=True, **kw)
+        L.load_random(seed=cfg.seed)
+        for _ in range(warmup):
+            L.step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            L.step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        base = base or ms
+        extra = f"  ({L.n_rows} of {cfg.T} rows)" if kw else ""
+        print(f"{label:32s} {ms * 1e3:9.1f} us/step  ({ms / base:.3f} x){extra}", flush=True)
+        del L
+        torch.cuda.empty_cache()
+
+
 def gemm_data_dependence(steps, warmup, dev="cuda:0"):
     """The same 8192^3 bf16 GEMM launches on operands of different bit activity.  The instruction stream is identical;
     what changes is the power drawn per MFMA, and with it the clock the chip sustains."""
@@ -208,7 +237,7 @@ def gemm_data_dependence(steps, warmup, dev="cuda:0"):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "optimizer", "gemm_data", "dropout", "stack", "all"])
+    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "optimizer", "gemm_data", "dropout", "stack", "bert_rows", "all"])
     ap.add_argument("--recompute", action="store_true",
                     help="checkpointed variant: re-run the layer's forward before its backward (activation recomputation)")
     ap.add_argument("--steps", type=int, default=20)
@@ -226,6 +255,9 @@ def main():
         return
     if args.sweep == "gemm_data":
         gemm_data_dependence(args.steps, args.warmup)
+        return
+    if args.sweep == "bert_rows":
+        bert_loss_rows_timing(args.steps, args.warmup)
         return
     if args.sweep == "stack":
         stack_timing(args.steps, args.warmup)

@@ -182,7 +182,7 @@ def test_small_bf16_dropout_layers(case):
 def test_full_size_8p3b_shape_dropout_and_embedding_all_shards():
     """The 8.3B-shaped layer (s = 1024, H = 3072, 32 heads of 96, vocabulary 51,200, 8 shards: the launch
     configuration of the benchmark, batch 2 of 8 to bound the oracle's s x s mask and probability tensors) with
-    dropout 0.1 at every site (Section 5) and the input embedding, all shards, against the oracle."""
+    dropout 0.1 at every site (Section 4.2) and the input embedding, all shards, against the oracle."""
     cfg = synth.with_batch(synth.CONFIGS["gpt2_8p3b"], 2)
     errs = run_dropout_layer(cfg, 0.1, 0.1, scale_w=1.0, embed=True)
     print("worst max-norm relative errors:", sorted(errs, key=lambda e: -e[1])[:6])
@@ -258,3 +258,60 @@ def test_dropout_recompute_and_determinism_bf16():
     for k, v in grads[0].items():
         assert torch.isfinite(v.float()).all(), k
         assert torch.equal(v, grads[1][k]), k
+
+
+# ------------------------------------------------------------------ loss on the masked rows only (BERT-shaped loss)
+def _run_loss_rows(cfg, scale_w, dropout=None):
+    inp = synth.make_inputs(cfg, nonzero_bias=True, random_ln=True)
+    for k in ("Wq", "Wk", "Wv", "Wo", "A", "B", "E"):
+        inp[k] = inp[k] * np.float32(scale_w)
+        if cfg.dtype == "bf16":
+            inp[k] = synth.round_to_bf16(inp[k])
+    if dropout:
+        inp["drop"] = R.layer_dropout_masks(cfg.b, cfg.s, cfg.H, cfg.h, cfg.p, BASE_SEED, OFFSETS, *dropout)
+    ref = O.sharded_reference(inp, spec_of(cfg), cfg.p)
+    L = LayerShards(cfg, list(range(cfg.p)), DEV, store_combined=True, loss_rows=True,
+                    dropout=dict(p_attn=dropout[0], p_hidden=dropout[1], base_seed=BASE_SEED, offsets=OFFSETS) if dropout else None)
+    L.load_host_inputs(inp)
+    L.step()
+    out = L.fetch()
+    tol = TOL[cfg.dtype]
+    rows = np.flatnonzero(inp["w"].reshape(-1) > 0)
+    assert np.array_equal(L.rep["row_idx"].cpu().numpy(), rows) and L.n_rows == rows.size     # integer work
+    errs = []
+    assert abs(out["loss"] - ref["loss"]) <= tol * abs(ref["loss"])
+    assert out["wsum"] == float(rows.size)
+    check("ce(rows)", out["ce"][:rows.size], ref["ce"][rows], tol, errs)
+    check("Hf_c", out["Hf_c"][:rows.size], ref["Hf"][rows], tol, errs)
+    assert np.all(out["Hf_c"][rows.size:] == 0.0)
+    got_dhf = out["dHf"]
+    assert np.all(got_dhf[np.setdiff1d(np.arange(cfg.T), rows)] == 0.0)         # rows without loss: exactly zero
+    check("dHf", got_dhf, ref["dHf"], tol, errs)
+    for k in ("dX2", "dX1", "dX", "dgf", "dbf", "dg2", "db1", "dc", "dbo"):
+        if k in ("dgf", "dbf") and not cfg.final_ln:
+            continue
+        check(k, out[k], ref[k], tol, errs)
+    for r in range(cfg.p):
+        g, rs = out["shards"][r], ref["shards"][r]
+        check(f"shard{r}.logits->dlogits", g["logits"][:rows.size], rs["dlogits"][rows], tol, errs)
+        for k in ("dE", "dA", "dB", "dWqkv", "dWo"):
+            check(f"shard{r}.{k}", g[k], rs[k], tol, errs)
+    return errs
+
+
+@pytest.mark.parametrize("variant", ["fp32", "fp32_no_final_ln", "bf16", "bf16_dropout"])
+def test_loss_rows_gather_matches_full_loss(variant):
+    kw = dict(b=3, s=136, H=128, h=2, F=512, V=640, p=2, causal=False, masked_lm=True)
+    if variant.startswith("fp32"):
+        cfg = synth.small_config(dtype="fp32", final_ln=variant == "fp32", **kw)
+    else:
+        cfg = synth.small_config(dtype="bf16", **kw)
+    errs = _run_loss_rows(cfg, 3.0, dropout=(0.1, 0.1) if variant.endswith("dropout") else None)
+    print(variant, "worst:", sorted(errs, key=lambda e: -e[1])[:4])
+
+
+def test_full_size_bert_shape_loss_rows_all_shards():
+    """The BERT-shaped workload (3.9B shape, 4 shards, masked-LM loss on ~15 % of the valid positions) with the logits
+    computed for the loss rows only, all shards, against the oracle of the full layer."""
+    errs = _run_loss_rows(synth.CONFIGS["bert_3p9b"], 1.0)
+    print("worst max-norm relative errors:", sorted(errs, key=lambda e: -e[1])[:6])

@@ -1,4 +1,4 @@
-"""CPU pins of the optimizer oracle (Section 5 of the paper: Adam with decoupled weight decay 0.01, global gradient
+"""CPU pins of the optimizer oracle (Section 4.2 of the paper: Adam with decoupled weight decay 0.01, global gradient
 norm clipping at 1.0).  None of these re-types the oracle's formula: they are closed forms, a hand-worked example
 and a library routine."""
 import math
