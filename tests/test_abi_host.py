@@ -114,3 +114,63 @@ def test_validation_of_fused_and_optimizer_entry_points():
     assert step(64, 1, 1.0, None) == -1            # clipping asked for without a norm
     assert L.mlm_adamw_step(0, ctypes.c_int64(64), ok, ok, ok, ok, None, None, f(0.0), f(1e-3), f(1.0), f(0.999),
                             f(1e-8), f(0.0), 1, None) == -2          # beta1 must be < 1
+
+
+def test_rng_stream_seeds_and_keep_words_are_exact():
+    """Integer host helpers of the dropout entry points against the oracle's rule and a direct count."""
+    from oracle import rng_embed_oracle as R
+    for base in (0, 1, 7, 2 ** 32 - 1, 2 ** 32, 2 ** 63, 2 ** 64 - 9, 2 ** 64 - 1):
+        for r in (0, 1, 7, 8, 511):
+            assert B.mlm_rng_stream_seed(base, B.STREAM_REPLICATED, r) == R.stream_seed(base, R.STREAM_REPLICATED, r)
+            assert B.mlm_rng_stream_seed(base, B.STREAM_MODEL_PARALLEL, r) == R.stream_seed(base, R.STREAM_MODEL_PARALLEL, r)
+    for bad in ((5, 2, 0), (5, 1, -1)):
+        with pytest.raises(B.MlmError) as ei:
+            B.mlm_rng_stream_seed(*bad)
+        assert ei.value.code == -2
+    for b, s, h, p in ((2, 128, 4, 2), (3, 200, 4, 4), (1, 40, 2, 1), (8, 1024, 32, 8)):
+        d = _dims(b=b, s=s, H=64 * h, h=h, F=256 * h, V=1024, p=p)
+        pitch = 4 * -(-s // 128)                    # whole 16-byte groups of 32-key words per query row
+        assert pitch * 32 >= s
+        assert B.mlm_attn_keep_words(d) == b * (h // p) * s * pitch
+
+
+def test_validation_of_dropout_embedding_and_row_entry_points():
+    """Bad arguments are refused on the host before any launch (the addresses below are never dereferenced)."""
+    L = B.lib()
+    d = _dims()                                    # b=2, s=128: T = 256
+    P = ctypes.c_void_p
+    ok, odd = P(4096), P(4100)
+    one = (P * 1)(4096)
+    drop = lambda p: ctypes.byref(B.make_dropout(p, 1, 2))
+    ref = ctypes.byref
+    # probability outside [0, 1)
+    assert L.mlm_combine_dropout(ref(d), one, 1, None, 1, drop(1.0), None, ok, None) == -2
+    assert L.mlm_combine_dropout(ref(d), one, 1, None, 1, drop(-0.5), None, ok, None) == -2
+    assert L.mlm_combine_dropout(ref(d), one, 1, ok, 0, None, None, ok, None) == -2          # bias rows < 1
+    assert L.mlm_combine_dropout(ref(d), one, 1, ok, 257, None, None, ok, None) == -2        # more bias rows than tokens
+    assert L.mlm_combine_dropout(ref(d), one, 1, None, 1, None, None, None, None) == -1
+    assert L.mlm_combine_dropout(ref(d), one, 1, None, 1, None, None, odd, None) == -5
+    # layer-norm backward with dropout needs somewhere to put dz, and not on top of dx
+    big = ctypes.c_size_t(1 << 30)
+    assert L.mlm_combine_layernorm_bwd_dropout(ref(d), one, 1, ok, ok, ok, ok, None, drop(0.1), None, ok, None, ok, ok,
+                                               None, ok, big, None) == -1
+    assert L.mlm_combine_layernorm_bwd_dropout(ref(d), one, 1, ok, ok, ok, ok, None, drop(0.1), None, ok, ok, ok, ok,
+                                               None, ok, big, None) == -1
+    # attention dropout: keep-bit buffer required, sequence length a multiple of 4
+    args = lambda dd, dr, kb: L.mlm_attn_shard_fwd_dropout(ref(dd), ok, ok, None, ok, None, dr, ok, ok, ok, kb, ok, ok,
+                                                           big, None)
+    assert args(d, drop(0.1), None) == -1
+    assert args(d, drop(0.1), odd) == -5
+    assert args(_dims(s=126), drop(0.1), ok) == -5
+    assert args(d, drop(1.5), ok) == -2
+    # embedding and row gather / scatter
+    assert L.mlm_embed_shard_fwd(ref(d), None, ok, ok, ok, None) == -1
+    assert L.mlm_embed_shard_fwd(ref(d), ok, odd, ok, ok, None) == -5
+    assert L.mlm_embed_bwd_replicated(ref(d), ok, None, None, None, None) == -1
+    assert L.mlm_embed_bwd_replicated(ref(d), ok, drop(0.1), None, ok, None) == -1            # dropout needs dz0
+    assert L.mlm_embed_shard_bwd(ref(d), ok, ok, ok, None, None) == -1
+    assert L.mlm_rows_gather(ref(d), ok, ok, 300, 304, ok, None) == -2                        # more rows than tokens
+    assert L.mlm_rows_gather(ref(d), ok, ok, 10, 8, ok, None) == -2                           # n_out < n
+    assert L.mlm_rows_gather(ref(d), ok, None, 10, 16, ok, None) == -1
+    assert L.mlm_rows_scatter(ref(d), ok, ok, -1, ok, None) == -2
+    assert L.mlm_rows_scatter(ref(d), odd, ok, 4, ok, None) == -5
