@@ -352,6 +352,37 @@ MLM_API int mlm_attn_shard_bwd_dropout(const mlm_dims* dims, const void* dx1, co
                                const uint32_t* keep_bits_r, void* dWqkv_r, void* dbqkv_r, void* dWo_r,
                                void* du_partial_r, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- backward of a layer shard with the weight gradients deferred ---------------
+ * Section 3 puts the synchronisation points on the ACTIVATION gradients (the operator f); a weight gradient
+ * dW = X^T dY is local to its GPU and nothing but the optimizer waits for it.  The two calls below are the
+ * backward calls above without their weight-gradient GEMMs -- they leave the gradients of the column-parallel
+ * activations in caller buffers instead -- and mlm_layer_shard_wgrads then computes the four weight gradients
+ * of the layer shard together: their GEMMs share one launch, hence one partially filled last round of the
+ * 256 compute units instead of four (each with its own k-split and fix-up pass). */
+
+/* mlm_mlp_shard_bwd without dA_r / dB_r.  dg_r: [T, F_l] dtype OUTPUT, dG = (dx2 B_r^T) o GeLU'(g_r). */
+MLM_API int mlm_mlp_shard_bwd_input(const mlm_dims* dims, const void* dx2, const void* A_r, const void* B_r,
+                            const void* g_r, void* dg_r, void* da_r, void* du2_partial_r,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* mlm_attn_shard_bwd(_dropout) without dWqkv_r / dWo_r.  dqkv_r: [T, 3 H_l] dtype OUTPUT, the gradient of
+ * qkv_r.  drop / keep_bits_r as in mlm_attn_shard_bwd_dropout (both NULL: no dropout). */
+MLM_API int mlm_attn_shard_bwd_input(const mlm_dims* dims, const void* dx1, const void* Wqkv_r, const void* Wo_r,
+                             const int32_t* key_len, const mlm_dropout* drop, const void* qkv_r,
+                             const void* ctx_r, const float* lse_r, const uint32_t* keep_bits_r,
+                             void* dqkv_r, void* dbqkv_r, void* du_partial_r,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* The four weight gradients of the layer shard:
+ *   dWqkv_r = u^T dqkv_r   [H, 3 H_l]      dWo_r = ctx_r^T dz1   [H_l, H]
+ *   dA_r    = u2^T dg_r    [H, F_l]        dB_r  = y_r^T dz2     [F_l, H]
+ * dz1 / dz2: the [T,H] gradients the two backward calls were given as dx1 / dx2 (still intact).
+ * ws: MLM_WS_MLP_BWD bytes is enough. */
+MLM_API int mlm_layer_shard_wgrads(const mlm_dims* dims, const void* u, const void* dqkv_r, const void* ctx_r,
+                           const void* dz1, const void* u2, const void* dg_r, const void* y_r, const void* dz2,
+                           void* dWqkv_r, void* dWo_r, void* dA_r, void* dB_r,
+                           void* ws, size_t ws_bytes, void* stream);
+
 /* ---- vocabulary-parallel input embedding (Section 3: the input embedding shares its weights with the
  *      output embedding E [H, v] and is split along the vocabulary like it; "an all-reduce (g operator)
  *      is required after the input embedding") ------------------------------------------------------ */

@@ -24,7 +24,8 @@ EXPORTS = ("mlm_shard_range", "mlm_workspace_bytes", "mlm_status_string", "mlm_l
            "mlm_adamw_step", "mlm_adamw_step_multi", "mlm_rng_stream_seed", "mlm_combine_dropout",
            "mlm_combine_layernorm_fwd_dropout", "mlm_combine_layernorm_bwd_dropout", "mlm_attn_keep_words",
            "mlm_attn_shard_fwd_dropout", "mlm_attn_shard_bwd_dropout", "mlm_embed_shard_fwd", "mlm_embed_bwd_replicated",
-           "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter")
+           "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter",
+           "mlm_mlp_shard_bwd_input", "mlm_attn_shard_bwd_input", "mlm_layer_shard_wgrads")
 STREAM_REPLICATED, STREAM_MODEL_PARALLEL = 0, 1
 
 
@@ -304,7 +305,8 @@ def mlm_embed_bwd_replicated(dims, dx0, drop, dz0, dpos, stream=None):
 
 def mlm_embed_shard_bwd(dims, ids, perm_r, dz0, dE_r, stream=None):
     _chk(lib().mlm_embed_shard_bwd(ctypes.byref(dims), _p(ids), _p(perm_r), _p(dz0), _p(dE_r), _st(stream)),
-         "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter")
+         "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter",
+           "mlm_mlp_shard_bwd_input", "mlm_attn_shard_bwd_input", "mlm_layer_shard_wgrads")
 
 
 def mlm_rows_gather(dims, x, row_idx, n, n_out, out, stream=None):
@@ -315,3 +317,22 @@ def mlm_rows_gather(dims, x, row_idx, n, n_out, out, stream=None):
 def mlm_rows_scatter(dims, y, row_idx, n, out, stream=None):
     _chk(lib().mlm_rows_scatter(ctypes.byref(dims), _p(y), _p(row_idx), ctypes.c_int32(n), _p(out), _st(stream)),
          "mlm_rows_scatter")
+
+
+# ---- backward with the weight gradients deferred to one grouped launch -------------------------------------------
+def mlm_mlp_shard_bwd_input(dims, dx2, A_r, B_r, g_r, dg_r, da_r, du2_partial_r, ws, stream=None):
+    _chk(lib().mlm_mlp_shard_bwd_input(ctypes.byref(dims), _p(dx2), _p(A_r), _p(B_r), _p(g_r), _p(dg_r), _p(da_r),
+                                       _p(du2_partial_r), *_ws(ws), _st(stream)), "mlm_mlp_shard_bwd_input")
+
+
+def mlm_attn_shard_bwd_input(dims, dx1, Wqkv_r, Wo_r, key_len, drop, qkv_r, ctx_r, lse_r, keep_bits_r, dqkv_r, dbqkv_r,
+                             du_partial_r, ws, stream=None):
+    _chk(lib().mlm_attn_shard_bwd_input(ctypes.byref(dims), _p(dx1), _p(Wqkv_r), _p(Wo_r), _p(key_len), _d(drop),
+                                        _p(qkv_r), _p(ctx_r), _p(lse_r), _p(keep_bits_r), _p(dqkv_r), _p(dbqkv_r),
+                                        _p(du_partial_r), *_ws(ws), _st(stream)), "mlm_attn_shard_bwd_input")
+
+
+def mlm_layer_shard_wgrads(dims, u, dqkv_r, ctx_r, dz1, u2, dg_r, y_r, dz2, dWqkv_r, dWo_r, dA_r, dB_r, ws, stream=None):
+    _chk(lib().mlm_layer_shard_wgrads(ctypes.byref(dims), _p(u), _p(dqkv_r), _p(ctx_r), _p(dz1), _p(u2), _p(dg_r),
+                                      _p(y_r), _p(dz2), _p(dWqkv_r), _p(dWo_r), _p(dA_r), _p(dB_r), *_ws(ws),
+                                      _st(stream)), "mlm_layer_shard_wgrads")

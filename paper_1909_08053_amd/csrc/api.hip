@@ -389,17 +389,20 @@ static int attn_shard_bwd_impl(const mlm_dims* dims, const void* dx1, const void
                                const void* Wo_r, const int32_t* key_len, const mlm_dropout* drop, const void* qkv_r,
                                const void* ctx_r, const float* lse_r, const uint32_t* keep_bits_r, void* dWqkv_r,
                                void* dbqkv_r, void* dWo_r, void* du_partial_r, void* ws, size_t ws_bytes,
-                               void* stream) {
+                               void* stream, void* dqkv_out = nullptr) {
+  // dqkv_out != NULL: input-gradient-only form -- the gradient of the QKV activations is left in dqkv_out for a later
+  // mlm_layer_shard_wgrads call and the two weight gradients are not computed here (u, dWqkv_r, dWo_r unused)
+  const bool defer = dqkv_out != nullptr;
   Local L;
   int rc = check_dims(dims, &L);
   if (rc) return rc;
   bool dropping;
   if ((rc = check_attn_drop(dims, drop, keep_bits_r, &dropping))) return rc;
-  if (!dx1 || !u || !Wqkv_r || !Wo_r || !qkv_r || !ctx_r || !lse_r || !dWqkv_r || !dbqkv_r || !dWo_r ||
-      !du_partial_r || !ws)
-    return MLM_E_NULL;
-  if (!aligned16(dx1) || !aligned16(u) || !aligned16(Wqkv_r) || !aligned16(Wo_r) || !aligned16(qkv_r) ||
-      !aligned16(ctx_r) || !aligned16(dWqkv_r) || !aligned16(dWo_r) || !aligned16(du_partial_r) || !aligned16(ws))
+  if (!dx1 || !Wqkv_r || !Wo_r || !qkv_r || !ctx_r || !lse_r || !dbqkv_r || !du_partial_r || !ws) return MLM_E_NULL;
+  if (!defer && (!u || !dWqkv_r || !dWo_r)) return MLM_E_NULL;
+  if (!aligned16(dx1) || !aligned16(Wqkv_r) || !aligned16(Wo_r) || !aligned16(qkv_r) || !aligned16(ctx_r) ||
+      !aligned16(du_partial_r) || !aligned16(ws) || (defer && !aligned16(dqkv_out)) ||
+      (!defer && (!aligned16(u) || !aligned16(dWqkv_r) || !aligned16(dWo_r))))
     return MLM_E_ALIGN;
   if ((rc = attn_supported(dims, L))) return rc;
   if (ws_bytes < ws_bytes_for(dims, L, MLM_WS_ATTN_BWD)) return MLM_E_WORKSPACE;
@@ -408,12 +411,12 @@ static int attn_shard_bwd_impl(const mlm_dims* dims, const void* dx1, const void
   const size_t T = (size_t)L.T;
   char* w = (char*)ws;
   void* dctx = w;                 w += align256(T * L.Hl * L.esz);
-  void* dqkv = w;                 w += align256(T * 3 * L.Hl * L.esz);
+  void* dqkv = defer ? dqkv_out : (void*)w;   w += align256(T * 3 * L.Hl * L.esz);
   float* delta = (float*)w;       w += align256((size_t)dims->b * L.hl * dims->s * 8);   // delta, and lse in log2 units
   float* csws = (float*)w;        w += align256(((T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock) * 3 * L.Hl * 4);
   float* sk = dt == MLM_BF16 ? (float*)w : nullptr;
   // output projection: dWo_r = ctx^T dx1, dctx = dx1 Wo_r^T
-  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(L.Hl, dims->H, L.T, ctx_r, dx1, dWo_r), st, sk));
+  if (!defer) MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(L.Hl, dims->H, L.T, ctx_r, dx1, dWo_r), st, sk));
   MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, L.Hl, dims->H, dx1, Wo_r, dctx), st, sk));
   // attention core
   // bf16: the dQ kernel computes delta itself (and stores it for the dK/dV kernel)
@@ -427,7 +430,7 @@ static int attn_shard_bwd_impl(const mlm_dims* dims, const void* dx1, const void
   a.keep_bits = const_cast<uint32_t*>(keep_bits_r); a.keep_pitch = keep_pitch_words(dims->s);
   MLM_TRY_HIP(dt == MLM_BF16 ? launch_attn_bwd_bf16(a, st) : launch_attn_bwd_f32(a, st));
   // QKV projection: dWqkv_r = u^T dqkv, dbqkv_r = column sums, du_partial_r = dqkv Wqkv_r^T
-  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, 3 * L.Hl, L.T, u, dqkv, dWqkv_r), st, sk));
+  if (!defer) MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, 3 * L.Hl, L.T, u, dqkv, dWqkv_r), st, sk));
   MLM_TRY_HIP(launch_colsum(dt, L.T, 3 * L.Hl, dqkv, dbqkv_r, csws, st));
   MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, 3 * L.Hl, dqkv, Wqkv_r, du_partial_r), st, sk));
   return MLM_OK;
@@ -438,6 +441,15 @@ MLM_API int mlm_attn_shard_bwd(const mlm_dims* dims, const void* dx1, const void
                        void* dbqkv_r, void* dWo_r, void* du_partial_r, void* ws, size_t ws_bytes, void* stream) {
   return attn_shard_bwd_impl(dims, dx1, u, Wqkv_r, Wo_r, key_len, nullptr, qkv_r, ctx_r, lse_r, nullptr, dWqkv_r, dbqkv_r,
                              dWo_r, du_partial_r, ws, ws_bytes, stream);
+}
+
+MLM_API int mlm_attn_shard_bwd_input(const mlm_dims* dims, const void* dx1, const void* Wqkv_r, const void* Wo_r,
+                                     const int32_t* key_len, const mlm_dropout* drop, const void* qkv_r,
+                                     const void* ctx_r, const float* lse_r, const uint32_t* keep_bits_r, void* dqkv_r,
+                                     void* dbqkv_r, void* du_partial_r, void* ws, size_t ws_bytes, void* stream) {
+  if (!dqkv_r) return MLM_E_NULL;
+  return attn_shard_bwd_impl(dims, dx1, nullptr, Wqkv_r, Wo_r, key_len, drop, qkv_r, ctx_r, lse_r, keep_bits_r, nullptr,
+                             dbqkv_r, nullptr, du_partial_r, ws, ws_bytes, stream, dqkv_r);
 }
 
 MLM_API int mlm_attn_shard_bwd_dropout(const mlm_dims* dims, const void* dx1, const void* u, const void* Wqkv_r,
@@ -473,34 +485,77 @@ MLM_API int mlm_mlp_shard_fwd(const mlm_dims* dims, const void* u2, const void* 
   return MLM_OK;
 }
 
-MLM_API int mlm_mlp_shard_bwd(const mlm_dims* dims, const void* dx2, const void* u2, const void* A_r, const void* B_r,
-                      const void* g_r, const void* y_r, void* dA_r, void* da_r, void* dB_r, void* du2_partial_r,
-                      void* ws, size_t ws_bytes, void* stream) {
+static int mlp_shard_bwd_impl(const mlm_dims* dims, const void* dx2, const void* u2, const void* A_r, const void* B_r,
+                              const void* g_r, const void* y_r, void* dA_r, void* da_r, void* dB_r,
+                              void* du2_partial_r, void* ws, size_t ws_bytes, void* stream, void* dg_out) {
+  // dg_out != NULL: input-gradient-only form (dG left in dg_out for mlm_layer_shard_wgrads; u2, y_r, dA_r, dB_r unused)
+  const bool defer = dg_out != nullptr;
   Local L;
   int rc = check_dims(dims, &L);
   if (rc) return rc;
-  if (!dx2 || !u2 || !A_r || !B_r || !g_r || !y_r || !dA_r || !da_r || !dB_r || !du2_partial_r || !ws)
-    return MLM_E_NULL;
-  if (!aligned16(dx2) || !aligned16(u2) || !aligned16(A_r) || !aligned16(B_r) || !aligned16(g_r) || !aligned16(y_r) ||
-      !aligned16(dA_r) || !aligned16(dB_r) || !aligned16(du2_partial_r) || !aligned16(ws))
+  if (!dx2 || !A_r || !B_r || !g_r || !da_r || !du2_partial_r || !ws) return MLM_E_NULL;
+  if (!defer && (!u2 || !y_r || !dA_r || !dB_r)) return MLM_E_NULL;
+  if (!aligned16(dx2) || !aligned16(A_r) || !aligned16(B_r) || !aligned16(g_r) || !aligned16(du2_partial_r) ||
+      !aligned16(ws) || (defer && !aligned16(dg_out)) ||
+      (!defer && (!aligned16(u2) || !aligned16(y_r) || !aligned16(dA_r) || !aligned16(dB_r))))
     return MLM_E_ALIGN;
   if (ws_bytes < ws_bytes_for(dims, L, MLM_WS_MLP_BWD)) return MLM_E_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const int dt = dims->dtype;
   const size_t T = (size_t)L.T;
   char* w = (char*)ws;
-  void* dg = w;                   w += align256(T * L.Fl * L.esz);
+  void* dg = defer ? dg_out : (void*)w;   w += align256(T * L.Fl * L.esz);
   float* csws = (float*)w;        w += align256(((T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock) * L.Fl * 4);
   float* sk = dt == MLM_BF16 ? (float*)w : nullptr;
-  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(L.Fl, dims->H, L.T, y_r, dx2, dB_r), st, sk));
+  if (!defer) MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(L.Fl, dims->H, L.T, y_r, dx2, dB_r), st, sk));
   GemmArgs g = gemm_dgrad(L.T, L.Fl, dims->H, dx2, B_r, dg);   // dG = (dX2 B_r^T) o GeLU'(G)
   g.epi = EPI_DGELU;
   g.aux = const_cast<void*>(g_r); g.ldaux = L.Fl;
   g.gelu_tanh = dims->gelu_tanh;
   MLM_TRY_HIP(run_gemm(dt, g, st, sk));
   MLM_TRY_HIP(launch_colsum(dt, L.T, L.Fl, dg, da_r, csws, st));
-  MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, L.Fl, L.T, u2, dg, dA_r), st, sk));
+  if (!defer) MLM_TRY_HIP(run_gemm(dt, gemm_wgrad(dims->H, L.Fl, L.T, u2, dg, dA_r), st, sk));
   MLM_TRY_HIP(run_gemm(dt, gemm_dgrad(L.T, dims->H, L.Fl, dg, A_r, du2_partial_r), st, sk));
+  return MLM_OK;
+}
+
+MLM_API int mlm_mlp_shard_bwd(const mlm_dims* dims, const void* dx2, const void* u2, const void* A_r, const void* B_r,
+                      const void* g_r, const void* y_r, void* dA_r, void* da_r, void* dB_r, void* du2_partial_r,
+                      void* ws, size_t ws_bytes, void* stream) {
+  return mlp_shard_bwd_impl(dims, dx2, u2, A_r, B_r, g_r, y_r, dA_r, da_r, dB_r, du2_partial_r, ws, ws_bytes, stream,
+                            nullptr);
+}
+
+MLM_API int mlm_mlp_shard_bwd_input(const mlm_dims* dims, const void* dx2, const void* A_r, const void* B_r,
+                                    const void* g_r, void* dg_r, void* da_r, void* du2_partial_r, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  if (!dg_r) return MLM_E_NULL;
+  return mlp_shard_bwd_impl(dims, dx2, nullptr, A_r, B_r, g_r, nullptr, nullptr, da_r, nullptr, du2_partial_r, ws,
+                            ws_bytes, stream, dg_r);
+}
+
+MLM_API int mlm_layer_shard_wgrads(const mlm_dims* dims, const void* u, const void* dqkv_r, const void* ctx_r,
+                                   const void* dz1, const void* u2, const void* dg_r, const void* y_r, const void* dz2,
+                                   void* dWqkv_r, void* dWo_r, void* dA_r, void* dB_r, void* ws, size_t ws_bytes,
+                                   void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  const void* in[8] = {u, dqkv_r, ctx_r, dz1, u2, dg_r, y_r, dz2};
+  void* out[4] = {dWqkv_r, dWo_r, dA_r, dB_r};
+  for (const void* p : in) if (!p) return MLM_E_NULL;
+  for (void* p : out) if (!p) return MLM_E_NULL;
+  for (const void* p : in) if (!aligned16(p)) return MLM_E_ALIGN;
+  for (void* p : out) if (!aligned16(p)) return MLM_E_ALIGN;
+  const size_t need = dims->dtype == MLM_BF16 ? kSplitKBytes : 0;
+  if (ws_bytes < need || (need && !ws)) return MLM_E_WORKSPACE;
+  if (ws && !aligned16(ws)) return MLM_E_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  // k = tokens in all four: dW = X^T dY
+  GemmArgs g[4] = {gemm_wgrad(L.Fl, dims->H, L.T, y_r, dz2, dB_r), gemm_wgrad(dims->H, L.Fl, L.T, u2, dg_r, dA_r),
+                   gemm_wgrad(dims->H, 3 * L.Hl, L.T, u, dqkv_r, dWqkv_r), gemm_wgrad(L.Hl, dims->H, L.T, ctx_r, dz1, dWo_r)};
+  if (dims->dtype == MLM_BF16) return hip_status(launch_gemm_bf16_wgrad_group(g, 4, (float*)ws, st));
+  for (int q = 0; q < 4; ++q) MLM_TRY_HIP(launch_gemm_f32(g[q], st));
   return MLM_OK;
 }
 

@@ -105,6 +105,8 @@ struct GemmArgs {
 int gemm_bf16_ce_col_tiles(int M, int N, int K);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t st);
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t st);
+// n weight-gradient GEMMs (A m-contiguous, B n-contiguous, plain store) in one launch where that is faster
+hipError_t launch_gemm_bf16_wgrad_group(const GemmArgs* probs, int n, float* splitk_ws, hipStream_t st);
 
 // ---- dropout site as the kernels see it (rng.h holds the generator) ---------------
 struct DropArgs {

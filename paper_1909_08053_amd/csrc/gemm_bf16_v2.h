@@ -21,6 +21,7 @@
 #pragma once
 #include "gemm_bf16.h"
 #include "lds_dma.h"
+#include <string.h>
 #include <type_traits>
 
 namespace mlm {
@@ -146,16 +147,16 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
 }
 
 // NW = waves per workgroup: 4 (2 x 2 waves of 128 x 128) or 8 (2 x 4 waves of 128 x 64, two waves per SIMD).
+// One work item (pid) of one GEMM: the body of the kernels below.
 template <bool A_KC, bool B_KC, int EPI, int NW>
-__global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan plan, float* splitk_ws) {
+__device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Plan& plan, float* splitk_ws, int pid,
+                                                  unsigned char* lds_raw) {
   constexpr int WAVES_N = NW / 2, WN = V2_B / WAVES_N, TN = WN / 32, QPW = 16 / NW;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_N) * 128, wn0 = (wave % WAVES_N) * WN;
 
   // work item: a full tile, or one k-piece of a tail tile
   int vt, piece = 0, npieces = 1;
-  const int pid = blockIdx.x;
   if (pid < plan.full_tiles) {
     vt = pid;
   } else {
@@ -317,6 +318,41 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Pla
   gemm_epilogue<V2_B, V2_B, 2, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
 }
 
+template <bool A_KC, bool B_KC, int EPI, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan plan, float* splitk_ws) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  gemm_v2_work_item<A_KC, B_KC, EPI, NW>(a, plan, splitk_ws, blockIdx.x, lds_raw);
+}
+
+// Several independent GEMMs of one operand layout in ONE launch (plain-store epilogue, no k-split): the tiles of
+// problem q follow those of problem q - 1 in the grid, so the launch pays the partially filled last round of the
+// 256 CUs once instead of once per GEMM.  Used for the weight gradients of a layer shard, which nothing but the
+// optimizer waits for: four GEMMs with 72 + 72 + 24 + 60 tiles at the 8.3B-shape 1/8 shard become one round.
+constexpr int kMaxGroup = 4;
+struct GemmGroup {
+  int n;
+  int tile_begin[kMaxGroup + 1];       // first work item of each problem; tile_begin[n] = grid size
+  GemmArgs args[kMaxGroup];
+  V2Plan plan[kMaxGroup];
+};
+
+template <bool A_KC, bool B_KC, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_group_kernel(GemmGroup g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  const int pid = blockIdx.x;
+  // the problem index is uniform over the workgroup: select its arguments with scalar compares
+  int q = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i) q += (i < g.n && pid >= g.tile_begin[i]) ? 1 : 0;
+  GemmArgs a = g.args[0];
+  V2Plan plan = g.plan[0];
+  int first = g.tile_begin[0];
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i)
+    if (q == i) { a = g.args[i]; plan = g.plan[i]; first = g.tile_begin[i]; }
+  gemm_v2_work_item<A_KC, B_KC, EPI_STORE, NW>(a, plan, nullptr, pid - first, lds_raw);
+}
+
 // Tail tiles: sum the k-pieces in piece order (deterministic) and apply the epilogue to the fp32 sums.  A wave owns
 // whole 256-column tile rows (a lane: 4 consecutive columns), so the row statistics of the cross-entropy epilogue are
 // one wave reduction.  Grid: (256 / kFixRows row groups, tail tiles), 4 waves, kFixRows / 4 rows per wave.
@@ -442,6 +478,35 @@ hipError_t launch_gemm_bf16_v2_nw(const GemmArgs& a, float* splitk_ws, hipStream
     e = hipGetLastError();
   }
   return e;
+}
+
+// Tiles (work items without a k-split) of one problem.
+inline int v2_tiles(const GemmArgs& a) { return ((a.M + V2_B - 1) / V2_B) * ((a.N + V2_B - 1) / V2_B); }
+
+template <bool A_KC, bool B_KC, int NW>
+hipError_t launch_gemm_bf16_v2_group_nw(const GemmArgs* probs, int n, hipStream_t st) {
+  auto kern = gemm_bf16_v2_group_kernel<A_KC, B_KC, NW>;
+  constexpr size_t kEpi = GemmTile<V2_B, V2_B, 2, NW / 2>::LDS_EPI;
+  constexpr size_t kLds = V2_LDS_BYTES > kEpi ? V2_LDS_BYTES : kEpi;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  GemmGroup g;
+  memset(&g, 0, sizeof(g));
+  g.n = n;
+  int total = 0;
+  for (int q = 0; q < n; ++q) {
+    g.args[q] = probs[q];
+    g.plan[q] = v2_plan(probs[q].M, probs[q].N, probs[q].K, false);
+    g.tile_begin[q] = total;
+    total += g.plan[q].full_tiles;
+  }
+  for (int q = n; q <= kMaxGroup; ++q) g.tile_begin[q] = total;
+  hipLaunchKernelGGL(kern, dim3(total), dim3(NW * 64), kLds, st, g);
+  return hipGetLastError();
 }
 
 template <bool A_KC, bool B_KC, int EPI>

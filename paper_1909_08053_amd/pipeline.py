@@ -24,7 +24,7 @@ def _tdtype(cfg: LayerConfig):
 class LayerShards:
     def __init__(self, cfg: LayerConfig, shards: Sequence[int], device: str = "cuda:0", store_logits: bool = True,
                  fused: bool = True, store_combined: bool = False, dropout: Optional[Dict[str, object]] = None,
-                 embed: bool = False, loss_rows: bool = False):
+                 embed: bool = False, loss_rows: bool = False, grouped_wgrads: bool = True):
         """fused: the combine that stands in for an all-reduce runs inside the layer-norm kernel that consumes it
         (and the layer-norm backward also emits the row-parallel bias gradient); store_combined: in fused mode,
         also store the combined gradients dHf / dU2 / dU (nothing in the path reads them).
@@ -35,10 +35,13 @@ class LayerShards:
         embedding) instead of being given, and its backward adds into the tied dE.
         loss_rows: the rows of the final hidden state that carry loss weight are gathered first and the vocabulary-
         parallel logits / loss / gradient calls run on that compact tensor only (BERT-style masked-LM loss: ~15 % of
-        the positions); the input gradient is scattered back with zeros elsewhere.  Same loss and gradients."""
+        the positions); the input gradient is scattered back with zeros elsewhere.  Same loss and gradients.
+        grouped_wgrads: the backward calls compute input gradients only and the four weight gradients of each layer
+        shard are computed afterwards by one mlm_layer_shard_wgrads call (one grouped GEMM launch)."""
         self.cfg, self.shards, self.dev = cfg, list(shards), torch.device(device)
         self.fused, self.store_combined = fused, store_combined
         self.dropout, self.embed, self.loss_rows = dropout, embed, loss_rows
+        self.grouped_wgrads = grouped_wgrads
         if dropout is not None and not fused:
             raise ValueError("dropout is wired into the fused combine + layer-norm calls only")
         self.dt = _tdtype(cfg)
@@ -181,6 +184,8 @@ class LayerShards:
                 "dA": e(H, self.Fl), "da": e(self.Fl), "dB": e(self.Fl, H), "du2_partial": e(T, H),
                 "dWqkv": e(H, 3 * self.Hl), "dbqkv": e(3 * self.Hl), "dWo": e(self.Hl, H), "du_partial": e(T, H),
             }
+            if self.grouped_wgrads:
+                self.sh[r]["dg"], self.sh[r]["dqkv"] = e(T, self.Fl), e(T, 3 * self.Hl)
             if self.dropout is not None:
                 self.sh[r]["keep_bits"] = torch.zeros(B.mlm_attn_keep_words(self.dims[r]), device=dev, dtype=torch.int32)
             if self.embed:
@@ -309,8 +314,12 @@ class LayerShards:
             B.mlm_colsum(d0, dx2, a["dc"], ws)
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
-            B.mlm_mlp_shard_bwd(self.dims[r], dz2 if drop else dx2, a["U2"], w["A"], w["B"], s["g"], s["y"], s["dA"],
-                                s["da"], s["dB"], s["du2_partial"], ws)
+            if self.grouped_wgrads:
+                B.mlm_mlp_shard_bwd_input(self.dims[r], dz2 if drop else dx2, w["A"], w["B"], s["g"], s["dg"], s["da"],
+                                          s["du2_partial"], ws)
+            else:
+                B.mlm_mlp_shard_bwd(self.dims[r], dz2 if drop else dx2, a["U2"], w["A"], w["B"], s["g"], s["y"],
+                                    s["dA"], s["da"], s["dB"], s["du2_partial"], ws)
         du2_partials = [self.sh[r]["du2_partial"] for r in self.shards]
         if drop:
             B.mlm_combine_layernorm_bwd_dropout(d0, du2_partials, a["X1"], rep["g2"], a["mu2"], a["rstd2"], dx2,
@@ -327,7 +336,14 @@ class LayerShards:
             B.mlm_colsum(d0, a["dX1"], a["dbo"], ws)
         for r in self.shards:
             w, s = self.w[r], self.sh[r]
-            if drop:
+            if self.grouped_wgrads:
+                B.mlm_attn_shard_bwd_input(self.dims[r], dz1 if drop else a["dX1"], w["Wqkv"], w["Wo"], kl,
+                                           self.drop["attn"][r] if drop else None, s["qkv"], s["ctx"], s["lse"],
+                                           s["keep_bits"] if drop else None, s["dqkv"], s["dbqkv"], s["du_partial"], ws)
+                B.mlm_layer_shard_wgrads(self.dims[r], a["U"], s["dqkv"], s["ctx"], dz1 if drop else a["dX1"], a["U2"],
+                                         s["dg"], s["y"], dz2 if drop else dx2, s["dWqkv"], s["dWo"], s["dA"], s["dB"],
+                                         ws)
+            elif drop:
                 B.mlm_attn_shard_bwd_dropout(self.dims[r], dz1, a["U"], w["Wqkv"], w["Wo"], kl, self.drop["attn"][r],
                                              s["qkv"], s["ctx"], s["lse"], s["keep_bits"], s["dWqkv"], s["dbqkv"],
                                              s["dWo"], s["du_partial"], ws)

@@ -320,3 +320,33 @@ def test_activation_recomputation_matches_stored_activations():
     for k, v in grads[0].items():
         assert torch.isfinite(v.float()).all(), k
         assert torch.equal(v, grads[1][k]), f"{k}: recomputed activations give a different gradient"
+
+
+@pytest.mark.parametrize("dtype,shape", [("fp32", "ragged"), ("bf16", "ragged"), ("bf16", "aligned"), ("bf16", "aligned_bert")])
+def test_grouped_weight_gradients_equal_the_separate_calls(dtype, shape):
+    """Deferring the four weight gradients of a layer shard to one mlm_layer_shard_wgrads call (one grouped GEMM launch
+    where the cost model picks it) changes no input gradient at all and the weight gradients only through the k-split
+    summation order of the separate GEMMs (none when neither form splits)."""
+    if shape == "ragged":        # T = 528 is no multiple of 64: the GEMMs run one by one (register-staged kernel)
+        cfg = synth.small_config(dtype=dtype, b=2, s=264, H=256, h=2, F=1024, V=528, p=2)
+    elif shape == "aligned":     # T = 512, 24 tiles in all: the cost model picks the single grouped launch
+        cfg = synth.small_config(dtype=dtype, b=2, s=256, H=512, h=4, F=2048, V=512, p=2)
+    else:
+        cfg = synth.small_config(dtype=dtype, b=4, s=128, H=512, h=8, F=2048, V=512, p=2, causal=False, masked_lm=True)
+    inp = synth.make_inputs(cfg, nonzero_bias=True, random_ln=True)
+    res = []
+    for grouped in (False, True):
+        L = LayerShards(cfg, [0, 1], DEV, grouped_wgrads=grouped)
+        L.load_host_inputs(inp)
+        L.step()
+        torch.cuda.synchronize()
+        res.append((L, {k: L.act[k].clone() for k in ("dX", "dX1", "dX2", "dg1", "db1", "dbo", "dc")}))
+    for k, v in res[0][1].items():
+        assert torch.equal(v, res[1][1][k]), k
+    ref = O.sharded_reference(inp, spec_of(cfg), cfg.p)
+    for r in (0, 1):
+        for k in ("dbqkv", "da", "du_partial", "du2_partial"):
+            assert torch.equal(res[0][0].sh[r][k], res[1][0].sh[r][k]), (r, k)
+        for k in ("dWqkv", "dWo", "dA", "dB"):
+            assert relerr(_dn(res[1][0].sh[r][k]), ref["shards"][r][k]) <= TOL[dtype], (r, k)
+            assert relerr(_dn(res[1][0].sh[r][k]), _dn(res[0][0].sh[r][k])) <= TOL[dtype] * 0.5, (r, k)
