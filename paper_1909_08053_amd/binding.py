@@ -24,8 +24,8 @@ EXPORTS = ("mlm_shard_range", "mlm_workspace_bytes", "mlm_status_string", "mlm_l
            "mlm_adamw_step", "mlm_adamw_step_multi", "mlm_rng_stream_seed", "mlm_combine_dropout",
            "mlm_combine_layernorm_fwd_dropout", "mlm_combine_layernorm_bwd_dropout", "mlm_attn_keep_words",
            "mlm_attn_shard_fwd_dropout", "mlm_attn_shard_bwd_dropout", "mlm_embed_shard_fwd", "mlm_embed_bwd_replicated",
-           "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter",
-           "mlm_mlp_shard_bwd_input", "mlm_attn_shard_bwd_input", "mlm_layer_shard_wgrads")
+           "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter", "mlm_mlp_shard_bwd_input",
+           "mlm_attn_shard_bwd_input", "mlm_layer_shard_wgrads")
 STREAM_REPLICATED, STREAM_MODEL_PARALLEL = 0, 1
 
 
@@ -305,8 +305,7 @@ def mlm_embed_bwd_replicated(dims, dx0, drop, dz0, dpos, stream=None):
 
 def mlm_embed_shard_bwd(dims, ids, perm_r, dz0, dE_r, stream=None):
     _chk(lib().mlm_embed_shard_bwd(ctypes.byref(dims), _p(ids), _p(perm_r), _p(dz0), _p(dE_r), _st(stream)),
-         "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter",
-           "mlm_mlp_shard_bwd_input", "mlm_attn_shard_bwd_input", "mlm_layer_shard_wgrads")
+         "mlm_embed_shard_bwd")
 
 
 def mlm_rows_gather(dims, x, row_idx, n, n_out, out, stream=None):

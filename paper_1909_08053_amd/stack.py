@@ -26,11 +26,13 @@ SITES = {"attn": 1, "hidden1": 2, "hidden2": 3}
 
 class ModelShards:
     def __init__(self, cfg: LayerConfig, n_layers: int, shards: Sequence[int], device: str = "cuda:0",
-                 dropout: Optional[Dict[str, object]] = None, checkpoint: bool = True):
+                 dropout: Optional[Dict[str, object]] = None, checkpoint: bool = True, grouped_wgrads: bool = True):
         """dropout: None or {"p_attn", "p_hidden", "base_seed", "step"}; site offsets are derived as
-        (step << 32) | (16 * layer + site) with the embedding site at layer index n_layers."""
+        (step << 32) | (16 * layer + site) with the embedding site at layer index n_layers.
+        grouped_wgrads: the layer backward computes input gradients only and each layer shard's four weight
+        gradients come from one mlm_layer_shard_wgrads call (one grouped GEMM launch)."""
         self.cfg, self.L, self.shards, self.dev = cfg, int(n_layers), list(shards), torch.device(device)
-        self.checkpoint, self.dropout = checkpoint, dropout
+        self.checkpoint, self.dropout, self.grouped_wgrads = checkpoint, dropout, grouped_wgrads
         self.dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
         self.code = B.MLM_BF16 if cfg.dtype == "bf16" else B.MLM_F32
         p = cfg.p
@@ -132,12 +134,19 @@ class ModelShards:
                      "S": e(T, dtype=f32), "loss": e(2, dtype=f32), "dgf": e(H), "dbf": e(H), "dpos": e(cfg.s, H)}
         self.hsh = {r: {"logits": e(T, self.Vl), "dE": e(H, self.Vl), "dhf_partial": e(T, H), "perm": e(T, dtype=torch.int32),
                         "embed_partial": e(T, H)} for r in self.shards}
-        self.dX = e(T, H)                                              # the one activation-gradient buffer of the chain
+        # activation gradients of the chain: dX2 of the current layer, its dX1, and the layer's input gradient rotate
+        # through three buffers, so that both block-output gradients are still intact when the layer's weight
+        # gradients are computed at the end of its backward pass
+        self.dXbuf = [e(T, H) for _ in range(3)]
+        self.dX = self.dXbuf[0]
         self.dZ = {k: e(T, H) for k in (("dZ1", "dZ2", "dZ0") if self.dropout is not None else ())}
         self.gsh = [{r: {"dWqkv": e(H, 3 * self.Hl), "dbqkv": e(3 * self.Hl), "dWo": e(self.Hl, H), "dA": e(H, self.Fl),
                          "da": e(self.Fl), "dB": e(self.Fl, H)} for r in self.shards} for _ in range(L)]
         self.grep = [{k: e(H) for k in ("dg1", "db1", "dbo", "dg2", "db2", "dc")} for _ in range(L)]
         self.part = {r: {"du_partial": e(T, H), "du2_partial": e(T, H)} for r in self.shards}
+        if self.grouped_wgrads:
+            for r in self.shards:
+                self.part[r]["dg"], self.part[r]["dqkv"] = e(T, self.Fl), e(T, 3 * self.Hl)
         wsb = max(B.mlm_workspace_bytes(self.d0, k) for k in range(8))
         self.ws = torch.empty(max(wsb, 256), device=self.dev, dtype=torch.uint8)
 
@@ -199,45 +208,61 @@ class ModelShards:
         rep, d0, ws, hd = self.rep, self.d0, self.ws, self.head
         drop = self.dropout is not None
         kl = rep["key_len"] if self.cfg.masked_lm else None
-        dX, dZ = self.dX, self.dZ
+        dZ = self.dZ
+        b2, b1, b0 = self.dXbuf                     # dX2 of the layer at hand, its dX1, the gradient of its input
         for r in self.shards:
             s = self.hsh[r]
             B.mlm_vocab_ce_shard_bwd(self.dims[r], hd["Hf"], self.E[r], rep["tgt"], rep["w"], hd["M"], hd["S"], hd["loss"],
                                      s["logits"], s["dE"], s["dhf_partial"], ws)
         last = self.L - 1
         B.mlm_combine_layernorm_bwd_dropout(d0, [self.hsh[r]["dhf_partial"] for r in self.shards], self.X[self.L],
-                                            rep["gf"], hd["muf"], hd["rstdf"], None, self._drop(last, "hidden2"), None, dX,
+                                            rep["gf"], hd["muf"], hd["rstdf"], None, self._drop(last, "hidden2"), None, b2,
                                             dZ.get("dZ2"), hd["dgf"], hd["dbf"], self.grep[last]["dc"], ws)
         for l in reversed(range(self.L)):
             if self.checkpoint:
                 self.recompute_layer(l)
             a, rp, gr = self.acts[l], rep["layers"][l], self.grep[l]
+            dz2 = dZ["dZ2"] if drop else b2
             for r in self.shards:
                 w, s, g = self.w[l][r], a["sh"][r], self.gsh[l][r]
-                B.mlm_mlp_shard_bwd(self.dims[r], dZ["dZ2"] if drop else dX, a["U2"], w["A"], w["B"], s["g"], s["y"],
-                                    g["dA"], g["da"], g["dB"], self.part[r]["du2_partial"], ws)
-            B.mlm_combine_layernorm_bwd_dropout(d0, [self.part[r]["du2_partial"] for r in self.shards], a["X1"], rp["g2"],
-                                                a["mu2"], a["rstd2"], dX, self._drop(l, "hidden1"), None, dX,
-                                                dZ.get("dZ1"), gr["dg2"], gr["db2"], gr["dbo"], ws)
-            for r in self.shards:
-                w, s, g = self.w[l][r], a["sh"][r], self.gsh[l][r]
-                if drop:
-                    B.mlm_attn_shard_bwd_dropout(self.dims[r], dZ["dZ1"], a["U"], w["Wqkv"], w["Wo"], kl,
-                                                 self._drop(l, "attn", r), s["qkv"], s["ctx"], s["lse"], s["keep_bits"],
-                                                 g["dWqkv"], g["dbqkv"], g["dWo"], self.part[r]["du_partial"], ws)
+                if self.grouped_wgrads:
+                    B.mlm_mlp_shard_bwd_input(self.dims[r], dz2, w["A"], w["B"], s["g"], self.part[r]["dg"], g["da"],
+                                              self.part[r]["du2_partial"], ws)
                 else:
-                    B.mlm_attn_shard_bwd(self.dims[r], dX, a["U"], w["Wqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
-                                         g["dWqkv"], g["dbqkv"], g["dWo"], self.part[r]["du_partial"], ws)
+                    B.mlm_mlp_shard_bwd(self.dims[r], dz2, a["U2"], w["A"], w["B"], s["g"], s["y"], g["dA"], g["da"],
+                                        g["dB"], self.part[r]["du2_partial"], ws)
+            B.mlm_combine_layernorm_bwd_dropout(d0, [self.part[r]["du2_partial"] for r in self.shards], a["X1"], rp["g2"],
+                                                a["mu2"], a["rstd2"], b2, self._drop(l, "hidden1"), None, b1,
+                                                dZ.get("dZ1"), gr["dg2"], gr["db2"], gr["dbo"], ws)
+            dz1 = dZ["dZ1"] if drop else b1
+            for r in self.shards:
+                w, s, g, pt = self.w[l][r], a["sh"][r], self.gsh[l][r], self.part[r]
+                if self.grouped_wgrads:
+                    B.mlm_attn_shard_bwd_input(self.dims[r], dz1, w["Wqkv"], w["Wo"], kl,
+                                               self._drop(l, "attn", r), s["qkv"], s["ctx"], s["lse"],
+                                               s["keep_bits"] if drop else None, pt["dqkv"], g["dbqkv"], pt["du_partial"], ws)
+                    # both block-output gradients of this layer are still intact here (the next call overwrites dZ2)
+                    B.mlm_layer_shard_wgrads(self.dims[r], a["U"], pt["dqkv"], s["ctx"], dz1, a["U2"], pt["dg"], s["y"],
+                                             dz2, g["dWqkv"], g["dWo"], g["dA"], g["dB"], ws)
+                elif drop:
+                    B.mlm_attn_shard_bwd_dropout(self.dims[r], dz1, a["U"], w["Wqkv"], w["Wo"], kl,
+                                                 self._drop(l, "attn", r), s["qkv"], s["ctx"], s["lse"], s["keep_bits"],
+                                                 g["dWqkv"], g["dbqkv"], g["dWo"], pt["du_partial"], ws)
+                else:
+                    B.mlm_attn_shard_bwd(self.dims[r], dz1, a["U"], w["Wqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
+                                         g["dWqkv"], g["dbqkv"], g["dWo"], pt["du_partial"], ws)
             du = [self.part[r]["du_partial"] for r in self.shards]
             if l > 0:
                 # LN1 of layer l consumed the output of layer l-1's MLP block: its backward also yields that block's
                 # pre-dropout gradient and bias gradient
-                B.mlm_combine_layernorm_bwd_dropout(d0, du, self.X[l], rp["g1"], a["mu1"], a["rstd1"], dX,
-                                                    self._drop(l - 1, "hidden2"), None, dX, dZ.get("dZ2"), gr["dg1"],
+                B.mlm_combine_layernorm_bwd_dropout(d0, du, self.X[l], rp["g1"], a["mu1"], a["rstd1"], b1,
+                                                    self._drop(l - 1, "hidden2"), None, b0, dZ.get("dZ2"), gr["dg1"],
                                                     gr["db1"], self.grep[l - 1]["dc"], ws)
             else:
-                B.mlm_combine_layernorm_bwd(d0, du, self.X[0], rp["g1"], a["mu1"], a["rstd1"], dX, None, dX, gr["dg1"],
+                B.mlm_combine_layernorm_bwd(d0, du, self.X[0], rp["g1"], a["mu1"], a["rstd1"], b1, None, b0, gr["dg1"],
                                             gr["db1"], None, ws)
+            b2, b1, b0 = b0, b2, b1                 # the input gradient is the next (lower) layer's dX2
+        dX = self.dX = b2
         B.mlm_embed_bwd_replicated(d0, dX, self._drop(self.L, "embed"), dZ["dZ0"] if drop else dX, hd["dpos"])
         for r in self.shards:
             B.mlm_embed_shard_bwd(self.dims[r], rep["ids"], self.hsh[r]["perm"], dZ["dZ0"] if drop else dX,
