@@ -238,7 +238,8 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
   // software-pipelined: strip s+1 is written while strip s is read back).  All element-wise work happens at
   // read-back time, where a lane owns 8 consecutive columns of one row: bias, the saved pre-activation and the
   // outputs are then 16-byte accesses with 128-byte contiguous row segments.
-  constexpr int NSTEP = TM * (TN / 2);
+  // (an odd TN leaves a last strip of 32 columns: half of the strip is then neither written nor read back)
+  constexpr int NH = (TN + 1) / 2, NSTEP = TM * NH;
   const int rb_r = lane >> 3, rb_c = (lane & 7) * 8;           // read-back: 8 rows x 8 column groups per iteration
   const bool full = (m0 + BM <= a.M) && (n0 + BN <= a.N);
   if ((EPI == EPI_STORE || EPI == EPI_CE) && bias == nullptr) {
@@ -250,12 +251,13 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
 #pragma unroll
     for (int step = 0; step <= NSTEP; ++step) {
       if (step < NSTEP) {
-        const int j = step / (TN / 2), h = step % (TN / 2);
+        const int j = step / NH, h = step % NH;
         bf16* strip = bstrip0 + (step & 1) * (32 * SWB);
 #pragma unroll
         for (int il = 0; il < 2; ++il)
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
+            if (2 * h + il >= TN) continue;
             const floatx16& t = acc[2 * h + il][j];
             bf16x4 v;
 #pragma unroll
@@ -266,15 +268,16 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
       __builtin_amdgcn_wave_barrier();
       if (step > 0) {
         const int ps = step - 1;
-        const int j = ps / (TN / 2), h = ps % (TN / 2);
+        const int j = ps / NH, h = ps % NH;
         const bf16* strip = bstrip0 + (ps & 1) * (32 * SWB);
         const int gn = n0 + wn0 + h * 64 + rb_c;
+        const bool colv = (TN % 2 == 0) || (h * 64 + rb_c < WN);
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
           const int r = rb_r + it * 8;
           const int gm = m0 + wm0 + j * 32 + r;
           const bf16x8 o = *reinterpret_cast<const bf16x8*>(strip + r * SWB + rb_c);
-          if (full || (gm < a.M && gn < a.N)) *reinterpret_cast<bf16x8*>(C + (size_t)gm * a.ldc + gn) = o;
+          if (colv && (full || (gm < a.M && gn < a.N))) *reinterpret_cast<bf16x8*>(C + (size_t)gm * a.ldc + gn) = o;
         }
       }
       __builtin_amdgcn_wave_barrier();
@@ -283,18 +286,18 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
   }
   constexpr int SW = 64 + 4;                                   // strip row stride in floats (272 B)
   static_assert(32 * SW * 4 <= Tcfg::STRIP * 2, "strip does not fit");
-  static_assert(TN % 2 == 0, "wave tile must be a multiple of 64 columns");
   float* strip0 = reinterpret_cast<float*>(lds + (size_t)wave * 2 * Tcfg::STRIP);
 
 #pragma unroll
   for (int step = 0; step <= NSTEP; ++step) {
     if (step < NSTEP) {
-      const int j = step / (TN / 2), h = step % (TN / 2);
+      const int j = step / NH, h = step % NH;
       float* strip = strip0 + (step & 1) * (Tcfg::STRIP / 2);
 #pragma unroll
       for (int il = 0; il < 2; ++il)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
+          if (2 * h + il >= TN) continue;
           const floatx16& t = acc[2 * h + il][j];
           const float4 v = make_float4(t[4 * g], t[4 * g + 1], t[4 * g + 2], t[4 * g + 3]);
           *reinterpret_cast<float4*>(strip + l32 * SW + il * 32 + 8 * g + 4 * lh) = v;
@@ -303,9 +306,10 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
     __builtin_amdgcn_wave_barrier();
     if (step > 0) {
       const int ps = step - 1;
-      const int j = ps / (TN / 2), h = ps % (TN / 2);
+      const int j = ps / NH, h = ps % NH;
       const float* strip = strip0 + (ps & 1) * (Tcfg::STRIP / 2);
       const int gn = n0 + wn0 + h * 64 + rb_c;                 // first of this lane's 8 columns
+      const bool colv = (TN % 2 == 0) || (h * 64 + rb_c < WN);
       const int gnc = min(gn, a.N - 8);
       float bvals[8];
       if ((EPI == EPI_STORE || EPI == EPI_BIAS_GELU) && bias != nullptr) {
@@ -324,7 +328,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
         const float4 lo = *reinterpret_cast<const float4*>(strip + r * SW + rb_c);
         const float4 hi = *reinterpret_cast<const float4*>(strip + r * SW + rb_c + 4);
         float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        const bool ok = full || (gm < a.M && gn < a.N);
+        const bool ok = colv && (full || (gm < a.M && gn < a.N));
         bf16x8 o;
         if (EPI == EPI_STORE || EPI == EPI_CE) {
 #pragma unroll

@@ -54,6 +54,16 @@ int gemm_v2_waves(bool a_kc, bool b_kc) {
   return (!a_kc && !b_kc) ? 4 : 8;
 }
 
+int gemm_v2_forced_bn() {
+  static int forced = -1;
+  if (forced < 0) {
+    const char* e = getenv("MLM_GEMM_BN");
+    const int v = e ? atoi(e) : 0;
+    forced = (v == 192 || v == 256) ? v : 0;
+  }
+  return forced;
+}
+
 int gemm_bf16_ce_col_tiles(int M, int N, int K) {
   GemmArgs probe;
   probe.K = K;

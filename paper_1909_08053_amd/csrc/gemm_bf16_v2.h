@@ -46,16 +46,15 @@ __device__ __forceinline__ int v2_mn_swizzle(int k) { return (k & 3) << 2; }
 // different bank groups.
 __device__ __forceinline__ int v2_kc_swizzle(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
 
-// Per-lane source pointers of one operand's DMA copies.  QPW = 16 / (waves per workgroup): 1-KB copies per wave,
-// operand and k-slice.
+// Per-lane source pointers of one operand's DMA copies (NP 1-KB copies per wave).
 //  * k-contiguous operand (KC): the ring holds two PAIRS of slices; a pair is [256 rows][64 k] = 128 bytes per row,
 //    so one copy instruction fetches 8 rows x one full 128-byte line (fetching the two 64-byte halves separately,
 //    slice by slice, costs twice the cache-line requests and was measured 40 % slower on the copy side).  A pair
 //    takes 2 QPW copies per wave and is fetched once every two slices.
 //  * operand contiguous along m / n (MN): a slice is [32 k][256 rows] = 512 bytes per k, QPW copies per slice.
-template <bool KC, int QPW>
+template <bool KC, int NP_>
 struct V2Src {
-  static constexpr int NP = KC ? 2 * QPW : QPW;
+  static constexpr int NP = NP_;       // KC: 1-KB copies per wave and PAIR (rows / (8 waves)); MN: per wave and slice
   const bf16* p[NP];
   size_t step;     // elements to advance per pair (KC) / per slice (MN)
   __device__ __forceinline__ void init(const bf16* P, int ld, int row0, int nrows, int k_begin, int wave, int lane) {
@@ -71,7 +70,7 @@ struct V2Src {
       // unit u of k-row holds row-chunk u ^ v2_mn_swizzle(k)
 #pragma unroll
       for (int q = 0; q < NP; ++q) {
-        const int k = 2 * (wave * QPW + q) + (lane >> 5);
+        const int k = 2 * (wave * NP + q) + (lane >> 5);
         const int u = (lane & 31) ^ v2_mn_swizzle(k);
         p[q] = P + (size_t)(k_begin + k) * ld + min(row0 + u * 8, nrows - 8);
       }
@@ -91,15 +90,16 @@ struct V2Src {
 
 // Operand registers (8 consecutive k of one row/column per lane) for the 32-row MFMA tile starting at row `r0`,
 // k-step ks (0 / 1) of the slice in ring stage `stage` of the operand ring at `ring`.
-template <bool KC>
+template <bool KC, int OPB = V2_OP_BYTES>     // OPB: bytes of one k-slice of the operand (rows x 32 k)
 __device__ __forceinline__ bf16x8 v2_frag(const unsigned char* ring, int stage, int r0, int ks, int lane) {
   const int l32 = lane & 31, lh = lane >> 5;
   if (KC) {
     const int row = r0 + l32;
     const int u = (stage & 1) * 4 + ks * 2 + lh;
-    return *reinterpret_cast<const bf16x8*>(ring + (stage >> 1) * (2 * V2_OP_BYTES) + row * 128 +
+    return *reinterpret_cast<const bf16x8*>(ring + (stage >> 1) * (2 * OPB) + row * 128 +
                                             ((u ^ v2_kc_swizzle(row)) << 4));
   } else {
+    static_assert(KC || OPB == V2_OP_BYTES, "the [k][row] layout and its swizzle are for 256-row operands");
     const unsigned char* op_base = ring + stage * V2_OP_BYTES;
     const int g = lane >> 4, i16 = lane & 15;
     const int u = (r0 >> 3) + 2 * (g & 1) + ((i16 & 3) >> 1);
@@ -116,44 +116,63 @@ __device__ __forceinline__ bf16x8 v2_frag(const unsigned char* ring, int stage, 
 
 struct V2Plan {
   int tiles_m, tiles_n, full_tiles, tail_tiles, split;   // grid = full_tiles + tail_tiles * split
+  int bn;                                                 // tile width (256, or 192 for the narrow-tile variant)
+  double cost;                                            // estimated kernel time in microseconds (host side only)
 };
+
+// Cost-model constants (microseconds, measured on MI355X): fixed cost of a tile (fill + epilogue) and cost of one
+// 32-deep k-slice, for the 256 x 256 tile and for the 256 x 192 tile (3/4 of the MFMA work per slice, but relatively
+// more LDS and copy traffic per MFMA).
+inline double v2_tile_fixed(int bn) { return bn == V2_B ? 5.3 : 4.6; }
+inline double v2_slice_cost(int bn) { return bn == V2_B ? 0.78 : 0.63; }
 
 // Decide whether, and how far, to split the last partial round along k.  Cost model in microseconds, measured on
 // MI355X with in-kernel timestamps: a tile costs about 5.3 (fill + epilogue) + 0.78 per 32-deep k-slice; the pieces
 // write fp32 partial tiles and the fix-up kernel (about 6 for launch + drain) reads them back, both at ~5 TB/s.
-inline V2Plan v2_plan(int M, int N, int K, bool allow_split) {
+inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B) {
   V2Plan p;
+  p.bn = bn;
   p.tiles_m = (M + V2_B - 1) / V2_B;
-  p.tiles_n = (N + V2_B - 1) / V2_B;
+  p.tiles_n = (N + bn - 1) / bn;
   const int tiles = p.tiles_m * p.tiles_n;
   const int rem = tiles % V2_CUS;
   const int nk = K / V2_BK;                           // even: K is a multiple of 64
+  const double fixed = v2_tile_fixed(bn), per_slice = v2_slice_cost(bn);
   int split = 1;
+  double tail = rem ? fixed + per_slice * nk : 0.0;   // unsplit tail round
   if (allow_split && rem != 0 && rem * 2 <= V2_CUS) {
     int smax = V2_CUS / rem;
     if (smax > 16) smax = 16;
-    double best = 5.3 + 0.78 * nk;                    // unsplit tail round
     for (int sp = 2; sp <= smax; ++sp) {
       if (nk / sp < 8) break;                         // keep at least 8 k-slices per piece
-      const double traffic = (double)rem * sp * (V2_B * V2_B * 4.0) / 5.0e6;
-      const double t = 5.3 + 0.78 * ((nk + sp - 1) / sp) + traffic + 6.0 + traffic;
-      if (t < best) { best = t; split = sp; }
+      const double traffic = (double)rem * sp * (V2_B * (double)bn * 4.0) / 5.0e6;
+      const double t = fixed + per_slice * ((nk + sp - 1) / sp) + traffic + 6.0 + traffic;
+      if (t < tail) { tail = t; split = sp; }
     }
   }
   p.split = split;
   p.tail_tiles = split > 1 ? rem : 0;
   p.full_tiles = tiles - p.tail_tiles;
+  p.cost = (tiles / V2_CUS) * (fixed + per_slice * nk) + tail;
   return p;
 }
 
 // NW = waves per workgroup: 4 (2 x 2 waves of 128 x 128) or 8 (2 x 4 waves of 128 x 64, two waves per SIMD).
 // One work item (pid) of one GEMM: the body of the kernels below.
-template <bool A_KC, bool B_KC, int EPI, int NW>
+// BN = 256: 2 x (NW / 2) waves of 128 x (512 / NW).  BN = 192 (8 waves, k-contiguous B only): 4 x 2 waves of 64 x 96 --
+// a tile count of 32 x (N / 192) fills the 256 CUs where N / 256 column tiles leave a quarter of them idle
+// (N = 1536: 256 tiles instead of 192) or a half-empty second round (N = 3072: 512 instead of 384).
+template <bool A_KC, bool B_KC, int EPI, int NW, int BN = V2_B>
 __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Plan& plan, float* splitk_ws, int pid,
                                                   unsigned char* lds_raw) {
-  constexpr int WAVES_N = NW / 2, WN = V2_B / WAVES_N, TN = WN / 32, QPW = 16 / NW;
+  static_assert(BN == V2_B || (BN == 192 && NW == 8 && B_KC), "narrow tile: 8 waves, k-contiguous B operand");
+  constexpr int WAVES_M = BN == V2_B ? 2 : 4, WAVES_N = NW / WAVES_M;
+  constexpr int WM = V2_B / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
+  constexpr int OPB_B = BN * V2_BK * 2;                        // bytes of one k-slice of the B operand
+  // 1-KB copies per wave: per pair of slices for a k-contiguous operand, per slice otherwise
+  constexpr int NPA = A_KC ? V2_B / (8 * NW) : 16 / NW, NPB = B_KC ? BN / (8 * NW) : 16 / NW;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm0 = (wave / WAVES_N) * 128, wn0 = (wave % WAVES_N) * WN;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
 
   // work item: a full tile, or one k-piece of a tail tile
   int vt, piece = 0, npieces = 1;
@@ -168,22 +187,22 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
   // Plain order, tile row fastest: the 256 concurrent tiles form 8 tile-columns of 32 tile-rows, and the ids that
   // share an XCD (congruent mod 8) share tile rows, so each XCD's L2 sees few distinct operand panels.
   const int tile_m = vt % plan.tiles_m, tile_n = vt / plan.tiles_m;
-  const int m0 = tile_m * V2_B, n0 = tile_n * V2_B;
+  const int m0 = tile_m * V2_B, n0 = tile_n * BN;
   const int np_total = a.K / (2 * V2_BK);            // k is walked in pairs of 32-deep slices
   const int kt_begin = 2 * (int)((long)np_total * piece / npieces);
   const int kt_end = 2 * (int)((long)np_total * (piece + 1) / npieces);
   const int nk = kt_end - kt_begin;                  // even, >= 2
 
-  V2Src<A_KC, QPW> sa;
-  V2Src<B_KC, QPW> sb;
+  V2Src<A_KC, NPA> sa;
+  V2Src<B_KC, NPB> sb;
   sa.init((const bf16*)a.A, a.lda, m0, a.M, kt_begin * V2_BK, wave, lane);
   sb.init((const bf16*)a.B, a.ldb, n0, a.N, kt_begin * V2_BK, wave, lane);
 
-  floatx16 acc[TN][4];
+  floatx16 acc[TN][TM];
 #pragma unroll
   for (int i = 0; i < TN; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < TM; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
@@ -199,11 +218,11 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     if (A_KC) sa.issue(ldsA + h * 2 * V2_OP_BYTES, wave_u, min(h, last_pair));
-    if (B_KC) sb.issue(ldsB + h * 2 * V2_OP_BYTES, wave_u, min(h, last_pair));
+    if (B_KC) sb.issue(ldsB + h * 2 * OPB_B, wave_u, min(h, last_pair));
 #pragma unroll
     for (int s = 2 * h; s < 2 * h + 2; ++s) {
       if (!A_KC) sa.issue(ldsA + s * V2_OP_BYTES, wave_u, min(s, last_slice));
-      if (!B_KC) sb.issue(ldsB + s * V2_OP_BYTES, wave_u, min(s, last_slice));
+      if (!B_KC) sb.issue(ldsB + s * OPB_B, wave_u, min(s, last_slice));
     }
   }
   // Software pipeline over half-slices (16 k each).  The operand registers of the NEXT half are read from LDS while
@@ -217,16 +236,20 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
   // (pairs first).  Copies return in order, so "slice kt+1 has landed" is a bound on the copies still outstanding:
   //   even kt: everything up to the hand-over of kt-3 must be done           -> at most EV + OD = 4 QPW outstanding
   //   odd kt:  the pair issued first at the hand-over of kt-2 must be done   -> at most 2 EV outstanding (if NKC > 0)
-  constexpr int EV = NMN * QPW, OD = NKC * 2 * QPW + NMN * QPW;
-  constexpr int W_INIT = 3 * NMN * QPW + 2 * NKC * QPW, W_EVEN = EV + OD, W_ODD = NKC > 0 ? 2 * EV : EV + OD;
-  constexpr int NMF = TN * 4;            // MFMAs per half-slice per wave
-  bf16x8 fa0[4], fb0[TN], fa1[4], fb1[TN];
+  constexpr int C_SLICE = (A_KC ? 0 : NPA) + (B_KC ? 0 : NPB);     // copies per wave that re-arm a slice stage
+  constexpr int C_PAIR = (A_KC ? NPA : 0) + (B_KC ? NPB : 0);      // copies per wave that re-arm a pair stage
+  constexpr int EV = C_SLICE, OD = C_PAIR + C_SLICE;
+  constexpr int W_INIT = 3 * C_SLICE + C_PAIR, W_EVEN = EV + OD, W_ODD = NKC > 0 ? 2 * EV : EV + OD;
+  constexpr int NMF = TN * TM;           // MFMAs per half-slice per wave
+  static_assert(NMF > TM + TN, "one fragment read after each MFMA but the first must cover all fragments");
+  (void)NMN;
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
   wait_vmcnt<W_INIT>();                  // slice 0 landed
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int j = 0; j < 4; ++j) fa0[j] = v2_frag<A_KC>(ringA, 0, wm0 + j * 32, 0, lane);
+  for (int j = 0; j < TM; ++j) fa0[j] = v2_frag<A_KC>(ringA, 0, wm0 + j * 32, 0, lane);
 #pragma unroll
-  for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC>(ringB, 0, wn0 + i * 32, 0, lane);
+  for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC, OPB_B>(ringB, 0, wn0 + i * 32, 0, lane);
 
   // one 32-deep slice; PAR = parity of kt (compile time: it fixes the ring stage bits and the copy schedule)
   auto slice = [&](auto par_c, int kt) {
@@ -239,12 +262,12 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
     // either hoists them above the loop-top wait or sinks them to the barrier; both expose their full latency.)
 #pragma unroll
     for (int idx = 0; idx < NMF; ++idx) {
-      acc[idx / 4][idx % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / 4], fa0[idx % 4], acc[idx / 4][idx % 4], 0, 0, 0);
-      if (idx >= 1 && idx - 1 < 4 + TN) {
+      acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / TM], fa0[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
+      if (idx >= 1 && idx - 1 < TM + TN) {
         const int q = idx - 1;
         __builtin_amdgcn_sched_barrier(0);
-        if (q < 4) fa1[q] = v2_frag<A_KC>(ringA, stage, wm0 + q * 32, 1, lane);
-        else fb1[q - 4] = v2_frag<B_KC>(ringB, stage, wn0 + (q - 4) * 32, 1, lane);
+        if (q < TM) fa1[q] = v2_frag<A_KC>(ringA, stage, wm0 + q * 32, 1, lane);
+        else fb1[q - TM] = v2_frag<B_KC, OPB_B>(ringB, stage, wn0 + (q - TM) * 32, 1, lane);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -260,32 +283,33 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
     const int nstage = (kt + 1) & (V2_STAGES - 1);
     constexpr int NC = PAR == 0 ? EV : OD;                 // copies to issue in this half
     const int pair_idx = min((kt + 3) >> 1, last_pair);    // PAR == 1: the pair two ahead of this slice's pair
-    const uint32_t pair_off = (uint32_t)(((kt + 3) >> 1) & 1) * (2 * V2_OP_BYTES);
+    const uint32_t pair_sel = (uint32_t)(((kt + 3) >> 1) & 1);
+    const uint32_t pair_off_a = pair_sel * (2 * V2_OP_BYTES), pair_off_b = pair_sel * (2 * OPB_B);
     const int slice_idx = min(kt + V2_STAGES, last_slice);
-    const uint32_t slice_off = (uint32_t)stage * V2_OP_BYTES;
+    const uint32_t slice_off_a = (uint32_t)stage * V2_OP_BYTES, slice_off_b = (uint32_t)stage * OPB_B;
 #pragma unroll
     for (int idx = 0; idx < NMF; ++idx) {
-      acc[idx / 4][idx % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[idx / 4], fa1[idx % 4], acc[idx / 4][idx % 4], 0, 0, 0);
+      acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[idx / TM], fa1[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (idx < 4 + TN) {
+      if (idx < TM + TN) {
         const int q = idx;
-        if (q < 4) fa0[q] = v2_frag<A_KC>(ringA, nstage, wm0 + q * 32, 0, lane);
-        else fb0[q - 4] = v2_frag<B_KC>(ringB, nstage, wn0 + (q - 4) * 32, 0, lane);
+        if (q < TM) fa0[q] = v2_frag<A_KC>(ringA, nstage, wm0 + q * 32, 0, lane);
+        else fb0[q - TM] = v2_frag<B_KC, OPB_B>(ringB, nstage, wn0 + (q - TM) * 32, 0, lane);
       }
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
         if ((c * NMF) / (NC > 0 ? NC : 1) != idx) continue;   // copy c goes after MFMA (c NMF) / NC
         // order: A's pair, B's pair (odd slices only), then A's slice, B's slice
         int r = c;
-        constexpr int KA = (PAR == 1 && A_KC) ? 2 * QPW : 0, KB = (PAR == 1 && B_KC) ? 2 * QPW : 0;
-        constexpr int MA = A_KC ? 0 : QPW;
-        if (r < KA) { sa.issue_one(ldsA + pair_off, wave_u, pair_idx, r); continue; }
+        constexpr int KA = (PAR == 1 && A_KC) ? NPA : 0, KB = (PAR == 1 && B_KC) ? NPB : 0;
+        constexpr int MA = A_KC ? 0 : NPA;
+        if (r < KA) { sa.issue_one(ldsA + pair_off_a, wave_u, pair_idx, r); continue; }
         r -= KA;
-        if (r < KB) { sb.issue_one(ldsB + pair_off, wave_u, pair_idx, r); continue; }
+        if (r < KB) { sb.issue_one(ldsB + pair_off_b, wave_u, pair_idx, r); continue; }
         r -= KB;
-        if (r < MA) { sa.issue_one(ldsA + slice_off, wave_u, slice_idx, r); continue; }
+        if (r < MA) { sa.issue_one(ldsA + slice_off_a, wave_u, slice_idx, r); continue; }
         r -= MA;
-        sb.issue_one(ldsB + slice_off, wave_u, slice_idx, r);
+        sb.issue_one(ldsB + slice_off_b, wave_u, slice_idx, r);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -301,27 +325,27 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
   __syncthreads();
 
   if (npieces > 1) {
-    // fp32 partial tile: piece-major [tail tile][piece][256][256]
+    // fp32 partial tile: piece-major [tail tile][piece][256][BN]
     const int l32 = lane & 31, lh = lane >> 5;
-    float* dst = splitk_ws + ((size_t)(vt - plan.full_tiles) * plan.split + piece) * (V2_B * V2_B);
+    float* dst = splitk_ws + ((size_t)(vt - plan.full_tiles) * plan.split + piece) * (V2_B * BN);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < TM; ++j)
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-          *reinterpret_cast<float4*>(dst + (wm0 + j * 32 + l32) * V2_B + wn0 + i * 32 + 8 * g + 4 * lh) = v;
+          *reinterpret_cast<float4*>(dst + (wm0 + j * 32 + l32) * BN + wn0 + i * 32 + 8 * g + 4 * lh) = v;
         }
     return;
   }
-  gemm_epilogue<V2_B, V2_B, 2, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
+  gemm_epilogue<V2_B, BN, WAVES_M, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
 }
 
-template <bool A_KC, bool B_KC, int EPI, int NW>
+template <bool A_KC, bool B_KC, int EPI, int NW, int BN = V2_B>
 __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan plan, float* splitk_ws) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  gemm_v2_work_item<A_KC, B_KC, EPI, NW>(a, plan, splitk_ws, blockIdx.x, lds_raw);
+  gemm_v2_work_item<A_KC, B_KC, EPI, NW, BN>(a, plan, splitk_ws, blockIdx.x, lds_raw);
 }
 
 // Several independent GEMMs of one operand layout in ONE launch (plain-store epilogue, no k-split): the tiles of
@@ -362,12 +386,14 @@ __global__ __launch_bounds__(256) void gemm_v2_fixup_kernel(GemmArgs a, V2Plan p
   const int t = blockIdx.y;                          // tail tile
   const int vt = plan.full_tiles + t;
   const int tile_n = vt / plan.tiles_m;
-  const int m0 = (vt % plan.tiles_m) * V2_B, n0 = tile_n * V2_B;
+  const int bn = plan.bn;                             // tile width: a partial tile is [256][bn] floats
+  const int m0 = (vt % plan.tiles_m) * V2_B, n0 = tile_n * bn;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = n0 + lane * 4;
-  const bool col_ok = n < a.N;                        // N is a multiple of 8: a 4-column group is all in or all out
+  const bool col_ok = n < a.N && lane * 4 < bn;       // N is a multiple of 8: a 4-column group is all in or all out
   const int nc = col_ok ? n : 0;
-  const float* base = ws + (size_t)t * plan.split * (V2_B * V2_B) + lane * 4;
+  const int lcol = lane * 4 < bn ? lane * 4 : 0;
+  const float* base = ws + (size_t)t * plan.split * (V2_B * bn) + lcol;
   float bv[4] = {0.f, 0.f, 0.f, 0.f};
   if ((EPI == EPI_STORE || EPI == EPI_BIAS_GELU) && a.bias != nullptr) {
     const bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16*)a.bias + nc);
@@ -382,7 +408,7 @@ __global__ __launch_bounds__(256) void gemm_v2_fixup_kernel(GemmArgs a, V2Plan p
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[i][e] = bv[e];
     for (int p = 0; p < plan.split; ++p) {
-      const float4 x = *reinterpret_cast<const float4*>(base + (size_t)p * (V2_B * V2_B) + r * V2_B);
+      const float4 x = *reinterpret_cast<const float4*>(base + (size_t)p * (V2_B * bn) + r * bn);
       v[i][0] += x.x; v[i][1] += x.y; v[i][2] += x.z; v[i][3] += x.w;
     }
   }
@@ -453,11 +479,12 @@ inline size_t v2_splitk_ws_bytes() { return (size_t)V2_CUS * V2_B * V2_B * sizeo
 
 int gemm_v2_waves(bool a_kc, bool b_kc);   // 4 or 8 waves per workgroup for this operand layout
 
-template <bool A_KC, bool B_KC, int EPI, int NW>
+template <bool A_KC, bool B_KC, int EPI, int NW, int BN = V2_B>
 hipError_t launch_gemm_bf16_v2_nw(const GemmArgs& a, float* splitk_ws, hipStream_t st) {
-  auto kern = gemm_bf16_v2_kernel<A_KC, B_KC, EPI, NW>;
+  auto kern = gemm_bf16_v2_kernel<A_KC, B_KC, EPI, NW, BN>;
   // the ring (128 KB) or, with 8 waves, the epilogue's staging strips (2 per wave) + reduction area, whichever is larger
-  constexpr size_t kEpi = GemmTile<V2_B, V2_B, 2, NW / 2>::LDS_EPI;
+  constexpr int WAVES_M = BN == V2_B ? 2 : 4;
+  constexpr size_t kEpi = GemmTile<V2_B, BN, WAVES_M, NW / WAVES_M>::LDS_EPI;
   constexpr size_t kLds = V2_LDS_BYTES > kEpi ? V2_LDS_BYTES : kEpi;
   static_assert(kLds <= 160 * 1024, "LDS budget");
   static bool attr_set = false;
@@ -467,7 +494,7 @@ hipError_t launch_gemm_bf16_v2_nw(const GemmArgs& a, float* splitk_ws, hipStream
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const V2Plan plan = v2_plan(a.M, a.N, a.K, splitk_ws != nullptr);
+  const V2Plan plan = v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, BN);
   const int grid = plan.full_tiles + plan.tail_tiles * plan.split;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), kLds, st, a, plan, splitk_ws);
   hipError_t e = hipGetLastError();
@@ -509,9 +536,21 @@ hipError_t launch_gemm_bf16_v2_group_nw(const GemmArgs* probs, int n, hipStream_
   return hipGetLastError();
 }
 
+int gemm_v2_forced_bn();                    // MLM_GEMM_BN=192|256 forces a tile width where both exist, else 0
+
 template <bool A_KC, bool B_KC, int EPI>
 hipError_t launch_gemm_bf16_v2(const GemmArgs& a, float* splitk_ws, hipStream_t st) {
-  if (gemm_v2_waves(A_KC, B_KC) == 8) return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 8>(a, splitk_ws, st);
+  if (gemm_v2_waves(A_KC, B_KC) == 8) {
+    if (A_KC && B_KC) {
+      // input-gradient layout: both tile widths exist; take the one the cost model prices lower for this shape
+      const int forced = gemm_v2_forced_bn();
+      const bool narrow = forced ? forced == 192
+                                 : v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, 192).cost <
+                                       v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, V2_B).cost;
+      if (narrow) return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 8, (A_KC && B_KC) ? 192 : V2_B>(a, splitk_ws, st);
+    }
+    return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 8>(a, splitk_ws, st);
+  }
   return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 4>(a, splitk_ws, st);
 }
 
