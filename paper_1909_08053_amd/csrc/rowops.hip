@@ -15,12 +15,13 @@ struct PartialPtrs { const void* p[kMaxPartials]; };
 // combine kernel would have stored.  All of a partial's vectors are loaded before they are added, so the loads of a
 // row overlap; a single partial with nothing to add is passed through untouched.  With dropout the row is
 // residual + dropout(sum partials + bias): the mask of element row_off + column comes from the counter-based generator.
-template <typename T, int NV>
+// (DROP is a template parameter: the generator's registers must not weigh on the dropout-free instantiation)
+template <typename T, int NV, bool DROP>
 __device__ __forceinline__ void combine_row(const PartialPtrs& ptrs, int n, const T* bias, const T* residual,
                                             size_t row_off, int lane, int nvec, Vec16<T> (&out)[NV],
                                             const DropArgs& drop) {
   constexpr int VN = Vec16<T>::N;
-  if (n == 1 && bias == nullptr && residual == nullptr && !drop.enabled) {
+  if (!DROP && n == 1 && bias == nullptr && residual == nullptr) {
     const T* p = (const T*)ptrs.p[0] + row_off;
 #pragma unroll
     for (int i = 0; i < NV; ++i)
@@ -33,7 +34,7 @@ __device__ __forceinline__ void combine_row(const PartialPtrs& ptrs, int n, cons
 #pragma unroll
     for (int e = 0; e < VN; ++e) acc[i][e] = 0.f;
   for (int k = 0; k < n + 2; ++k) {
-    if (k == n + 1 && drop.enabled) {                 // uniform: everything but the residual is in, drop it out
+    if (DROP && k == n + 1) {                         // everything but the residual is in: drop it out
 #pragma unroll
       for (int i = 0; i < NV; ++i)
         if (lane + 64 * i < nvec) drop_apply<VN>(drop, row_off + (size_t)(lane + 64 * i) * VN, acc[i]);
@@ -60,7 +61,7 @@ __device__ __forceinline__ void combine_row(const PartialPtrs& ptrs, int n, cons
 // ------------------------------------------------------------------------------ layer norm forward
 // FUSED: the input row is first formed as sum of partials + bias + residual (the single-GPU stand-in for the
 // all-reduce followed by the bias/residual add), stored to x_out, and normalised from registers.
-template <typename T, int NV, bool FUSED>
+template <typename T, int NV, bool FUSED, bool DROP>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int H, float eps, const T* __restrict__ x,
                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
                                                      T* __restrict__ y, float* __restrict__ mean,
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int H, float eps,
   const T* xr = x + (size_t)row * H;
   Vec16<T> v[NV];
   float sum = 0.f;
-  if (FUSED) combine_row<T, NV>(ptrs, n, bias, residual, (size_t)row * H, lane, nvec, v, drop);
+  if (FUSED) combine_row<T, NV, DROP>(ptrs, n, bias, residual, (size_t)row * H, lane, nvec, v, drop);
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int idx = lane + 64 * i;
@@ -123,12 +124,16 @@ static hipError_t ln_fwd_dispatch(int rows, int H, float eps, const void* x, con
   for (int k = 0; k < kMaxPartials; ++k) none.p[k] = nullptr;
 #define MLM_LN_FWD(NVV)                                                                                    \
   case NVV:                                                                                                \
-    if (pp)                                                                                                \
-      hipLaunchKernelGGL((ln_fwd_kernel<T, NVV, true>), grid, block, 0, st, rows, H, eps, (const T*)x,     \
+    if (pp && drop.enabled)                                                                                \
+      hipLaunchKernelGGL((ln_fwd_kernel<T, NVV, true, true>), grid, block, 0, st, rows, H, eps, (const T*)x, \
+                         (const T*)gamma, (const T*)beta, (T*)y, mean, rstd, *pp, n, (const T*)bias,       \
+                         (const T*)residual, (T*)x_out, drop);                                             \
+    else if (pp)                                                                                           \
+      hipLaunchKernelGGL((ln_fwd_kernel<T, NVV, true, false>), grid, block, 0, st, rows, H, eps, (const T*)x, \
                          (const T*)gamma, (const T*)beta, (T*)y, mean, rstd, *pp, n, (const T*)bias,       \
                          (const T*)residual, (T*)x_out, drop);                                             \
     else                                                                                                   \
-      hipLaunchKernelGGL((ln_fwd_kernel<T, NVV, false>), grid, block, 0, st, rows, H, eps, (const T*)x,    \
+      hipLaunchKernelGGL((ln_fwd_kernel<T, NVV, false, false>), grid, block, 0, st, rows, H, eps, (const T*)x, \
                          (const T*)gamma, (const T*)beta, (T*)y, mean, rstd, none, 0, (const T*)nullptr,   \
                          (const T*)nullptr, (T*)nullptr, drop);                                            \
     break;
@@ -175,7 +180,9 @@ hipError_t launch_combine_layernorm_fwd(int dtype, int T, int H, float eps, cons
 // as a third per-column partial next to dgamma / dbeta.
 constexpr int kLnBwdBatch = 4;
 
-template <typename T, bool FUSED, bool SUM>
+// DZ: also emit dz_out = dropout-mask(dx) / (1 - p) (and sum ITS columns); a template parameter so that the generator
+// costs the plain instantiations no registers.
+template <typename T, bool FUSED, bool SUM, bool DZ>
 __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy, const T* __restrict__ x,
                                                      const T* __restrict__ gamma, const float* __restrict__ mean,
                                                      const float* __restrict__ rstd, const T* residual, T* dx,
@@ -288,10 +295,10 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
           float v = rs[j] * (d * gam[e] - s1 - xh * s2);
           if (residual) v += vres[j].get(e);
           o.set(e, v);
-          if (SUM && dz_out == nullptr) dsum[e] += o.get(e);   // the stored (rounded) value, as a separate column sum would read it
+          if (SUM && !DZ) dsum[e] += o.get(e);   // the stored (rounded) value, as a separate column sum would read it
         }
         o.store(dx + (size_t)(r0 + j) * H + col0);
-        if (dz_out != nullptr) {
+        if (DZ) {
           // this layer norm's input was residual + dropout(z): emit dz = mask o dx / (1 - p) and sum ITS columns
           float z[VN];
 #pragma unroll
@@ -362,13 +369,15 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
   for (int k = 0; k < kMaxPartials; ++k) none.p[k] = nullptr;
   const int np = (pp && dx_colsum) ? 3 : 2;
   dim3 grid(nblk), block(nwaves * 64);
-#define MLM_LN_BWD_GO(F, S)                                                                                 \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, F, S>), grid, block, 0, st, rows, H, (const T*)dy, (const T*)x,      \
+#define MLM_LN_BWD_GO(F, S, Z)                                                                              \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, F, S, Z>), grid, block, 0, st, rows, H, (const T*)dy, (const T*)x,   \
                      (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws, pp ? *pp : none, n,       \
                      (T*)dy_out, drop, (T*)dz_out)
-  if (pp && dx_colsum) MLM_LN_BWD_GO(true, true);
-  else if (pp) MLM_LN_BWD_GO(true, false);
-  else MLM_LN_BWD_GO(false, false);
+  if (pp && dx_colsum && dz_out) MLM_LN_BWD_GO(true, true, true);
+  else if (pp && dz_out) MLM_LN_BWD_GO(true, false, true);
+  else if (pp && dx_colsum) MLM_LN_BWD_GO(true, true, false);
+  else if (pp) MLM_LN_BWD_GO(true, false, false);
+  else MLM_LN_BWD_GO(false, false, false);
 #undef MLM_LN_BWD_GO
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -593,25 +602,45 @@ hipError_t launch_ce_rows_f32(int T, int Vl, const float* logits, const int32_t*
 // summed in a fixed order.
 __global__ __launch_bounds__(1024) void ce_merge_kernel(int T, int n_shards, const float* __restrict__ m,
                                                         const float* __restrict__ s, const float* __restrict__ tl,
-                                                        const float* __restrict__ loss_w, float* ce, float* Mo,
-                                                        float* So, float* loss_out) {
+                                                        const float* __restrict__ loss_w, float* __restrict__ ce,
+                                                        float* __restrict__ Mo, float* __restrict__ So,
+                                                        float* __restrict__ loss_out) {
   __shared__ float red_l[16], red_w[16];
   float accl = 0.f, accw = 0.f;
-  for (int t = threadIdx.x; t < T; t += 1024) {
-    float M = -INFINITY;
-    for (int r = 0; r < n_shards; ++r) M = fmaxf(M, m[(size_t)r * T + t]);
-    float S = 0.f, tt = 0.f;
-    for (int r = 0; r < n_shards; ++r) {
-      S += s[(size_t)r * T + t] * expf(m[(size_t)r * T + t] - M);
-      tt += tl[(size_t)r * T + t];
+  // a thread's tokens are independent: four at a time, so that their (dependent-free) loads are in flight together
+  // instead of one round trip to memory per token
+  constexpr int U = 4;
+  for (int t0 = threadIdx.x; t0 < T; t0 += 1024 * U) {
+    float M[U], S[U], tt[U], w[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = min(t0 + 1024 * u, T - 1);
+      M[u] = -INFINITY;
+      for (int r = 0; r < n_shards; ++r) M[u] = fmaxf(M[u], m[(size_t)r * T + t]);
+      w[u] = loss_w ? loss_w[t] : 1.0f;
     }
-    const float c = logf(S) + M - tt;
-    ce[t] = c;
-    Mo[t] = M;
-    So[t] = S;
-    const float w = loss_w ? loss_w[t] : 1.0f;
-    accl += w * c;
-    accw += w;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = min(t0 + 1024 * u, T - 1);
+      S[u] = 0.f;
+      tt[u] = 0.f;
+      for (int r = 0; r < n_shards; ++r) {
+        S[u] += s[(size_t)r * T + t] * expf(m[(size_t)r * T + t] - M[u]);
+        tt[u] += tl[(size_t)r * T + t];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + 1024 * u;
+      if (t < T) {
+        const float c = logf(S[u]) + M[u] - tt[u];
+        ce[t] = c;
+        Mo[t] = M[u];
+        So[t] = S[u];
+        accl += w[u] * c;
+        accw += w[u];
+      }
+    }
   }
   accl = wave_sum(accl);
   accw = wave_sum(accw);
