@@ -335,6 +335,64 @@ def backward(inp: Dict[str, np.ndarray], c: Dict[str, np.ndarray], spec: Spec) -
     return g
 
 
+# --------------------------------------------------------------------------- the original (post-LN) arrangement
+def forward_post_ln(inp: Dict[str, np.ndarray], spec: Spec) -> Dict[str, np.ndarray]:
+    """The layer in the ORIGINAL BERT arrangement that the paper compares against (Section 5.3, architecture (a) of
+    its layer-norm figure): layer norm AFTER each residual add, X1 = LN(X + Attn(X)), X2 = LN(X1 + MLP(X1)); the
+    logits are taken from X2 directly.  Reading (the figure itself is not in the text): g1/b1 normalise the attention
+    block's sum, g2/b2 the MLP block's; gf/bf are unused.  No dropout here."""
+    p = _f64(inp)
+    b, s, H, T = spec.b, spec.s, spec.H, spec.T
+    X = p["X"].reshape(T, H)
+    c: Dict[str, np.ndarray] = {}
+    c["Q"], c["K"], c["Vv"] = X @ p["Wq"] + p["bq"], X @ p["Wk"] + p["bk"], X @ p["Wv"] + p["bv"]
+    C, Pm, LSE = attention_fwd(c["Q"].reshape(b, s, H), c["K"].reshape(b, s, H), c["Vv"].reshape(b, s, H), spec,
+                               p["key_len"])
+    c["C"], c["P"], c["LSE"] = C.reshape(T, H), Pm, LSE
+    c["S1"] = X + c["C"] @ p["Wo"] + p["bo"]
+    c["X1"], c["mu1"], c["rstd1"] = layernorm_fwd(c["S1"], p["g1"], p["b1"], spec.ln_eps)
+    c["G"] = c["X1"] @ p["A"] + p["a"]
+    c["Y"] = gelu(c["G"], spec.gelu_tanh)
+    c["S2"] = c["X1"] + c["Y"] @ p["B"] + p["c"]
+    c["X2"], c["mu2"], c["rstd2"] = layernorm_fwd(c["S2"], p["g2"], p["b2"], spec.ln_eps)
+    c["L"] = c["X2"] @ p["E"]
+    tgt = p["tgt"].reshape(T).astype(np.int64)
+    w = np.asarray(p["w"], F64).reshape(T)
+    c["loss"], c["ce"], c["M"], c["S"] = cross_entropy_fwd(c["L"], tgt, w)
+    return c
+
+
+def backward_post_ln(inp: Dict[str, np.ndarray], c: Dict[str, np.ndarray], spec: Spec) -> Dict[str, np.ndarray]:
+    """Analytic gradients of forward_post_ln."""
+    p = _f64(inp)
+    b, s, H, T = spec.b, spec.s, spec.H, spec.T
+    X = p["X"].reshape(T, H)
+    tgt = p["tgt"].reshape(T).astype(np.int64)
+    w = np.asarray(p["w"], F64).reshape(T)
+    g: Dict[str, np.ndarray] = {}
+    g["dL"] = cross_entropy_bwd(c["L"], tgt, w, c["M"], c["S"])
+    g["dE"] = c["X2"].T @ g["dL"]
+    g["dX2"] = g["dL"] @ p["E"].T
+    g["dS2"], g["dg2"], g["db2"] = layernorm_bwd(g["dX2"], c["S2"], p["g2"], c["mu2"], c["rstd2"])
+    g["dc"] = g["dS2"].sum(axis=0)
+    g["dB"] = c["Y"].T @ g["dS2"]
+    g["dG"] = (g["dS2"] @ p["B"].T) * gelu_grad(c["G"], spec.gelu_tanh)
+    g["da"] = g["dG"].sum(axis=0)
+    g["dA"] = c["X1"].T @ g["dG"]
+    g["dX1"] = g["dS2"] + g["dG"] @ p["A"].T                 # residual branch + through the MLP
+    g["dS1"], g["dg1"], g["db1"] = layernorm_bwd(g["dX1"], c["S1"], p["g1"], c["mu1"], c["rstd1"])
+    g["dbo"] = g["dS1"].sum(axis=0)
+    g["dWo"] = c["C"].T @ g["dS1"]
+    dC = g["dS1"] @ p["Wo"].T
+    dQ, dK, dV = attention_bwd(dC.reshape(b, s, H), c["Q"].reshape(b, s, H), c["K"].reshape(b, s, H),
+                               c["Vv"].reshape(b, s, H), c["P"], spec)
+    dQ, dK, dV = dQ.reshape(T, H), dK.reshape(T, H), dV.reshape(T, H)
+    g["dWq"], g["dWk"], g["dWv"] = X.T @ dQ, X.T @ dK, X.T @ dV
+    g["dbq"], g["dbk"], g["dbv"] = dQ.sum(axis=0), dK.sum(axis=0), dV.sum(axis=0)
+    g["dX"] = g["dS1"] + dQ @ p["Wq"].T + dK @ p["Wk"].T + dV @ p["Wv"].T
+    return g
+
+
 def loss_only(inp: Dict[str, np.ndarray], spec: Spec) -> float:
     return forward(inp, spec)["loss"]
 

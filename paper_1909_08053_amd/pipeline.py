@@ -24,7 +24,7 @@ def _tdtype(cfg: LayerConfig):
 class LayerShards:
     def __init__(self, cfg: LayerConfig, shards: Sequence[int], device: str = "cuda:0", store_logits: bool = True,
                  fused: bool = True, store_combined: bool = False, dropout: Optional[Dict[str, object]] = None,
-                 embed: bool = False, loss_rows: bool = False, grouped_wgrads: bool = True):
+                 embed: bool = False, loss_rows: bool = False, grouped_wgrads: bool = True, post_ln: bool = False):
         """fused: the combine that stands in for an all-reduce runs inside the layer-norm kernel that consumes it
         (and the layer-norm backward also emits the row-parallel bias gradient); store_combined: in fused mode,
         also store the combined gradients dHf / dU2 / dU (nothing in the path reads them).
@@ -37,11 +37,16 @@ class LayerShards:
         parallel logits / loss / gradient calls run on that compact tensor only (BERT-style masked-LM loss: ~15 % of
         the positions); the input gradient is scattered back with zeros elsewhere.  Same loss and gradients.
         grouped_wgrads: the backward calls compute input gradients only and the four weight gradients of each layer
-        shard are computed afterwards by one mlm_layer_shard_wgrads call (one grouped GEMM launch)."""
+        shard are computed afterwards by one mlm_layer_shard_wgrads call (one grouped GEMM launch).
+        post_ln: the ORIGINAL BERT arrangement the paper compares against (Section 5.3): layer norm after each
+        residual add, X1 = LN(X + Attn(X)), X2 = LN(X1 + MLP(X1)), logits from X2; same entry points, other call order."""
         self.cfg, self.shards, self.dev = cfg, list(shards), torch.device(device)
         self.fused, self.store_combined = fused, store_combined
         self.dropout, self.embed, self.loss_rows = dropout, embed, loss_rows
         self.grouped_wgrads = grouped_wgrads
+        self.post_ln = post_ln
+        if post_ln and (dropout is not None or embed or loss_rows or not fused):
+            raise ValueError("the post-LN arrangement is wired for the plain fused path only")
         if dropout is not None and not fused:
             raise ValueError("dropout is wired into the fused combine + layer-norm calls only")
         self.dt = _tdtype(cfg)
@@ -230,7 +235,59 @@ class LayerShards:
             w, s = self.w[r], self.sh[r]
             B.mlm_mlp_shard_fwd(self.dims[r], a["U2"], w["A"], w["a"], w["B"], s["g"], s["y"], s["mlp_partial"], ws)
 
+    # ---- the original (post-LN) arrangement: a["X1"] / a["X2"] hold the SUMS before the layer norms (the tensors the
+    #      norms' backward needs), a["U2"] the normalised attention-block output (= the MLP's input and residual) and
+    #      a["Hf"] the normalised layer output
+    def _forward_post_ln(self):
+        cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
+        d0 = self.dims[self.shards[0]]
+        kl = rep["key_len"] if cfg.masked_lm else None
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_attn_shard_fwd(self.dims[r], rep["X"], w["Wqkv"], w["bqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
+                                 s["attn_partial"], ws)
+        B.mlm_combine_layernorm_fwd(d0, [self.sh[r]["attn_partial"] for r in self.shards], rep["bo"], rep["X"], a["X1"],
+                                    rep["g1"], rep["b1"], a["U2"], a["mu1"], a["rstd1"])
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_mlp_shard_fwd(self.dims[r], a["U2"], w["A"], w["a"], w["B"], s["g"], s["y"], s["mlp_partial"], ws)
+        B.mlm_combine_layernorm_fwd(d0, [self.sh[r]["mlp_partial"] for r in self.shards], rep["c"], a["U2"], a["X2"],
+                                    rep["g2"], rep["b2"], a["Hf"], a["mu2"], a["rstd2"])
+        self._hf = a["Hf"]
+        for i, r in enumerate(self.shards):
+            B.mlm_vocab_ce_shard_fwd(self.dims[r], a["Hf"], self.w[r]["E"], rep["tgt"], a["m"][i], a["s"][i], a["t"][i],
+                                     self.sh[r]["logits"], ws)
+        B.mlm_vocab_ce_merge(d0, a["m"], a["s"], a["t"], len(self.shards), rep["w"], a["ce"], a["M"], a["S"], a["loss"])
+
+    def _backward_post_ln(self):
+        cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
+        d0 = self.dims[self.shards[0]]
+        kl = rep["key_len"] if cfg.masked_lm else None
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_vocab_ce_shard_bwd(self.dims[r], a["Hf"], w["E"], rep["tgt"], rep["w"], a["M"], a["S"], a["loss"],
+                                     s["logits"], s["dE"], s["dhf_partial"], ws)
+        # LN2 backward on dX2 = sum of the logits input-gradient partials: gradient of the MLP block's sum S2
+        B.mlm_combine_layernorm_bwd(d0, [self.sh[r]["dhf_partial"] for r in self.shards], a["X2"], rep["g2"], a["mu2"],
+                                    a["rstd2"], None, None, a["dX2"], a["dg2"], a["db2"], a["dc"], ws)
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_mlp_shard_bwd(self.dims[r], a["dX2"], a["U2"], w["A"], w["B"], s["g"], s["y"], s["dA"], s["da"],
+                                s["dB"], s["du2_partial"], ws)
+        # the attention block's normalised output fed the MLP AND its residual: its gradient is the MLP input-gradient
+        # partials plus dS2 -- one more term of the same sum -- and LN1's backward turns it into the gradient of S1
+        B.mlm_combine_layernorm_bwd(d0, [self.sh[r]["du2_partial"] for r in self.shards] + [a["dX2"]], a["X1"], rep["g1"],
+                                    a["mu1"], a["rstd1"], None, None, a["dX1"], a["dg1"], a["db1"], a["dbo"], ws)
+        for r in self.shards:
+            w, s = self.w[r], self.sh[r]
+            B.mlm_attn_shard_bwd(self.dims[r], a["dX1"], rep["X"], w["Wqkv"], w["Wo"], kl, s["qkv"], s["ctx"], s["lse"],
+                                 s["dWqkv"], s["dbqkv"], s["dWo"], s["du_partial"], ws)
+        B.mlm_combine(d0, [self.sh[r]["du_partial"] for r in self.shards], None, a["dX1"], a["dX"])
+        self._dx2 = a["dX2"]
+
     def forward(self):
+        if self.post_ln:
+            return self._forward_post_ln()
         cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
         d0 = self.dims[self.shards[0]]
         if self.embed:
@@ -267,6 +324,8 @@ class LayerShards:
         B.mlm_vocab_ce_merge(dc0, a["m"], a["s"], a["t"], len(self.shards), lw, a["ce"], a["M"], a["S"], a["loss"])
 
     def backward(self):
+        if self.post_ln:
+            return self._backward_post_ln()
         cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws
         d0 = self.dims[self.shards[0]]
         kl = rep["key_len"] if cfg.masked_lm else None

@@ -350,3 +350,39 @@ def test_grouped_weight_gradients_equal_the_separate_calls(dtype, shape):
         for k in ("dWqkv", "dWo", "dA", "dB"):
             assert relerr(_dn(res[1][0].sh[r][k]), ref["shards"][r][k]) <= TOL[dtype], (r, k)
             assert relerr(_dn(res[1][0].sh[r][k]), _dn(res[0][0].sh[r][k])) <= TOL[dtype] * 0.5, (r, k)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_post_ln_arrangement_all_shards(dtype):
+    """The original BERT arrangement (layer norm after each residual add; Section 5.3 of the paper compares it with
+    the pre-LN one): same entry points in another order, against the oracle's post-LN definition."""
+    cfg = synth.small_config(dtype=dtype, b=3, s=136, H=256, h=4, F=1024, V=512, p=2, causal=False, masked_lm=True)
+    inp = synth.make_inputs(cfg, nonzero_bias=True, random_ln=True)
+    for k in ("Wq", "Wk", "Wv", "Wo", "A", "B", "E"):
+        inp[k] = inp[k] * np.float32(3.0)
+        if dtype == "bf16":
+            inp[k] = synth.round_to_bf16(inp[k])
+    spec = spec_of(cfg)
+    c = O.forward_post_ln(inp, spec)
+    g = O.backward_post_ln(inp, c, spec)
+    L = LayerShards(cfg, [0, 1], DEV, post_ln=True)
+    L.load_host_inputs(inp)
+    L.step()
+    out = L.fetch()
+    tol = TOL[dtype]
+    errs = []
+    assert abs(out["loss"] - c["loss"]) <= tol * abs(c["loss"])
+    for k, ref in (("X1", c["S1"]), ("U2", c["X1"]), ("X2", c["S2"]), ("Hf", c["X2"]), ("ce", c["ce"]),
+                   ("dX2", g["dS2"]), ("dX1", g["dS1"]), ("dX", g["dX"]), ("dg1", g["dg1"]), ("db1", g["db1"]),
+                   ("dg2", g["dg2"]), ("db2", g["db2"]), ("dbo", g["dbo"]), ("dc", g["dc"])):
+        check(k, out[k], ref, tol, errs)
+    Hl, Fl, Vl = cfg.H // 2, cfg.F // 2, cfg.V // 2
+    for r in (0, 1):
+        cs, fs, vs = slice(r * Hl, (r + 1) * Hl), slice(r * Fl, (r + 1) * Fl), slice(r * Vl, (r + 1) * Vl)
+        sh = out["shards"][r]
+        check(f"{r}.dWqkv", sh["dWqkv"], np.concatenate([g["dWq"][:, cs], g["dWk"][:, cs], g["dWv"][:, cs]], axis=1), tol, errs)
+        check(f"{r}.dWo", sh["dWo"], g["dWo"][cs, :], tol, errs)
+        check(f"{r}.dA", sh["dA"], g["dA"][:, fs], tol, errs)
+        check(f"{r}.dB", sh["dB"], g["dB"][fs, :], tol, errs)
+        check(f"{r}.dE", sh["dE"], g["dE"][:, vs], tol, errs)
+    print("worst:", sorted(errs, key=lambda e: -e[1])[:4])

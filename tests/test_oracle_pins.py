@@ -410,3 +410,45 @@ def test_bf16_rounding_helper():
     ref = torch.tensor(x).to(torch.bfloat16).to(torch.float32).numpy()
     assert np.array_equal(r, ref)
     assert np.array_equal(synth.bf16_bits(r), (r.view(np.uint32) >> 16).astype(np.uint16))
+
+
+# ------------------------------------------------------------------ the original (post-LN) arrangement
+def test_post_ln_layer_against_library_autograd_and_finite_differences():
+    cfg = synth.small_config(b=2, s=12, H=32, h=4, F=128, V=48, causal=False, masked_lm=True)
+    inp = synth.make_inputs(cfg, nonzero_bias=True, random_ln=True)
+    for k in ("Wq", "Wk", "Wv", "Wo", "A", "B", "E"):
+        inp[k] = inp[k] * 8.0
+    spec = spec_of(cfg)
+    c = O.forward_post_ln(inp, spec)
+    g = O.backward_post_ln(inp, c, spec)
+    t = {k: (torch.tensor(np.asarray(v, np.float64), requires_grad=True) if np.asarray(v).dtype.kind == "f" and k != "w"
+             else torch.tensor(np.asarray(v))) for k, v in inp.items()}
+    b, s, H, h, d, T = spec.b, spec.s, spec.H, spec.h, spec.d, spec.T
+    X = t["X"].reshape(T, H)
+    heads = lambda z: z.reshape(b, s, h, d).permute(0, 2, 1, 3)
+    mask = torch.tensor(np.stack([O.allowed_mask(s, spec.causal, int(k)) for k in inp["key_len"]]))[:, None]
+    C = TF.scaled_dot_product_attention(heads(X @ t["Wq"] + t["bq"]), heads(X @ t["Wk"] + t["bk"]),
+                                        heads(X @ t["Wv"] + t["bv"]), attn_mask=mask).permute(0, 2, 1, 3).reshape(T, H)
+    X1 = TF.layer_norm(X + C @ t["Wo"] + t["bo"], (H,), t["g1"], t["b1"], spec.ln_eps)
+    X2 = TF.layer_norm(X1 + TF.gelu(X1 @ t["A"] + t["a"], approximate="tanh") @ t["B"] + t["c"], (H,), t["g2"], t["b2"],
+                       spec.ln_eps)
+    w = np.asarray(inp["w"]).reshape(T)
+    tgt = torch.tensor(np.where(w > 0, np.asarray(inp["tgt"]).reshape(T), -100).astype(np.int64))
+    loss = TF.cross_entropy(X2 @ t["E"], tgt, ignore_index=-100)
+    assert abs(loss.item() - c["loss"]) < 1e-12
+    loss.backward()
+    for name, gname in GRAD_NAMES.items():
+        if name in ("gf", "bf"):
+            continue
+        ref = t[name].grad.numpy().reshape(g[gname].shape)
+        assert np.max(np.abs(g[gname] - ref)) / max(np.max(np.abs(ref)), 1e-6) < 1e-10, name
+    # the two arrangements are different functions of the same parameters
+    assert abs(O.forward(inp, spec)["loss"] - c["loss"]) > 1e-3
+    # properties the arrangement fixes: the block outputs are normalised rows (gamma 1, beta 0 => zero mean)
+    plain = dict(inp)
+    for k in ("g1", "g2"):
+        plain[k] = np.ones_like(inp[k])
+    for k in ("b1", "b2"):
+        plain[k] = np.zeros_like(inp[k])
+    cp = O.forward_post_ln(plain, spec)
+    assert np.max(np.abs(cp["X1"].mean(axis=-1))) < 1e-12 and np.max(np.abs(cp["X2"].mean(axis=-1))) < 1e-12
