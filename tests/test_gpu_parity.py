@@ -386,3 +386,48 @@ def test_post_ln_arrangement_all_shards(dtype):
         check(f"{r}.dB", sh["dB"], g["dB"][fs, :], tol, errs)
         check(f"{r}.dE", sh["dE"], g["dE"][:, vs], tol, errs)
     print("worst:", sorted(errs, key=lambda e: -e[1])[:4])
+
+
+def test_step_is_capturable_in_a_hip_graph_and_replays_bit_identically():
+    """The library allocates nothing, creates no stream and never synchronises, so a whole forward + backward step can
+    be captured into a HIP graph on the caller's stream.  Replays (with eager steps and synchronisations in between)
+    must reproduce the eager result bit for bit, also after the inputs changed in place."""
+    cfg = synth.small_config(dtype="bf16", b=2, s=256, H=512, h=4, F=2048, V=1024, p=2)
+    L = LayerShards(cfg, [0, 1], DEV, dropout=dict(p_attn=0.1, p_hidden=0.1, base_seed=5,
+                                                   offsets={"attn": 1, "hidden1": 2, "hidden2": 3, "embed": 4}), embed=True)
+    L.load_random(seed=1)
+    names = ("dX", "dX1", "dg1", "dbo", "dc", "dpos", "loss")
+    snap = lambda: {k: L.act[k].clone() for k in names} | {f"{r}.{k}": L.sh[r][k].clone() for r in (0, 1)
+                                                          for k in ("dWqkv", "dWo", "dA", "dB", "dE")}
+    L.step()                                   # warm-up outside the capture (first-use function attributes)
+    torch.cuda.synchronize()
+    eager = snap()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            L.step()
+    torch.cuda.current_stream().wait_stream(side)
+    for it in range(3):
+        for v in list(L.act.values()):
+            if v.dtype == L.dt:
+                v.fill_(float("nan"))           # poison everything the step writes
+        graph.replay()
+        torch.cuda.synchronize()
+        got = snap()
+        for k, v in eager.items():
+            assert torch.equal(v.view(torch.uint8), got[k].view(torch.uint8)), (it, k)
+        L.step()                                # eager work between replays
+        torch.cuda.synchronize()
+    # new token ids in place: the replay follows the data
+    L.rep["ids"].copy_(torch.randint(0, cfg.V, (cfg.T,), device=DEV, dtype=torch.int32))
+    L.step()
+    torch.cuda.synchronize()
+    eager2 = snap()
+    graph.replay()
+    torch.cuda.synchronize()
+    got = snap()
+    for k, v in eager2.items():
+        assert torch.equal(v.view(torch.uint8), got[k].view(torch.uint8)), ("new ids", k)
+    assert not torch.equal(eager["loss"], eager2["loss"])
