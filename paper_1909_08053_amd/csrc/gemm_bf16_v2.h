@@ -41,6 +41,22 @@ constexpr int V2_CUS = 256;
 // LDS bank-conflict counter: an earlier swizzle that only spread the rows over 128 bytes showed 50 % conflict cycles).
 __device__ __forceinline__ int v2_mn_swizzle(int k) { return (k & 3) << 2; }
 
+// LDS position (16-byte unit inside the k-row) of logical row-chunk u of k-row k, and its inverse, for a [k][ROWS]
+// tile.  256 rows: the XOR above.  192 rows: a k-row is 384 bytes = 24 units and starts at bank 0 or 32 alternately
+// (384 = 256 + 128), so the four k-rows of a pass would pair up on the same 64-byte slots; rotating the rows with
+// bit 1 of k set by four units sends the four 64-byte windows to the four different slots of the 256-byte bank row
+// (slot = (6 k + position / 4) mod 4 -> 0, 2, 1, 3), wrap-around included.
+template <int ROWS> __device__ __forceinline__ int v2_mn_pos(int u, int k) {
+  if (ROWS == V2_B) return u ^ v2_mn_swizzle(k);
+  const int t = u + (((k >> 1) & 1) << 2);
+  return t >= ROWS / 8 ? t - ROWS / 8 : t;
+}
+template <int ROWS> __device__ __forceinline__ int v2_mn_chunk(int pos, int k) {
+  if (ROWS == V2_B) return pos ^ v2_mn_swizzle(k);
+  const int t = pos - (((k >> 1) & 1) << 2);
+  return t < 0 ? t + ROWS / 8 : t;
+}
+
 // Bank swizzle of a k-contiguous operand's ring: rows of 128 bytes (two consecutive k-slices side by side, eight
 // 16-byte units), unit index XORed with this value; 16 consecutive rows reading the same logical unit then hit 16
 // different bank groups.
@@ -52,9 +68,13 @@ __device__ __forceinline__ int v2_kc_swizzle(int row) { return (((row >> 1) & 1)
 //    slice by slice, costs twice the cache-line requests and was measured 40 % slower on the copy side).  A pair
 //    takes 2 QPW copies per wave and is fetched once every two slices.
 //  * operand contiguous along m / n (MN): a slice is [32 k][256 rows] = 512 bytes per k, QPW copies per slice.
-template <bool KC, int NP_>
+template <bool KC, int NP_, int ROWS = V2_B>
 struct V2Src {
   static constexpr int NP = NP_;       // KC: 1-KB copies per wave and PAIR (rows / (8 waves)); MN: per wave and slice
+  // MN: a slice is ROWS / 16 one-KB copies; where that is no multiple of the wave count (192 rows: 12 copies, 8
+  // waves x 2) the surplus copies repeat the last one (same source, same destination: harmless, keeps the per-wave
+  // copy count -- and with it the vmcnt bookkeeping -- uniform)
+  static constexpr int LAST = KC ? (1 << 20) : ROWS / 16 - 1;
   const bf16* p[NP];
   size_t step;     // elements to advance per pair (KC) / per slice (MN)
   __device__ __forceinline__ void init(const bf16* P, int ld, int row0, int nrows, int k_begin, int wave, int lane) {
@@ -70,8 +90,9 @@ struct V2Src {
       // unit u of k-row holds row-chunk u ^ v2_mn_swizzle(k)
 #pragma unroll
       for (int q = 0; q < NP; ++q) {
-        const int k = 2 * (wave * NP + q) + (lane >> 5);
-        const int u = (lane & 31) ^ v2_mn_swizzle(k);
+        const int g = 64 * min(wave * NP + q, LAST) + lane;      // linear 16-byte unit of the slice buffer
+        const int k = g / (ROWS / 8);
+        const int u = v2_mn_chunk<ROWS>(g % (ROWS / 8), k);
         p[q] = P + (size_t)(k_begin + k) * ld + min(row0 + u * 8, nrows - 8);
       }
       step = (size_t)V2_BK * ld;
@@ -80,7 +101,7 @@ struct V2Src {
   // dst: LDS byte address of the pair's (KC) / slice's (MN) buffer; idx: pair / slice index relative to k_begin;
   // wave_u: wave index as a uniform (SGPR) value
   __device__ __forceinline__ void issue_one(uint32_t dst, int wave_u, int idx, int q) const {
-    dma16(p[q] + (size_t)idx * step, dst + (wave_u * NP + q) * 1024);
+    dma16(p[q] + (size_t)idx * step, dst + min(wave_u * NP + q, LAST) * 1024);
   }
   __device__ __forceinline__ void issue(uint32_t dst, int wave_u, int idx) const {
 #pragma unroll
@@ -90,8 +111,9 @@ struct V2Src {
 
 // Operand registers (8 consecutive k of one row/column per lane) for the 32-row MFMA tile starting at row `r0`,
 // k-step ks (0 / 1) of the slice in ring stage `stage` of the operand ring at `ring`.
-template <bool KC, int OPB = V2_OP_BYTES>     // OPB: bytes of one k-slice of the operand (rows x 32 k)
+template <bool KC, int ROWS = V2_B>           // ROWS: rows of the operand's tile
 __device__ __forceinline__ bf16x8 v2_frag(const unsigned char* ring, int stage, int r0, int ks, int lane) {
+  constexpr int OPB = ROWS * V2_BK * 2;       // bytes of one k-slice of the operand
   const int l32 = lane & 31, lh = lane >> 5;
   if (KC) {
     const int row = r0 + l32;
@@ -99,15 +121,14 @@ __device__ __forceinline__ bf16x8 v2_frag(const unsigned char* ring, int stage, 
     return *reinterpret_cast<const bf16x8*>(ring + (stage >> 1) * (2 * OPB) + row * 128 +
                                             ((u ^ v2_kc_swizzle(row)) << 4));
   } else {
-    static_assert(KC || OPB == V2_OP_BYTES, "the [k][row] layout and its swizzle are for 256-row operands");
-    const unsigned char* op_base = ring + stage * V2_OP_BYTES;
+    const unsigned char* op_base = ring + stage * OPB;
     const int g = lane >> 4, i16 = lane & 15;
     const int u = (r0 >> 3) + 2 * (g & 1) + ((i16 & 3) >> 1);
     v4s_t h[2];
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
       const int k = ks * 16 + 8 * (g >> 1) + 4 * r + (i16 >> 2);
-      h[r] = lds_read_tr16(op_base + k * 512 + ((u ^ v2_mn_swizzle(k)) * 16) + (i16 & 1) * 8);
+      h[r] = lds_read_tr16(op_base + k * (ROWS * 2) + (v2_mn_pos<ROWS>(u, k) * 16) + (i16 & 1) * 8);
     }
     const v8s_t v = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
@@ -120,16 +141,18 @@ struct V2Plan {
   double cost;                                            // estimated kernel time in microseconds (host side only)
 };
 
-// Cost-model constants (microseconds, measured on MI355X): fixed cost of a tile (fill + epilogue) and cost of one
-// 32-deep k-slice, for the 256 x 256 tile and for the 256 x 192 tile (3/4 of the MFMA work per slice, but relatively
-// more LDS and copy traffic per MFMA).
-inline double v2_tile_fixed(int bn) { return bn == V2_B ? 5.3 : 4.6; }
-inline double v2_slice_cost(int bn) { return bn == V2_B ? 0.78 : 0.63; }
+// Cost-model constants (microseconds, fitted to measurements on MI355X): fixed cost of a tile (fill + epilogue) and
+// cost of one 32-deep k-slice, for the 256 x 256 tile and for the 256 x 192 tile.  The narrow tile does 3/4 of the
+// MFMA work per slice in 0.8 of the time (0.88 when its B operand is the [k][n] layout: a third more copy traffic
+// for the padded 12-copy slices) but was measured with a larger fixed part, so it wins where it saves a round or
+// fills one, not on short-k multi-round shapes.
+inline double v2_tile_fixed(int bn) { return bn == V2_B ? 5.3 : 9.0; }
+inline double v2_slice_cost(int bn, bool b_mn) { return bn == V2_B ? 0.78 : (b_mn ? 0.69 : 0.64); }
 
 // Decide whether, and how far, to split the last partial round along k.  Cost model in microseconds, measured on
 // MI355X with in-kernel timestamps: a tile costs about 5.3 (fill + epilogue) + 0.78 per 32-deep k-slice; the pieces
 // write fp32 partial tiles and the fix-up kernel (about 6 for launch + drain) reads them back, both at ~5 TB/s.
-inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B) {
+inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B, bool b_mn = false) {
   V2Plan p;
   p.bn = bn;
   p.tiles_m = (M + V2_B - 1) / V2_B;
@@ -137,7 +160,7 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B) {
   const int tiles = p.tiles_m * p.tiles_n;
   const int rem = tiles % V2_CUS;
   const int nk = K / V2_BK;                           // even: K is a multiple of 64
-  const double fixed = v2_tile_fixed(bn), per_slice = v2_slice_cost(bn);
+  const double fixed = v2_tile_fixed(bn), per_slice = v2_slice_cost(bn, b_mn);
   int split = 1;
   double tail = rem ? fixed + per_slice * nk : 0.0;   // unsplit tail round
   if (allow_split && rem != 0 && rem * 2 <= V2_CUS) {
@@ -165,12 +188,12 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B) {
 template <bool A_KC, bool B_KC, int EPI, int NW, int BN = V2_B>
 __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Plan& plan, float* splitk_ws, int pid,
                                                   unsigned char* lds_raw) {
-  static_assert(BN == V2_B || (BN == 192 && NW == 8 && B_KC), "narrow tile: 8 waves, k-contiguous B operand");
+  static_assert(BN == V2_B || (BN == 192 && NW == 8), "narrow tile: 8 waves");
   constexpr int WAVES_M = BN == V2_B ? 2 : 4, WAVES_N = NW / WAVES_M;
   constexpr int WM = V2_B / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   constexpr int OPB_B = BN * V2_BK * 2;                        // bytes of one k-slice of the B operand
   // 1-KB copies per wave: per pair of slices for a k-contiguous operand, per slice otherwise
-  constexpr int NPA = A_KC ? V2_B / (8 * NW) : 16 / NW, NPB = B_KC ? BN / (8 * NW) : 16 / NW;
+  constexpr int NPA = A_KC ? V2_B / (8 * NW) : 16 / NW, NPB = B_KC ? BN / (8 * NW) : (BN / 16 + NW - 1) / NW;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
 
@@ -194,7 +217,7 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
   const int nk = kt_end - kt_begin;                  // even, >= 2
 
   V2Src<A_KC, NPA> sa;
-  V2Src<B_KC, NPB> sb;
+  V2Src<B_KC, NPB, BN> sb;
   sa.init((const bf16*)a.A, a.lda, m0, a.M, kt_begin * V2_BK, wave, lane);
   sb.init((const bf16*)a.B, a.ldb, n0, a.N, kt_begin * V2_BK, wave, lane);
 
@@ -249,7 +272,7 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
 #pragma unroll
   for (int j = 0; j < TM; ++j) fa0[j] = v2_frag<A_KC>(ringA, 0, wm0 + j * 32, 0, lane);
 #pragma unroll
-  for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC, OPB_B>(ringB, 0, wn0 + i * 32, 0, lane);
+  for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC, BN>(ringB, 0, wn0 + i * 32, 0, lane);
 
   // one 32-deep slice; PAR = parity of kt (compile time: it fixes the ring stage bits and the copy schedule)
   auto slice = [&](auto par_c, int kt) {
@@ -267,7 +290,7 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
         const int q = idx - 1;
         __builtin_amdgcn_sched_barrier(0);
         if (q < TM) fa1[q] = v2_frag<A_KC>(ringA, stage, wm0 + q * 32, 1, lane);
-        else fb1[q - TM] = v2_frag<B_KC, OPB_B>(ringB, stage, wn0 + (q - TM) * 32, 1, lane);
+        else fb1[q - TM] = v2_frag<B_KC, BN>(ringB, stage, wn0 + (q - TM) * 32, 1, lane);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -294,7 +317,7 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
       if (idx < TM + TN) {
         const int q = idx;
         if (q < TM) fa0[q] = v2_frag<A_KC>(ringA, nstage, wm0 + q * 32, 0, lane);
-        else fb0[q - TM] = v2_frag<B_KC, OPB_B>(ringB, nstage, wn0 + (q - TM) * 32, 0, lane);
+        else fb0[q - TM] = v2_frag<B_KC, BN>(ringB, nstage, wn0 + (q - TM) * 32, 0, lane);
       }
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
@@ -494,7 +517,7 @@ hipError_t launch_gemm_bf16_v2_nw(const GemmArgs& a, float* splitk_ws, hipStream
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const V2Plan plan = v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, BN);
+  const V2Plan plan = v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, BN, !B_KC);
   const int grid = plan.full_tiles + plan.tail_tiles * plan.split;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), kLds, st, a, plan, splitk_ws);
   hipError_t e = hipGetLastError();
@@ -541,13 +564,15 @@ int gemm_v2_forced_bn();                    // MLM_GEMM_BN=192|256 forces a tile
 template <bool A_KC, bool B_KC, int EPI>
 hipError_t launch_gemm_bf16_v2(const GemmArgs& a, float* splitk_ws, hipStream_t st) {
   if (gemm_v2_waves(A_KC, B_KC) == 8) {
-    if (A_KC && B_KC) {
-      // input-gradient layout: both tile widths exist; take the one the cost model prices lower for this shape
+    // both tile widths exist for the input-gradient layout and for the plain / bias + GeLU forward GEMMs: take the
+    // one the cost model prices lower for this shape
+    constexpr bool kHasNarrow = A_KC && (B_KC || EPI == EPI_STORE || EPI == EPI_BIAS_GELU);
+    if (kHasNarrow) {
       const int forced = gemm_v2_forced_bn();
       const bool narrow = forced ? forced == 192
-                                 : v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, 192).cost <
-                                       v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, V2_B).cost;
-      if (narrow) return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 8, (A_KC && B_KC) ? 192 : V2_B>(a, splitk_ws, st);
+                                 : v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, 192, !B_KC).cost <
+                                       v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, V2_B, !B_KC).cost;
+      if (narrow) return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 8, kHasNarrow ? 192 : V2_B>(a, splitk_ws, st);
     }
     return launch_gemm_bf16_v2_nw<A_KC, B_KC, EPI, 8>(a, splitk_ws, st);
   }
