@@ -431,3 +431,31 @@ def test_step_is_capturable_in_a_hip_graph_and_replays_bit_identically():
     for k, v in eager2.items():
         assert torch.equal(v.view(torch.uint8), got[k].view(torch.uint8)), ("new ids", k)
     assert not torch.equal(eager["loss"], eager2["loss"])
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_degenerate_key_length_one(dtype):
+    """A sequence whose only valid key is key 0 (key_len = 1): every query's probability row is exactly (1, 0, 0, ...),
+    so its context equals V[0] bit for bit, and the whole layer still matches the oracle."""
+    cfg = synth.small_config(dtype=dtype, b=2, s=136, H=128, h=2, F=512, V=256, p=1, causal=False, masked_lm=True)
+    inp = synth.make_inputs(cfg, nonzero_bias=True, random_ln=True)
+    inp["key_len"] = np.array([1, cfg.s], np.int32)
+    inp["w"] = np.zeros((cfg.b, cfg.s), np.float32)
+    inp["w"][0, 0] = 1.0
+    inp["w"][1, ::7] = 1.0
+    ref = O.sharded_reference(inp, spec_of(cfg), 1)
+    L = LayerShards(cfg, [0], DEV)
+    L.load_host_inputs(inp)
+    L.step()
+    out = L.fetch()
+    sh = out["shards"][0]
+    ctx = sh["ctx"].reshape(cfg.b, cfg.s, cfg.H)
+    v0 = sh["qkv"].reshape(cfg.b, cfg.s, 3 * cfg.H)[0, 0, 2 * cfg.H:]
+    assert np.array_equal(ctx[0], np.broadcast_to(v0, (cfg.s, cfg.H)))
+    tol = TOL[dtype]
+    errs = []
+    assert abs(out["loss"] - ref["loss"]) <= tol * abs(ref["loss"])
+    for k in ("X2", "dX", "dX1", "dg1", "dbo"):
+        check(k, out[k], ref[k], tol, errs)
+    for k in ("lse", "dWqkv", "dbqkv", "dWo", "dE"):
+        check(k, sh[k], ref["shards"][0][k], tol, errs)
