@@ -607,36 +607,46 @@ __global__ __launch_bounds__(1024) void ce_merge_kernel(int T, int n_shards, con
                                                         float* __restrict__ loss_out) {
   __shared__ float red_l[16], red_w[16];
   float accl = 0.f, accw = 0.f;
-  // a thread's tokens are independent: four at a time, so that their (dependent-free) loads are in flight together
-  // instead of one round trip to memory per token
-  constexpr int U = 4;
-  for (int t0 = threadIdx.x; t0 < T; t0 += 1024 * U) {
-    float M[U], S[U], tt[U], w[U];
+  // A thread takes four CONSECUTIVE tokens per step: with 16-byte loads (T a multiple of 4) a step is a handful of
+  // independent loads in flight together instead of one round trip to memory per token and shard.
+  const bool vec = (T & 3) == 0;
+  auto load4 = [&](const float* base, int t0, float (&v)[4]) {
+    if (vec) {
+      const float4 x = *reinterpret_cast<const float4*>(base + t0);
+      v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    } else {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int t = min(t0 + 1024 * u, T - 1);
-      M[u] = -INFINITY;
-      for (int r = 0; r < n_shards; ++r) M[u] = fmaxf(M[u], m[(size_t)r * T + t]);
-      w[u] = loss_w ? loss_w[t] : 1.0f;
+      for (int u = 0; u < 4; ++u) v[u] = base[min(t0 + u, T - 1)];
     }
+  };
+  for (int t0 = 4 * threadIdx.x; t0 < T; t0 += 4 * 1024) {
+    float M[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, S[4] = {0.f, 0.f, 0.f, 0.f}, tt[4] = {0.f, 0.f, 0.f, 0.f};
+    float w[4] = {1.f, 1.f, 1.f, 1.f};
+    if (loss_w) load4(loss_w, t0, w);
+    for (int r = 0; r < n_shards; ++r) {
+      float mv[4];
+      load4(m + (size_t)r * T, t0, mv);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int t = min(t0 + 1024 * u, T - 1);
-      S[u] = 0.f;
-      tt[u] = 0.f;
-      for (int r = 0; r < n_shards; ++r) {
-        S[u] += s[(size_t)r * T + t] * expf(m[(size_t)r * T + t] - M[u]);
-        tt[u] += tl[(size_t)r * T + t];
+      for (int u = 0; u < 4; ++u) M[u] = fmaxf(M[u], mv[u]);
+    }
+    for (int r = 0; r < n_shards; ++r) {             // second pass over the (cached) maxima
+      float mv[4], sv[4], tv[4];
+      load4(m + (size_t)r * T, t0, mv);
+      load4(s + (size_t)r * T, t0, sv);
+      load4(tl + (size_t)r * T, t0, tv);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        S[u] += sv[u] * expf(mv[u] - M[u]);
+        tt[u] += tv[u];
       }
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int t = t0 + 1024 * u;
-      if (t < T) {
+    for (int u = 0; u < 4; ++u) {
+      if (t0 + u < T) {
         const float c = logf(S[u]) + M[u] - tt[u];
-        ce[t] = c;
-        Mo[t] = M[u];
-        So[t] = S[u];
+        ce[t0 + u] = c;
+        Mo[t0 + u] = M[u];
+        So[t0 + u] = S[u];
         accl += w[u] * c;
         accw += w[u];
       }
