@@ -484,7 +484,10 @@ class LayerShards:
     # ------------------------------------------------------------------ results (host copies, fp64)
     def fetch(self) -> Dict[str, object]:
         torch.cuda.synchronize(self.dev)
-        cp = lambda t: t.detach().float().cpu().numpy().astype(np.float64)
+        def cp(t):
+            # buffers a mode never writes are copied too; their uninitialised bit patterns may be signalling NaNs
+            with np.errstate(invalid="ignore"):
+                return t.detach().float().cpu().numpy().astype(np.float64)
         skip = ()
         if self.fused and not self.store_combined:      # never written in this mode
             skip = ("dU2", "dU") + (("dHf",) if self.cfg.final_ln else ())
