@@ -166,14 +166,16 @@ hipError_t launch_combine_layernorm_fwd(int dtype, int T, int H, float eps, cons
 }
 
 // ------------------------------------------------------------------------------ layer norm backward
-// Block = one wave per 64 vectors of a row (6 waves for 3072 bf16 columns), kLnBwdRowsPerBlock rows in batches of
-// kLnBwdBatch.  A lane owns ONE 16-byte vector of columns in every row, so its dgamma / dbeta (/ dx column-sum)
-// partials are a handful of registers and several waves fit on a SIMD (a wave-per-row layout needs the partials of
-// the whole row per lane: ~150 registers, one wave per SIMD, and ran at half the HBM rate).  The row statistics
-// s1 = mean(dy gamma), s2 = mean(dy gamma xhat) need the whole row: every wave reduces its slab, the per-wave
-// partials meet in LDS and are added in wave order (deterministic); one barrier per batch (the exchange buffer
-// alternates).  The next batch is prefetched while the current one is worked on.  The block's column partials go
-// to the workspace and reduce_cols_kernel sums them over the blocks.
+// Block = one wave per 64 vectors of a row (6 waves for 3072 bf16 columns); the grid has one block per
+// kLnBwdRowsPerBlock rows and the rows are dealt to the blocks in batches of kLnBwdBatch, round-robin.  A lane owns
+// ONE 16-byte vector of columns in every row, so its dgamma / dbeta (/ dx column-sum) partials are a handful of
+// registers and several waves fit on a SIMD (a wave-per-row layout needs the partials of the whole row per lane:
+// ~150 registers, one wave per SIMD, and ran at half the HBM rate).  The row statistics s1 = mean(dy gamma),
+// s2 = mean(dy gamma xhat) need the whole row: every wave reduces its slab, the per-wave partials meet in LDS and are
+// added in wave order (deterministic); one barrier per batch (the exchange buffer alternates).  Everything that needs
+// no row statistic (dgamma, dbeta) is accumulated in the pass before the barrier; the pass after it is two fused
+// multiply-adds per element.  The next batch (and its rows' mean / rstd) is prefetched while the current one is
+// worked on.  The block's column partials go to the workspace and reduce_cols_kernel sums them over the blocks.
 //
 // FUSED: dy is formed on the fly as the sum of n partial tensors (stored to dy_out if that is not NULL).
 // SUM: the column sums of dx (the bias gradient of the layer that produced this layer norm's input) are accumulated
@@ -189,13 +191,16 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
                                                      float* __restrict__ ws, PartialPtrs ptrs, int n, T* dy_out,
                                                      DropArgs drop, T* dz_out) {
   constexpr int VN = Vec16<T>::N, RB = kLnBwdBatch, NP = SUM ? 3 : 2;
-  __shared__ float red[2][RB][2][8];
+  __shared__ __attribute__((aligned(16))) float red[2][RB][2][8];
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  const int wave = threadIdx.x >> 6;
   const int idx = threadIdx.x;                      // this lane's vector of every row
   const bool active = idx < H / VN;
   const size_t col0 = (size_t)idx * VN;
   const float invH = 1.0f / (float)H;
+  // slots of waves that do not exist stay zero, so the exchange can always add all eight in order
+  for (int i = threadIdx.x; i < 2 * RB * 2 * 8; i += blockDim.x) (&red[0][0][0][0])[i] = 0.f;
+  __syncthreads();
   float gam[VN], dg[VN], db[VN], dsum[VN];
   {
     Vec16<T> g;
@@ -206,13 +211,18 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
       dg[e] = 0.f; db[e] = 0.f; dsum[e] = 0.f;
     }
   }
-  const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
-  const int row_end = min(rows, row0 + kLnBwdRowsPerBlock);
+  // batches are dealt round-robin over the blocks: at any moment the grid reads ONE contiguous window of each tensor
+  // (a block that owned a contiguous chunk of rows would make all blocks walk memory at the same offset of a fixed
+  // stride, which concentrates the traffic on a part of the memory channels)
+  const int nbatch = (rows + RB - 1) / RB, row_end = rows;
   Vec16<T> vdy[RB], vx[RB], vres[RB], ndy[RB], nx[RB], nres[RB];
+  float mu[RB], rs[RB], nmu[RB], nrs[RB];
   auto load_batch = [&](int r0) {
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
       const int r = r0 + j;
+      nmu[j] = mean[min(r, row_end - 1)];
+      nrs[j] = rstd[min(r, row_end - 1)];
       if (r < row_end && active) {
         const size_t off = (size_t)r * H + col0;
         if (FUSED) {
@@ -240,27 +250,30 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
       }
     }
   };
-  load_batch(row0);
+  if ((int)blockIdx.x < nbatch) load_batch(blockIdx.x * RB);
   int it = 0;
-  for (int r0 = row0; r0 < row_end; r0 += RB, ++it) {
+  for (int bt = blockIdx.x; bt < nbatch; bt += gridDim.x, ++it) {
+    const int r0 = bt * RB;
 #pragma unroll
-    for (int j = 0; j < RB; ++j) { vdy[j] = ndy[j]; vx[j] = nx[j]; vres[j] = nres[j]; }
-    if (r0 + RB < row_end) load_batch(r0 + RB);
-    float mu[RB], rs[RB], ps1[RB], ps2[RB];
+    for (int j = 0; j < RB; ++j) { vdy[j] = ndy[j]; vx[j] = nx[j]; vres[j] = nres[j]; mu[j] = nmu[j]; rs[j] = nrs[j]; }
+    if (bt + (int)gridDim.x < nbatch) load_batch((bt + gridDim.x) * RB);
+    // first pass over the batch: everything that needs no row statistic -- the partial sums of s1 and s2 and the
+    // column sums dgamma += dy xhat, dbeta += dy
+    float ps1[RB], ps2[RB];
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
-      const int r = min(r0 + j, row_end - 1);
-      mu[j] = mean[r];
-      rs[j] = rstd[r];
       ps1[j] = 0.f;
       ps2[j] = 0.f;
       if (r0 + j < row_end && active) {
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
           const float xh = (vx[j].get(e) - mu[j]) * rs[j];
-          const float g = vdy[j].get(e) * gam[e];
+          const float d = vdy[j].get(e);
+          const float g = d * gam[e];
           ps1[j] += g;
           ps2[j] = fmaf(g, xh, ps2[j]);
+          dg[e] = fmaf(d, xh, dg[e]);
+          db[e] += d;
         }
       }
     }
@@ -277,22 +290,21 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
       for (int j = 0; j < RB; ++j) { red[it & 1][j][0][wave] = ps1[j]; red[it & 1][j][1][wave] = ps2[j]; }
     }
     __syncthreads();
+    // second pass: dx = rstd (dy gamma - s1 - xhat s2) written as (rstd dy gamma - rstd s1) - xhat (rstd s2)
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
       if (r0 + j >= row_end) break;                  // block-uniform
-      float s1 = 0.f, s2 = 0.f;
-      for (int w = 0; w < nwaves; ++w) { s1 += red[it & 1][j][0][w]; s2 += red[it & 1][j][1][w]; }
-      s1 *= invH;
-      s2 *= invH;
+      const float4* rr = reinterpret_cast<const float4*>(&red[it & 1][j][0][0]);
+      const float4 a0 = rr[0], a1 = rr[1], b0 = rr[2], b1 = rr[3];
+      const float s1 = (((((((a0.x + a0.y) + a0.z) + a0.w) + a1.x) + a1.y) + a1.z) + a1.w) * invH;
+      const float s2 = (((((((b0.x + b0.y) + b0.z) + b0.w) + b1.x) + b1.y) + b1.z) + b1.w) * invH;
+      const float rs1 = rs[j] * s1, rs2 = rs[j] * s2;
       if (active) {
         Vec16<T> o;
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
           const float xh = (vx[j].get(e) - mu[j]) * rs[j];
-          const float d = vdy[j].get(e);
-          dg[e] = fmaf(d, xh, dg[e]);
-          db[e] += d;
-          float v = rs[j] * (d * gam[e] - s1 - xh * s2);
+          float v = fmaf(-xh, rs2, fmaf(vdy[j].get(e) * gam[e], rs[j], -rs1));
           if (residual) v += vres[j].get(e);
           o.set(e, v);
           if (SUM && !DZ) dsum[e] += o.get(e);   // the stored (rounded) value, as a separate column sum would read it
@@ -604,12 +616,11 @@ __global__ __launch_bounds__(1024) void ce_merge_kernel(int T, int n_shards, con
                                                         const float* __restrict__ s, const float* __restrict__ tl,
                                                         const float* __restrict__ loss_w, float* __restrict__ ce,
                                                         float* __restrict__ Mo, float* __restrict__ So,
-                                                        float* __restrict__ loss_out) {
+                                                        float* __restrict__ loss_out, bool vec) {
   __shared__ float red_l[16], red_w[16];
   float accl = 0.f, accw = 0.f;
-  // A thread takes four CONSECUTIVE tokens per step: with 16-byte loads (T a multiple of 4) a step is a handful of
+  // A thread takes four CONSECUTIVE tokens per step: with 16-byte loads (T a multiple of 4, 16-byte aligned buffers) a step is a handful of
   // independent loads in flight together instead of one round trip to memory per token and shard.
-  const bool vec = (T & 3) == 0;
   auto load4 = [&](const float* base, int t0, float (&v)[4]) {
     if (vec) {
       const float4 x = *reinterpret_cast<const float4*>(base + t0);
@@ -619,36 +630,72 @@ __global__ __launch_bounds__(1024) void ce_merge_kernel(int T, int n_shards, con
       for (int u = 0; u < 4; ++u) v[u] = base[min(t0 + u, T - 1)];
     }
   };
-  for (int t0 = 4 * threadIdx.x; t0 < T; t0 += 4 * 1024) {
-    float M[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, S[4] = {0.f, 0.f, 0.f, 0.f}, tt[4] = {0.f, 0.f, 0.f, 0.f};
-    float w[4] = {1.f, 1.f, 1.f, 1.f};
-    if (loss_w) load4(loss_w, t0, w);
-    for (int r = 0; r < n_shards; ++r) {
-      float mv[4];
-      load4(m + (size_t)r * T, t0, mv);
+  // ... and two such groups per pass over the block (8192 tokens per pass), all of their loads issued before the
+  // first use when there is one shard (then the merge is the identity and needs no second pass over the maxima)
+  constexpr int G = 2;
+  for (int base = 0; base < T; base += G * 4096) {
+    float M[G][4], S[G][4], tt[G][4], w[G][4];
+    int t0[G];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) M[u] = fmaxf(M[u], mv[u]);
+    for (int g = 0; g < G; ++g) {
+      t0[g] = base + g * 4096 + 4 * threadIdx.x;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { M[g][u] = -INFINITY; S[g][u] = 0.f; tt[g][u] = 0.f; w[g][u] = 1.f; }
     }
-    for (int r = 0; r < n_shards; ++r) {             // second pass over the (cached) maxima
-      float mv[4], sv[4], tv[4];
-      load4(m + (size_t)r * T, t0, mv);
-      load4(s + (size_t)r * T, t0, sv);
-      load4(tl + (size_t)r * T, t0, tv);
+    if (n_shards == 1) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        S[u] += sv[u] * expf(mv[u] - M[u]);
-        tt[u] += tv[u];
+      for (int g = 0; g < G; ++g)
+        if (t0[g] < T) {
+          if (loss_w) load4(loss_w, t0[g], w[g]);
+          load4(m, t0[g], M[g]);
+          load4(s, t0[g], S[g]);
+          load4(tl, t0[g], tt[g]);
+        }
+    } else {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (t0[g] >= T) continue;
+        if (loss_w) load4(loss_w, t0[g], w[g]);
+        for (int r = 0; r < n_shards; ++r) {
+          float mv[4];
+          load4(m + (size_t)r * T, t0[g], mv);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) M[g][u] = fmaxf(M[g][u], mv[u]);
+        }
+        for (int r = 0; r < n_shards; ++r) {           // second pass over the (cached) maxima
+          float mv[4], sv[4], tv[4];
+          load4(m + (size_t)r * T, t0[g], mv);
+          load4(s + (size_t)r * T, t0[g], sv);
+          load4(tl + (size_t)r * T, t0[g], tv);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            S[g][u] += sv[u] * expf(mv[u] - M[g][u]);
+            tt[g][u] += tv[u];
+          }
+        }
       }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (t0 + u < T) {
-        const float c = logf(S[u]) + M[u] - tt[u];
-        ce[t0 + u] = c;
-        Mo[t0 + u] = M[u];
-        So[t0 + u] = S[u];
-        accl += w[u] * c;
-        accw += w[u];
+    for (int g = 0; g < G; ++g) {
+      float c[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        c[u] = logf(S[g][u]) + M[g][u] - tt[g][u];
+        if (t0[g] + u < T) {
+          accl += w[g][u] * c[u];
+          accw += w[g][u];
+        }
+      }
+      if (vec) {                                       // T % 4 == 0: a group is inside [0, T) or outside
+        if (t0[g] < T) {
+          *reinterpret_cast<float4*>(ce + t0[g]) = make_float4(c[0], c[1], c[2], c[3]);
+          *reinterpret_cast<float4*>(Mo + t0[g]) = make_float4(M[g][0], M[g][1], M[g][2], M[g][3]);
+          *reinterpret_cast<float4*>(So + t0[g]) = make_float4(S[g][0], S[g][1], S[g][2], S[g][3]);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (t0[g] + u < T) { ce[t0[g] + u] = c[u]; Mo[t0[g] + u] = M[g][u]; So[t0[g] + u] = S[g][u]; }
       }
     }
   }
@@ -666,7 +713,9 @@ __global__ __launch_bounds__(1024) void ce_merge_kernel(int T, int n_shards, con
 
 hipError_t launch_ce_merge(int T, int n_shards, const float* m, const float* s, const float* t, const float* loss_w,
                            float* ce, float* M, float* S, float* loss_out, hipStream_t st) {
-  hipLaunchKernelGGL(ce_merge_kernel, dim3(1), dim3(1024), 0, st, T, n_shards, m, s, t, loss_w, ce, M, S, loss_out);
+  auto a16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  const bool vec = (T & 3) == 0 && a16(m) && a16(s) && a16(t) && a16(loss_w) && a16(ce) && a16(M) && a16(S);
+  hipLaunchKernelGGL(ce_merge_kernel, dim3(1), dim3(1024), 0, st, T, n_shards, m, s, t, loss_w, ce, M, S, loss_out, vec);
   return hipGetLastError();
 }
 
