@@ -278,8 +278,8 @@ MLM_API int mlm_adamw_step_multi(int32_t dtype, int32_t n_tensors, const int64_t
                          const float* weight_decays, const float* total_sqnorm, float max_norm, float lr,
                          float beta1, float beta2, float eps, int32_t step, void* stream);
 
-/* ---- dropout with the two model-parallel random streams (Appendix B.2; Section 4.2: "a dropout of
- *      0.1 is used") and the variants of the calls above that apply it ---------------------- */
+/* ---- dropout with the two model-parallel random streams (Appendix B.2; the rate, p = 0.1 everywhere,
+ *      is in Section 4.2) and the variants of the calls above that apply it ------------------- */
 
 /* One dropout site.  The paper asks for two random streams: one seeded identically on every
  * model-parallel worker for the dropouts OUTSIDE the model-parallel regions (embedding output, the two
@@ -303,8 +303,8 @@ enum { MLM_STREAM_REPLICATED = 0, MLM_STREAM_MODEL_PARALLEL = 1 };
  * one and from every other worker's.  seed: host pointer.  MLM_E_SHAPE for an unknown stream or r < 0. */
 MLM_API int mlm_rng_stream_seed(uint64_t base_seed, int32_t stream, int32_t r, uint64_t* seed);
 
-/* mlm_combine with dropout on the reduced block output (Section 3: "run dropout and residual connection
- * on these tensors"):  out = residual + dropout(sum_i partials[i] + bias).  bias is [bias_rows, H]
+/* mlm_combine with dropout on the reduced block output (Section 3: dropout and the residual add are
+ * replicated work on the reduced tensor):  out = residual + dropout(sum_i partials[i] + bias).  bias is [bias_rows, H]
  * (row t uses bias row t mod bias_rows; bias_rows = 1 is the ordinary bias vector, bias_rows = s adds a
  * position embedding) or NULL.  drop NULL or p = 0: no dropout.  Element index of the site: t H + column. */
 MLM_API int mlm_combine_dropout(const mlm_dims* dims, const void* const* partials, int32_t n_partials,
@@ -384,8 +384,8 @@ MLM_API int mlm_layer_shard_wgrads(const mlm_dims* dims, const void* u, const vo
                            void* ws, size_t ws_bytes, void* stream);
 
 /* ---- vocabulary-parallel input embedding (Section 3: the input embedding shares its weights with the
- *      output embedding E [H, v] and is split along the vocabulary like it; "an all-reduce (g operator)
- *      is required after the input embedding") ------------------------------------------------------ */
+ *      output embedding E [H, v] and is split along the vocabulary like it; a shard holds only its slice of
+ *      the table, so the shards' lookups are partial results that the operator g sums) ------------------ */
 
 /* Forward of shard r:  partial_r[t, :] = E_r[:, ids[t] - r V_l] if the id lies in the shard's range,
  * else 0.  ids: [T] int32 GLOBAL ids in [0, V); E_r: [H, V_l] (the matrix of mlm_vocab_ce_shard_fwd);
