@@ -32,6 +32,25 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr int ANW = 4;              // waves per workgroup: 32 owned rows each
 constexpr int ANT = ANW * 64;
 
+// Workgroup id -> (block along the sequence, local head, batch).  Workgroups are handed to the eight XCDs round-robin
+// by id and every XCD has its own L2, so the (batch, head) index takes the low three bits of the id: all sequence
+// blocks of one (batch, head) pair -- they stream the same K / V (or Q / dO) rows -- run on ONE XCD and re-read those
+// rows from its L2 (x-fastest ids put the eight blocks of a pair on eight XCDs and every XCD fetched every pair).
+// Within an XCD the ids keep the sequence block as the faster index, so the longest causal blocks still start first.
+// Grid: attn_grid(nx, hl, b) workgroups in x; ids whose pair does not exist (hl b not a multiple of 8) exit at once.
+struct AttnBlock { int xb, hd, bi; bool valid; };
+__device__ __forceinline__ AttnBlock attn_block(int nx, int hl, int b) {
+  const int id = blockIdx.x, r = id >> 3;
+  const int bh = (r / nx) * 8 + (id & 7);
+  AttnBlock o;
+  o.xb = r % nx;
+  o.valid = bh < hl * b;
+  o.hd = bh % hl;
+  o.bi = bh / hl;
+  return o;
+}
+static inline dim3 attn_grid(int nx, int hl, int b) { return dim3(8 * nx * ((hl * b + 7) / 8)); }
+
 __device__ __forceinline__ bf16x8 pack8(const floatx16& v, int off) {
   bf16x8 r;
 #pragma unroll
@@ -127,8 +146,10 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(A
   const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave inside its group: 32 queries
   const int wave_u = wave;
   const int nqb = (a.s + BQ - 1) / BQ;
-  const int qb = nqb - 1 - blockIdx.x;            // longest (causal) blocks first
-  const int hd = blockIdx.y, bi = blockIdx.z;
+  const AttnBlock blk = attn_block(nqb, a.hl, a.b);
+  if (!blk.valid) return;
+  const int qb = nqb - 1 - blk.xb;                // longest (causal) blocks first
+  const int hd = blk.hd, bi = blk.bi;
   const int ld = 3 * a.hl * D;
   const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
   const int klen = a.key_len ? min(a.key_len[bi], a.s) : a.s;
@@ -315,8 +336,10 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
   const int grp = NG == 1 ? 0 : __builtin_amdgcn_readfirstlane(tid >> 8);   // wave group: even / odd tiles
   const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave inside its group (uniform: scalar mask branches)
   const int nqb = (a.s + BQ - 1) / BQ;
-  const int qb = nqb - 1 - blockIdx.x;
-  const int hd = blockIdx.y, bi = blockIdx.z;
+  const AttnBlock blk = attn_block(nqb, a.hl, a.b);
+  if (!blk.valid) return;
+  const int qb = nqb - 1 - blk.xb;
+  const int hd = blk.hd, bi = blk.bi;
   const int ld = 3 * a.hl * D;
   const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
   const int klen = a.key_len ? min(a.key_len[bi], a.s) : a.s;
@@ -489,9 +512,11 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known wave-uniform: mask tests become scalar branches
-  const int kb = blockIdx.x / DS;                  // key block; for causal, block 0 has the most queries: first
-  const int dh0 = (blockIdx.x % DS) * DH;          // first of this workgroup's dK / dV columns
-  const int hd = blockIdx.y, bi = blockIdx.z;
+  const AttnBlock blk = attn_block(((a.s + 32 * ANW - 1) / (32 * ANW)) * DS, a.hl, a.b);
+  if (!blk.valid) return;
+  const int kb = blk.xb / DS;                      // key block; for causal, block 0 has the most queries: first
+  const int dh0 = (blk.xb % DS) * DH;              // first of this workgroup's dK / dV columns
+  const int hd = blk.hd, bi = blk.bi;
   const int ld = 3 * a.hl * D;
   const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
   const int klen = a.key_len ? min(a.key_len[bi], a.s) : a.s;
@@ -639,7 +664,7 @@ static hipError_t launch_fwd_dd(const AttnArgs& a, hipStream_t st) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
+  const dim3 grid = attn_grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
   hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, DROP>), grid, dim3(attn_groups<D>() * ANT), lds, st, a);
   return hipGetLastError();
 }
@@ -651,7 +676,8 @@ static hipError_t launch_fwd_d(const AttnArgs& a, hipStream_t st) {
 
 template <int D, bool DROP>
 static hipError_t launch_bwd_dd(const AttnArgs& a, hipStream_t st) {
-  dim3 grid((a.s + 32 * ANW - 1) / (32 * ANW), a.hl, a.b);
+  const int nblk = (a.s + 32 * ANW - 1) / (32 * ANW);
+  const dim3 grid = attn_grid(nblk, a.hl, a.b);
   const size_t lds_q = (size_t)attn_groups<D>() * group_stages<D>() * 2 * ATile<D>::BYTES;
   hipError_t e;
   if (lds_q > 64 * 1024) {
@@ -669,7 +695,7 @@ static hipError_t launch_bwd_dd(const AttnArgs& a, hipStream_t st) {
                             (int)lds_kv);
     if (e != hipSuccess) return e;
   }
-  dim3 grid_kv(grid.x * dkv_dsplit<D>(), grid.y, grid.z);
+  const dim3 grid_kv = attn_grid(nblk * dkv_dsplit<D>(), a.hl, a.b);
   hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D, DROP>), grid_kv, dim3(ANT), lds_kv, st, a);
   return hipGetLastError();
 }
