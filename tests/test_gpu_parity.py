@@ -459,3 +459,45 @@ def test_degenerate_key_length_one(dtype):
         check(k, out[k], ref[k], tol, errs)
     for k in ("lse", "dWqkv", "dbqkv", "dWo", "dE"):
         check(k, sh[k], ref["shards"][0][k], tol, errs)
+
+
+# ------------------------------------------------------------------ loss merge over shards, called directly
+@pytest.mark.parametrize("T,n_shards,weighted,misalign", [(74, 3, True, 0), (74, 1, False, 0), (8200, 3, True, 0),
+                                                          (8200, 1, False, 0), (16388, 2, True, 0), (1024, 3, True, 1),
+                                                          (4, 1, True, 0), (1, 2, False, 0)])
+def test_loss_merge_over_shards_ragged_multi_pass_and_unaligned(T, n_shards, weighted, misalign):
+    """mlm_vocab_ce_merge on per-shard (max, sum-exp, target-logit) triples built from the definition of the call's
+    inputs, against the plain cross entropy of the full logits: token counts that are not a multiple of 4, that need
+    more than one pass of the single block (> 8192), one shard (identity merge) and several, and buffers that are only
+    4-byte aligned (the kernel must then leave its 16-byte path)."""
+    p, Vl = 3, 8
+    V = p * Vl
+    dims = B.make_dims(1, T, 24, 3, 96, V, p, 0, B.MLM_F32)
+    rng = np.random.default_rng(T + 7 * n_shards)
+    Vn = n_shards * Vl                                     # the merge sees the first n_shards shards only
+    L = (4.0 * rng.standard_normal((T, Vn))).astype(np.float32).astype(np.float64)
+    L[0, :Vl] = -60.0                                      # a shard whose maximum is far below the row's maximum
+    tgt = rng.integers(0, Vn, T)
+    w = (rng.random(T) < 0.3).astype(np.float64) if weighted else np.ones(T)
+    w[0] = 1.0
+    m = np.stack([L[:, r * Vl:(r + 1) * Vl].max(1) for r in range(n_shards)])
+    s = np.stack([np.exp(L[:, r * Vl:(r + 1) * Vl] - m[r][:, None]).sum(1) for r in range(n_shards)])
+    t = np.stack([np.where((tgt >= r * Vl) & (tgt < (r + 1) * Vl), L[np.arange(T), tgt], 0.0) for r in range(n_shards)])
+    loss_r, ce_r, mx_r, se_r = O.cross_entropy_fwd(L, tgt, w)
+
+    def dev(a):                                            # optionally a view that starts 4 bytes into its buffer
+        flat = torch.zeros(a.size + 4, device=DEV, dtype=torch.float32)
+        v = flat[misalign:misalign + a.size]
+        v.copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).reshape(-1))
+        return v
+    md, sd, td = dev(m), dev(s), dev(t)
+    wd = dev(w) if weighted else None
+    ce, M, S = dev(np.zeros(T)), dev(np.zeros(T)), dev(np.zeros(T))
+    loss = torch.zeros(2, device=DEV, dtype=torch.float32)
+    B.mlm_vocab_ce_merge(dims, md, sd, td, n_shards, wd, ce, M, S, loss)
+    errs = []
+    check("merge.ce", _dn(ce), ce_r, 1e-5, errs)
+    check("merge.M", _dn(M), mx_r, 1e-6, errs)
+    check("merge.S", _dn(S), se_r, 1e-5, errs)
+    assert abs(float(loss[0]) - loss_r) <= 1e-5 * abs(loss_r)
+    assert float(loss[1]) == w.sum()                       # the weight count is integer work: exact
