@@ -127,6 +127,9 @@ def main():
     dense_flops, _ = shard_flops(cfg, causal_algorithmic=False)
     value = flops / (ms_per_step * 1e-3) / 1e12
     k_ms = sum(x.elapsed_time(y) for x, y in ce_events) / len(ce_events)
+    # step periods from the events already in the stream (start of the timed call in consecutive steps): spread only
+    periods = sorted(ce_events[i][0].elapsed_time(ce_events[i + 1][0]) for i in range(len(ce_events) - 1))
+    step_ms = ({"median": periods[len(periods) // 2], "min": periods[0], "max": periods[-1]} if periods else None)
     achieved = logits_flops / (k_ms * 1e-3) / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -156,7 +159,7 @@ def main():
                                   f"causal={cfg.causal}, fwd+bwd layer shard + vocab-parallel CE",
                       "model_tflop_per_step": flops / 1e12, "dense_equivalent_tflop_per_step": dense_flops / 1e12,
                       "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS, "loss": loss},
-           "roofline": roofline}
+           "roofline": roofline, "step_ms": step_ms}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
