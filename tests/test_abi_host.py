@@ -174,3 +174,13 @@ def test_validation_of_dropout_embedding_and_row_entry_points():
     assert L.mlm_rows_gather(ref(d), ok, None, 10, 16, ok, None) == -1
     assert L.mlm_rows_scatter(ref(d), ok, ok, -1, ok, None) == -2
     assert L.mlm_rows_scatter(ref(d), odd, ok, 4, ok, None) == -5
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build has no collectives: bench.py must say so and exit non-zero for --gpus > 1 (before touching the GPU)."""
+    import subprocess
+    import sys as _sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([_sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
