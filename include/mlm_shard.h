@@ -171,7 +171,8 @@ MLM_API int mlm_colsum(const mlm_dims* dims, const void* dy, void* dbias, void* 
  * u: [T,H]; Wqkv_r: [H, 3 H_l]; bqkv_r: [3 H_l] or NULL; Wo_r: [H_l, H];
  * key_len: [b] int32 or NULL -- keys j >= key_len[batch] are excluded for every query
  * (BERT-style padding); with causal also j > i is excluded.  Excluded keys get probability
- * exactly 0.  Every query row must keep at least one key (key_len >= 1).
+ * exactly 0.  Every query row must keep at least one key: key_len is device memory the
+ * host cannot validate, so every kernel reads it as max(1, min(key_len[batch], s)).
  * qkv_r, ctx_r, lse_r are saved for the backward call.  ws: MLM_WS_ATTN_FWD bytes. */
 MLM_API int mlm_attn_shard_fwd(const mlm_dims* dims, const void* u, const void* Wqkv_r, const void* bqkv_r,
                        const void* Wo_r, const int32_t* key_len,

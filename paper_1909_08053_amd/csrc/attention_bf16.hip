@@ -152,7 +152,7 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(A
   const int hd = blk.hd, bi = blk.bi;
   const int ld = 3 * a.hl * D;
   const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
-  const int klen = a.key_len ? min(a.key_len[bi], a.s) : a.s;
+  const int klen = attn_key_len(a.key_len, bi, a.s);
   const int q0 = qb * BQ, qw0 = q0 + wave * 32, qi = qw0 + l32;
 
   bf16x8 qf[D / 16];
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
   const int hd = blk.hd, bi = blk.bi;
   const int ld = 3 * a.hl * D;
   const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
-  const int klen = a.key_len ? min(a.key_len[bi], a.s) : a.s;
+  const int klen = attn_key_len(a.key_len, bi, a.s);
   const int q0 = qb * BQ, qw0 = q0 + wave * 32, qi = qw0 + l32;
   const int qc = min(qi, a.s - 1);
 
@@ -519,7 +519,7 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   const int hd = blk.hd, bi = blk.bi;
   const int ld = 3 * a.hl * D;
   const bf16* base = (const bf16*)a.qkv + (size_t)bi * a.s * ld;
-  const int klen = a.key_len ? min(a.key_len[bi], a.s) : a.s;
+  const int klen = attn_key_len(a.key_len, bi, a.s);
   const int kb0 = kb * BKB, kw0 = kb0 + wave * 32, kj = kw0 + l32;
   const int kc = min(kj, a.s - 1);
 

@@ -26,7 +26,7 @@ __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(AttnArgs a) {
   const int ld = 3 * a.hl * D;
   const float* qkv = (const float*)a.qkv;
   const size_t tok0 = (size_t)bi * a.s;
-  const int klen = a.key_len ? a.key_len[bi] : a.s;
+  const int klen = attn_key_len(a.key_len, bi, a.s);
   const bool active = i < a.s;
   const float scale = 1.0f / sqrtf((float)D);
   float q[D], o[D];
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_f32_kernel(AttnArgs a) {
   const float* qkv = (const float*)a.qkv;
   const float* dctx = (const float*)a.dctx;
   const size_t tok0 = (size_t)bi * a.s;
-  const int klen = a.key_len ? a.key_len[bi] : a.s;
+  const int klen = attn_key_len(a.key_len, bi, a.s);
   const bool active = i < a.s;
   const float scale = 1.0f / sqrtf((float)D);
   float q[D], dq[D];
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_f32_kernel(AttnArgs a) {
   const float* qkv = (const float*)a.qkv;
   const float* dctx = (const float*)a.dctx;
   const size_t tok0 = (size_t)bi * a.s;
-  const int klen = a.key_len ? a.key_len[bi] : a.s;
+  const int klen = attn_key_len(a.key_len, bi, a.s);
   const bool active = j < a.s && j < klen;
   const float scale = 1.0f / sqrtf((float)D);
   float dk[D], dv[D];

@@ -133,6 +133,12 @@ struct AttnArgs {
   uint32_t* keep_bits;      // [b, hl, s, keep_pitch] words; bit (j % 32) of word j / 32 of row (b, head, i): key j kept
   int keep_pitch;           // words per query row: 4 ceil(s / 128)
 };
+// Number of visible keys of batch row bi: key_len lives in device memory and cannot be validated by the host, so every
+// kernel clamps it to [1, s] (0 or a negative length would index tiles before the buffer, a length above s keys that do
+// not exist).
+__device__ __forceinline__ int attn_key_len(const int32_t* key_len, int bi, int s) {
+  return key_len ? max(1, min(key_len[bi], s)) : s;
+}
 bool attn_bf16_supported(int d);
 hipError_t launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_bwd_bf16(const AttnArgs& a, hipStream_t st);

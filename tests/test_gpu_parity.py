@@ -461,6 +461,31 @@ def test_degenerate_key_length_one(dtype):
         check(k, sh[k], ref["shards"][0][k], tol, errs)
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_key_lengths_outside_the_contract_are_clamped(dtype):
+    """key_len lives in device memory, so the kernels clamp it to [1, s] themselves: 0 and negative lengths behave as 1,
+    lengths above s as s (the tile index arithmetic of the streamed kernels then never leaves the buffer)."""
+    cfg = synth.small_config(dtype=dtype, b=4, s=200, H=128, h=2, F=512, V=256, p=1, causal=False, masked_lm=True)
+    inp = synth.make_inputs(cfg, nonzero_bias=True, random_ln=True)
+    inp["w"] = np.zeros((cfg.b, cfg.s), np.float32)
+    inp["w"][:, ::5] = 1.0
+    given = np.array([0, -3, cfg.s + 1, 10 * cfg.s], np.int32)
+    inp["key_len"] = np.clip(given, 1, cfg.s).astype(np.int32)
+    ref = O.sharded_reference(inp, spec_of(cfg), 1)
+    inp["key_len"] = given
+    L = LayerShards(cfg, [0], DEV)
+    L.load_host_inputs(inp)
+    L.step()
+    out = L.fetch()
+    tol = TOL[dtype]
+    errs = []
+    assert abs(out["loss"] - ref["loss"]) <= tol * abs(ref["loss"])
+    for k in ("X2", "dX", "dX1"):
+        check(k, out[k], ref[k], tol, errs)
+    for k in ("ctx", "lse", "dWqkv", "dbqkv", "dWo"):
+        check(k, out["shards"][0][k], ref["shards"][0][k], tol, errs)
+
+
 # ------------------------------------------------------------------ loss merge over shards, called directly
 @pytest.mark.parametrize("T,n_shards,weighted,misalign", [(74, 3, True, 0), (74, 1, False, 0), (8200, 3, True, 0),
                                                           (8200, 1, False, 0), (16388, 2, True, 0), (1024, 3, True, 1),
