@@ -52,15 +52,8 @@ def build(jobs: int = 8, verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    # stand-alone ceilings microbenchmark (MFMA rate, LDS and HBM bandwidth) used by profiles/
-    tool = os.path.join(HERE, "mlm_microbench")
-    r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang",
-                        "-packed-fp32-ops", os.path.join(CSRC, "tools", "microbench.hip"), "-o", tool],
-                       capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("microbench build failed:\n" + r.stderr)
     if verbose:
-        print(f"built {LIB} ({os.path.getsize(LIB) / 1e6:.1f} MB) and {tool}")
+        print(f"built {LIB} ({os.path.getsize(LIB) / 1e6:.1f} MB)")
     return LIB
 
 

@@ -1,12 +1,15 @@
-// On-box ceilings for the roofline discussion: bf16 MFMA issue rate, LDS read bandwidth, HBM copy bandwidth.
-// Stand-alone program (no library code): hipcc --offload-arch=gfx950 -O3 microbench.hip -o mlm_microbench
+// On-box ceilings for the roofline discussion: bf16 MFMA issue rate on constant and on normally distributed operands,
+// the same with the GEMM main loop's LDS fragment reads and with its HBM -> LDS copies added, LDS read bandwidth, HBM
+// copy bandwidth.  Stand-alone program (no library code, not part of the library build):
+//   hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops microbench.hip -o mlm_microbench
 #include <hip/hip_runtime.h>
+#include <stdint.h>
 #include <stdio.h>
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); return 1; } } while (0)
 
-// NACC independent accumulators per wave, back-to-back v_mfma_f32_32x32x16_bf16
+// NACC independent accumulators per wave, back-to-back v_mfma_f32_32x32x16_bf16, loop-constant small-integer operands
 template <int NACC>
 __global__ __launch_bounds__(256) void k_mfma(float* out, int iters) {
   floatx16 acc[NACC];
@@ -21,6 +24,132 @@ __global__ __launch_bounds__(256) void k_mfma(float* out, int iters) {
   float s = 0.f;
   for (int i = 0; i < NACC; ++i)
     for (int e = 0; e < 16; ++e) s += acc[i][e];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// ---- the GEMM main loop's three streams, one at a time --------------------------------------------------------
+// Workgroup = 8 waves (two per SIMD), each with the 128 x 64 wave tile of the library's 256 x 256 GEMM: per 16-deep
+// half slice a wave issues 8 MFMAs on 4 + 2 operand fragments.  LEVEL 0: the fragments are a register-resident set of
+// normally distributed bf16 values (activations ~ N(0, 1), weights ~ N(0, 0.02^2)) that rotates every half slice, so
+// every MFMA sees operands that differ from its predecessor's -- the matrix pipe alone on real data, no memory
+// traffic.  LEVEL 1: the fragments are read from a 128-KB LDS ring of such values with the library's k-contiguous
+// addressing (six 16-byte reads per lane and half slice, one after each MFMA).  LEVEL 2: additionally every wave
+// re-arms the ring with four 1-KB HBM -> LDS copies per slice (32 KB per slice and workgroup, from a 64-MB buffer),
+// (the stage whose operands were just pulled into registers gets the slice four ahead, so three slices of copies are
+// in flight) and meets the other waves at one barrier per slice, as the GEMM does.  WINDOW = slices of 32 KB a
+// workgroup cycles through: 1024 (32 MB per workgroup, 64 MB in all: served by the memory-side cache) or 16 with all
+// workgroups on the same 512 KB (served by the L2s).
+typedef __attribute__((address_space(3))) void lds_void_t;
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ uint32_t hash32(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+__device__ __forceinline__ float gauss(uint32_t i) {           // Box-Muller on two hashed uniforms
+  const float u1 = (hash32(2 * i + 1) >> 8) * (1.0f / 16777216.0f) + 1e-7f;
+  const float u2 = (hash32(2 * i + 2) >> 8) * (1.0f / 16777216.0f);
+  return sqrtf(-2.0f * __logf(u1)) * __cosf(6.2831853f * u2);
+}
+__global__ void k_fill_gauss(__bf16* p, size_t n, float sigma) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = (__bf16)(sigma * gauss((uint32_t)i));
+}
+
+constexpr int RING = 128 * 1024;
+template <int LEVEL, int WINDOW = 1024>
+__global__ __launch_bounds__(512) void k_loop(float* out, const __bf16* __restrict__ src, size_t src_elems, int slices) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave >> 2) * 128, wn0 = (wave & 3) * 64, l32 = lane & 31, lh = lane >> 5;
+  // ring: [A: 4 stages x 16 KB][B: 4 stages x 16 KB], filled with N(0,1) / N(0, 0.02^2) values
+  for (int i = tid; i < RING / 2; i += 512)
+    ((__bf16*)lds)[i] = (__bf16)((i < RING / 4 ? 1.0f : 0.02f) * gauss(blockIdx.x * 65536u + i));
+  __syncthreads();
+  floatx16 acc[2][4];
+  for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 4; ++j)
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  constexpr int R = 4;                       // LEVEL 0: rotating register sets
+  bf16x8 ra[R][4], rb[R][2];
+  if (LEVEL == 0) {
+    for (int r = 0; r < R; ++r) {
+      for (int j = 0; j < 4; ++j)
+        for (int e = 0; e < 8; ++e) ra[r][j][e] = (__bf16)gauss(((blockIdx.x * 512 + tid) * 64 + (r * 4 + j) * 8 + e) * 2654435761u);
+      for (int i = 0; i < 2; ++i)
+        for (int e = 0; e < 8; ++e) rb[r][i][e] = (__bf16)(0.02f * gauss(((blockIdx.x * 512 + tid) * 64 + 32 + (r * 2 + i) * 8 + e) * 40503u));
+    }
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+  // this lane's 16 bytes of each of the wave's four 1-KB copies of a slice (rows of 64 bytes in memory order)
+  const size_t slice_elems = 16 * 1024;      // 32 KB per slice and workgroup
+  const __bf16* gsrc = src + (WINDOW == 1024 ? (size_t)blockIdx.x * 977 % 1024 : 0) * slice_elems + (size_t)(wave * 4) * 512 + lane * 8;
+  (void)src_elems;                           // host guarantees >= 2048 slices of 32 KB
+  auto frag = [&](const unsigned char* ring, int stage, int r0, int ks) {
+    const int row = r0 + l32;
+    const int u = (stage & 1) * 4 + ks * 2 + lh;
+    const int sw = (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    return *reinterpret_cast<const bf16x8*>(ring + (stage >> 1) * 32768 + row * 128 + ((u ^ sw) << 4));
+  };
+  bf16x8 fa[4], fb[2];
+  if (LEVEL >= 1) {
+    for (int j = 0; j < 4; ++j) fa[j] = frag(lds, 0, wm0 + j * 32, 0);
+    for (int i = 0; i < 2; ++i) fb[i] = frag(lds + RING / 2, 0, wn0 + i * 32, 0);
+  }
+  for (int kt2 = 0; kt2 < slices; kt2 += 2)
+#pragma unroll
+  for (int par = 0; par < 2; ++par) {
+    const int kt = kt2 + par;
+    const int stage = kt & 3;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      bf16x8 na[4], nb[2];
+#pragma unroll
+      for (int idx = 0; idx < 8; ++idx) {
+        if (LEVEL == 0) {
+          const int r = (2 * par + half) % R;          // compile-time: the slice loop is unrolled by two
+          acc[idx >> 2][idx & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rb[r][idx >> 2], ra[r][idx & 3], acc[idx >> 2][idx & 3], 0, 0, 0);
+        } else {
+          acc[idx >> 2][idx & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[idx >> 2], fa[idx & 3], acc[idx >> 2][idx & 3], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (idx >= 1 && idx <= 6) {                  // one fragment read after each MFMA but the first
+            const int q = idx - 1;
+            const int nst = half == 0 ? stage : ((kt + 1) & 3), nks = half == 0 ? 1 : 0;
+            if (q < 4) na[q] = frag(lds, nst, wm0 + q * 32, nks);
+            else nb[q - 4] = frag(lds + RING / 2, nst, wn0 + (q - 4) * 32, nks);
+          }
+          if (LEVEL == 2 && half == 1 && (idx & 1) == 0) {
+            // re-arm this slice's stage (its operands are all in registers by now): copy idx / 2 of this wave's four
+            const int c = idx >> 1;
+            const size_t sl = (size_t)(kt & (WINDOW - 1));
+            dma16(gsrc + sl * slice_elems + c * 512,
+                  lds0 + (c >> 1) * (RING / 2) + stage * 16384 + (wave * 2 + (c & 1)) * 1024);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      if (LEVEL >= 1) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fa[j] = na[j];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) fb[i] = nb[i];
+        if (half == 0) {
+          if (LEVEL == 2) wait_vmcnt<8>();             // the copies issued three slices ago (for the next slice) have landed
+          __builtin_amdgcn_s_waitcnt(0xC07F);
+          __builtin_amdgcn_s_barrier();
+        }
+      }
+    }
+  }
+  if (LEVEL == 2) wait_vmcnt<0>();
+  float s = 0.f;
+  for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 4; ++j)
+      for (int e = 0; e < 16; ++e) s += acc[i][j][e];
   out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
@@ -47,6 +176,31 @@ __global__ __launch_bounds__(256) void k_copy(const float4* __restrict__ in, flo
   if (i < n) o[i] = in[i];
 }
 
+template <int LEVEL, int WINDOW = 1024>
+static int run_loop(const char* what, float* out, const __bf16* src, size_t src_elems) {
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  CK(hipFuncSetAttribute((const void*)k_loop<LEVEL, WINDOW>, hipFuncAttributeMaxDynamicSharedMemorySize, RING));
+  const int slices = 20000;                   // 2 x 10^4 slices of 32: about 10-20 ms per launch
+  k_loop<LEVEL, WINDOW><<<256, 512, RING>>>(out, src, src_elems, 2000);
+  CK(hipDeviceSynchronize());
+  float best = 1e30f, sum = 0.f;
+  for (int rep = 0; rep < 5; ++rep) {
+    float ms;
+    CK(hipEventRecord(e0));
+    k_loop<LEVEL, WINDOW><<<256, 512, RING>>>(out, src, src_elems, slices);
+    CK(hipEventRecord(e1));
+    CK(hipDeviceSynchronize());
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    best = ms < best ? ms : best;
+    sum += ms;
+  }
+  const double flops = 256.0 * 8 * slices * 16 * 32 * 32 * 16 * 2;
+  printf("%s: %.1f TFLOP/s mean of 5, %.1f best\n", what, flops * 5 / sum / 1e9, flops / best / 1e9);
+  return 0;
+}
+
 int main() {
   float* out;
   CK(hipMalloc(&out, 1 << 24));
@@ -62,14 +216,26 @@ int main() {
   CK(hipEventRecord(e1));
   CK(hipDeviceSynchronize());
   CK(hipEventElapsedTime(&ms, e0, e1));
-  printf("mfma_f32_32x32x16_bf16, 1 wave per SIMD (256 blocks x 4 waves): %.1f TFLOP/s\n",
+  printf("mfma_f32_32x32x16_bf16, constant operands, 1 wave per SIMD (256 blocks x 4 waves): %.1f TFLOP/s\n",
          256.0 * 4 * iters * 8 * 8 * 32 * 32 * 16 * 2 / ms / 1e9);
   CK(hipEventRecord(e0));
   k_mfma<4><<<2048, 256>>>(out, iters);
   CK(hipEventRecord(e1));
   CK(hipDeviceSynchronize());
   CK(hipEventElapsedTime(&ms, e0, e1));
-  printf("mfma_f32_32x32x16_bf16, 2048 blocks x 4 waves: %.1f TFLOP/s\n", 2048.0 * 4 * iters * 4 * 32 * 32 * 16 * 2 / ms / 1e9);
+  printf("mfma_f32_32x32x16_bf16, constant operands, 2048 blocks x 4 waves: %.1f TFLOP/s\n", 2048.0 * 4 * iters * 4 * 32 * 32 * 16 * 2 / ms / 1e9);
+
+  // normally distributed operands: matrix pipe alone, + LDS fragment reads, + HBM -> LDS copies
+  const size_t src_elems = (size_t)32 << 20;      // 64 MB of N(0, 1) bf16
+  __bf16* src;
+  CK(hipMalloc(&src, src_elems * 2));
+  k_fill_gauss<<<(unsigned)(src_elems / 256), 256>>>(src, src_elems, 1.0f);
+  CK(hipDeviceSynchronize());
+  if (run_loop<0>("GEMM wave tile (8 waves, 128 x 64), N(0,1) x N(0,0.02) operands rotating in registers, MFMA only", out, src, src_elems)) return 1;
+  if (run_loop<1>("  + operand fragments read from LDS (6 x 16 B per lane and 8 MFMAs), one barrier per slice", out, src, src_elems)) return 1;
+  if (run_loop<2, 16>("  + 32 KB per slice copied -> LDS by global_load_lds (4 x 1 KB per wave), source served by the L2s", out, src, src_elems)) return 1;
+  if (run_loop<2, 1024>("  + the same copies, source served by the memory-side cache (64 MB window)", out, src, src_elems)) return 1;
+
   CK(hipFuncSetAttribute((const void*)k_lds, hipFuncAttributeMaxDynamicSharedMemorySize, 65536));
   for (int stride : {72, 64}) {
     const int li = 20000;
@@ -85,14 +251,14 @@ int main() {
            bytes / ms / 1e9, bytes / 256 / (ms * 1e-3 * 2.4e9));
   }
   const size_t n = (size_t)1 << 26;   // 1 GiB in, 1 GiB out
-  float4 *src, *dst;
-  CK(hipMalloc(&src, n * 16));
+  float4 *csrc, *dst;
+  CK(hipMalloc(&csrc, n * 16));
   CK(hipMalloc(&dst, n * 16));
-  CK(hipMemset(src, 1, n * 16));
-  k_copy<<<(unsigned)(n / 256), 256>>>(src, dst, n);
+  CK(hipMemset(csrc, 1, n * 16));
+  k_copy<<<(unsigned)(n / 256), 256>>>(csrc, dst, n);
   CK(hipDeviceSynchronize());
   CK(hipEventRecord(e0));
-  for (int r = 0; r < 5; ++r) k_copy<<<(unsigned)(n / 256), 256>>>(src, dst, n);
+  for (int r = 0; r < 5; ++r) k_copy<<<(unsigned)(n / 256), 256>>>(csrc, dst, n);
   CK(hipEventRecord(e1));
   CK(hipDeviceSynchronize());
   CK(hipEventElapsedTime(&ms, e0, e1));
