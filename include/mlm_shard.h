@@ -160,6 +160,20 @@ MLM_API int mlm_combine_layernorm_bwd(const mlm_dims* dims, const void* const* p
  * ws: MLM_WS_COLSUM bytes. */
 MLM_API int mlm_colsum(const mlm_dims* dims, const void* dy, void* dbias, void* ws, size_t ws_bytes, void* stream);
 
+/* mlm_colsum for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace,
+ * same kernels, same result bit for bit.  The per-chunk partial sums go to a static device
+ * array inside the library (4 MiB per GPU, held until the process ends) instead of a caller
+ * workspace; the call allocates and frees nothing.
+ * Limit: ceil(T / 64) * H <= 1,048,576 floats (e.g. T = 8192 with H <= 8192); beyond that
+ * MLM_E_WORKSPACE is returned and nothing is launched.
+ * The first call on a device looks up that device's copy of the array (once per device; make
+ * that call outside a graph capture).  All calls on one GPU share the array: calls that
+ * overlap in time on the same GPU (different streams) race and must be serialised by the
+ * caller.  Nothing in the array has to start at zero (every slot a call reads, it has
+ * written first), so it is never cleared. */
+MLM_API int mlm_colsum_noalloc(const mlm_dims* dims, const void* dy, void* dbias, void* stream);
+
 /* ---- self-attention block of shard r (Section 3, Fig. 3b) ---------------------- */
 
 /* Forward.  h_l = h/p local heads, H_l = h_l * d.

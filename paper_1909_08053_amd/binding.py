@@ -25,7 +25,7 @@ EXPORTS = ("mlm_shard_range", "mlm_workspace_bytes", "mlm_status_string", "mlm_l
            "mlm_combine_layernorm_fwd_dropout", "mlm_combine_layernorm_bwd_dropout", "mlm_attn_keep_words",
            "mlm_attn_shard_fwd_dropout", "mlm_attn_shard_bwd_dropout", "mlm_embed_shard_fwd", "mlm_embed_bwd_replicated",
            "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter", "mlm_mlp_shard_bwd_input",
-           "mlm_attn_shard_bwd_input", "mlm_layer_shard_wgrads")
+           "mlm_attn_shard_bwd_input", "mlm_layer_shard_wgrads", "mlm_colsum_noalloc")
 STREAM_REPLICATED, STREAM_MODEL_PARALLEL = 0, 1
 
 
@@ -165,6 +165,10 @@ def mlm_combine_layernorm_bwd(dims, partials: Sequence[torch.Tensor], x, gamma, 
 
 def mlm_colsum(dims, dy, dbias, ws, stream=None):
     _chk(lib().mlm_colsum(ctypes.byref(dims), _p(dy), _p(dbias), *_ws(ws), _st(stream)), "mlm_colsum")
+
+
+def mlm_colsum_noalloc(dims, dy, dbias, stream=None):
+    _chk(lib().mlm_colsum_noalloc(ctypes.byref(dims), _p(dy), _p(dbias), _st(stream)), "mlm_colsum_noalloc")
 
 
 def mlm_attn_shard_fwd(dims, u, Wqkv_r, bqkv_r, Wo_r, key_len, qkv_r, ctx_r, lse_r, partial_r, ws=None, stream=None):

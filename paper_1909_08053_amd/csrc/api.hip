@@ -121,7 +121,7 @@ MLM_API const char* mlm_status_string(int code) {
     case MLM_E_NULL: return "MLM_E_NULL: required pointer is NULL";
     case MLM_E_SHAPE: return "MLM_E_SHAPE: bad size or indivisible shard";
     case MLM_E_DTYPE: return "MLM_E_DTYPE: unknown dtype";
-    case MLM_E_WORKSPACE: return "MLM_E_WORKSPACE: workspace too small";
+    case MLM_E_WORKSPACE: return "MLM_E_WORKSPACE: workspace too small, or problem larger than the static scratch of a no-allocation call";
     case MLM_E_ALIGN: return "MLM_E_ALIGN: size or pointer alignment";
     case MLM_E_HIP: return "MLM_E_HIP: HIP call or launch failed";
     case MLM_E_UNSUPPORTED: return "MLM_E_UNSUPPORTED: configuration not compiled in";
@@ -304,6 +304,17 @@ MLM_API int mlm_colsum(const mlm_dims* dims, const void* dy, void* dbias, void* 
   if (!aligned16(dy) || !aligned16(ws)) return MLM_E_ALIGN;
   if (ws_bytes < ws_bytes_for(dims, L, MLM_WS_COLSUM)) return MLM_E_WORKSPACE;
   return hip_status(launch_colsum(dims->dtype, L.T, dims->H, dy, dbias, (float*)ws, (hipStream_t)stream));
+}
+
+MLM_API int mlm_colsum_noalloc(const mlm_dims* dims, const void* dy, void* dbias, void* stream) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if (!dy || !dbias) return MLM_E_NULL;
+  if (!aligned16(dy)) return MLM_E_ALIGN;
+  const size_t chunks = ((size_t)L.T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
+  if (chunks * (size_t)dims->H > kStaticScratchFloats) return MLM_E_WORKSPACE;   // beyond the static scratch
+  return hip_status(launch_colsum_static(dims->dtype, L.T, dims->H, dy, dbias, (hipStream_t)stream));
 }
 
 static int keep_pitch_words(int s) { return 4 * ((s + 127) / 128); }

@@ -174,6 +174,9 @@ hipError_t launch_combine(int dtype, int T, int H, const void* const* partials, 
                           int bias_rows, const void* residual, void* out, const mlm_dropout* drop, hipStream_t st);
 // ws: [ceil(T/kColsumRowsPerBlock)][N] float
 hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, float* ws, hipStream_t st);
+// same with the partials in a static device array of kStaticScratchFloats floats (no workspace argument)
+constexpr size_t kStaticScratchFloats = (size_t)1 << 20;      // 4 MiB per GPU
+hipError_t launch_colsum_static(int dtype, int T, int N, const void* dy, void* dbias, hipStream_t st);
 hipError_t launch_ce_tile_merge(int T, int ntiles, const float* part_m, const float* part_s, const float* t_ws,
                                 const int32_t* targets, int v0, int v1, float* m_r, float* s_r, float* t_r,
                                 hipStream_t st);

@@ -3,6 +3,7 @@
 // partial merges (Section 3 of the paper: replicated LN/residual, g/f reductions, loss fused
 // with the vocabulary-parallel logits).  One wavefront (64 lanes) owns one token row; row
 // statistics are wave-level shuffles, HBM access is 16-byte vectors, coalesced along H.
+#include <mutex>
 #include "common.h"
 #include "rng.h"
 
@@ -859,6 +860,43 @@ hipError_t launch_attn_delta(int dtype, int T, int hl, int d, int b, int s, cons
     hipLaunchKernelGGL((attn_delta_kernel<float>), grid, dim3(256), 0, st, T, hl, d, s, (const float*)ctx,
                        (const float*)dctx, delta);
   return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------ column sums without a workspace
+// For callers that cannot allocate (code under graph capture, serving loops): the chunk partials of the column sum
+// live in a file-scope device array instead of a caller workspace.  Every GPU holds its own copy of the array at its
+// own address until the process ends; the address is looked up once per device, with that device current, and host
+// code uses only that looked-up pointer (the array's name is a host-side stand-in, not a device address).
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+
+static hipError_t static_scratch_ptr(float** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static float* per_device[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (per_device[dev] == nullptr) {
+    float* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    per_device[dev] = ptr;
+  }
+  *out = per_device[dev];
+  return hipSuccess;
+}
+
+// Same kernels as launch_colsum, partials in the static array.  Every [chunk][column] slot that the reduction reads
+// is written by the partial kernel of the same call first, so nothing has to start at zero and stale contents of an
+// earlier (larger) call are never read.  The caller has checked ceil(T / kColsumRowsPerBlock) * N <= kStaticScratchFloats.
+hipError_t launch_colsum_static(int dtype, int T, int N, const void* dy, void* dbias, hipStream_t st) {
+  float* ws = nullptr;
+  hipError_t e = static_scratch_ptr(&ws);
+  if (e != hipSuccess) return e;
+  return launch_colsum(dtype, T, N, dy, dbias, ws, st);
 }
 
 }  // namespace mlm
