@@ -29,8 +29,20 @@
  *     enqueued on the given stream (a hipStream_t passed as void*, NULL = default).
  *     Inputs are read-only; outputs are fully overwritten unless stated otherwise.
  *   - Errors: every call returns 0 (MLM_OK) or a negative mlm_status.  Arguments are
- *     validated on the host before anything is launched, so a failing call has
- *     launched nothing.  No exceptions cross the ABI and there is no global state.
+ *     validated on the host before anything is launched, so a call that fails
+ *     validation has launched nothing; MLM_E_HIP (a launch that the runtime refused)
+ *     can leave the earlier kernels of the same call enqueued.  No exceptions cross
+ *     the ABI.
+ *   - Process-wide state: none that a result depends on.  The library keeps (a) per
+ *     kernel and device, whether its dynamic-LDS attribute has been set; (b) the
+ *     address of mlm_colsum_noalloc's static scratch per device; (c) five tuning
+ *     overrides that are read from the environment ONCE per process, at the first
+ *     bf16 GEMM: MLM_GEMM_V2=0 (register-staged kernel instead of the direct-to-LDS
+ *     one), MLM_GEMM_TILE=0|1|2 (tile of the register-staged kernel), MLM_GEMM_WAVES=4|8,
+ *     MLM_GEMM_BN=192|256 (tile width where both exist), MLM_GEMM_GROUP=0 (weight
+ *     gradients launched one by one).  They choose between kernels that compute the
+ *     same sums in a different order and exist for A/B measurements; unset, the
+ *     library chooses by its cost model.  Calls may come from several host threads.
  *   - H, H/p, F/p, V/p and the head size must be multiples of 8 and pointers 16-byte
  *     aligned (MLM_E_ALIGN otherwise).  Supported head sizes: 64, 96, 128, 192 (MLM_BF16);
  *     any multiple of 16 up to 128 (MLM_F32).  H <= 4096 (MLM_BF16) / 2048 (MLM_F32).
@@ -51,7 +63,8 @@ extern "C" {
 typedef enum mlm_status {
   MLM_OK = 0,
   MLM_E_NULL = -1,       /* a required pointer is NULL                              */
-  MLM_E_SHAPE = -2,      /* non-positive size, h % p, F % p, V % p, H % h != 0, r outside [0,p) */
+  MLM_E_SHAPE = -2,      /* non-positive size, h % p, F % p, V % p, H % h != 0, r outside [0,p), or a size
+                            beyond the launch limits: b*s <= 2^21 tokens, b <= 65535, H, F/p, V/p <= 2^20 */
   MLM_E_DTYPE = -3,      /* dtype is neither MLM_F32 nor MLM_BF16                   */
   MLM_E_WORKSPACE = -4,  /* workspace smaller than mlm_workspace_bytes reports      */
   MLM_E_ALIGN = -5,      /* size or pointer alignment requirement of MLM_BF16 violated */
@@ -446,7 +459,9 @@ MLM_API int mlm_rows_scatter(const mlm_dims* dims, const void* y, const int32_t*
  *   trans_a == 0: A is [M,K] (lda = K);  trans_a == 1: A is stored [K,M] (lda = M)
  *   trans_b == 0: B is [K,N] (ldb = N);  trans_b == 1: B is stored [N,K] (ldb = K)
  * C: [M,N]; bias: [N] or NULL.  dtype as in mlm_dims.  This is the kernel the block calls
- * above are built from (forward: 0/0, input gradient: 0/1, weight gradient: 1/0). */
+ * above are built from (forward: 0/0, input gradient: 0/1, weight gradient: 1/0).
+ * M, N, K multiples of 8; M, N <= 2^21, K <= 2^24 (MLM_E_SHAPE beyond); both operands
+ * transposed is MLM_E_UNSUPPORTED. */
 MLM_API int mlm_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K,
              const void* A, const void* B, void* C, const void* bias, void* stream);
 

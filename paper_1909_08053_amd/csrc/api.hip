@@ -23,7 +23,10 @@ int check_dims(const mlm_dims* dm, Local* L) {
     return MLM_E_SHAPE;
   if (dm->r < 0 || dm->r >= dm->p) return MLM_E_SHAPE;
   if (dm->H % dm->h || dm->h % dm->p || dm->F % dm->p || dm->V % dm->p) return MLM_E_SHAPE;
-  if ((int64_t)dm->b * dm->s > (int64_t)1 << 24) return MLM_E_SHAPE;
+  // launch-grid limits: token and column counts index 1-D grids (products below 2^31), row tiles and the batch index
+  // 2-D / 3-D grids (below 65536)
+  if ((int64_t)dm->b * dm->s > (int64_t)1 << 21 || dm->b > 65535) return MLM_E_SHAPE;
+  if (dm->H > (1 << 20) || dm->F / dm->p > (1 << 20) || dm->V / dm->p > (1 << 20)) return MLM_E_SHAPE;
   L->T = dm->b * dm->s;
   L->d = dm->H / dm->h;
   L->hl = dm->h / dm->p;
@@ -706,7 +709,7 @@ MLM_API int mlm_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int64_t M,
              const void* B, void* C, const void* bias, void* stream) {
   if (dtype != MLM_F32 && dtype != MLM_BF16) return MLM_E_DTYPE;
   if (!A || !B || !C) return MLM_E_NULL;
-  if (M <= 0 || N <= 0 || K <= 0 || M > (1 << 24) || N > (1 << 24) || K > (1 << 24)) return MLM_E_SHAPE;
+  if (M <= 0 || N <= 0 || K <= 0 || M > (1 << 21) || N > (1 << 21) || K > (1 << 24)) return MLM_E_SHAPE;
   if ((trans_a != 0 && trans_a != 1) || (trans_b != 0 && trans_b != 1)) return MLM_E_SHAPE;
   if (trans_a && trans_b) return MLM_E_UNSUPPORTED;
   if (M % 8 || N % 8 || K % 8) return MLM_E_ALIGN;

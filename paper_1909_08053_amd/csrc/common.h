@@ -15,6 +15,23 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
 constexpr int kWave = 64;
 
+// hipFuncSetAttribute(kernel, MaxDynamicSharedMemorySize, bytes) once per (kernel instantiation, device): the attribute
+// belongs to the device's copy of the kernel, so the "done" state is a bit per device (devices beyond 63 set it on
+// every launch).  A race between two host threads only repeats the idempotent call.
+struct LdsAttrOnce {
+  unsigned long long done = 0;
+  hipError_t ensure(const void* kernel, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = (dev >= 0 && dev < 64) ? (1ull << dev) : 0ull;
+    if (bit && (__atomic_load_n(&done, __ATOMIC_ACQUIRE) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && bit) __atomic_fetch_or(&done, bit, __ATOMIC_RELEASE);
+    return e;
+  }
+};
+
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f32(float v);

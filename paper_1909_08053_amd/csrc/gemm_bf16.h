@@ -450,13 +450,8 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, int EP
 hipError_t launch_gemm_bf16_cfg(const GemmArgs& a, hipStream_t st) {
   typedef GemmTile<BM, BN, WAVES_M, WAVES_N> Tcfg;
   auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, EPI>;
-  static bool attr_set = false;   // per instantiation; idempotent, so a race only repeats the call
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)Tcfg::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce attr;         // per instantiation and device
+  if (hipError_t e = attr.ensure((const void*)kern, (int)Tcfg::LDS_BYTES); e != hipSuccess) return e;
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(Tcfg::NT), Tcfg::LDS_BYTES, st, a);
   return hipGetLastError();

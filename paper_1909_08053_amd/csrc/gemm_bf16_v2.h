@@ -510,13 +510,8 @@ hipError_t launch_gemm_bf16_v2_nw(const GemmArgs& a, float* splitk_ws, hipStream
   constexpr size_t kEpi = GemmTile<V2_B, BN, WAVES_M, NW / WAVES_M>::LDS_EPI;
   constexpr size_t kLds = V2_LDS_BYTES > kEpi ? V2_LDS_BYTES : kEpi;
   static_assert(kLds <= 160 * 1024, "LDS budget");
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce attr;         // per instantiation and device
+  if (hipError_t e = attr.ensure((const void*)kern, (int)kLds); e != hipSuccess) return e;
   const V2Plan plan = v2_plan(a.M, a.N, a.K, splitk_ws != nullptr, BN, !B_KC);
   const int grid = plan.full_tiles + plan.tail_tiles * plan.split;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), kLds, st, a, plan, splitk_ws);
@@ -538,12 +533,8 @@ hipError_t launch_gemm_bf16_v2_group_nw(const GemmArgs* probs, int n, hipStream_
   auto kern = gemm_bf16_v2_group_kernel<A_KC, B_KC, NW>;
   constexpr size_t kEpi = GemmTile<V2_B, V2_B, 2, NW / 2>::LDS_EPI;
   constexpr size_t kLds = V2_LDS_BYTES > kEpi ? V2_LDS_BYTES : kEpi;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce attr;
+  if (hipError_t e = attr.ensure((const void*)kern, (int)kLds); e != hipSuccess) return e;
   GemmGroup g;
   memset(&g, 0, sizeof(g));
   g.n = n;

@@ -488,9 +488,11 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(int rows, int N, co
   constexpr int VN = Vec16<T>::N;
   __shared__ float red[4][64 * VN + 1];
   const int vx = threadIdx.x & 63, sl = threadIdx.x >> 6;
-  const int vcol = blockIdx.x * 64 + vx;
+  const int ncb = (N / VN + 63) / 64;                 // column blocks; grid.x = chunks x column blocks (column block fastest)
+  const int chunk = blockIdx.x / ncb;
+  const int vcol = (blockIdx.x - chunk * ncb) * 64 + vx;
   const bool ok = vcol * VN < N;
-  const int r0 = blockIdx.y * kColsumRowsPerBlock;
+  const int r0 = chunk * kColsumRowsPerBlock;
   const int r1 = min(rows, r0 + kColsumRowsPerBlock);
   float acc[VN];
 #pragma unroll
@@ -511,7 +513,7 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(int rows, int N, co
 #pragma unroll
     for (int e = 0; e < VN; ++e) {
       const float t = (red[0][e * 64 + vx] + red[1][e * 64 + vx]) + (red[2][e * 64 + vx] + red[3][e * 64 + vx]);
-      ws[(size_t)blockIdx.y * N + (size_t)vcol * VN + e] = t;
+      ws[(size_t)chunk * N + (size_t)vcol * VN + e] = t;
     }
   }
 }
@@ -519,12 +521,12 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(int rows, int N, co
 hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, float* ws, hipStream_t st) {
   const int nchunk = (T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
   if (dtype == MLM_BF16) {
-    dim3 grid((N / 8 + 63) / 64, nchunk);
+    dim3 grid(((N / 8 + 63) / 64) * nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<bf16>), grid, dim3(256), 0, st, T, N, (const bf16*)dy, ws);
     hipLaunchKernelGGL((reduce_cols_kernel<bf16>), dim3((N + 63) / 64), dim3(256), 0, st, nchunk, N, ws,
                        (bf16*)dbias, (bf16*)dbias, (bf16*)dbias, N);
   } else {
-    dim3 grid((N / 4 + 63) / 64, nchunk);
+    dim3 grid(((N / 4 + 63) / 64) * nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(256), 0, st, T, N, (const float*)dy, ws);
     hipLaunchKernelGGL((reduce_cols_kernel<float>), dim3((N + 63) / 64), dim3(256), 0, st, nchunk, N, ws,
                        (float*)dbias, (float*)dbias, (float*)dbias, N);
@@ -728,8 +730,9 @@ __global__ __launch_bounds__(256) void dlogits_inplace_kernel(int Vl, T* logits,
                                                               const float* __restrict__ loss_w,
                                                               const float* __restrict__ loss_stats) {
   constexpr int VN = Vec16<T>::N;
-  const int t = blockIdx.y;
-  const int vcol = blockIdx.x * 256 + threadIdx.x;
+  const int ncb = (Vl / VN + 255) / 256;              // grid.x = tokens x column blocks (column block fastest)
+  const int t = blockIdx.x / ncb;
+  const int vcol = (blockIdx.x - t * ncb) * 256 + threadIdx.x;
   if (vcol * VN >= Vl) return;
   const float coef = (loss_w ? loss_w[t] : 1.0f) / loss_stats[1];
   const float Mt = M[t];
@@ -751,11 +754,11 @@ hipError_t launch_dlogits_inplace(int dtype, int T, int Vl, void* logits, const 
                                   const float* M, const float* S, const float* loss_w, const float* loss_stats,
                                   hipStream_t st) {
   if (dtype == MLM_BF16) {
-    dim3 grid((Vl / 8 + 255) / 256, T);
+    dim3 grid(((Vl / 8 + 255) / 256) * T);
     hipLaunchKernelGGL((dlogits_inplace_kernel<bf16>), grid, dim3(256), 0, st, Vl, (bf16*)logits, targets, v0, M, S,
                        loss_w, loss_stats);
   } else {
-    dim3 grid((Vl / 4 + 255) / 256, T);
+    dim3 grid(((Vl / 4 + 255) / 256) * T);
     hipLaunchKernelGGL((dlogits_inplace_kernel<float>), grid, dim3(256), 0, st, Vl, (float*)logits, targets, v0, M, S,
                        loss_w, loss_stats);
   }

@@ -60,45 +60,53 @@ __global__ void k_fill_gauss(__bf16* p, size_t n, float sigma) {
   if (i < n) p[i] = (__bf16)(sigma * gauss((uint32_t)i));
 }
 
-constexpr int RING = 128 * 1024;
-template <int LEVEL, int WINDOW = 1024>
-__global__ __launch_bounds__(512) void k_loop(float* out, const __bf16* __restrict__ src, size_t src_elems, int slices) {
+// Wave-tile shapes: NW waves as 2 x NW/2, each TM x TN MFMA tiles of 32 x 32; block tile 64 TM x 16 NW TN.
+//   8 waves, 4 x 2: the library's 256 x 256 tile with two waves per SIMD (6 fragment reads per 8 MFMAs, 32 KB per slice)
+//   4 waves, 4 x 4: 256 x 256 with one wave per SIMD (8 reads per 16 MFMAs)
+// (a 256 x 384 tile -- 4 waves of 4 x 6, 0.83 x the copy bytes per flop -- needs 384 accumulator registers per lane;
+// the compiler spills several hundred of them, so that shape is not measured)
+template <int LEVEL, int WINDOW, int NW, int TM, int TN>
+__global__ __launch_bounds__(NW * 64) void k_loop(float* out, const __bf16* __restrict__ src, int slices) {
+  constexpr int WN = NW / 2, BM = 64 * TM, BN = 32 * WN * TN, NT = NW * 64;
+  constexpr int STAGE = (BM + BN) * 64, RING = 4 * STAGE, NC = STAGE / 1024 / NW, NMF = TM * TN;
+  static_assert(STAGE % (1024 * NW) == 0 && NMF > TM + TN, "shape");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm0 = (wave >> 2) * 128, wn0 = (wave & 3) * 64, l32 = lane & 31, lh = lane >> 5;
-  // ring: [A: 4 stages x 16 KB][B: 4 stages x 16 KB], filled with N(0,1) / N(0, 0.02^2) values
-  for (int i = tid; i < RING / 2; i += 512)
-    ((__bf16*)lds)[i] = (__bf16)((i < RING / 4 ? 1.0f : 0.02f) * gauss(blockIdx.x * 65536u + i));
+  const int wm0 = (wave / WN) * (32 * TM), wn0 = (wave % WN) * (32 * TN), l32 = lane & 31, lh = lane >> 5;
+  // ring: A's two pair buffers ([BM rows][64 k]) then B's ([BN rows][64 k]), filled with N(0,1) / N(0, 0.02^2) values
+  for (int i = tid; i < RING / 2; i += NT)
+    ((__bf16*)lds)[i] = (__bf16)((i < 2 * BM * 64 ? 1.0f : 0.02f) * gauss(blockIdx.x * 131072u + i));
   __syncthreads();
-  floatx16 acc[2][4];
-  for (int i = 0; i < 2; ++i)
-    for (int j = 0; j < 4; ++j)
+  floatx16 acc[TN][TM];
+  for (int i = 0; i < TN; ++i)
+    for (int j = 0; j < TM; ++j)
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  constexpr int R = 4;                       // LEVEL 0: rotating register sets
-  bf16x8 ra[R][4], rb[R][2];
+  constexpr int R = LEVEL == 0 ? 4 : 1;      // LEVEL 0: rotating register sets
+  bf16x8 ra[R][TM], rb[R][TN];
   if (LEVEL == 0) {
     for (int r = 0; r < R; ++r) {
-      for (int j = 0; j < 4; ++j)
-        for (int e = 0; e < 8; ++e) ra[r][j][e] = (__bf16)gauss(((blockIdx.x * 512 + tid) * 64 + (r * 4 + j) * 8 + e) * 2654435761u);
-      for (int i = 0; i < 2; ++i)
-        for (int e = 0; e < 8; ++e) rb[r][i][e] = (__bf16)(0.02f * gauss(((blockIdx.x * 512 + tid) * 64 + 32 + (r * 2 + i) * 8 + e) * 40503u));
+      for (int j = 0; j < TM; ++j)
+        for (int e = 0; e < 8; ++e) ra[r][j][e] = (__bf16)gauss(((blockIdx.x * NT + tid) * 128 + (r * TM + j) * 8 + e) * 2654435761u);
+      for (int i = 0; i < TN; ++i)
+        for (int e = 0; e < 8; ++e) rb[r][i][e] = (__bf16)(0.02f * gauss(((blockIdx.x * NT + tid) * 128 + 64 + (r * TN + i) * 8 + e) * 40503u));
     }
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
-  // this lane's 16 bytes of each of the wave's four 1-KB copies of a slice (rows of 64 bytes in memory order)
-  const size_t slice_elems = 16 * 1024;      // 32 KB per slice and workgroup
-  const __bf16* gsrc = src + (WINDOW == 1024 ? (size_t)blockIdx.x * 977 % 1024 : 0) * slice_elems + (size_t)(wave * 4) * 512 + lane * 8;
-  (void)src_elems;                           // host guarantees >= 2048 slices of 32 KB
-  auto frag = [&](const unsigned char* ring, int stage, int r0, int ks) {
+  // this lane's 16 bytes of each of the wave's NC 1-KB copies of a slice
+  constexpr size_t slice_elems = STAGE / 2;
+  const __bf16* gsrc = src + (WINDOW == 1024 ? (size_t)blockIdx.x * 977 % 512 : 0) * slice_elems + (size_t)(wave * NC) * 512 + lane * 8;
+  auto frag = [&](const unsigned char* ring, int rows, int stage, int r0, int ks) {
     const int row = r0 + l32;
     const int u = (stage & 1) * 4 + ks * 2 + lh;
     const int sw = (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
-    return *reinterpret_cast<const bf16x8*>(ring + (stage >> 1) * 32768 + row * 128 + ((u ^ sw) << 4));
+    return *reinterpret_cast<const bf16x8*>(ring + (stage >> 1) * (rows * 128) + row * 128 + ((u ^ sw) << 4));
   };
-  bf16x8 fa[4], fb[2];
+  const unsigned char* ringA = lds;
+  const unsigned char* ringB = lds + 4 * BM * 64;
+  bf16x8 fa[TM], fb[TN];
   if (LEVEL >= 1) {
-    for (int j = 0; j < 4; ++j) fa[j] = frag(lds, 0, wm0 + j * 32, 0);
-    for (int i = 0; i < 2; ++i) fb[i] = frag(lds + RING / 2, 0, wn0 + i * 32, 0);
+    for (int j = 0; j < TM; ++j) fa[j] = frag(ringA, BM, 0, wm0 + j * 32, 0);
+    for (int i = 0; i < TN; ++i) fb[i] = frag(ringB, BN, 0, wn0 + i * 32, 0);
   }
   for (int kt2 = 0; kt2 < slices; kt2 += 2)
 #pragma unroll
@@ -107,38 +115,40 @@ __global__ __launch_bounds__(512) void k_loop(float* out, const __bf16* __restri
     const int stage = kt & 3;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-      bf16x8 na[4], nb[2];
+      bf16x8 na[TM], nb[TN];
 #pragma unroll
-      for (int idx = 0; idx < 8; ++idx) {
+      for (int idx = 0; idx < NMF; ++idx) {
         if (LEVEL == 0) {
           const int r = (2 * par + half) % R;          // compile-time: the slice loop is unrolled by two
-          acc[idx >> 2][idx & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rb[r][idx >> 2], ra[r][idx & 3], acc[idx >> 2][idx & 3], 0, 0, 0);
+          acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rb[r][idx / TM], ra[r][idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
         } else {
-          acc[idx >> 2][idx & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[idx >> 2], fa[idx & 3], acc[idx >> 2][idx & 3], 0, 0, 0);
+          acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[idx / TM], fa[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
-          if (idx >= 1 && idx <= 6) {                  // one fragment read after each MFMA but the first
+          if (idx >= 1 && idx <= TM + TN) {            // one fragment read after each MFMA but the first
             const int q = idx - 1;
             const int nst = half == 0 ? stage : ((kt + 1) & 3), nks = half == 0 ? 1 : 0;
-            if (q < 4) na[q] = frag(lds, nst, wm0 + q * 32, nks);
-            else nb[q - 4] = frag(lds + RING / 2, nst, wn0 + (q - 4) * 32, nks);
+            if (q < TM) na[q] = frag(ringA, BM, nst, wm0 + q * 32, nks);
+            else nb[q - TM] = frag(ringB, BN, nst, wn0 + (q - TM) * 32, nks);
           }
-          if (LEVEL == 2 && half == 1 && (idx & 1) == 0) {
-            // re-arm this slice's stage (its operands are all in registers by now): copy idx / 2 of this wave's four
-            const int c = idx >> 1;
-            const size_t sl = (size_t)(kt & (WINDOW - 1));
-            dma16(gsrc + sl * slice_elems + c * 512,
-                  lds0 + (c >> 1) * (RING / 2) + stage * 16384 + (wave * 2 + (c & 1)) * 1024);
+          if (LEVEL == 2 && half == 1) {
+            // re-arm this slice's stage (its operands are all in registers by now), copies spread over the MFMAs
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+              if ((c * NMF) / NC != idx) continue;
+              const size_t sl = (size_t)(kt & (WINDOW / 2 - 1));
+              dma16(gsrc + sl * slice_elems + c * 512, lds0 + stage * STAGE + (wave * NC + c) * 1024);
+            }
           }
           __builtin_amdgcn_sched_barrier(0);
         }
       }
       if (LEVEL >= 1) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fa[j] = na[j];
+        for (int j = 0; j < TM; ++j) fa[j] = na[j];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) fb[i] = nb[i];
+        for (int i = 0; i < TN; ++i) fb[i] = nb[i];
         if (half == 0) {
-          if (LEVEL == 2) wait_vmcnt<8>();             // the copies issued three slices ago (for the next slice) have landed
+          if (LEVEL == 2) wait_vmcnt<2 * NC>();        // the copies issued three slices ago (for the next slice) have landed
           __builtin_amdgcn_s_waitcnt(0xC07F);
           __builtin_amdgcn_s_barrier();
         }
@@ -147,8 +157,8 @@ __global__ __launch_bounds__(512) void k_loop(float* out, const __bf16* __restri
   }
   if (LEVEL == 2) wait_vmcnt<0>();
   float s = 0.f;
-  for (int i = 0; i < 2; ++i)
-    for (int j = 0; j < 4; ++j)
+  for (int i = 0; i < TN; ++i)
+    for (int j = 0; j < TM; ++j)
       for (int e = 0; e < 16; ++e) s += acc[i][j][e];
   out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
@@ -176,28 +186,40 @@ __global__ __launch_bounds__(256) void k_copy(const float4* __restrict__ in, flo
   if (i < n) o[i] = in[i];
 }
 
-template <int LEVEL, int WINDOW = 1024>
-static int run_loop(const char* what, float* out, const __bf16* src, size_t src_elems) {
+template <int LEVEL, int WINDOW, int NW, int TM, int TN>
+static int run_loop(const char* what, float* out, const __bf16* src) {
+  constexpr int RING = 4 * (64 * TM + 16 * NW * TN) * 64;
   hipEvent_t e0, e1;
   CK(hipEventCreate(&e0));
   CK(hipEventCreate(&e1));
-  CK(hipFuncSetAttribute((const void*)k_loop<LEVEL, WINDOW>, hipFuncAttributeMaxDynamicSharedMemorySize, RING));
-  const int slices = 20000;                   // 2 x 10^4 slices of 32: about 10-20 ms per launch
-  k_loop<LEVEL, WINDOW><<<256, 512, RING>>>(out, src, src_elems, 2000);
+  auto kern = k_loop<LEVEL, WINDOW, NW, TM, TN>;
+  CK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, RING));
+  const int slices = 20000;                   // 2 x 10^4 slices of 32: 10-20 ms per launch
+  kern<<<256, NW * 64, RING>>>(out, src, 2000);
   CK(hipDeviceSynchronize());
   float best = 1e30f, sum = 0.f;
   for (int rep = 0; rep < 5; ++rep) {
     float ms;
     CK(hipEventRecord(e0));
-    k_loop<LEVEL, WINDOW><<<256, 512, RING>>>(out, src, src_elems, slices);
+    kern<<<256, NW * 64, RING>>>(out, src, slices);
     CK(hipEventRecord(e1));
     CK(hipDeviceSynchronize());
     CK(hipEventElapsedTime(&ms, e0, e1));
     best = ms < best ? ms : best;
     sum += ms;
   }
-  const double flops = 256.0 * 8 * slices * 16 * 32 * 32 * 16 * 2;
-  printf("%s: %.1f TFLOP/s mean of 5, %.1f best\n", what, flops * 5 / sum / 1e9, flops / best / 1e9);
+  const double flops = 256.0 * NW * slices * 2.0 * TM * TN * 32 * 32 * 16 * 2;
+  printf("%-58s %7.1f TFLOP/s mean of 5, %7.1f best\n", what, flops * 5 / sum / 1e9, flops / best / 1e9);
+  return 0;
+}
+
+template <int NW, int TM, int TN>
+static int run_shape(const char* name, float* out, const __bf16* src) {
+  printf("%s, operands N(0,1) x N(0,0.02):\n", name);
+  if (run_loop<0, 1024, NW, TM, TN>("  MFMA only (operand sets rotating in registers)", out, src)) return 1;
+  if (run_loop<1, 1024, NW, TM, TN>("  + fragments read from LDS, one barrier per slice", out, src)) return 1;
+  if (run_loop<2, 16, NW, TM, TN>("  + slices copied to LDS by global_load_lds, from the L2s", out, src)) return 1;
+  if (run_loop<2, 1024, NW, TM, TN>("  + same copies, from the memory-side cache (64 MB)", out, src)) return 1;
   return 0;
 }
 
@@ -231,10 +253,8 @@ int main() {
   CK(hipMalloc(&src, src_elems * 2));
   k_fill_gauss<<<(unsigned)(src_elems / 256), 256>>>(src, src_elems, 1.0f);
   CK(hipDeviceSynchronize());
-  if (run_loop<0>("GEMM wave tile (8 waves, 128 x 64), N(0,1) x N(0,0.02) operands rotating in registers, MFMA only", out, src, src_elems)) return 1;
-  if (run_loop<1>("  + operand fragments read from LDS (6 x 16 B per lane and 8 MFMAs), one barrier per slice", out, src, src_elems)) return 1;
-  if (run_loop<2, 16>("  + 32 KB per slice copied -> LDS by global_load_lds (4 x 1 KB per wave), source served by the L2s", out, src, src_elems)) return 1;
-  if (run_loop<2, 1024>("  + the same copies, source served by the memory-side cache (64 MB window)", out, src, src_elems)) return 1;
+  if (run_shape<8, 4, 2>("8 waves of 128 x 64 (256 x 256 tile, 6 fragment reads per 8 MFMAs, 32 KB per slice)", out, src)) return 1;
+  if (run_shape<4, 4, 4>("4 waves of 128 x 128 (256 x 256 tile, 8 reads per 16 MFMAs, 32 KB per slice)", out, src)) return 1;
 
   CK(hipFuncSetAttribute((const void*)k_lds, hipFuncAttributeMaxDynamicSharedMemorySize, 65536));
   for (int stride : {72, 64}) {

@@ -26,10 +26,46 @@ def relerr(got, ref):
     return float(np.max(np.abs(got - ref))) / den
 
 
+# Per-block check next to the whole-tensor bound: a tensor is cut into blocks of BLOCK_ROWS x BLOCK_COLS (the last axis
+# is the column axis), and every block whose own largest magnitude is at least BLOCK_MIN_FRAC of the tensor's must keep
+# max|got - ref| / max|ref| OVER THE BLOCK within BLOCK_OWN_MULT x tol.  A wrong ragged edge tile of a weight gradient or
+# a wrong padded row has a block-relative error of order 1 and fails this even where its values are small against the
+# tensor's maximum; rounding noise, which scales with the tensor's typical magnitude, stays far below it.
+BLOCK_ROWS, BLOCK_COLS = 64, 256
+BLOCK_OWN_MULT = 8.0
+BLOCK_MIN_FRAC = 0.02
+
+
+def _block_max(a2, br, bc):
+    r = np.maximum.reduceat(a2, np.arange(0, a2.shape[0], br), axis=0)
+    return np.maximum.reduceat(r, np.arange(0, a2.shape[1], bc), axis=1)
+
+
+def block_relerr(got, ref):
+    """Largest block-relative error max_block(max|got - ref| / max|ref| over the block) over the blocks that carry
+    signal, and the RMS-relative error of the whole tensor."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    g2 = got.reshape(1, -1) if got.ndim < 2 else got.reshape(-1, got.shape[-1])
+    r2 = ref.reshape(g2.shape)
+    diff = np.abs(g2 - r2)
+    rms = float(np.sqrt(np.mean(diff * diff)) / max(np.sqrt(np.mean(r2 * r2)), 1e-30))
+    eb = _block_max(diff, BLOCK_ROWS, BLOCK_COLS)
+    mb = _block_max(np.abs(r2), BLOCK_ROWS, BLOCK_COLS)
+    live = mb >= BLOCK_MIN_FRAC * max(float(mb.max()), 1e-30)
+    worst = float(np.max(eb[live] / mb[live])) if np.any(live) else 0.0
+    return worst, rms
+
+
 def check(name, got, ref, tol, errors):
+    """Gate: whole-tensor max-norm relative error <= tol.  Hardening: every block with signal within BLOCK_OWN_MULT x tol
+    of its own maximum.  Logged in `errors`: (name, max-norm relative, worst block-relative, RMS-relative)."""
     e = relerr(got, ref)
-    errors.append((name, e))
+    eb, rms = block_relerr(got, ref)
+    errors.append((name, e, eb, rms))
     assert e <= tol, f"{name}: max-norm relative error {e:.3e} > {tol:.1e}"
+    assert eb <= BLOCK_OWN_MULT * tol, (f"{name}: a {BLOCK_ROWS}x{BLOCK_COLS} block is off by {eb:.3e} of its own "
+                                        f"maximum (> {BLOCK_OWN_MULT:g} x {tol:.1e}); whole-tensor error {e:.3e}")
 
 
 def make_stack_model(cfg, n_layers, scale=8.0, dropout=None, seed=0, base_seed=5, offsets=None, round_bf16=False):

@@ -452,3 +452,20 @@ def test_post_ln_layer_against_library_autograd_and_finite_differences():
         plain[k] = np.zeros_like(inp[k])
     cp = O.forward_post_ln(plain, spec)
     assert np.max(np.abs(cp["X1"].mean(axis=-1))) < 1e-12 and np.max(np.abs(cp["X2"].mean(axis=-1))) < 1e-12
+
+
+def test_block_check_catches_a_wrong_low_magnitude_edge_tile():
+    """The parity helper's per-block bound: an edge tile that is 30 % off but 17 x smaller than the tensor's maximum
+    passes the whole-tensor max-norm bound and must fail the block bound; a uniformly rounded tensor passes both."""
+    from helpers import check
+    rng = np.random.default_rng(0)
+    ref = rng.standard_normal((1000, 700))
+    ref[960:, 512:] *= 0.06
+    good = ref * (1 + 1e-3 * rng.standard_normal(ref.shape))
+    errs = []
+    check("rounded", good, ref, 2e-2, errs)
+    assert errs[0][1] < 2e-2 and errs[0][2] < 2e-2 and errs[0][3] < 2e-3
+    bad = good.copy()
+    bad[960:, 512:] *= 0.7
+    with pytest.raises(AssertionError, match="block"):
+        check("edge", bad, ref, 2e-2, errs)
