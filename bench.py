@@ -27,6 +27,10 @@ if ROOT not in sys.path:
 METRIC = "layer-shard fwd+bwd TFLOP/s (bf16) and % MFMA peak, 8.3B-shape 1/8 shard"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (published)
 PEAK_HBM_GBS = 8000.0
+# The matrix pipe alone on this chip, measured: back-to-back v_mfma_f32_32x32x16_bf16 on normally distributed operands
+# that change every instruction, no memory traffic (csrc/tools/microbench.hip; profiles/mfma_lds_microbench.txt).
+# Loop-constant operands reach 2.03-2.08 PFLOP/s with the same loop: the difference is clock lost to switching power.
+MEASURED_MFMA_TFLOPS = 1757.0
 
 
 def shard_flops(cfg, causal_algorithmic=True):
@@ -42,9 +46,9 @@ def shard_flops(cfg, causal_algorithmic=True):
     return 3.0 * fwd, gemm(T, H, Vl)
 
 
-def cpu_baseline(cfg, sample_b=4):
-    """Time the fp64 oracle (as it stands) on the host cores on a bounded sample: the UNSHARDED layer + loss of the
-    same model shape with batch `sample_b` (all p shards' work for that batch)."""
+def cpu_baseline(cfg, sample_b=None):
+    """Time the fp64 oracle (as it stands) on the host cores: the UNSHARDED layer + loss of the same model shape at the
+    full batch (all p shards' work; about 20 s on the box's 16 cores)."""
     import numpy as np
     from oracle import layer_oracle as O
     from paper_1909_08053_amd import synth
@@ -53,6 +57,7 @@ def cpu_baseline(cfg, sample_b=4):
         threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
+    sample_b = cfg.b if sample_b is None else sample_b
     small = synth.with_batch(cfg, sample_b)
     inp = synth.make_inputs(small)
     spec = O.Spec(b=small.b, s=small.s, H=small.H, h=small.h, F=small.F, V=small.V, causal=small.causal,
@@ -64,17 +69,104 @@ def cpu_baseline(cfg, sample_b=4):
     flops = O.model_flops(spec, p=1)["fwd_bwd"]
     assert np.isfinite(c["loss"]) and np.all(np.isfinite(g["dX"]))
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"unsharded {cfg.name} layer+loss fwd+bwd in fp64, batch {sample_b} of {cfg.b} "
+            "sample": f"unsharded {cfg.name} layer+loss fwd+bwd in fp64, batch {sample_b} of {cfg.b} (nothing extrapolated) "
                       f"({flops / 1e12:.3f} model TFLOP in {dt:.1f} s)", "seconds": dt}
+
+
+# Work of every call of one benchmark step, for the per-call table: ("flop", model flops) for the calls that hold the
+# MFMA kernels, ("byte", algorithmic bytes: every tensor read or written once) for the bandwidth-bound row kernels.
+def call_work(cfg):
+    T, H, d, p = cfg.T, cfg.H, cfg.H // cfg.h, cfg.p
+    hl, Fl, Vl = cfg.h // p, cfg.F // p, cfg.V // p
+    Hl = hl * d
+    gemm = lambda M, K, N: 2.0 * M * K * N
+    att = 2.0 * (2.0 * cfg.b * hl * cfg.s * cfg.s * d) * (0.5 if cfg.causal else 1.0)
+    TH = T * H * 2.0
+    return [
+        ("mlm_layernorm_fwd", "F1 layer norm 1", "byte", 2 * TH),
+        ("mlm_attn_shard_fwd", "F2-F4 QKV GEMM + attention + projection GEMM", "flop",
+         gemm(T, H, 3 * Hl) + att + gemm(T, Hl, H)),
+        ("mlm_combine_layernorm_fwd", "F5+F6 reduction + bias + residual + layer norm 2", "byte", 4 * TH),
+        ("mlm_mlp_shard_fwd", "F7-F8 FC1 GEMM + bias + GeLU, FC2 GEMM", "flop", gemm(T, H, Fl) + gemm(T, Fl, H)),
+        ("mlm_combine_layernorm_fwd", "F9+F10 reduction + bias + residual + final layer norm", "byte", 4 * TH),
+        ("mlm_vocab_ce_shard_fwd", "F11 logits GEMM + cross-entropy partials (+ tail fix-up, tile merge)", "flop",
+         gemm(T, H, Vl)),
+        ("mlm_vocab_ce_merge", "F12 loss merge", "byte", 7 * T * 4.0),
+        ("mlm_vocab_ce_shard_bwd", "B1 dlogits + dE GEMM + dHf GEMM", "flop", 2 * gemm(T, H, Vl)),
+        ("mlm_combine_layernorm_bwd", "B2 reduction + final layer norm backward (+ column sums)", "byte", 3 * TH),
+        ("mlm_mlp_shard_bwd_input", "B3-B5 dG GEMM + GeLU', da, dU2 GEMM", "flop", gemm(T, H, Fl) + gemm(T, Fl, H)),
+        ("mlm_combine_layernorm_bwd", "B6 reduction + layer norm 2 backward + residual (+ column sums)", "byte", 4 * TH),
+        ("mlm_attn_shard_bwd_input", "B7-B9 dC GEMM, attention backward, dbqkv, dU GEMM", "flop",
+         gemm(T, H, Hl) + 2 * att + gemm(T, 3 * Hl, H)),
+        ("mlm_layer_shard_wgrads", "B3,B5,B7,B9 weight gradients dB, dA, dWqkv, dWo", "flop",
+         gemm(T, H, Fl) + gemm(T, Fl, H) + gemm(T, H, 3 * Hl) + gemm(T, Hl, H)),
+        ("mlm_combine_layernorm_bwd", "B10 reduction + layer norm 1 backward + residual (+ column sums)", "byte", 4 * TH),
+    ]
+
+
+def per_call_table(L, P, cfg, steps):
+    """Event brackets around every library call of `steps` extra steps (outside the timed region): median duration of
+    each call position, its algorithmic rate, and the sums over the MFMA calls and over the row-kernel calls."""
+    import torch
+    work = call_work(cfg)
+    names = sorted(set(w[0] for w in work))
+    orig = {n: getattr(P.B, n) for n in names}
+    rec = []
+
+    def wrap(name):
+        def f(*a, **k):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            orig[name](*a, **k)
+            e1.record()
+            rec.append((name, e0, e1))
+        return f
+
+    for n in names:
+        setattr(P.B, n, wrap(n))
+    per_pos = [[] for _ in work]
+    try:
+        for _ in range(steps):
+            rec.clear()
+            L.step()
+            torch.cuda.synchronize()
+            if [r[0] for r in rec] != [w[0] for w in work]:
+                return None                      # another call sequence (other options than the benchmark's): no table
+            for i, (_, e0, e1) in enumerate(rec):
+                per_pos[i].append(e0.elapsed_time(e1))
+    finally:
+        for n in names:
+            setattr(P.B, n, orig[n])
+    calls, mf_ms, mf_fl, row_ms, row_by = [], 0.0, 0.0, 0.0, 0.0
+    for (name, what, kind, w), v in zip(work, per_pos):
+        ms = sorted(v)[len(v) // 2]
+        if kind == "flop":
+            calls.append({"call": name, "what": what, "ms": round(ms, 4), "TFLOP/s": round(w / ms / 1e9, 1)})
+            mf_ms += ms
+            mf_fl += w
+        else:
+            calls.append({"call": name, "what": what, "ms": round(ms, 4), "GB/s": round(w / ms / 1e6, 1)})
+            if name != "mlm_vocab_ce_merge":
+                row_ms += ms
+                row_by += w
+    return {"calls": calls,
+            "mfma_calls": {"ms": round(mf_ms, 4), "TFLOP/s": round(mf_fl / mf_ms / 1e9, 1),
+                           "frac_of_bf16_mfma_peak": round(mf_fl / mf_ms / 1e9 / PEAK_BF16_TFLOPS, 4),
+                           "note": "sum over the seven calls that hold the GEMM and attention kernels; their brackets "
+                                   "also hold the small kernels those calls launch (dlogits, column sums, fix-ups)"},
+            "row_calls": {"ms": round(row_ms, 4), "GB/s": round(row_by / row_ms / 1e6, 1),
+                          "frac_of_hbm_peak": round(row_by / row_ms / 1e6 / PEAK_HBM_GBS, 4),
+                          "note": "layer-norm forward / backward calls incl. their column-sum finishing launch"}}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="gpt2_8p3b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-call-table", action="store_true", help="skip the per-call event table (10 extra untimed steps)")
     ap.add_argument("--breakdown", action="store_true", help="print per-call timings to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run three plain [T,H] copies (mlm_combine with one partial) so that a "
@@ -97,8 +189,8 @@ def main():
     torch.cuda.synchronize()
 
     # The dominant kernel (logits GEMM fused with the cross-entropy partials) is timed live, inside the timed steps,
-    # with events recorded on the launch stream around the one call that enqueues it (the bracket also holds that
-    # GEMM's tail fix-up kernel and the few-microsecond partial-merge kernel of the same call).
+    # with events recorded on the launch stream around the one call that enqueues it.  That bracket holds three
+    # launches: the GEMM, the fix-up of its split last round and the few-microsecond merge of the per-tile partials.
     from paper_1909_08053_amd import pipeline as P
     ce_events = []
     real_ce_fwd = B.mlm_vocab_ce_shard_fwd
@@ -131,18 +223,22 @@ def main():
     periods = sorted(ce_events[i][0].elapsed_time(ce_events[i + 1][0]) for i in range(len(ce_events) - 1))
     step_ms = ({"median": periods[len(periods) // 2], "min": periods[0], "max": periods[-1]} if periods else None)
     achieved = logits_flops / (k_ms * 1e-3) / 1e12
-    traffic = None
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get(args.config, {}).get("logits_ce_fwd_bytes")
+            traffic_src = ("profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the GEMM kernel of this "
+                           "call, scaled by a copy of known size (not re-measured in this run)")
         except Exception:
             traffic = None
     roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
-                "kernel": "gemm_bf16_v2_kernel<true,false,EPI_CE,8> (logits GEMM + cross-entropy partials)",
-                "kernel_ms": k_ms, "flops_per_launch": logits_flops}
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
+                "kernel": "gemm_bf16_v2_kernel<true,false,EPI_CE,8> (logits GEMM + cross-entropy partials), timed as "
+                          "the whole mlm_vocab_ce_shard_fwd call: + gemm_v2_fixup_kernel<EPI_CE> + ce_tile_merge_kernel",
+                "kernel_ms": k_ms, "launches_in_bracket": 3, "flops_per_launch": logits_flops}
 
+    table = None if args.no_call_table else per_call_table(L, P, cfg, 10)
     if args.breakdown:
         breakdown(L, B, cfg)
     if args.copy_calibration:
@@ -158,8 +254,12 @@ def main():
                                   f"{cfg.h // cfg.p} d={cfg.H // cfg.h} F_local={cfg.F // cfg.p} V_local={cfg.V // cfg.p}, "
                                   f"causal={cfg.causal}, fwd+bwd layer shard + vocab-parallel CE",
                       "model_tflop_per_step": flops / 1e12, "dense_equivalent_tflop_per_step": dense_flops / 1e12,
-                      "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS, "loss": loss},
+                      "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
+                      "frac_of_measured_mfma_peak": value / MEASURED_MFMA_TFLOPS,
+                      "measured_mfma_peak_tflops": MEASURED_MFMA_TFLOPS, "loss": loss},
            "roofline": roofline, "step_ms": step_ms}
+    if table is not None:
+        out.update(table)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
