@@ -38,7 +38,7 @@ bool gemm_use_v2(const GemmArgs& a) {
     const char* e = getenv("MLM_GEMM_V2");
     enabled = (e && atoi(e) == 0) ? 0 : 1;
   }
-  return enabled && a.K % 64 == 0 && a.K >= 64;
+  return enabled && a.K % 32 == 0 && a.K >= 64;
 }
 
 // Waves per workgroup of the 256 x 256 tile: 8 (two per SIMD) wherever a k-contiguous operand is involved; the

@@ -12,7 +12,10 @@
 //     slice are pulled into registers half a slice ahead, so its stage is re-armed while it is still being
 //     multiplied: three slices are in flight and one is landed, about 3500 MFMA clocks of prefetch distance,
 //     one barrier per slice.
-// Requirements: K % 64 == 0 (the dispatcher falls back to the register-staged kernel otherwise).
+// Requirements: K % 32 == 0 and K >= 64 (the dispatcher falls back to the register-staged kernel otherwise).  k is
+// walked in pairs of 32-deep slices; when K is an odd multiple of 32 the LAST pair starts at K - 64, i.e. it overlaps
+// the pair before it by one slice, and the MFMAs of its first (already counted) slice are skipped: every copy stays
+// inside the operand and the instruction stream of the steady state is unchanged.
 //
 // Tail split: when the tile count does not fill a whole number of rounds of the 256 CUs, the tiles of the last
 // partial round are split along k into f pieces (f = floor(256 / remainder)); each piece writes an fp32 partial
@@ -76,7 +79,7 @@ struct V2Src {
   // copy count -- and with it the vmcnt bookkeeping -- uniform)
   static constexpr int LAST = KC ? (1 << 20) : ROWS / 16 - 1;
   const bf16* p[NP];
-  size_t step;     // elements to advance per pair (KC) / per slice (MN)
+  size_t step;     // elements to advance per 32-deep k-slice
   __device__ __forceinline__ void init(const bf16* P, int ld, int row0, int nrows, int k_begin, int wave, int lane) {
     if (KC) {
 #pragma unroll
@@ -85,7 +88,7 @@ struct V2Src {
         const int u = (lane & 7) ^ v2_kc_swizzle(row);
         p[q] = P + (size_t)min(row0 + row, nrows - 1) * ld + k_begin + u * 8;
       }
-      step = 2 * V2_BK;
+      step = V2_BK;
     } else {
       // unit u of k-row holds row-chunk u ^ v2_mn_swizzle(k)
 #pragma unroll
@@ -98,14 +101,14 @@ struct V2Src {
       step = (size_t)V2_BK * ld;
     }
   }
-  // dst: LDS byte address of the pair's (KC) / slice's (MN) buffer; idx: pair / slice index relative to k_begin;
-  // wave_u: wave index as a uniform (SGPR) value
-  __device__ __forceinline__ void issue_one(uint32_t dst, int wave_u, int idx, int q) const {
-    dma16(p[q] + (size_t)idx * step, dst + min(wave_u * NP + q, LAST) * 1024);
+  // dst: LDS byte address of the pair's (KC) / slice's (MN) buffer; ks: first 32-deep k-slice of the pair / the slice,
+  // relative to k_begin; wave_u: wave index as a uniform (SGPR) value
+  __device__ __forceinline__ void issue_one(uint32_t dst, int wave_u, int ks, int q) const {
+    dma16(p[q] + (ptrdiff_t)ks * (ptrdiff_t)step, dst + min(wave_u * NP + q, LAST) * 1024);
   }
-  __device__ __forceinline__ void issue(uint32_t dst, int wave_u, int idx) const {
+  __device__ __forceinline__ void issue(uint32_t dst, int wave_u, int ks) const {
 #pragma unroll
-    for (int q = 0; q < NP; ++q) issue_one(dst, wave_u, idx, q);
+    for (int q = 0; q < NP; ++q) issue_one(dst, wave_u, ks, q);
   }
 };
 
@@ -159,7 +162,7 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B, bool
   p.tiles_n = (N + bn - 1) / bn;
   const int tiles = p.tiles_m * p.tiles_n;
   const int rem = tiles % V2_CUS;
-  const int nk = K / V2_BK;                           // even: K is a multiple of 64
+  const int nk = 2 * ((K / V2_BK + 1) / 2);           // slices walked: pairs of 32 (an odd count repeats one slice)
   const double fixed = v2_tile_fixed(bn), per_slice = v2_slice_cost(bn, b_mn);
   int split = 1;
   double tail = rem ? fixed + per_slice * nk : 0.0;   // unsplit tail round
@@ -211,10 +214,17 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
   // share an XCD (congruent mod 8) share tile rows, so each XCD's L2 sees few distinct operand panels.
   const int tile_m = vt % plan.tiles_m, tile_n = vt / plan.tiles_m;
   const int m0 = tile_m * V2_B, n0 = tile_n * BN;
-  const int np_total = a.K / (2 * V2_BK);            // k is walked in pairs of 32-deep slices
+  const int ns_total = a.K / V2_BK;                  // 32-deep k-slices of the problem
+  const int np_total = (ns_total + 1) / 2;           // k is walked in pairs of slices
   const int kt_begin = 2 * (int)((long)np_total * piece / npieces);
   const int kt_end = 2 * (int)((long)np_total * (piece + 1) / npieces);
   const int nk = kt_end - kt_begin;                  // even, >= 2
+  // Odd slice count: the last pair of the problem starts one slice early (at K - 64) and its first slice, which the
+  // pair before it has already multiplied, is skipped.  shift = 1 for the piece that holds that pair.
+  const int shift = (kt_end > ns_total) ? 1 : 0;
+  // first k-slice (relative to kt_begin) of walked slice kt / of walked pair pr
+  auto slice_of = [&](int kt) { return kt - (kt >= nk - 2 ? shift : 0); };
+  auto pair_of = [&](int pr) { return 2 * pr - (pr == nk / 2 - 1 ? shift : 0); };
 
   V2Src<A_KC, NPA> sa;
   V2Src<B_KC, NPB, BN> sb;
@@ -240,12 +250,12 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
   const int last_pair = nk / 2 - 1, last_slice = nk - 1;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    if (A_KC) sa.issue(ldsA + h * 2 * V2_OP_BYTES, wave_u, min(h, last_pair));
-    if (B_KC) sb.issue(ldsB + h * 2 * OPB_B, wave_u, min(h, last_pair));
+    if (A_KC) sa.issue(ldsA + h * 2 * V2_OP_BYTES, wave_u, pair_of(min(h, last_pair)));
+    if (B_KC) sb.issue(ldsB + h * 2 * OPB_B, wave_u, pair_of(min(h, last_pair)));
 #pragma unroll
     for (int s = 2 * h; s < 2 * h + 2; ++s) {
-      if (!A_KC) sa.issue(ldsA + s * V2_OP_BYTES, wave_u, min(s, last_slice));
-      if (!B_KC) sb.issue(ldsB + s * OPB_B, wave_u, min(s, last_slice));
+      if (!A_KC) sa.issue(ldsA + s * V2_OP_BYTES, wave_u, slice_of(min(s, last_slice)));
+      if (!B_KC) sb.issue(ldsB + s * OPB_B, wave_u, slice_of(min(s, last_slice)));
     }
   }
   // Software pipeline over half-slices (16 k each).  The operand registers of the NEXT half are read from LDS while
@@ -274,8 +284,10 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
 #pragma unroll
   for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC, BN>(ringB, 0, wn0 + i * 32, 0, lane);
 
-  // one 32-deep slice; PAR = parity of kt (compile time: it fixes the ring stage bits and the copy schedule)
-  auto slice = [&](auto par_c, int kt) {
+  // one 32-deep slice; PAR = parity of kt (compile time: it fixes the ring stage bits and the copy schedule);
+  // live: false for the slice that repeats one multiplied already (odd slice count): everything but its MFMAs runs.
+  // It is a compile-time true in the steady-state loop and a wave-uniform flag (scalar branches) in the peeled last pair.
+  auto slice = [&](auto par_c, auto live, int kt) {
     constexpr int PAR = decltype(par_c)::value;
     const int stage = kt & (V2_STAGES - 1);
     // First half.  Order pinned with scheduling barriers: one MFMA first (its operands were read half a slice ago,
@@ -285,7 +297,7 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
     // either hoists them above the loop-top wait or sinks them to the barrier; both expose their full latency.)
 #pragma unroll
     for (int idx = 0; idx < NMF; ++idx) {
-      acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / TM], fa0[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
+      if (live) acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / TM], fa0[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
       if (idx >= 1 && idx - 1 < TM + TN) {
         const int q = idx - 1;
         __builtin_amdgcn_sched_barrier(0);
@@ -305,14 +317,14 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
     // re-arm the freed stage(s) spread evenly between the MFMAs.
     const int nstage = (kt + 1) & (V2_STAGES - 1);
     constexpr int NC = PAR == 0 ? EV : OD;                 // copies to issue in this half
-    const int pair_idx = min((kt + 3) >> 1, last_pair);    // PAR == 1: the pair two ahead of this slice's pair
+    const int pair_idx = pair_of(min((kt + 3) >> 1, last_pair));   // PAR == 1: the pair two ahead of this slice's pair
     const uint32_t pair_sel = (uint32_t)(((kt + 3) >> 1) & 1);
     const uint32_t pair_off_a = pair_sel * (2 * V2_OP_BYTES), pair_off_b = pair_sel * (2 * OPB_B);
-    const int slice_idx = min(kt + V2_STAGES, last_slice);
+    const int slice_idx = slice_of(min(kt + V2_STAGES, last_slice));
     const uint32_t slice_off_a = (uint32_t)stage * V2_OP_BYTES, slice_off_b = (uint32_t)stage * OPB_B;
 #pragma unroll
     for (int idx = 0; idx < NMF; ++idx) {
-      acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[idx / TM], fa1[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
+      if (live) acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[idx / TM], fa1[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       if (idx < TM + TN) {
         const int q = idx;
@@ -337,10 +349,14 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  for (int kt = 0; kt < nk; kt += 2) {
-    slice(std::integral_constant<int, 0>{}, kt);
-    slice(std::integral_constant<int, 1>{}, kt + 1);
+  typedef std::integral_constant<int, 0> c0_t;
+  typedef std::integral_constant<int, 1> c1_t;
+  for (int kt = 0; kt < nk - 2; kt += 2) {
+    slice(c0_t{}, std::true_type{}, kt);
+    slice(c1_t{}, std::true_type{}, kt + 1);
   }
+  slice(c0_t{}, shift == 0, nk - 2);                  // odd slice count: this one repeats slice nk - 3, copies only
+  slice(c1_t{}, std::true_type{}, nk - 1);
   // The ring is kept full to the end, so copies of the (clamped) last slice are still in flight here.  They were
   // issued from inline assembly, which the compiler's wait-count tracking does not see: wait for them explicitly
   // before the epilogue reuses the ring's memory for its staging strips.

@@ -110,7 +110,7 @@ class LayerShards:
         cfg, dev, dt, f32 = self.cfg, self.dev, self.dt, torch.float32
         idx = torch.nonzero(self.rep["w"] > 0).reshape(-1).to(torch.int32)
         n = int(idx.numel())
-        n_pad = max(8, (n + 7) // 8 * 8)
+        n_pad = max(64, (n + 63) // 64 * 64)      # k of the dE GEMM: a multiple of 32 keeps it on the direct-to-LDS kernel
         self.n_rows, self.n_pad = n, n_pad
         self.rep["row_idx"] = idx.contiguous()
         tgt_c = torch.zeros(n_pad, device=dev, dtype=torch.int32)

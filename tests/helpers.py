@@ -32,7 +32,7 @@ def relerr(got, ref):
 # a wrong padded row has a block-relative error of order 1 and fails this even where its values are small against the
 # tensor's maximum; rounding noise, which scales with the tensor's typical magnitude, stays far below it.
 BLOCK_ROWS, BLOCK_COLS = 64, 256
-BLOCK_OWN_MULT = 8.0
+BLOCK_OWN_MULT = 4.0
 BLOCK_MIN_FRAC = 0.02
 
 

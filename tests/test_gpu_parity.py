@@ -23,7 +23,9 @@ def _dn(t):
 
 # ------------------------------------------------------------------ GEMM building block
 GEMM_SHAPES = [(256, 256, 256), (512, 384, 192), (264, 136, 72), (1000, 520, 328), (128, 1152, 3072 // 4),
-               (8, 8, 8), (1032, 952, 640), (72, 7648, 136)]
+               (8, 8, 8), (1032, 952, 640), (72, 7648, 136),
+               # K an odd multiple of 32 (the last pair of k-slices overlaps the one before it): shortest, short, long
+               (264, 200, 96), (520, 264, 160), (136, 520, 7648), (296, 392, 2016)]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
