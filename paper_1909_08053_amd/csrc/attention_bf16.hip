@@ -121,7 +121,6 @@ struct ATileSrc {
 // Workgroup = 128 queries of one (batch, head), 4 waves of 32 queries.  K and V tiles of 64 keys stream through a
 // three-stage LDS ring filled by DMA two tiles ahead; per tile: S^T = K Q^T (12 MFMAs at d = 96), online softmax in
 // registers, O^T += V^T P^T with V read through the transposing LDS loads (12 MFMAs).  One barrier per tile.
-constexpr int ANST = 3;             // ring stages of the one-group kernel (dK/dV)
 // Forward and dQ run TWO wave groups (8 waves) per 128 owned rows: group g takes the streamed tiles 2j + g, each
 // group has its own DMA ring, and the groups' partial results are merged through LDS at the end.  That halves the
 // serial chain of the longest (causal) blocks and puts two waves on every SIMD, so one wave's exp2 / VALU work
@@ -131,6 +130,11 @@ constexpr int ANST = 3;             // ring stages of the one-group kernel (dK/d
 template <int D> constexpr int attn_groups() { return D > 128 ? 1 : 2; }
 template <int D> constexpr int group_stages() { return D == 128 ? 2 : 3; }
 template <int D> constexpr int dkv_dsplit() { return D >= 128 ? 2 : 1; }
+// dK/dV: two wave groups (alternate query tiles, merged through LDS at the end) for the head sizes whose registers
+// allow two waves per SIMD once the wave's own K / V rows are kept in LDS instead of registers; ring stages per group
+// by the LDS budget (rings + the 128 owned K and V rows).
+template <int D> constexpr int dkv_groups() { return D <= 96 ? 2 : 1; }
+template <int D> constexpr int dkv_stages() { return D == 96 ? 2 : 3; }
 
 // (two waves per SIMD requested: with at most 256 registers per lane the MFMA accumulators live in ordinary VGPRs, so
 // the softmax arithmetic needs no accumulator-register moves)
@@ -491,19 +495,25 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
 }
 
 // ------------------------------------------------------------------------------------------ backward: dK, dV
-// Workgroup = 128 keys of one (batch, head), a wave owns 32 keys (K and V rows in registers).  Q and dO tiles of 64
-// queries stream through the DMA ring together with the tile's log-sum-exp (log2 units) and delta vectors, which
-// the dQ kernel left in the workspace.  Per 32-query half tile: S = Q K^T and dP = dO V^T (contraction along D),
-// P = exp2(S sc - lse), dS = P o (dP - delta), then dV^T += dO^T P and dK^T += Q^T dS with Q and dO read a second
-// time through the transposing loads.
-// (No two-waves-per-SIMD request here: with the 256-register cap the dK / dV accumulators spill, which was measured
-// twice as slow as letting them live in the accumulation registers.)
+// Workgroup = 128 keys of one (batch, head), a wave owns 32 keys.  Q and dO tiles of 64 queries stream through the DMA
+// ring together with the tile's log-sum-exp (log2 units) and delta vectors, which the dQ kernel left in the workspace.
+// Per 32-query half tile: S = Q K^T and dP = dO V^T (contraction along D), P = exp2(S sc - lse), dS = P o (dP - delta),
+// then dV^T += dO^T P and dK^T += Q^T dS with Q and dO read a second time through the transposing loads.
+// Head sizes up to 96 run TWO wave groups (8 waves, two per SIMD): group g takes the query tiles 2 j + g through its own
+// ring and the groups' dK / dV sums are added through LDS at the end, which halves the serial chain of the key blocks
+// with the most queries (for causal masks block 0 streams every query tile and sets the kernel's duration).  Two waves
+// per SIMD leave 256 registers per lane, so the wave's own K and V rows are not held in registers there: the block's
+// 128 K and V rows are copied to LDS once and their fragments are read per use.
+// Larger heads keep one group (their accumulators alone need more registers) and split the D columns of dK / dV over
+// two workgroups instead.
 template <int D, bool DROP>
-__global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(dkv_groups<D>() * ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   typedef ATile<D> TL;
   constexpr int BKB = 32 * ANW, VEC = 2 * ATILE * 4;          // VEC: bytes of the lse + delta vectors of a tile
   constexpr int KBB = DROP ? ATILE * 16 : 0;                  // keep bits of the tile: 64 queries x 128 keys
   constexpr int STAGE = 2 * TL::BYTES + VEC + KBB, LPT = 2 * TL::QPW + 1 + (DROP ? 1 : 0);
+  constexpr int NG = dkv_groups<D>(), NST = dkv_stages<D>();
+  constexpr bool OWN_LDS = NG == 2;                           // own K / V rows in LDS (after the rings)
   // Large heads: the dK / dV accumulators of all D columns plus the owned K / V rows do not fit the register file
   // (they spilled: 2.3x / 5.6x the d = 96 time at d = 128 / 192).  Two workgroups then share a key block, each
   // accumulating one half of the D columns of dK and dV (the scores are computed by both); this also doubles the
@@ -511,7 +521,9 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   constexpr int DS = dkv_dsplit<D>(), DH = D / DS;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lh = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known wave-uniform: mask tests become scalar branches
+  // known wave-uniform: mask tests become scalar branches
+  const int grp = NG == 1 ? 0 : __builtin_amdgcn_readfirstlane(tid >> 8);   // wave group: even / odd query tiles
+  const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);         // wave inside its group: 32 keys
   const AttnBlock blk = attn_block(((a.s + 32 * ANW - 1) / (32 * ANW)) * DS, a.hl, a.b);
   if (!blk.valid) return;
   const int kb = blk.xb / DS;                      // key block; for causal, block 0 has the most queries: first
@@ -522,9 +534,22 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   const int klen = attn_key_len(a.key_len, bi, a.s);
   const int kb0 = kb * BKB, kw0 = kb0 + wave * 32, kj = kw0 + l32;
   const int kc = min(kj, a.s - 1);
+  ATileSrc<D> src;
+  src.init(wave, lane);
+  const uint32_t lds0 = lds_offset_of(lds_raw);
 
-  bf16x8 kf[D / 16], vf[D / 16];
-  {
+  // the block's own K and V rows: registers (one group) or two 64-row tiles each in LDS (two groups; rows past the
+  // end of the sequence repeat the last row, exactly as the register path clamps them)
+  bf16x8 kf[OWN_LDS ? 1 : D / 16], vf[OWN_LDS ? 1 : D / 16];
+  const unsigned char* ownK = lds_raw + NG * NST * STAGE;
+  const unsigned char* ownV = ownK + 2 * TL::BYTES;
+  if (OWN_LDS) {
+    // group 0 copies the K rows, group 1 the V rows (two tiles of 64 rows each)
+    const bf16* P = base + ((grp == 0 ? a.hl : 2 * a.hl) + hd) * D;
+    const uint32_t dst = lds0 + NG * NST * STAGE + grp * 2 * TL::BYTES;
+    src.issue(P, ld, kb0, a.s, dst, wave);
+    src.issue(P, ld, kb0 + ATILE, a.s, dst + TL::BYTES, wave);
+  } else {
     const bf16* krow = base + (size_t)kc * ld + (a.hl + hd) * D;
     const bf16* vrow = base + (size_t)kc * ld + (2 * a.hl + hd) * D;
 #pragma unroll
@@ -533,6 +558,9 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
       vf[ks] = *reinterpret_cast<const bf16x8*>(vrow + ks * 16 + lh * 8);
     }
   }
+  const unsigned char* myK = ownK + (wave >> 1) * TL::BYTES;   // the tile that holds this wave's 32 rows, at (wave & 1) 32
+  const unsigned char* myV = ownV + (wave >> 1) * TL::BYTES;
+  const int own_r0 = (wave & 1) * 32;
   floatx16 dk[DH / 32], dv[DH / 32];
 #pragma unroll
   for (int dt = 0; dt < DH / 32; ++dt)
@@ -544,18 +572,18 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   int qt0 = a.causal ? kb0 / ATILE : 0;
   if (kb0 >= klen) qt0 = nqt;                     // every key of the block is padding: gradients are zero
   const int nt = nqt - qt0;                       // tiles to stream (block-uniform)
+  const int njt = (nt + NG - 1) / NG;             // steps: group g handles tile NG j + g in step j (if it exists)
   const bf16* Qb = base + hd * D;
   const int ldo = a.hl * D;
   const bf16* dOb = (const bf16*)a.dctx + (size_t)bi * a.s * ldo + hd * D;
   // per-query vectors in the workspace: [0] delta, [1] log-sum-exp in log2 units (both written by the dQ kernel)
   const size_t nrow_all = (size_t)a.b * a.hl * a.s;
   const float* vec_b = ((wave & 1) ? a.delta + nrow_all : a.delta) + ((size_t)bi * a.hl + hd) * a.s;
-  ATileSrc<D> src;
-  src.init(wave, lane);
-  const uint32_t lds0 = lds_offset_of(lds_raw);
+  unsigned char* ring = lds_raw + grp * (NST * STAGE);        // this group's ring
+  const uint32_t ring0 = lds0 + grp * (NST * STAGE);
   auto issue_tile = [&](int t, int st) {          // tile index relative to qt0 (clamped), ring stage
     const int r0 = (qt0 + min(t, nt - 1)) * ATILE;
-    const uint32_t sb = lds0 + st * STAGE;
+    const uint32_t sb = ring0 + st * STAGE;
     src.issue(Qb, ld, r0, a.s, sb, wave);
     src.issue(dOb, ldo, r0, a.s, sb + TL::BYTES, wave);
     // waves 0, 2 copy the delta vector, waves 1, 3 the log-sum-exp vector (same data twice: uniform copy counts)
@@ -570,21 +598,22 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   };
   if (nt > 0) {
 #pragma unroll
-    for (int t = 0; t < ANST - 1; ++t) issue_tile(t, t);
+    for (int t = 0; t < NST - 1; ++t) issue_tile(NG * t + grp, t);
   }
   int stage = 0;
-  for (int t = 0; t < nt; ++t) {
+  for (int j = 0; j < njt; ++j) {
+    const int t = NG * j + grp;
     const int q0 = (qt0 + t) * ATILE;
-    wait_vmcnt<LPT*(ANST - 2)>();
-    __builtin_amdgcn_s_barrier();
-    issue_tile(t + ANST - 1, stage == 0 ? ANST - 1 : stage - 1);
-    const unsigned char* sQ = lds_raw + stage * STAGE;
+    wait_vmcnt<LPT*(NST - 2)>();                   // this wave's copies of step j (and of the own rows) have landed
+    __builtin_amdgcn_s_barrier();                 // everyone's have; and everyone is done with step j - 1
+    issue_tile(t + NG * (NST - 1), stage == 0 ? NST - 1 : stage - 1);
+    const unsigned char* sQ = ring + stage * STAGE;
     const unsigned char* sdO = sQ + TL::BYTES;
     const float* sDl = reinterpret_cast<const float*>(sdO + TL::BYTES);
     const float* sLse = sDl + ATILE;
     const uint32_t* sBits = reinterpret_cast<const uint32_t*>(sLse + ATILE);   // [64 queries][4 words]
-    stage = stage == ANST - 1 ? 0 : stage + 1;
-    if (a.causal && q0 + ATILE - 1 < kw0) continue;   // every query of the tile precedes this wave's keys
+    stage = stage == NST - 1 ? 0 : stage + 1;
+    if (t >= nt || (a.causal && q0 + ATILE - 1 < kw0)) continue;   // no such tile / every query precedes this wave's keys
     const bool need_mask = (a.causal && q0 < kw0 + 31) || (kw0 + 32 > klen) || (q0 + ATILE > a.s);   // wave-uniform
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
@@ -593,8 +622,10 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
       for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; pacc[e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sQ, qs * 32, ks, lane), kf[ks], sacc, 0, 0, 0);    // S[query][key]
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sdO, qs * 32, ks, lane), vf[ks], pacc, 0, 0, 0);   // dP[query][key]
+        const bf16x8 kk = OWN_LDS ? TL::frag_kc(myK, own_r0, ks, lane) : kf[OWN_LDS ? 0 : ks];
+        const bf16x8 vv = OWN_LDS ? TL::frag_kc(myV, own_r0, ks, lane) : vf[OWN_LDS ? 0 : ks];
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sQ, qs * 32, ks, lane), kk, sacc, 0, 0, 0);    // S[query][key]
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_kc(sdO, qs * 32, ks, lane), vv, pacc, 0, 0, 0);   // dP[query][key]
       }
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -634,6 +665,30 @@ __global__ __launch_bounds__(ANT) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
     }
   }
   wait_vmcnt<0>();
+  // dK, dV = group 0's sums + group 1's sums (group 1 parks its accumulators in LDS: [wave][value][lane])
+  if (NG == 2) {
+    __syncthreads();
+    constexpr int NV = 2 * (DH / 32) * 16;
+    float* park = reinterpret_cast<float*>(lds_raw) + (size_t)wave * NV * 64 + lane;
+    if (grp == 1) {
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          park[(dt * 16 + e) * 64] = dk[dt][e];
+          park[((DH / 32 + dt) * 16 + e) * 64] = dv[dt][e];
+        }
+    }
+    __syncthreads();
+    if (grp == 1) return;
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        dk[dt][e] += park[(dt * 16 + e) * 64];
+        dv[dt][e] += park[((DH / 32 + dt) * 16 + e) * 64];
+      }
+  }
   if (kj < a.s) {
     bf16* krow = (bf16*)a.dqkv + ((size_t)bi * a.s + kj) * ld + (a.hl + hd) * D;
     bf16* vrow = (bf16*)a.dqkv + ((size_t)bi * a.s + kj) * ld + (2 * a.hl + hd) * D;
@@ -688,15 +743,20 @@ static hipError_t launch_bwd_dd(const AttnArgs& a, hipStream_t st) {
   hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D, DROP>), grid, dim3(attn_groups<D>() * ANT), lds_q, st, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const size_t lds_kv = (size_t)ANST * (2 * ATile<D>::BYTES + 2 * ATILE * 4 + (DROP ? ATILE * 16 : 0));
-  static_assert((size_t)ANST * (2 * ATile<D>::BYTES + 2 * ATILE * 4 + ATILE * 16) <= 160 * 1024, "LDS budget");
+  constexpr int NGK = dkv_groups<D>(), NSK = dkv_stages<D>();
+  constexpr size_t kStageKv = 2 * ATile<D>::BYTES + 2 * ATILE * 4;
+  // rings, the owned K / V rows (two groups), and at the end the parked accumulators of group 1
+  constexpr size_t kOwn = NGK == 2 ? 4 * ATile<D>::BYTES : 0, kPark = NGK == 2 ? (size_t)ANW * 2 * (D / 32) * 16 * 64 * 4 : 0;
+  static_assert((size_t)NGK * NSK * (kStageKv + ATILE * 16) + kOwn <= 160 * 1024 && kPark <= 160 * 1024, "LDS budget");
+  size_t lds_kv = (size_t)NGK * NSK * (kStageKv + (DROP ? ATILE * 16 : 0)) + kOwn;
+  if (lds_kv < kPark) lds_kv = kPark;
   if (lds_kv > 64 * 1024) {
     e = hipFuncSetAttribute((const void*)attn_bwd_dkv_bf16_kernel<D, DROP>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds_kv);
     if (e != hipSuccess) return e;
   }
   const dim3 grid_kv = attn_grid(nblk * dkv_dsplit<D>(), a.hl, a.b);
-  hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D, DROP>), grid_kv, dim3(ANT), lds_kv, st, a);
+  hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<D, DROP>), grid_kv, dim3(NGK * ANT), lds_kv, st, a);
   return hipGetLastError();
 }
 
