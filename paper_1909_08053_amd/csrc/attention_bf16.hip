@@ -133,8 +133,9 @@ template <int D> constexpr int dkv_dsplit() { return D >= 128 ? 2 : 1; }
 // dK/dV: two wave groups (alternate query tiles, merged through LDS at the end) for the head sizes whose registers
 // allow two waves per SIMD once the wave's own K / V rows are kept in LDS instead of registers; ring stages per group
 // by the LDS budget (rings + the 128 owned K and V rows).
-template <int D> constexpr int dkv_groups() { return D <= 96 ? 2 : 1; }
-template <int D> constexpr int dkv_stages() { return D == 96 ? 2 : 3; }
+template <int D> constexpr int dkv_groups() { return D <= 128 ? 2 : 1; }
+template <int D> constexpr int dkv_stages() { return (D == 96 || D == 128) ? 2 : 3; }
+template <int D> constexpr bool dkv_own_lds() { return D <= 96; }    // d = 128: half the D columns per workgroup, rows stay in registers
 
 // (two waves per SIMD requested: with at most 256 registers per lane the MFMA accumulators live in ordinary VGPRs, so
 // the softmax arithmetic needs no accumulator-register moves)
@@ -513,7 +514,7 @@ __global__ __launch_bounds__(dkv_groups<D>() * ANT) void attn_bwd_dkv_bf16_kerne
   constexpr int KBB = DROP ? ATILE * 16 : 0;                  // keep bits of the tile: 64 queries x 128 keys
   constexpr int STAGE = 2 * TL::BYTES + VEC + KBB, LPT = 2 * TL::QPW + 1 + (DROP ? 1 : 0);
   constexpr int NG = dkv_groups<D>(), NST = dkv_stages<D>();
-  constexpr bool OWN_LDS = NG == 2;                           // own K / V rows in LDS (after the rings)
+  constexpr bool OWN_LDS = NG == 2 && dkv_own_lds<D>();        // own K / V rows in LDS (after the rings)
   // Large heads: the dK / dV accumulators of all D columns plus the owned K / V rows do not fit the register file
   // (they spilled: 2.3x / 5.6x the d = 96 time at d = 128 / 192).  Two workgroups then share a key block, each
   // accumulating one half of the D columns of dK and dV (the scores are computed by both); this also doubles the
@@ -746,7 +747,8 @@ static hipError_t launch_bwd_dd(const AttnArgs& a, hipStream_t st) {
   constexpr int NGK = dkv_groups<D>(), NSK = dkv_stages<D>();
   constexpr size_t kStageKv = 2 * ATile<D>::BYTES + 2 * ATILE * 4;
   // rings, the owned K / V rows (two groups), and at the end the parked accumulators of group 1
-  constexpr size_t kOwn = NGK == 2 ? 4 * ATile<D>::BYTES : 0, kPark = NGK == 2 ? (size_t)ANW * 2 * (D / 32) * 16 * 64 * 4 : 0;
+  constexpr size_t kOwn = (NGK == 2 && dkv_own_lds<D>()) ? 4 * ATile<D>::BYTES : 0;
+  constexpr size_t kPark = NGK == 2 ? (size_t)ANW * 2 * (D / dkv_dsplit<D>() / 32) * 16 * 64 * 4 : 0;
   static_assert((size_t)NGK * NSK * (kStageKv + ATILE * 16) + kOwn <= 160 * 1024 && kPark <= 160 * 1024, "LDS budget");
   size_t lds_kv = (size_t)NGK * NSK * (kStageKv + (DROP ? ATILE * 16 : 0)) + kOwn;
   if (lds_kv < kPark) lds_kv = kPark;

@@ -8,6 +8,8 @@ namespace mlm {
 // Cost model: (number of scheduling rounds) x (tile area) / (relative efficiency of the tile shape); the larger
 // tiles reuse LDS data more per MFMA but quantise worse on small N.  MLM_GEMM_TILE=0/1/2 forces a configuration
 // (used by the tuning sweeps).
+int gemm_cu_count();
+
 int pick_tile(int M, int N, int K) {
   (void)K;
   static int forced = -2;
@@ -23,7 +25,7 @@ int pick_tile(int M, int N, int K) {
   double best_cost = 1e300;
   for (int t = 0; t < TILE_COUNT; ++t) {
     const long tiles = (long)((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]);
-    const long slots = 256L * per_cu[t];
+    const long slots = (long)gemm_cu_count() * per_cu[t];
     const long rounds = (tiles + slots - 1) / slots;
     const double cost = (double)rounds * bm[t] * bn[t] * per_cu[t] / eff[t];
     if (cost < best_cost) { best_cost = cost; best = t; }
@@ -62,6 +64,21 @@ int gemm_v2_forced_bn() {
     forced = (v == 192 || v == 256) ? v : 0;
   }
   return forced;
+}
+
+// Compute units of the current device, capped at the tail-split workspace's bound; one query per device.
+int gemm_cu_count() {
+  constexpr int kMaxDevices = 64, kCap = 256;
+  static int cached[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return kCap;
+  int n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = kCap;
+    if (n > kCap) n = kCap;
+    __atomic_store_n(&cached[dev], n, __ATOMIC_RELAXED);
+  }
+  return n;
 }
 
 int gemm_bf16_ce_col_tiles(int M, int N, int K) {

@@ -35,7 +35,10 @@ constexpr int V2_STAGES = 4;
 constexpr int V2_OP_BYTES = V2_B * V2_BK * 2;          // 16 KB per operand per stage
 constexpr int V2_REGION_BYTES = V2_STAGES * V2_OP_BYTES;   // 64 KB ring per operand: A's ring, then B's ring
 constexpr size_t V2_LDS_BYTES = (size_t)2 * V2_REGION_BYTES;          // 128 KB
-constexpr int V2_CUS = 256;
+constexpr int V2_MAX_CUS = 256;              // bound of the tail-split workspace: at most this many fp32 partial tiles
+// Compute units of the current device (tiles that run concurrently: one 128-KB workgroup per unit), capped at
+// V2_MAX_CUS; asked from the runtime once per device.
+int gemm_cu_count();
 
 // Bank swizzle of the [k][row] tile layout (XOR on the 16-byte unit index of a 512-byte k-row).  A transposing read
 // is served in two passes of 32 lanes; a pass reads 64 contiguous bytes (four units) of each of four consecutive
@@ -156,6 +159,7 @@ inline double v2_slice_cost(int bn, bool b_mn) { return bn == V2_B ? 0.78 : (b_m
 // MI355X with in-kernel timestamps: a tile costs about 5.3 (fill + epilogue) + 0.78 per 32-deep k-slice; the pieces
 // write fp32 partial tiles and the fix-up kernel (about 6 for launch + drain) reads them back, both at ~5 TB/s.
 inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B, bool b_mn = false) {
+  const int V2_CUS = gemm_cu_count();
   V2Plan p;
   p.bn = bn;
   p.tiles_m = (M + V2_B - 1) / V2_B;
@@ -514,7 +518,7 @@ __global__ __launch_bounds__(256) void gemm_v2_fixup_kernel(GemmArgs a, V2Plan p
   }
 }
 
-inline size_t v2_splitk_ws_bytes() { return (size_t)V2_CUS * V2_B * V2_B * sizeof(float); }   // 64 MB upper bound
+inline size_t v2_splitk_ws_bytes() { return (size_t)V2_MAX_CUS * V2_B * V2_B * sizeof(float); }   // 64 MB upper bound
 
 int gemm_v2_waves(bool a_kc, bool b_kc);   // 4 or 8 waves per workgroup for this operand layout
 

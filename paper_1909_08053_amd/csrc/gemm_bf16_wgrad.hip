@@ -15,6 +15,7 @@ hipError_t launch_gemm_bf16_wgrad(const GemmArgs& a, hipStream_t st) {
 // tail split, and of a set of them launched as one group without a split.
 static double wgrad_cost_alone(const GemmArgs& a) {
   const V2Plan p = v2_plan(a.M, a.N, a.K, true);
+  const int V2_CUS = gemm_cu_count();
   const int nk = 2 * ((a.K / V2_BK + 1) / 2);
   const int rounds_full = (p.full_tiles + V2_CUS - 1) / V2_CUS;
   double t = rounds_full * (5.3 + 0.78 * nk);
@@ -39,6 +40,7 @@ hipError_t launch_gemm_bf16_wgrad_group(const GemmArgs* probs, int n, float* spl
   }
   if (groupable) {
     const int nk = 2 * ((probs[0].K / V2_BK + 1) / 2);
+    const int V2_CUS = gemm_cu_count();
     const double grouped = ((tiles + V2_CUS - 1) / V2_CUS) * (5.3 + 0.78 * nk) + 2.0;
     static const bool off = [] { const char* e = getenv("MLM_GEMM_GROUP"); return e && atoi(e) == 0; }();
     if (!off && grouped < alone) return launch_gemm_bf16_v2_group_nw<false, false, 4>(probs, n, st);

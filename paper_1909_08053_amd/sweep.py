@@ -204,40 +204,9 @@ def bert_loss_rows_timing(steps, warmup, dev="cuda:0"):
         torch.cuda.empty_cache()
 
 
-def gemm_data_dependence(steps, warmup, dev="cuda:0"):
-    """The same 8192^3 bf16 GEMM launches on operands of different bit activity.  The instruction stream is identical;
-    what changes is the power drawn per MFMA, and with it the clock the chip sustains."""
-    import torch
-    from . import binding as B
-    M = N = K = 8192
-    makers = {
-        "normal(0,1)": lambda *s: torch.randn(*s, device=dev).to(torch.bfloat16),
-        "zeros": lambda *s: torch.zeros(*s, device=dev, dtype=torch.bfloat16),
-        "ones": lambda *s: torch.ones(*s, device=dev, dtype=torch.bfloat16),
-        "0/1 random": lambda *s: torch.randint(0, 2, s, device=dev).to(torch.bfloat16),
-    }
-    print(f"# mlm_gemm {M}x{N}x{K} bf16, operand data varied")
-    for name, ta, tb in (("forward layout", 0, 0), ("input-gradient layout", 0, 1), ("weight-gradient layout", 1, 0)):
-        for data, mk in makers.items():
-            A = mk(K, M) if ta else mk(M, K)
-            Bm = mk(N, K) if tb else mk(K, N)
-            C = torch.empty(M, N, device=dev, dtype=torch.bfloat16)
-            for _ in range(warmup):
-                B.mlm_gemm(B.MLM_BF16, ta, tb, M, N, K, A, Bm, C)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(steps):
-                B.mlm_gemm(B.MLM_BF16, ta, tb, M, N, K, A, Bm, C)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / steps
-            print(f"{name:24s} {data:12s} {ms * 1e3:8.1f} us  {2.0 * M * N * K / ms / 1e9:8.1f} TFLOP/s", flush=True)
-
-
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "optimizer", "gemm_data", "dropout", "stack", "bert_rows", "all"])
+    ap.add_argument("--sweep", default="all", choices=["heads", "strong_1p2b", "table1", "optimizer", "dropout", "stack", "bert_rows", "all"])
     ap.add_argument("--recompute", action="store_true",
                     help="checkpointed variant: re-run the layer's forward before its backward (activation recomputation)")
     ap.add_argument("--steps", type=int, default=20)
@@ -252,9 +221,6 @@ def main():
     names = ["heads", "strong_1p2b", "table1"] if args.sweep == "all" else [args.sweep]
     if args.sweep == "optimizer":
         optimizer_timing(args.steps, args.warmup)
-        return
-    if args.sweep == "gemm_data":
-        gemm_data_dependence(args.steps, args.warmup)
         return
     if args.sweep == "bert_rows":
         bert_loss_rows_timing(args.steps, args.warmup)
