@@ -57,15 +57,36 @@ template <> struct Vec16<bf16> {
   __device__ __forceinline__ void set(int i, float v) { raw[i] = (bf16)v; }
 };
 
+// Wave-wide reductions on the data-parallel-primitive path of the vector ALU (row shifts inside 16-lane rows, then two
+// row broadcasts): seven dependent VALU operations instead of six round trips through the LDS crossbar that a shuffle
+// butterfly costs.  The total ends up in lane 63 and is handed to every lane as a scalar.  The order of the additions
+// is fixed, so results are reproducible run to run.
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ __forceinline__ float dpp_move(float identity, float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, identity), __builtin_bit_cast(int, v),
+                                                               CTRL, ROW_MASK, BANK_MASK, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  // lanes the shift leaves without a source, and lanes masked out, take the identity 0
+  float a = v + dpp_move<0x111, 0xf, 0xf>(0.f, v);            // row_shr:1
+  a += dpp_move<0x112, 0xf, 0xf>(0.f, v);                     // row_shr:2
+  a += dpp_move<0x113, 0xf, 0xf>(0.f, v);                     // row_shr:3  -> sums of 4 consecutive lanes
+  a += dpp_move<0x114, 0xf, 0xe>(0.f, a);                     // row_shr:4  -> of 8
+  a += dpp_move<0x118, 0xf, 0xc>(0.f, a);                     // row_shr:8  -> lane 15 of each row: the row's 16
+  a += dpp_move<0x142, 0xa, 0xf>(0.f, a);                     // row_bcast:15 into rows 1 and 3
+  a += dpp_move<0x143, 0xc, 0xf>(0.f, a);                     // row_bcast:31 into rows 2 and 3 -> lane 63: all 64
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  const float ninf = -INFINITY;
+  float a = fmaxf(v, dpp_move<0x111, 0xf, 0xf>(ninf, v));
+  a = fmaxf(a, dpp_move<0x112, 0xf, 0xf>(ninf, v));
+  a = fmaxf(a, dpp_move<0x113, 0xf, 0xf>(ninf, v));
+  a = fmaxf(a, dpp_move<0x114, 0xf, 0xe>(ninf, a));
+  a = fmaxf(a, dpp_move<0x118, 0xf, 0xc>(ninf, a));
+  a = fmaxf(a, dpp_move<0x142, 0xa, 0xf>(ninf, a));
+  a = fmaxf(a, dpp_move<0x143, 0xc, 0xf>(ninf, a));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), 63));
 }
 
 // GeLU and its derivative.  tanh form: 0.5 x (1 + tanh(u)) = x sigmoid(2u) with u = sqrt(2/pi)(x + 0.044715 x^3);

@@ -278,14 +278,12 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
         }
       }
     }
-    // 2 RB independent butterflies: their shuffles overlap
+    // 2 RB independent wave reductions: their dependent chains interleave
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-#pragma unroll
-      for (int j = 0; j < RB; ++j) {
-        ps1[j] += __shfl_xor(ps1[j], o, 64);
-        ps2[j] += __shfl_xor(ps2[j], o, 64);
-      }
+    for (int j = 0; j < RB; ++j) {
+      ps1[j] = wave_sum(ps1[j]);
+      ps2[j] = wave_sum(ps2[j]);
+    }
     if (lane == 0) {
 #pragma unroll
       for (int j = 0; j < RB; ++j) { red[it & 1][j][0][wave] = ps1[j]; red[it & 1][j][1][wave] = ps2[j]; }
