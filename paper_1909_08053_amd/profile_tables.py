@@ -323,6 +323,8 @@ def sweeps(raw):
             m = re.match(r"^(\S.*?)\s+([0-9.]+) us/step", l)
             if m:
                 key = re.sub(r"\s+p=.*$", "", m.group(1)).strip()
+                if key.startswith("logits for"):
+                    key = "bert_3p9b, " + key
                 table.setdefault(key, {})[c] = float(m.group(2))
     L = ["Effect of the two schedule-level GEMM choices on every benchmark shape (one shard, forward + backward, bf16, one MI355X,",
          "one box, back to back): the grouped launch of a layer shard's weight gradients and the 256 x 192 tile, each switched off",
