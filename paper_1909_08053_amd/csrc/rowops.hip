@@ -30,6 +30,32 @@ __device__ __forceinline__ void combine_row(const PartialPtrs& ptrs, int n, cons
     return;
   }
   float acc[NV][VN];
+  if (!DROP && n == 1) {
+    // one partial (the usual case on a GPU that holds one shard): the loads of all three sources are issued before the
+    // first use, so a row costs one trip to memory instead of three; the sums are formed in the same order as below
+    // (partial, then bias, then residual), hence bit-identical
+    Vec16<T> tp[NV], tb[NV], tr[NV];
+    const T* pp = (const T*)ptrs.p[0] + row_off;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (lane + 64 * i < nvec) {
+        tp[i].load(pp + (size_t)(lane + 64 * i) * VN);
+        if (bias) tb[i].load(bias + (size_t)(lane + 64 * i) * VN);
+        if (residual) tr[i].load(residual + row_off + (size_t)(lane + 64 * i) * VN);
+      }
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (lane + 64 * i < nvec) {
+#pragma unroll
+        for (int e = 0; e < VN; ++e) {
+          float a = 0.f + tp[i].get(e);
+          if (bias) a += tb[i].get(e);
+          if (residual) a += tr[i].get(e);
+          out[i].set(e, a);
+        }
+      }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < NV; ++i)
 #pragma unroll
