@@ -184,3 +184,45 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([_sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0
     assert "ONE GPU" in (r.stderr + r.stdout)
+
+
+def test_attention_tile_walk_stays_inside_the_buffers_for_any_key_length():
+    """Host-side model of the streamed attention kernels' index arithmetic (forward / dQ: key tiles of 64 through a ring
+    kept full by re-reading the last tile; dK/dV: query tiles): with the kernels' clamp max(1, min(key_len, s)) every
+    tile index and every row index that a copy is issued for lies inside [0, s) -- for key_len = 0, negative, 1, s and
+    beyond s alike.  (Without the lower clamp key_len = 0 gives nt = 0 and a first tile index of -1.)"""
+    ATILE, BQ = 64, 128
+    for s in (8, 64, 136, 200, 1024):
+        for causal in (False, True):
+            for given in (-3, 0, 1, s - 1, s, s + 1, 10 * s):
+                klen = max(1, min(given, s))
+                assert 1 <= klen <= s
+                nqb = (s + BQ - 1) // BQ
+                for qb in range(nqb):
+                    q0 = qb * BQ
+                    kv_end = min(klen, q0 + BQ) if causal else klen
+                    nt = (kv_end + ATILE - 1) // ATILE
+                    assert nt >= 1
+                    for ng, nst in ((2, 3), (2, 2), (1, 3)):
+                        njt = (nt + ng - 1) // ng
+                        for grp in range(ng):
+                            tiles = [min(ng * t + grp, nt - 1) for t in range(nst - 1)]
+                            tiles += [min(ng * j + grp + ng * (nst - 1), nt - 1) for j in range(njt)]
+                            for t in tiles:
+                                assert 0 <= t < nt
+                                for row in (0, ATILE - 1):
+                                    r = min(t * ATILE + row, s - 1)
+                                    assert 0 <= r < s
+                # dK/dV: key blocks of 128, query tiles from the block's first tile (causal) or 0
+                nqt = (s + ATILE - 1) // ATILE
+                for kb in range((s + 127) // 128):
+                    kb0 = kb * 128
+                    qt0 = kb0 // ATILE if causal else 0
+                    if kb0 >= klen:
+                        qt0 = nqt
+                    nt = nqt - qt0
+                    assert nt >= 0
+                    for t in range(nt + 2):
+                        if nt > 0:
+                            r0 = (qt0 + min(t, nt - 1)) * ATILE
+                            assert 0 <= r0 < s and 0 <= min(r0 + 63, s - 1) < s
