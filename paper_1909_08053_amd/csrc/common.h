@@ -57,6 +57,19 @@ template <> struct Vec16<bf16> {
   __device__ __forceinline__ void set(int i, float v) { raw[i] = (bf16)v; }
 };
 
+// Vector of BYTES (16 or 8) bytes of storage elements.  The narrow form exists for kernels in which a lane owns one
+// vector of every row: half the elements per lane means twice the waves per row.
+template <typename T, int BYTES> struct VecB;
+template <typename T> struct VecB<T, 16> : Vec16<T> {};
+template <> struct VecB<bf16, 8> {
+  static constexpr int N = 4;
+  bf16x4 raw;
+  __device__ __forceinline__ void load(const bf16* p) { raw = *reinterpret_cast<const bf16x4*>(p); }
+  __device__ __forceinline__ void store(bf16* p) const { *reinterpret_cast<bf16x4*>(p) = raw; }
+  __device__ __forceinline__ float get(int i) const { return (float)raw[i]; }
+  __device__ __forceinline__ void set(int i, float v) { raw[i] = (bf16)v; }
+};
+
 // Wave-wide reductions on the data-parallel-primitive path of the vector ALU (row shifts inside 16-lane rows, then two
 // row broadcasts): seven dependent VALU operations instead of six round trips through the LDS crossbar that a shuffle
 // butterfly costs.  The total ends up in lane 63 and is handed to every lane as a scalar.  The order of the additions
@@ -66,13 +79,21 @@ __device__ __forceinline__ float dpp_move(float identity, float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, identity), __builtin_bit_cast(int, v),
                                                                CTRL, ROW_MASK, BANK_MASK, false));
 }
-__device__ __forceinline__ float wave_sum(float v) {
+// Sum over each row of 16 lanes; the total is in lane 15 of the row (the other lanes hold partial sums).
+__device__ __forceinline__ float row16_sum(float v) {
   // lanes the shift leaves without a source, and lanes masked out, take the identity 0
   float a = v + dpp_move<0x111, 0xf, 0xf>(0.f, v);            // row_shr:1
   a += dpp_move<0x112, 0xf, 0xf>(0.f, v);                     // row_shr:2
   a += dpp_move<0x113, 0xf, 0xf>(0.f, v);                     // row_shr:3  -> sums of 4 consecutive lanes
   a += dpp_move<0x114, 0xf, 0xe>(0.f, a);                     // row_shr:4  -> of 8
   a += dpp_move<0x118, 0xf, 0xc>(0.f, a);                     // row_shr:8  -> lane 15 of each row: the row's 16
+  return a;
+}
+__device__ __forceinline__ float lane_value(float v, int lane) {   // lane: compile-time or wave-uniform
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  float a = row16_sum(v);
   a += dpp_move<0x142, 0xa, 0xf>(0.f, a);                     // row_bcast:15 into rows 1 and 3
   a += dpp_move<0x143, 0xc, 0xf>(0.f, a);                     // row_bcast:31 into rows 2 and 3 -> lane 63: all 64
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), 63));

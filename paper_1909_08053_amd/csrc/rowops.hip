@@ -193,16 +193,19 @@ hipError_t launch_combine_layernorm_fwd(int dtype, int T, int H, float eps, cons
 }
 
 // ------------------------------------------------------------------------------ layer norm backward
-// Block = one wave per 64 vectors of a row (6 waves for 3072 bf16 columns); the grid has one block per
+// Block = one wave per 64 vectors of a row; the grid has one block per
 // kLnBwdRowsPerBlock rows and the rows are dealt to the blocks in batches of kLnBwdBatch, round-robin.  A lane owns
 // ONE 16-byte vector of columns in every row, so its dgamma / dbeta (/ dx column-sum) partials are a handful of
 // registers and several waves fit on a SIMD (a wave-per-row layout needs the partials of the whole row per lane:
 // ~150 registers, one wave per SIMD, and ran at half the HBM rate).  The row statistics s1 = mean(dy gamma),
 // s2 = mean(dy gamma xhat) need the whole row: every wave reduces its slab, the per-wave partials meet in LDS and are
-// added in wave order (deterministic); one barrier per batch (the exchange buffer alternates).  Everything that needs
+// added in a fixed order (deterministic); one barrier per batch (the exchange buffer alternates).  Everything that needs
 // no row statistic (dgamma, dbeta) is accumulated in the pass before the barrier; the pass after it is two fused
 // multiply-adds per element.  The next batch (and its rows' mean / rstd) is prefetched while the current one is
 // worked on.  The block's column partials go to the workspace and reduce_cols_kernel sums them over the blocks.
+// VB = bytes per lane and row.  The kernel is bound by vector-ALU issue, not by memory (in-kernel timestamps: with
+// 16-byte vectors a 3072-column bf16 row makes 6 waves, i.e. two of the four SIMDs carry two waves, and the barrier of
+// every batch waits for those two); with 8-byte vectors the same row is 12 waves of half the work, three per SIMD.
 //
 // FUSED: dy is formed on the fly as the sum of n partial tensors (stored to dy_out if that is not NULL).
 // SUM: the column sums of dx (the bias gradient of the layer that produced this layer norm's input) are accumulated
@@ -211,26 +214,30 @@ constexpr int kLnBwdBatch = 4;
 
 // DZ: also emit dz_out = dropout-mask(dx) / (1 - p) (and sum ITS columns); a template parameter so that the generator
 // costs the plain instantiations no registers.
-template <typename T, bool FUSED, bool SUM, bool DZ>
-__global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy, const T* __restrict__ x,
+template <typename T, int VB, bool FUSED, bool SUM, bool DZ>
+__global__ __launch_bounds__(VB == 8 ? 768 : 512) void ln_bwd_kernel(int rows, int H, const T* __restrict__ dy, const T* __restrict__ x,
                                                      const T* __restrict__ gamma, const float* __restrict__ mean,
                                                      const float* __restrict__ rstd, const T* residual, T* dx,
                                                      float* __restrict__ ws, PartialPtrs ptrs, int n, T* dy_out,
                                                      DropArgs drop, T* dz_out) {
-  constexpr int VN = Vec16<T>::N, RB = kLnBwdBatch, NP = SUM ? 3 : 2;
-  __shared__ __attribute__((aligned(16))) float red[2][RB][2][8];
+  typedef VecB<T, VB> V;
+  constexpr int VN = V::N, RB = kLnBwdBatch, NP = SUM ? 3 : 2;
+  static_assert(RB % 2 == 0, "two rows share one 64-lane exchange line");
+  // exchange line h of a batch: quantity q = 2 (row & 1) + {0: s1, 1: s2} of rows 2h, 2h + 1 in lanes [16 q, 16 q + 16),
+  // one slot per wave
+  __shared__ __attribute__((aligned(16))) float red[2][RB / 2][64];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int idx = threadIdx.x;                      // this lane's vector of every row
   const bool active = idx < H / VN;
   const size_t col0 = (size_t)idx * VN;
   const float invH = 1.0f / (float)H;
-  // slots of waves that do not exist stay zero, so the exchange can always add all eight in order
-  for (int i = threadIdx.x; i < 2 * RB * 2 * 8; i += blockDim.x) (&red[0][0][0][0])[i] = 0.f;
+  // slots of waves that do not exist stay zero, so the exchange can always add all sixteen
+  for (int i = threadIdx.x; i < 2 * (RB / 2) * 64; i += blockDim.x) (&red[0][0][0])[i] = 0.f;
   __syncthreads();
   float gam[VN], dg[VN], db[VN], dsum[VN];
   {
-    Vec16<T> g;
+    V g;
     if (active) g.load(gamma + col0);
 #pragma unroll
     for (int e = 0; e < VN; ++e) {
@@ -242,64 +249,59 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
   // (a block that owned a contiguous chunk of rows would make all blocks walk memory at the same offset of a fixed
   // stride, which concentrates the traffic on a part of the memory channels)
   const int nbatch = (rows + RB - 1) / RB, row_end = rows;
-  Vec16<T> vdy[RB], vx[RB], vres[RB], ndy[RB], nx[RB], nres[RB];
-  float mu[RB], rs[RB], nmu[RB], nrs[RB];
-  auto load_batch = [&](int r0) {
+  struct Batch { V dy[RB], x[RB], res[RB]; float mu[RB], rs[RB]; };
+  auto load_batch = [&](Batch& nb, int r0) {
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
       const int r = r0 + j;
-      nmu[j] = mean[min(r, row_end - 1)];
-      nrs[j] = rstd[min(r, row_end - 1)];
+      nb.mu[j] = mean[min(r, row_end - 1)];       // (loads only: arithmetic here would wait for them at once)
+      nb.rs[j] = rstd[min(r, row_end - 1)];
       if (r < row_end && active) {
         const size_t off = (size_t)r * H + col0;
         if (FUSED) {
           if (n == 1) {
-            ndy[j].load((const T*)ptrs.p[0] + off);
+            nb.dy[j].load((const T*)ptrs.p[0] + off);
           } else {                                   // fixed order k = 0..n-1, fp32, rounded once
             float acc[VN];
 #pragma unroll
             for (int e = 0; e < VN; ++e) acc[e] = 0.f;
             for (int k = 0; k < n; ++k) {
-              Vec16<T> t;
+              V t;
               t.load((const T*)ptrs.p[k] + off);
 #pragma unroll
               for (int e = 0; e < VN; ++e) acc[e] += t.get(e);
             }
 #pragma unroll
-            for (int e = 0; e < VN; ++e) ndy[j].set(e, acc[e]);
+            for (int e = 0; e < VN; ++e) nb.dy[j].set(e, acc[e]);
           }
-          if (dy_out) ndy[j].store(dy_out + off);
+          if (dy_out) nb.dy[j].store(dy_out + off);
         } else {
-          ndy[j].load(dy + off);
+          nb.dy[j].load(dy + off);
         }
-        nx[j].load(x + off);
-        if (residual) nres[j].load(residual + off);
+        nb.x[j].load(x + off);
+        if (residual) nb.res[j].load(residual + off);
       }
     }
   };
-  if ((int)blockIdx.x < nbatch) load_batch(blockIdx.x * RB);
-  int it = 0;
-  for (int bt = blockIdx.x; bt < nbatch; bt += gridDim.x, ++it) {
-    const int r0 = bt * RB;
-#pragma unroll
-    for (int j = 0; j < RB; ++j) { vdy[j] = ndy[j]; vx[j] = nx[j]; vres[j] = nres[j]; mu[j] = nmu[j]; rs[j] = nrs[j]; }
-    if (bt + (int)gridDim.x < nbatch) load_batch((bt + gridDim.x) * RB);
-    // first pass over the batch: everything that needs no row statistic -- the partial sums of s1 and s2 and the
-    // column sums dgamma += dy xhat, dbeta += dy
-    float ps1[RB], ps2[RB];
+  // one batch; par = which half of the exchange buffer (alternates, so one barrier per batch is enough)
+  auto work = [&](const Batch& c, int r0, int par) {
+    // first pass: everything that needs no row statistic -- the partial sums of s1 and s2 and the column sums
+    // dgamma += dy xhat, dbeta += dy; xhat and dy gamma are kept for the second pass
+    float xh[RB][VN], gg[RB][VN], ps1[RB], ps2[RB];
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
       ps1[j] = 0.f;
       ps2[j] = 0.f;
+      const float nmr = -c.mu[j] * c.rs[j];          // xhat = x rstd - mean rstd
       if (r0 + j < row_end && active) {
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
-          const float xh = (vx[j].get(e) - mu[j]) * rs[j];
-          const float d = vdy[j].get(e);
-          const float g = d * gam[e];
-          ps1[j] += g;
-          ps2[j] = fmaf(g, xh, ps2[j]);
-          dg[e] = fmaf(d, xh, dg[e]);
+          const float d = c.dy[j].get(e);
+          xh[j][e] = fmaf(c.x[j].get(e), c.rs[j], nmr);
+          gg[j][e] = d * gam[e];
+          ps1[j] += gg[j][e];
+          ps2[j] = fmaf(gg[j][e], xh[j][e], ps2[j]);
+          dg[e] = fmaf(d, xh[j][e], dg[e]);
           db[e] += d;
         }
       }
@@ -312,25 +314,30 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
     }
     if (lane == 0) {
 #pragma unroll
-      for (int j = 0; j < RB; ++j) { red[it & 1][j][0][wave] = ps1[j]; red[it & 1][j][1][wave] = ps2[j]; }
+      for (int j = 0; j < RB; ++j) {
+        red[par][j >> 1][(2 * (j & 1) + 0) * 16 + wave] = ps1[j];
+        red[par][j >> 1][(2 * (j & 1) + 1) * 16 + wave] = ps2[j];
+      }
     }
     __syncthreads();
+    // the waves' partials are added by the 16-lane row reduction (fixed order): one LDS read and five vector
+    // operations per exchange line instead of a chain of adds per quantity in every lane
+    float tot[RB / 2];
+#pragma unroll
+    for (int h = 0; h < RB / 2; ++h) tot[h] = row16_sum(red[par][h][lane]);
     // second pass: dx = rstd (dy gamma - s1 - xhat s2) written as (rstd dy gamma - rstd s1) - xhat (rstd s2)
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
       if (r0 + j >= row_end) break;                  // block-uniform
-      const float4* rr = reinterpret_cast<const float4*>(&red[it & 1][j][0][0]);
-      const float4 a0 = rr[0], a1 = rr[1], b0 = rr[2], b1 = rr[3];
-      const float s1 = (((((((a0.x + a0.y) + a0.z) + a0.w) + a1.x) + a1.y) + a1.z) + a1.w) * invH;
-      const float s2 = (((((((b0.x + b0.y) + b0.z) + b0.w) + b1.x) + b1.y) + b1.z) + b1.w) * invH;
-      const float rs1 = rs[j] * s1, rs2 = rs[j] * s2;
+      const float s1 = lane_value(tot[j >> 1], (2 * (j & 1) + 0) * 16 + 15) * invH;
+      const float s2 = lane_value(tot[j >> 1], (2 * (j & 1) + 1) * 16 + 15) * invH;
+      const float rs1 = c.rs[j] * s1, rs2 = c.rs[j] * s2;
       if (active) {
-        Vec16<T> o;
+        V o;
 #pragma unroll
         for (int e = 0; e < VN; ++e) {
-          const float xh = (vx[j].get(e) - mu[j]) * rs[j];
-          float v = fmaf(-xh, rs2, fmaf(vdy[j].get(e) * gam[e], rs[j], -rs1));
-          if (residual) v += vres[j].get(e);
+          float v = fmaf(-xh[j][e], rs2, fmaf(gg[j][e], c.rs[j], -rs1));
+          if (residual) v += c.res[j].get(e);
           o.set(e, v);
           if (SUM && !DZ) dsum[e] += o.get(e);   // the stored (rounded) value, as a separate column sum would read it
         }
@@ -341,7 +348,7 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
 #pragma unroll
           for (int e = 0; e < VN; ++e) z[e] = o.get(e);
           if (drop.enabled) drop_apply<VN>(drop, (size_t)(r0 + j) * H + col0, z);
-          Vec16<T> oz;
+          V oz;
 #pragma unroll
           for (int e = 0; e < VN; ++e) {
             oz.set(e, z[e]);
@@ -351,6 +358,19 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(int rows, int H, const T* _
         }
       }
     }
+  };
+  // The next batch is in flight while the current one is worked on.  The batch is COPIED out of the registers the
+  // loads target at the top of the loop: that is the one point where the wave waits for memory, and the compiler can
+  // place it exactly (with buffers that swap roles, the conditional prefetch makes the count of younger loads depend
+  // on the path, and the wait it then inserts before the first use also waits for the prefetch just issued).
+  Batch cur, nxt;
+  const int G = gridDim.x;
+  if ((int)blockIdx.x < nbatch) load_batch(nxt, blockIdx.x * RB);
+  int par = 0;
+  for (int bt = blockIdx.x; bt < nbatch; bt += G, par ^= 1) {
+    cur = nxt;
+    if (bt + G < nbatch) load_batch(nxt, (bt + G) * RB);
+    work(cur, bt * RB, par);
   }
   if (active) {
     float* out = ws + (size_t)blockIdx.x * NP * H + col0;
@@ -398,24 +418,35 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
                                   const float* mean, const float* rstd, const void* residual, void* dx,
                                   void* dgamma, void* dbeta, float* ws, const PartialPtrs* pp, int n, void* dy_out,
                                   void* dx_colsum, const DropArgs& drop, void* dz_out, hipStream_t st) {
-  constexpr int VN = Vec16<T>::N;
-  const int nwaves = (H / VN + 63) / 64;
-  if (nwaves < 1 || nwaves > 8) return hipErrorInvalidValue;
+  // bf16 rows of up to 3072 columns (a multiple of 4) take the 8-byte form: twice the waves per row, at most 12
+  constexpr bool kNarrow = sizeof(T) == 2;
+  const bool narrow = kNarrow && H % 4 == 0 && H / 4 <= 768;
+  const int vn = narrow ? 8 / (int)sizeof(T) : Vec16<T>::N;
+  const int nwaves = (H / vn + 63) / 64;
+  if (nwaves < 1 || nwaves > (narrow ? 12 : 8)) return hipErrorInvalidValue;
   const int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
   PartialPtrs none;
   for (int k = 0; k < kMaxPartials; ++k) none.p[k] = nullptr;
   const int np = (pp && dx_colsum) ? 3 : 2;
   dim3 grid(nblk), block(nwaves * 64);
+#define MLM_LN_BWD_VB(VBYTES, F, S, Z)                                                                      \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, VBYTES, F, S, Z>), grid, block, 0, st, rows, H, (const T*)dy,        \
+                     (const T*)x, (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws,              \
+                     pp ? *pp : none, n, (T*)dy_out, drop, (T*)dz_out)
 #define MLM_LN_BWD_GO(F, S, Z)                                                                              \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, F, S, Z>), grid, block, 0, st, rows, H, (const T*)dy, (const T*)x,   \
-                     (const T*)gamma, mean, rstd, (const T*)residual, (T*)dx, ws, pp ? *pp : none, n,       \
-                     (T*)dy_out, drop, (T*)dz_out)
+  do {                                                                                                      \
+    if constexpr (kNarrow) {                                                                                \
+      if (narrow) { MLM_LN_BWD_VB(8, F, S, Z); break; }                                                     \
+    }                                                                                                       \
+    MLM_LN_BWD_VB(16, F, S, Z);                                                                             \
+  } while (0)
   if (pp && dx_colsum && dz_out) MLM_LN_BWD_GO(true, true, true);
   else if (pp && dz_out) MLM_LN_BWD_GO(true, false, true);
   else if (pp && dx_colsum) MLM_LN_BWD_GO(true, true, false);
   else if (pp) MLM_LN_BWD_GO(true, false, false);
   else MLM_LN_BWD_GO(false, false, false);
 #undef MLM_LN_BWD_GO
+#undef MLM_LN_BWD_VB
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((reduce_cols_kernel<T>), dim3((np * H + 63) / 64), dim3(256), 0, st, nblk, np * H, ws,
