@@ -110,6 +110,9 @@ struct ATileSrc {
     }
   }
   // P: element (0, 0) of the streamed matrix (row stride ld); rows beyond nrows - 1 re-read the last row (callers mask)
+  __device__ __forceinline__ void issue_one(const bf16* P, int ld, int row0, int nrows, uint32_t lds_tile, int wave_u, int i) const {
+    dma16(P + (size_t)min(row0 + row[i], nrows - 1) * ld + col[i], lds_tile + (wave_u * TL::QPW + i) * 1024);
+  }
   __device__ __forceinline__ void issue(const bf16* P, int ld, int row0, int nrows, uint32_t lds_tile, int wave_u) const {
 #pragma unroll
     for (int i = 0; i < TL::QPW; ++i)
@@ -198,16 +201,25 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(A
     const int k0 = t * ATILE;
     wait_vmcnt<LPT*(NST - 2)>();                   // this wave's copies of step j have landed; step j + 1 may be in flight
     __builtin_amdgcn_s_barrier();                 // everyone's have; and everyone is done with step j - 1
-    {
-      const int pst = stage == 0 ? NST - 1 : stage - 1;           // stage of step j - 1 = stage of step j + NST - 1
-      const int tc = min(t + NG * (NST - 1), nt - 1) * ATILE;
-      src.issue(Kb, ld, tc, a.s, lds0 + pst * STAGE, wave_u);
-      src.issue(Vb, ld, tc, a.s, lds0 + pst * STAGE + TL::BYTES, wave_u);
-    }
+    // The copies that re-arm the stage of step j - 1 (= stage of step j + NST - 1) are NOT issued here in one burst:
+    // all eight waves leave the barrier together, 48 one-KB copies queue in the CU's address unit and every wave sits
+    // in front of its first fragment read for 0.6 us of a 2-us step (in-kernel timestamps).  They are issued one at
+    // a time between the exponentials below, where the wave has no LDS read in flight that the copy's compiler-level
+    // memory barrier would pin (placed behind the MFMAs of the two products instead, it measured no gain: 24.9 against
+    // 23.5 us).  Head sizes above 96 keep the burst: the longer live ranges cost them registers they do not have.
+    const int pst = stage == 0 ? NST - 1 : stage - 1;
+    const int tc_next = min(t + NG * (NST - 1), nt - 1) * ATILE;
+    const uint32_t dstK = lds0 + pst * STAGE, dstV = dstK + TL::BYTES;
     const unsigned char* sK = ring + stage * STAGE;
     const unsigned char* sV = sK + TL::BYTES;
     stage = stage == NST - 1 ? 0 : stage + 1;
-    if (t >= nt || (a.causal && k0 > qw0 + 31)) continue;   // no such tile / entirely above this wave's diagonal (wave-uniform)
+    constexpr bool SPREAD = D <= 96;
+    const bool live = t < nt && !(a.causal && k0 > qw0 + 31);   // else: no such tile / entirely above this wave's diagonal (wave-uniform)
+    if (!SPREAD || !live) {
+      src.issue(Kb, ld, tc_next, a.s, dstK, wave_u);
+      src.issue(Vb, ld, tc_next, a.s, dstV, wave_u);
+    }
+    if (!live) continue;
     floatx16 sacc[2];
     float lsum_t = 0.f;
 #pragma unroll
@@ -249,6 +261,14 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_fwd_bf16_kernel(A
         const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kt][e], sc, -mn));
         sacc[kt][e] = p;
         lsum_t += p;
+        if (SPREAD) {
+#pragma unroll
+          for (int c = 0; c < LPT; ++c)                    // copy c after element (32 c + 16) / LPT of the 32
+            if (kt * 16 + e == (32 * c + 16) / LPT) {
+              if (c < TL::QPW) src.issue_one(Kb, ld, tc_next, a.s, dstK, wave_u, c);
+              else src.issue_one(Vb, ld, tc_next, a.s, dstV, wave_u, c - TL::QPW);
+            }
+        }
       }
     // rescale the running sums only when some row's maximum moved (wave-uniform test)
     if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
@@ -402,16 +422,29 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
     const int k0 = t * ATILE;
     wait_vmcnt<LPT*(NST - 2)>();
     __builtin_amdgcn_s_barrier();
-    {
-      const int pst = stage == 0 ? NST - 1 : stage - 1;
-      const int tc = min(t + NG * (NST - 1), nt - 1) * ATILE;
-      src.issue(Kb, ld, tc, a.s, lds0 + pst * STAGE, wave);
-      src.issue(Vb, ld, tc, a.s, lds0 + pst * STAGE + TL::BYTES, wave);
-    }
+    // the copies that re-arm the stage of step j - 1 are issued one at a time inside the element-wise pass below
+    // (as in the forward kernel: a burst here holds every wave of the CU in front of its first fragment read)
+    constexpr bool SPREAD = D <= 96;
+    const int pst = stage == 0 ? NST - 1 : stage - 1;
+    const int tc_next = min(t + NG * (NST - 1), nt - 1) * ATILE;
+    const uint32_t dstK = lds0 + pst * STAGE, dstV = dstK + TL::BYTES;
+    auto copy_after = [&](int el) {                  // el: element index 0..31 of the pass (compile time after unrolling)
+#pragma unroll
+      for (int c = 0; c < LPT; ++c)
+        if (el == (32 * c + 16) / LPT) {
+          if (c < TL::QPW) src.issue_one(Kb, ld, tc_next, a.s, dstK, wave, c);
+          else src.issue_one(Vb, ld, tc_next, a.s, dstV, wave, c - TL::QPW);
+        }
+    };
     const unsigned char* sK = ring + stage * STAGE;
     const unsigned char* sV = sK + TL::BYTES;
     stage = stage == NST - 1 ? 0 : stage + 1;
-    if (t >= nt || (a.causal && k0 > qw0 + 31)) continue;
+    const bool live = t < nt && !(a.causal && k0 > qw0 + 31);
+    if (!SPREAD || !live) {
+      src.issue(Kb, ld, tc_next, a.s, dstK, wave);
+      src.issue(Vb, ld, tc_next, a.s, dstV, wave);
+    }
+    if (!live) continue;
     uint2 kw = make_uint2(0xFFFFFFFFu, 0xFFFFFFFFu);          // keep bits of this query row, keys k0 .. k0 + 63
     if (DROP) kw = *reinterpret_cast<const uint2*>(kbrow + (k0 >> 5));
     floatx16 sacc[2], pacc[2];
@@ -447,13 +480,16 @@ __global__ __launch_bounds__(attn_groups<D>() * ANT) void attn_bwd_dq_bf16_kerne
           const bool off = key >= klen || (a.causal && key > qi);
           const float p = off ? 0.f : __builtin_amdgcn_exp2f(fmaf(sacc[kt][e], sc, -lse2));
           sacc[kt][e] = p * (pacc[kt][e] - dl);     // dS^T
+          if (SPREAD) copy_after(kt * 16 + e);
         }
     } else {
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
+        for (int e = 0; e < 16; ++e) {
           sacc[kt][e] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][e], sc, -lse2)) * (pacc[kt][e] - dl);
+          if (SPREAD) copy_after(kt * 16 + e);
+        }
     }
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -607,6 +643,9 @@ __global__ __launch_bounds__(dkv_groups<D>() * ANT) void attn_bwd_dkv_bf16_kerne
     const int q0 = (qt0 + t) * ATILE;
     wait_vmcnt<LPT*(NST - 2)>();                   // this wave's copies of step j (and of the own rows) have landed
     __builtin_amdgcn_s_barrier();                 // everyone's have; and everyone is done with step j - 1
+    // (issued in one burst: spreading these copies over the element-wise passes, as the forward and dQ kernels do,
+    // measured slower here -- the passes read the per-query vectors from LDS and the copies' compiler-level memory
+    // barrier pins those reads)
     issue_tile(t + NG * (NST - 1), stage == 0 ? NST - 1 : stage - 1);
     const unsigned char* sQ = ring + stage * STAGE;
     const unsigned char* sdO = sQ + TL::BYTES;
