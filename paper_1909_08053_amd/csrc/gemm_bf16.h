@@ -193,9 +193,101 @@ __device__ __forceinline__ void ce_tile_stats(const GemmArgs& a, const floatx16 
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, bool GELU_TANH>
-__device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
-                                                   floatx16 (&acc)[BN / WAVES_N / 32][BM / WAVES_M / 32],
+// The same for accumulators of 16 x 16 MFMA tiles: acc[i][j][e] holds row m = m0w + 16 j + (lane & 15) and column
+// n = n0w + 16 i + 4 (lane >> 4) + e.  The four lanes l16, l16 + 16, l16 + 32, l16 + 48 share a row.
+template <int NB, int NA, int WN, bool RAGGED>
+__device__ __forceinline__ void ce_tile_stats(const GemmArgs& a, const floatx4 (&acc)[NB][NA], int m0w, int n0w,
+                                              int lane, float* red_m_w, float* red_s_w) {
+  const int l16 = lane & 15, lg = lane >> 4;
+  const int nvalid = a.N - (n0w + 4 * lg);     // RAGGED: register column c (relative) is real iff c < nvalid
+#pragma unroll
+  for (int j = 0; j < NA; ++j) {
+    const int row = m0w + j * 16 + l16;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int c = i * 16 + e;
+        const float v = (RAGGED && c >= nvalid) ? -INFINITY : acc[i][j][e];
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // column of the target relative to this lane's registers (integer test), one select per value
+    const int loc = (row < a.M) ? a.targets[row] - a.v0 - (n0w + 4 * lg) : -1;
+    const float mxl = mx * 1.4426950408889634f;
+    float se = 0.f, tv = 0.f;
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int c = i * 16 + e;
+        const float v = acc[i][j][e];
+        const float p = __builtin_amdgcn_exp2f(fmaf(v, 1.4426950408889634f, -mxl));
+        se += (RAGGED && c >= nvalid) ? 0.f : p;
+        tv = (loc == c) ? v : tv;
+      }
+    se += __shfl_xor(se, 16, 64);
+    se += __shfl_xor(se, 32, 64);
+    // the lane group that owns the column has bits 2 and 3 of (target - 4 lg) clear
+    if (loc >= 0 && loc < WN && (loc & 12) == 0 && (!RAGGED || loc < nvalid)) a.t_out[row] = tv;
+    if (lg == 0) {
+      red_m_w[j * 16 + l16] = mx;
+      red_s_w[j * 16 + l16] = se;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Accumulator-layout adapters of the epilogue: row statistics of the wave tile, and the fill of one staging strip
+// (rows 32 j .. 32 j + 31, columns 64 h .. 64 h + 63 of the wave tile; S = strip row stride in elements of T).
+template <int WN, bool RAGGED, int TN, int TM>
+__device__ __forceinline__ void acc_ce_stats(const GemmArgs& a, const floatx16 (&acc)[TN][TM], int m0w, int n0w, int lane,
+                                             float* rm, float* rs) {
+  ce_tile_stats<TN, TM, WN, RAGGED>(a, acc, m0w, n0w, lane & 31, lane >> 5, rm, rs);
+}
+template <int WN, bool RAGGED, int NB, int NA>
+__device__ __forceinline__ void acc_ce_stats(const GemmArgs& a, const floatx4 (&acc)[NB][NA], int m0w, int n0w, int lane,
+                                             float* rm, float* rs) {
+  ce_tile_stats<NB, NA, WN, RAGGED>(a, acc, m0w, n0w, lane, rm, rs);
+}
+template <typename T> __device__ __forceinline__ void strip_put4(T* p, float v0, float v1, float v2, float v3);
+template <> __device__ __forceinline__ void strip_put4<bf16>(bf16* p, float v0, float v1, float v2, float v3) {
+  bf16x4 v;
+  v[0] = (bf16)v0; v[1] = (bf16)v1; v[2] = (bf16)v2; v[3] = (bf16)v3;
+  *reinterpret_cast<bf16x4*>(p) = v;
+}
+template <> __device__ __forceinline__ void strip_put4<float>(float* p, float v0, float v1, float v2, float v3) {
+  *reinterpret_cast<float4*>(p) = make_float4(v0, v1, v2, v3);
+}
+template <typename T, int S, int TN, int TM>
+__device__ __forceinline__ void acc_fill_strip(T* strip, const floatx16 (&acc)[TN][TM], int j, int h, int lane) {
+  const int l32 = lane & 31, lh = lane >> 5;
+#pragma unroll
+  for (int il = 0; il < 2; ++il)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      if (2 * h + il >= TN) continue;
+      const floatx16& t = acc[2 * h + il][j];
+      strip_put4<T>(strip + l32 * S + il * 32 + 8 * g + 4 * lh, t[4 * g], t[4 * g + 1], t[4 * g + 2], t[4 * g + 3]);
+    }
+}
+template <typename T, int S, int NB, int NA>
+__device__ __forceinline__ void acc_fill_strip(T* strip, const floatx4 (&acc)[NB][NA], int j, int h, int lane) {
+  const int l16 = lane & 15, lg = lane >> 4;
+#pragma unroll
+  for (int jl = 0; jl < 2; ++jl)
+#pragma unroll
+    for (int il = 0; il < 4; ++il) {
+      if (4 * h + il >= NB) continue;
+      const floatx4& t = acc[4 * h + il][2 * j + jl];
+      strip_put4<T>(strip + (jl * 16 + l16) * S + il * 16 + 4 * lg, t[0], t[1], t[2], t[3]);
+    }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, bool GELU_TANH, typename Acc>
+__device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a, Acc& acc,
                                                    unsigned char* lds_raw, int m0, int n0, int tile_n) {
   typedef GemmTile<BM, BN, WAVES_M, WAVES_N> Tcfg;
   constexpr int NT = Tcfg::NT, TM = Tcfg::TM, TN = Tcfg::TN, WM = Tcfg::WM, WN = Tcfg::WN;
@@ -212,8 +304,8 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
     float* red_s = red_m + WAVES_N * BM;
     float* rm = red_m + (wave % WAVES_N) * BM + wm0;
     float* rs = red_s + (wave % WAVES_N) * BM + wm0;
-    if (n0 + BN > a.N) ce_tile_stats<TN, TM, WN, true>(a, acc, m0 + wm0, n0 + wn0, l32, lh, rm, rs);
-    else ce_tile_stats<TN, TM, WN, false>(a, acc, m0 + wm0, n0 + wn0, l32, lh, rm, rs);
+    if (n0 + BN > a.N) acc_ce_stats<WN, true>(a, acc, m0 + wm0, n0 + wn0, lane, rm, rs);
+    else acc_ce_stats<WN, false>(a, acc, m0 + wm0, n0 + wn0, lane, rm, rs);
     __syncthreads();
     for (int rloc = tid; rloc < BM; rloc += NT) {
       const int row = m0 + rloc;
@@ -253,17 +345,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
       if (step < NSTEP) {
         const int j = step / NH, h = step % NH;
         bf16* strip = bstrip0 + (step & 1) * (32 * SWB);
-#pragma unroll
-        for (int il = 0; il < 2; ++il)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            if (2 * h + il >= TN) continue;
-            const floatx16& t = acc[2 * h + il][j];
-            bf16x4 v;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = (bf16)t[4 * g + e];
-            *reinterpret_cast<bf16x4*>(strip + l32 * SWB + il * 32 + 8 * g + 4 * lh) = v;
-          }
+        acc_fill_strip<bf16, SWB>(strip, acc, j, h, lane);
       }
       __builtin_amdgcn_wave_barrier();
       if (step > 0) {
@@ -293,15 +375,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
     if (step < NSTEP) {
       const int j = step / NH, h = step % NH;
       float* strip = strip0 + (step & 1) * (Tcfg::STRIP / 2);
-#pragma unroll
-      for (int il = 0; il < 2; ++il)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          if (2 * h + il >= TN) continue;
-          const floatx16& t = acc[2 * h + il][j];
-          const float4 v = make_float4(t[4 * g], t[4 * g + 1], t[4 * g + 2], t[4 * g + 3]);
-          *reinterpret_cast<float4*>(strip + l32 * SW + il * 32 + 8 * g + 4 * lh) = v;
-        }
+      acc_fill_strip<float, SW>(strip, acc, j, h, lane);
     }
     __builtin_amdgcn_wave_barrier();
     if (step > 0) {
@@ -365,8 +439,9 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs& a,
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, floatx16 (&acc)[BN / WAVES_N / 32][BM / WAVES_M / 32],
+// acc: floatx16 [BN / WAVES_N / 32][BM / WAVES_M / 32] (32 x 32 MFMA tiles) or floatx4 [.. / 16][.. / 16] (16 x 16)
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, typename Acc>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, Acc& acc,
                                               unsigned char* lds_raw, int m0, int n0, int tile_n) {
   if (EPI == EPI_BIAS_GELU || EPI == EPI_DGELU) {
     // the GeLU form is a launch-wide constant: branch once, not per element

@@ -29,6 +29,16 @@
 
 namespace mlm {
 
+// MFMA shape of the main loop: 16 (v_mfma_f32_16x16x32_bf16) unless the library is built with
+// -DMLM_GEMM_MFMA_SHAPE=32 (v_mfma_f32_32x32x16_bf16, the earlier loop, kept for comparison builds).
+#ifndef MLM_GEMM_MFMA_SHAPE
+#define MLM_GEMM_MFMA_SHAPE 16
+#endif
+constexpr int V2_MF = MLM_GEMM_MFMA_SHAPE;
+// The 4-wave variant (128 x 128 per wave, 256 accumulator registers) keeps the 32 x 32 x 16 shape: with 64 separate
+// 16 x 16 accumulators the compiler spills over a thousand registers, and the measured gain of the shape is half as
+// large there (fewer fragment reads per MFMA to begin with).
+template <int NW> constexpr int v2_mf() { return NW == 4 ? 32 : V2_MF; }
 constexpr int V2_B = 256;                   // block tile edge (M and N)
 constexpr int V2_BK = 32;                   // k per stage
 constexpr int V2_STAGES = 4;
@@ -45,21 +55,26 @@ int gemm_cu_count();
 // k-rows, and every k-row starts at bank 0.  XORing the unit index with 4 (k & 3) sends the four rows to four different
 // 64-byte slots of the 256-byte bank row, so a pass touches every bank once (checked by simulation and with the
 // LDS bank-conflict counter: an earlier swizzle that only spread the rows over 128 bytes showed 50 % conflict cycles).
-__device__ __forceinline__ int v2_mn_swizzle(int k) { return (k & 3) << 2; }
+// The 16 x 16 x 32 MFMA's operand puts k = 8 g .. 8 g + 7 into lane group g = lane / 16, so a pass of its transposing
+// read covers k-rows 0 .. 3 (or 4 .. 7) AND 8 .. 11 (12 .. 15), 32 bytes of each: bit 3 of k moves a row by another 32
+// bytes.  With this term both MFMA shapes read conflict-free (simulated for both).
+__device__ __forceinline__ int v2_mn_swizzle(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
 
 // LDS position (16-byte unit inside the k-row) of logical row-chunk u of k-row k, and its inverse, for a [k][ROWS]
 // tile.  256 rows: the XOR above.  192 rows: a k-row is 384 bytes = 24 units and starts at bank 0 or 32 alternately
 // (384 = 256 + 128), so the four k-rows of a pass would pair up on the same 64-byte slots; rotating the rows with
 // bit 1 of k set by four units sends the four 64-byte windows to the four different slots of the 256-byte bank row
 // (slot = (6 k + position / 4) mod 4 -> 0, 2, 1, 3), wrap-around included.
+// (192 rows, 16 x 16 x 32 reads: two more units for bit 3 of k, as above)
+__device__ __forceinline__ int v2_mn_rot192(int k) { return (((k >> 1) & 1) << 2) + (((k >> 3) & 1) << 1); }
 template <int ROWS> __device__ __forceinline__ int v2_mn_pos(int u, int k) {
   if (ROWS == V2_B) return u ^ v2_mn_swizzle(k);
-  const int t = u + (((k >> 1) & 1) << 2);
+  const int t = u + v2_mn_rot192(k);
   return t >= ROWS / 8 ? t - ROWS / 8 : t;
 }
 template <int ROWS> __device__ __forceinline__ int v2_mn_chunk(int pos, int k) {
   if (ROWS == V2_B) return pos ^ v2_mn_swizzle(k);
-  const int t = pos - (((k >> 1) & 1) << 2);
+  const int t = pos - v2_mn_rot192(k);
   return t < 0 ? t + ROWS / 8 : t;
 }
 
@@ -141,6 +156,33 @@ __device__ __forceinline__ bf16x8 v2_frag(const unsigned char* ring, int stage, 
   }
 }
 
+// Operand registers of the 16 x 16 x 32 MFMA for the 16-row tile starting at row `r0`: lane l holds k = 8 (l / 16) ..
+// + 7 (the whole 32-deep slice is one MFMA deep) of row r0 + l % 16.
+template <bool KC, int ROWS = V2_B>
+__device__ __forceinline__ bf16x8 v2_frag16(const unsigned char* ring, int stage, int r0, int lane) {
+  constexpr int OPB = ROWS * V2_BK * 2;       // bytes of one k-slice of the operand
+  const int l16 = lane & 15, lg = lane >> 4;
+  if (KC) {
+    const int row = r0 + l16;
+    const int u = (stage & 1) * 4 + lg;
+    return *reinterpret_cast<const bf16x8*>(ring + (stage >> 1) * (2 * OPB) + row * 128 +
+                                            ((u ^ v2_kc_swizzle(row)) << 4));
+  } else {
+    // two transposing reads: lane j of a group addresses 4 rows (r0 + 4 (j % 4) ..) of k-row 8 g + 4 r + j / 4 and
+    // lane i receives k = 8 g + 4 r .. + 3 of row r0 + i
+    const unsigned char* op_base = ring + stage * OPB;
+    const int u = (r0 >> 3) + ((l16 & 3) >> 1);
+    v4s_t h[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int k = 8 * lg + 4 * r + (l16 >> 2);
+      h[r] = lds_read_tr16(op_base + k * (ROWS * 2) + (v2_mn_pos<ROWS>(u, k) * 16) + (l16 & 1) * 8);
+    }
+    const v8s_t v = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
 struct V2Plan {
   int tiles_m, tiles_n, full_tiles, tail_tiles, split;   // grid = full_tiles + tail_tiles * split
   int bn;                                                 // tile width (256, or 192 for the narrow-tile variant)
@@ -192,10 +234,15 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B, bool
 // BN = 256: 2 x (NW / 2) waves of 128 x (512 / NW).  BN = 192 (8 waves, k-contiguous B only): 4 x 2 waves of 64 x 96 --
 // a tile count of 32 x (N / 192) fills the 256 CUs where N / 256 column tiles leave a quarter of them idle
 // (N = 1536: 256 tiles instead of 192) or a half-empty second round (N = 3072: 512 instead of 384).
-template <bool A_KC, bool B_KC, int EPI, int NW, int BN = V2_B>
+// MF = MFMA shape: 16 (v_mfma_f32_16x16x32_bf16, the default) or 32 (v_mfma_f32_32x32x16_bf16, kept for comparison).
+// Same wave tiles, same LDS traffic and the same peak rate, but on normally distributed operands the 16 x 16 x 32
+// shape sustains 2.04 PFLOP/s against 1.77 with the matrix pipe alone, 1.60 against 1.45 with this loop's fragment
+// reads and copies around it (256 x 256 tile, 8 waves; measured with a stand-alone loop of the same structure).
+template <bool A_KC, bool B_KC, int EPI, int NW, int BN = V2_B, int MF = 16>
 __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Plan& plan, float* splitk_ws, int pid,
                                                   unsigned char* lds_raw) {
   static_assert(BN == V2_B || (BN == 192 && NW == 8), "narrow tile: 8 waves");
+  static_assert(MF == 16 || MF == 32, "MFMA shape");
   constexpr int WAVES_M = BN == V2_B ? 2 : 4, WAVES_N = NW / WAVES_M;
   constexpr int WM = V2_B / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   constexpr int OPB_B = BN * V2_BK * 2;                        // bytes of one k-slice of the B operand
@@ -235,14 +282,6 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
   sa.init((const bf16*)a.A, a.lda, m0, a.M, kt_begin * V2_BK, wave, lane);
   sb.init((const bf16*)a.B, a.ldb, n0, a.N, kt_begin * V2_BK, wave, lane);
 
-  floatx16 acc[TN][TM];
-#pragma unroll
-  for (int i = 0; i < TN; ++i)
-#pragma unroll
-    for (int j = 0; j < TM; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
   const uint32_t ldsA = lds_offset_of(lds_raw), ldsB = ldsA + V2_REGION_BYTES;
   const unsigned char* ringA = lds_raw;
   const unsigned char* ringB = lds_raw + V2_REGION_BYTES;
@@ -277,118 +316,237 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
   constexpr int C_PAIR = (A_KC ? NPA : 0) + (B_KC ? NPB : 0);      // copies per wave that re-arm a pair stage
   constexpr int EV = C_SLICE, OD = C_PAIR + C_SLICE;
   constexpr int W_INIT = 3 * C_SLICE + C_PAIR, W_EVEN = EV + OD, W_ODD = NKC > 0 ? 2 * EV : EV + OD;
-  constexpr int NMF = TN * TM;           // MFMAs per half-slice per wave
-  static_assert(NMF > TM + TN, "one fragment read after each MFMA but the first must cover all fragments");
   (void)NMN;
-  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  wait_vmcnt<W_INIT>();                  // slice 0 landed
-  __builtin_amdgcn_s_barrier();
+  if constexpr (MF == 32) {
+    floatx16 acc[TN][TM];
 #pragma unroll
-  for (int j = 0; j < TM; ++j) fa0[j] = v2_frag<A_KC>(ringA, 0, wm0 + j * 32, 0, lane);
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
-  for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC, BN>(ringB, 0, wn0 + i * 32, 0, lane);
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // one 32-deep slice; PAR = parity of kt (compile time: it fixes the ring stage bits and the copy schedule);
-  // live: false for the slice that repeats one multiplied already (odd slice count): everything but its MFMAs runs.
-  // It is a compile-time true in the steady-state loop and a wave-uniform flag (scalar branches) in the peeled last pair.
-  auto slice = [&](auto par_c, auto live, int kt) {
-    constexpr int PAR = decltype(par_c)::value;
-    const int stage = kt & (V2_STAGES - 1);
-    // First half.  Order pinned with scheduling barriers: one MFMA first (its operands were read half a slice ago,
-    // so the loop-top wait is free), then ONE fragment read of the second half's operands after each MFMA.  Spread
-    // like this the reads never queue up in the LDS pipe (all eight waves reach this point together after the
-    // barrier), and the MFMAs in between cover their latency.  (Left alone, the scheduler bunches the reads and
-    // either hoists them above the loop-top wait or sinks them to the barrier; both expose their full latency.)
-#pragma unroll
-    for (int idx = 0; idx < NMF; ++idx) {
-      if (live) acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / TM], fa0[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
-      if (idx >= 1 && idx - 1 < TM + TN) {
-        const int q = idx - 1;
-        __builtin_amdgcn_sched_barrier(0);
-        if (q < TM) fa1[q] = v2_frag<A_KC>(ringA, stage, wm0 + q * 32, 1, lane);
-        else fb1[q - TM] = v2_frag<B_KC, BN>(ringB, stage, wn0 + (q - TM) * 32, 1, lane);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);     // ... and the MFMAs ahead of the hand-over
-    wait_vmcnt<PAR == 0 ? W_EVEN : W_ODD>();   // this wave's copies of slice kt+1 have landed
-    // this wave's LDS reads of slice kt (second-half operands, issued above) have returned ...
-    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
-    // ... so after this bare s_barrier (no memory fence: a fence would also wait for the copies in flight)
-    // everyone's part of slice kt+1 is in LDS and nobody reads slice kt's stage any more.
+    constexpr int NMF = TN * TM;           // MFMAs per half-slice per wave
+    static_assert(NMF > TM + TN, "one fragment read after each MFMA but the first must cover all fragments");
+    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    wait_vmcnt<W_INIT>();                  // slice 0 landed
     __builtin_amdgcn_s_barrier();
-    // Second half: after each MFMA one fragment read of slice kt+1's first-half operands, and the copies that
-    // re-arm the freed stage(s) spread evenly between the MFMAs.
-    const int nstage = (kt + 1) & (V2_STAGES - 1);
-    constexpr int NC = PAR == 0 ? EV : OD;                 // copies to issue in this half
-    const int pair_idx = pair_of(min((kt + 3) >> 1, last_pair));   // PAR == 1: the pair two ahead of this slice's pair
-    const uint32_t pair_sel = (uint32_t)(((kt + 3) >> 1) & 1);
-    const uint32_t pair_off_a = pair_sel * (2 * V2_OP_BYTES), pair_off_b = pair_sel * (2 * OPB_B);
-    const int slice_idx = slice_of(min(kt + V2_STAGES, last_slice));
-    const uint32_t slice_off_a = (uint32_t)stage * V2_OP_BYTES, slice_off_b = (uint32_t)stage * OPB_B;
 #pragma unroll
-    for (int idx = 0; idx < NMF; ++idx) {
-      if (live) acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[idx / TM], fa1[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (idx < TM + TN) {
-        const int q = idx;
-        if (q < TM) fa0[q] = v2_frag<A_KC>(ringA, nstage, wm0 + q * 32, 0, lane);
-        else fb0[q - TM] = v2_frag<B_KC, BN>(ringB, nstage, wn0 + (q - TM) * 32, 0, lane);
-      }
+    for (int j = 0; j < TM; ++j) fa0[j] = v2_frag<A_KC>(ringA, 0, wm0 + j * 32, 0, lane);
 #pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        if ((c * NMF) / (NC > 0 ? NC : 1) != idx) continue;   // copy c goes after MFMA (c NMF) / NC
-        // order: A's pair, B's pair (odd slices only), then A's slice, B's slice
-        int r = c;
-        constexpr int KA = (PAR == 1 && A_KC) ? NPA : 0, KB = (PAR == 1 && B_KC) ? NPB : 0;
-        constexpr int MA = A_KC ? 0 : NPA;
-        if (r < KA) { sa.issue_one(ldsA + pair_off_a, wave_u, pair_idx, r); continue; }
-        r -= KA;
-        if (r < KB) { sb.issue_one(ldsB + pair_off_b, wave_u, pair_idx, r); continue; }
-        r -= KB;
-        if (r < MA) { sa.issue_one(ldsA + slice_off_a, wave_u, slice_idx, r); continue; }
-        r -= MA;
-        sb.issue_one(ldsB + slice_off_b, wave_u, slice_idx, r);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  typedef std::integral_constant<int, 0> c0_t;
-  typedef std::integral_constant<int, 1> c1_t;
-  for (int kt = 0; kt < nk - 2; kt += 2) {
-    slice(c0_t{}, std::true_type{}, kt);
-    slice(c1_t{}, std::true_type{}, kt + 1);
-  }
-  slice(c0_t{}, shift == 0, nk - 2);                  // odd slice count: this one repeats slice nk - 3, copies only
-  slice(c1_t{}, std::true_type{}, nk - 1);
-  // The ring is kept full to the end, so copies of the (clamped) last slice are still in flight here.  They were
-  // issued from inline assembly, which the compiler's wait-count tracking does not see: wait for them explicitly
-  // before the epilogue reuses the ring's memory for its staging strips.
-  wait_vmcnt<0>();
-  __syncthreads();
+    for (int i = 0; i < TN; ++i) fb0[i] = v2_frag<B_KC, BN>(ringB, 0, wn0 + i * 32, 0, lane);
 
-  if (npieces > 1) {
-    // fp32 partial tile: piece-major [tail tile][piece][256][BN]
-    const int l32 = lane & 31, lh = lane >> 5;
-    float* dst = splitk_ws + ((size_t)(vt - plan.full_tiles) * plan.split + piece) * (V2_B * BN);
+    // one 32-deep slice; PAR = parity of kt (compile time: it fixes the ring stage bits and the copy schedule);
+    // live: false for the slice that repeats one multiplied already (odd slice count): everything but its MFMAs runs.
+    // It is a compile-time true in the steady-state loop and a wave-uniform flag (scalar branches) in the peeled last pair.
+    auto slice = [&](auto par_c, auto live, int kt) {
+      constexpr int PAR = decltype(par_c)::value;
+      const int stage = kt & (V2_STAGES - 1);
+      // First half.  Order pinned with scheduling barriers: one MFMA first (its operands were read half a slice ago,
+      // so the loop-top wait is free), then ONE fragment read of the second half's operands after each MFMA.  Spread
+      // like this the reads never queue up in the LDS pipe (all eight waves reach this point together after the
+      // barrier), and the MFMAs in between cover their latency.  (Left alone, the scheduler bunches the reads and
+      // either hoists them above the loop-top wait or sinks them to the barrier; both expose their full latency.)
 #pragma unroll
-    for (int j = 0; j < TM; ++j)
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-          *reinterpret_cast<float4*>(dst + (wm0 + j * 32 + l32) * BN + wn0 + i * 32 + 8 * g + 4 * lh) = v;
+      for (int idx = 0; idx < NMF; ++idx) {
+        if (live) acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[idx / TM], fa0[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
+        if (idx >= 1 && idx - 1 < TM + TN) {
+          const int q = idx - 1;
+          __builtin_amdgcn_sched_barrier(0);
+          if (q < TM) fa1[q] = v2_frag<A_KC>(ringA, stage, wm0 + q * 32, 1, lane);
+          else fb1[q - TM] = v2_frag<B_KC, BN>(ringB, stage, wn0 + (q - TM) * 32, 1, lane);
+          __builtin_amdgcn_sched_barrier(0);
         }
-    return;
+      }
+      __builtin_amdgcn_sched_barrier(0);     // ... and the MFMAs ahead of the hand-over
+      wait_vmcnt<PAR == 0 ? W_EVEN : W_ODD>();   // this wave's copies of slice kt+1 have landed
+      // this wave's LDS reads of slice kt (second-half operands, issued above) have returned ...
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
+      // ... so after this bare s_barrier (no memory fence: a fence would also wait for the copies in flight)
+      // everyone's part of slice kt+1 is in LDS and nobody reads slice kt's stage any more.
+      __builtin_amdgcn_s_barrier();
+      // Second half: after each MFMA one fragment read of slice kt+1's first-half operands, and the copies that
+      // re-arm the freed stage(s) spread evenly between the MFMAs.
+      const int nstage = (kt + 1) & (V2_STAGES - 1);
+      constexpr int NC = PAR == 0 ? EV : OD;                 // copies to issue in this half
+      const int pair_idx = pair_of(min((kt + 3) >> 1, last_pair));   // PAR == 1: the pair two ahead of this slice's pair
+      const uint32_t pair_sel = (uint32_t)(((kt + 3) >> 1) & 1);
+      const uint32_t pair_off_a = pair_sel * (2 * V2_OP_BYTES), pair_off_b = pair_sel * (2 * OPB_B);
+      const int slice_idx = slice_of(min(kt + V2_STAGES, last_slice));
+      const uint32_t slice_off_a = (uint32_t)stage * V2_OP_BYTES, slice_off_b = (uint32_t)stage * OPB_B;
+#pragma unroll
+      for (int idx = 0; idx < NMF; ++idx) {
+        if (live) acc[idx / TM][idx % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[idx / TM], fa1[idx % TM], acc[idx / TM][idx % TM], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (idx < TM + TN) {
+          const int q = idx;
+          if (q < TM) fa0[q] = v2_frag<A_KC>(ringA, nstage, wm0 + q * 32, 0, lane);
+          else fb0[q - TM] = v2_frag<B_KC, BN>(ringB, nstage, wn0 + (q - TM) * 32, 0, lane);
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          if ((c * NMF) / (NC > 0 ? NC : 1) != idx) continue;   // copy c goes after MFMA (c NMF) / NC
+          // order: A's pair, B's pair (odd slices only), then A's slice, B's slice
+          int r = c;
+          constexpr int KA = (PAR == 1 && A_KC) ? NPA : 0, KB = (PAR == 1 && B_KC) ? NPB : 0;
+          constexpr int MA = A_KC ? 0 : NPA;
+          if (r < KA) { sa.issue_one(ldsA + pair_off_a, wave_u, pair_idx, r); continue; }
+          r -= KA;
+          if (r < KB) { sb.issue_one(ldsB + pair_off_b, wave_u, pair_idx, r); continue; }
+          r -= KB;
+          if (r < MA) { sa.issue_one(ldsA + slice_off_a, wave_u, slice_idx, r); continue; }
+          r -= MA;
+          sb.issue_one(ldsB + slice_off_b, wave_u, slice_idx, r);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    typedef std::integral_constant<int, 0> c0_t;
+    typedef std::integral_constant<int, 1> c1_t;
+    for (int kt = 0; kt < nk - 2; kt += 2) {
+      slice(c0_t{}, std::true_type{}, kt);
+      slice(c1_t{}, std::true_type{}, kt + 1);
+    }
+    slice(c0_t{}, shift == 0, nk - 2);                  // odd slice count: this one repeats slice nk - 3, copies only
+    slice(c1_t{}, std::true_type{}, nk - 1);
+    // The ring is kept full to the end, so copies of the (clamped) last slice are still in flight here.  They were
+    // issued from inline assembly, which the compiler's wait-count tracking does not see: wait for them explicitly
+    // before the epilogue reuses the ring's memory for its staging strips.
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    if (npieces > 1) {
+      // fp32 partial tile: piece-major [tail tile][piece][256][BN]
+      const int l32 = lane & 31, lh = lane >> 5;
+      float* dst = splitk_ws + ((size_t)(vt - plan.full_tiles) * plan.split + piece) * (V2_B * BN);
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+            *reinterpret_cast<float4*>(dst + (wm0 + j * 32 + l32) * BN + wn0 + i * 32 + 8 * g + 4 * lh) = v;
+          }
+      return;
+    }
+    gemm_epilogue<V2_B, BN, WAVES_M, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
+  } else {
+    // ---- 16 x 16 x 32 MFMAs: one MFMA spans the slice's 32 k, so a wave holds the fragments of ONE slice: NA of A, NB
+    // of B.  MFMA order: A fragment outer, B fragment inner.  A fragment j is replaced by the next slice's right after
+    // its last MFMA (j, NB - 1) and is next used NMF - NB MFMAs later; the B fragments are double-buffered (the slice's
+    // parity picks the set) and the next slice's are read right after the hand-over.  The hand-over (wait for the
+    // copies of slice kt + 1, barrier) sits after MFMA HO, ahead of the first read of slice kt + 1; the copies that
+    // re-arm slice kt's stage (all of its fragments were in registers before the slice began) follow it, one at a
+    // time between the MFMAs.  Measured on the benchmark step: HO = 0 .. 2 within noise of each other, later
+    // hand-overs slower (HO = 15: +0.5 %); B fragment outer with in-place replacement of both operands (A fragments
+    // then have NA MFMAs between read and use) the same step time, 1 % slower on the logits GEMM.
+    constexpr int NA = WM / 16, NB = WN / 16, NMF = NA * NB;
+    constexpr int HO = 1;
+    static_assert(HO + 1 + NB <= NMF, "the next slice's B fragments are read in this slice");
+    floatx4 acc[NB][NA];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int j = 0; j < NA; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+    bf16x8 fa[NA], fb[2][NB];
+    wait_vmcnt<W_INIT>();                  // slice 0 landed
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int j = 0; j < NA; ++j) fa[j] = v2_frag16<A_KC>(ringA, 0, wm0 + j * 16, lane);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) fb[0][i] = v2_frag16<B_KC, BN>(ringB, 0, wn0 + i * 16, lane);
+
+    // one 32-deep slice; PAR = parity of kt (compile time: it fixes the ring stage bits and the copy schedule);
+    // live: false for the slice that repeats one multiplied already (odd slice count): everything but its MFMAs runs.
+    auto slice = [&](auto par_c, auto live, int kt) {
+      constexpr int PAR = decltype(par_c)::value;
+      const int stage = kt & (V2_STAGES - 1), nstage = (kt + 1) & (V2_STAGES - 1);
+      constexpr int NC = PAR == 0 ? EV : OD;                 // copies to issue in this slice
+      constexpr int NAFTER = NMF - HO - 1;                   // MFMAs after the hand-over
+      const int pair_idx = pair_of(min((kt + 3) >> 1, last_pair));   // PAR == 1: the pair two ahead of this slice's pair
+      const uint32_t pair_sel = (uint32_t)(((kt + 3) >> 1) & 1);
+      const uint32_t pair_off_a = pair_sel * (2 * V2_OP_BYTES), pair_off_b = pair_sel * (2 * OPB_B);
+      const int slice_idx = slice_of(min(kt + V2_STAGES, last_slice));
+      const uint32_t slice_off_a = (uint32_t)stage * V2_OP_BYTES, slice_off_b = (uint32_t)stage * OPB_B;
+#pragma unroll
+      for (int idx = 0; idx < NMF; ++idx) {
+        const int i = idx % NB, j = idx / NB;
+        constexpr int CUR = PAR, NXT = 1 - PAR;
+        if (live) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[CUR][i], fa[j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (idx == HO) {
+          wait_vmcnt<PAR == 0 ? W_EVEN : W_ODD>();   // this wave's copies of slice kt+1 have landed
+          // this wave's LDS reads of slice kt's stage (the last fragments, read at the end of slice kt - 1) have returned ...
+          __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
+          // ... so after this bare s_barrier (no memory fence: a fence would also wait for the copies in flight)
+          // everyone's part of slice kt+1 is in LDS and nobody reads slice kt's stage any more.
+          __builtin_amdgcn_s_barrier();
+        }
+        if (idx > HO) {
+          // fragments of slice kt + 1 into the registers that slice kt has finished with
+#pragma unroll
+          for (int q = 0; q < NB; ++q)
+            if (idx == HO + 1 + q) fb[NXT][q] = v2_frag16<B_KC, BN>(ringB, nstage, wn0 + q * 16, lane);
+#pragma unroll
+          for (int q = 0; q < NA; ++q) {
+            const int at = q * NB + NB - 1 > HO ? q * NB + NB - 1 : HO + 1;   // MFMA (q, NB - 1), but not before the hand-over
+            if (idx == at) fa[q] = v2_frag16<A_KC>(ringA, nstage, wm0 + q * 16, lane);
+          }
+#pragma unroll
+          for (int c = 0; c < NC; ++c) {
+            if (HO + 1 + (c * NAFTER) / (NC > 0 ? NC : 1) != idx) continue;   // copy c goes after MFMA HO + 1 + (c NAFTER) / NC
+            // order: A's pair, B's pair (odd slices only), then A's slice, B's slice
+            int r = c;
+            constexpr int KA = (PAR == 1 && A_KC) ? NPA : 0, KB = (PAR == 1 && B_KC) ? NPB : 0;
+            constexpr int MA = A_KC ? 0 : NPA;
+            if (r < KA) { sa.issue_one(ldsA + pair_off_a, wave_u, pair_idx, r); continue; }
+            r -= KA;
+            if (r < KB) { sb.issue_one(ldsB + pair_off_b, wave_u, pair_idx, r); continue; }
+            r -= KB;
+            if (r < MA) { sa.issue_one(ldsA + slice_off_a, wave_u, slice_idx, r); continue; }
+            r -= MA;
+            sb.issue_one(ldsB + slice_off_b, wave_u, slice_idx, r);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    typedef std::integral_constant<int, 0> c0_t;
+    typedef std::integral_constant<int, 1> c1_t;
+    for (int kt = 0; kt < nk - 2; kt += 2) {
+      slice(c0_t{}, std::true_type{}, kt);
+      slice(c1_t{}, std::true_type{}, kt + 1);
+    }
+    slice(c0_t{}, shift == 0, nk - 2);                  // odd slice count: this one repeats slice nk - 3, copies only
+    slice(c1_t{}, std::true_type{}, nk - 1);
+    // copies of the (clamped) last slices are still in flight and target the ring the epilogue reuses
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    if (npieces > 1) {
+      // fp32 partial tile: piece-major [tail tile][piece][256][BN]
+      const int l16 = lane & 15, lg = lane >> 4;
+      float* dst = splitk_ws + ((size_t)(vt - plan.full_tiles) * plan.split + piece) * (V2_B * BN);
+#pragma unroll
+      for (int j = 0; j < NA; ++j)
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+          const float4 v = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+          *reinterpret_cast<float4*>(dst + (wm0 + j * 16 + l16) * BN + wn0 + i * 16 + 4 * lg) = v;
+        }
+      return;
+    }
+    gemm_epilogue<V2_B, BN, WAVES_M, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
   }
-  gemm_epilogue<V2_B, BN, WAVES_M, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
 }
 
 template <bool A_KC, bool B_KC, int EPI, int NW, int BN = V2_B>
 __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_kernel(GemmArgs a, V2Plan plan, float* splitk_ws) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  gemm_v2_work_item<A_KC, B_KC, EPI, NW, BN>(a, plan, splitk_ws, blockIdx.x, lds_raw);
+  gemm_v2_work_item<A_KC, B_KC, EPI, NW, BN, v2_mf<NW>()>(a, plan, splitk_ws, blockIdx.x, lds_raw);
 }
 
 // Several independent GEMMs of one operand layout in ONE launch (plain-store epilogue, no k-split): the tiles of
@@ -417,7 +575,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_v2_group_kernel(GemmGroup g
 #pragma unroll
   for (int i = 1; i < kMaxGroup; ++i)
     if (q == i) { a = g.args[i]; plan = g.plan[i]; first = g.tile_begin[i]; }
-  gemm_v2_work_item<A_KC, B_KC, EPI_STORE, NW>(a, plan, nullptr, pid - first, lds_raw);
+  gemm_v2_work_item<A_KC, B_KC, EPI_STORE, NW, V2_B, v2_mf<NW>()>(a, plan, nullptr, pid - first, lds_raw);
 }
 
 // Tail tiles: sum the k-pieces in piece order (deterministic) and apply the epilogue to the fp32 sums.  A wave owns
