@@ -43,17 +43,18 @@ bool gemm_use_v2(const GemmArgs& a) {
   return enabled && a.K % 32 == 0 && a.K >= 64;
 }
 
-// Waves per workgroup of the 256 x 256 tile: 8 (two per SIMD) wherever a k-contiguous operand is involved; the
-// weight-gradient layout (both operands read through the transposing loads) measured ~3 % faster with 4 waves of
-// 128 x 128 (fewer LDS bytes per MFMA).  MLM_GEMM_WAVES=4|8 forces one variant.
+// Waves per workgroup of the 256 x 256 tile: 8 (2 x 4 waves of 128 x 64, two per SIMD) for every operand layout.
+// (With the 32 x 32 x 16 MFMA the weight-gradient layout -- both operands read through the transposing loads -- was
+// ~3 % faster with 4 waves of 128 x 128; with the 16 x 16 x 32 MFMA, which only the 8-wave variant uses, 8 waves win by
+// 10 % on the 3072 x 6400 x 8192 gradient of the output embedding.)  MLM_GEMM_WAVES=4|8 forces one variant.
 int gemm_v2_waves(bool a_kc, bool b_kc) {
+  (void)a_kc; (void)b_kc;
   static int forced = -1;
   if (forced < 0) {
     const char* e = getenv("MLM_GEMM_WAVES");
     forced = e ? (atoi(e) == 4 ? 4 : 8) : 0;
   }
-  if (forced) return forced;
-  return (!a_kc && !b_kc) ? 4 : 8;
+  return forced ? forced : 8;
 }
 
 int gemm_v2_forced_bn() {

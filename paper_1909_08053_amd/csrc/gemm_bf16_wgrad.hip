@@ -29,7 +29,7 @@ static double wgrad_cost_alone(const GemmArgs& a) {
 // The weight gradients of a layer shard (same operand layout, same k = tokens).  One grouped launch when the cost
 // model says the shared last round beats the separate launches with their k-splits; separate launches otherwise.
 hipError_t launch_gemm_bf16_wgrad_group(const GemmArgs* probs, int n, float* splitk_ws, hipStream_t st) {
-  bool groupable = n >= 2 && n <= kMaxGroup && gemm_v2_waves(false, false) == 4;
+  bool groupable = n >= 2 && n <= kMaxGroup;
   double alone = 0.0;
   int tiles = 0;
   for (int q = 0; q < n && groupable; ++q) {
@@ -43,7 +43,9 @@ hipError_t launch_gemm_bf16_wgrad_group(const GemmArgs* probs, int n, float* spl
     const int V2_CUS = gemm_cu_count();
     const double grouped = ((tiles + V2_CUS - 1) / V2_CUS) * (5.3 + 0.78 * nk) + 2.0;
     static const bool off = [] { const char* e = getenv("MLM_GEMM_GROUP"); return e && atoi(e) == 0; }();
-    if (!off && grouped < alone) return launch_gemm_bf16_v2_group_nw<false, false, 4>(probs, n, st);
+    if (!off && grouped < alone)
+      return gemm_v2_waves(false, false) == 4 ? launch_gemm_bf16_v2_group_nw<false, false, 4>(probs, n, st)
+                                              : launch_gemm_bf16_v2_group_nw<false, false, 8>(probs, n, st);
   }
   for (int q = 0; q < n; ++q) {
     GemmArgs a = probs[q];
