@@ -27,10 +27,11 @@ if ROOT not in sys.path:
 METRIC = "layer-shard fwd+bwd TFLOP/s (bf16) and % MFMA peak, 8.3B-shape 1/8 shard"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (published)
 PEAK_HBM_GBS = 8000.0
-# The matrix pipe alone on this chip, measured: back-to-back v_mfma_f32_32x32x16_bf16 on normally distributed operands
-# that change every instruction, no memory traffic (csrc/tools/microbench.hip; profiles/mfma_lds_microbench.txt).
-# Loop-constant operands reach 2.03-2.08 PFLOP/s with the same loop: the difference is clock lost to switching power.
-MEASURED_MFMA_TFLOPS = 1757.0
+# The matrix pipe alone on this chip, measured: back-to-back v_mfma_f32_16x16x32_bf16 (the shape the GEMM loop uses) on
+# normally distributed operands that change every instruction, no memory traffic (csrc/tools/microbench.hip;
+# profiles/mfma_lds_microbench.txt; 2.03-2.05 PFLOP/s on three boxes).  The 32 x 32 x 16 shape reaches 1.72-1.79 on the
+# same operands, both reach 2.44-2.46 on loop-constant operands: the difference is clock lost to switching power.
+MEASURED_MFMA_TFLOPS = 2040.0
 
 
 def shard_flops(cfg, causal_algorithmic=True):

@@ -186,6 +186,125 @@ __global__ __launch_bounds__(256) void k_copy(const float4* __restrict__ in, flo
   if (i < n) o[i] = in[i];
 }
 
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+// The same ladder with v_mfma_f32_16x16x32_bf16 (the shape the library's 8-wave GEMM loop uses): one MFMA spans the
+// slice's 32 k, a wave holds the NA + NB fragments of one slice and replaces each by the next slice's right after its
+// last MFMA (B fragment outer, A fragment inner); hand-over after MFMA HO of the slice, re-arm copies after it.
+// NW = 8: 2 x 4 waves of 128 x 64 (NA = 8, NB = 4); NW = 4: 2 x 2 waves of 128 x 128 (NA = 8, NB = 8)
+template <int LEVEL, int WINDOW, bool CONSTANT, int NW, int HO>
+__global__ __launch_bounds__(NW * 64) void k_loop16(float* out, const __bf16* __restrict__ src, int slices) {
+  constexpr int BM = 256, BN = 256, NT = NW * 64, NA = 8, NB = NW == 8 ? 4 : 8, WN = NW / 2;
+  constexpr int STAGE = (BM + BN) * 64, RING = 4 * STAGE, NC = STAGE / 1024 / NW;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave / WN) * 128, wn0 = (wave % WN) * (16 * NB), l16 = lane & 15, lg = lane >> 4;
+  for (int i = tid; i < RING / 2; i += NT)
+    ((__bf16*)lds)[i] = CONSTANT ? (__bf16)1.0f : (__bf16)((i < 2 * BM * 64 ? 1.0f : 0.02f) * gauss(blockIdx.x * 131072u + i));
+  __syncthreads();
+  floatx4 acc[NB][NA];
+  for (int i = 0; i < NB; ++i) for (int j = 0; j < NA; ++j) for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+  constexpr int R = LEVEL == 0 ? 2 : 1;
+  bf16x8 ra[R][NA], rb[R][NB];
+  if (LEVEL == 0) {
+    for (int r = 0; r < R; ++r) {
+      for (int j = 0; j < NA; ++j)
+        for (int e = 0; e < 8; ++e) ra[r][j][e] = CONSTANT ? (__bf16)1.0f : (__bf16)gauss(((blockIdx.x * NT + tid) * 128 + (r * NA + j) * 8 + e) * 2654435761u);
+      for (int i = 0; i < NB; ++i)
+        for (int e = 0; e < 8; ++e) rb[r][i][e] = CONSTANT ? (__bf16)1.0f : (__bf16)(0.02f * gauss(((blockIdx.x * NT + tid) * 128 + 64 + (r * NB + i) * 8 + e) * 40503u));
+    }
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+  constexpr size_t slice_elems = STAGE / 2;
+  const __bf16* gsrc = src + (WINDOW == 1024 ? (size_t)blockIdx.x * 977 % 512 : 0) * slice_elems + (size_t)(wave * NC) * 512 + lane * 8;
+  auto frag = [&](const unsigned char* ring, int rows, int stage, int r0) {
+    const int row = r0 + l16;
+    const int u = (stage & 1) * 4 + lg;
+    const int sw = (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    return *reinterpret_cast<const bf16x8*>(ring + (stage >> 1) * (rows * 128) + row * 128 + ((u ^ sw) << 4));
+  };
+  const unsigned char* ringA = lds;
+  const unsigned char* ringB = lds + 4 * BM * 64;
+  bf16x8 fa[NA], fb[NB];
+  if (LEVEL >= 1) {
+    for (int j = 0; j < NA; ++j) fa[j] = frag(ringA, BM, 0, wm0 + j * 16);
+    for (int i = 0; i < NB; ++i) fb[i] = frag(ringB, BN, 0, wn0 + i * 16);
+  }
+  constexpr int NMF = NA * NB;
+  for (int kt2 = 0; kt2 < slices; kt2 += 2)
+#pragma unroll
+  for (int par = 0; par < 2; ++par) {
+    const int kt = kt2 + par;
+    const int stage = kt & 3, nst = (kt + 1) & 3;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+#pragma unroll
+      for (int j = 0; j < NA; ++j) {
+        if (LEVEL == 0) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rb[par % R][i], ra[par % R][j], acc[i][j], 0, 0, 0);
+        } else {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (i == NB - 1) fa[j] = frag(ringA, BM, nst, wm0 + j * 16);          // last use of fa[j] in this slice
+          if (j == NA - 1) fb[i] = frag(ringB, BN, nst, wn0 + i * 16);          // last use of fb[i]
+          if (LEVEL == 2 && i >= 1) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+              if ((c * ((NB - 1) * NA)) / NC != (i - 1) * NA + j) continue;
+              const size_t sl = (size_t)(kt & (WINDOW / 2 - 1));
+              dma16(gsrc + sl * slice_elems + c * 512, lds0 + stage * STAGE + (wave * NC + c) * 1024);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (i == 0 && j == HO) {
+            // hand-over, placed before the first read of the next slice (the reload of fb[0] after MFMA (0, NA - 1))
+            if (LEVEL == 2) wait_vmcnt<2 * NC>();
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
+          }
+        }
+      }
+    }
+  }
+  if (LEVEL == 2) wait_vmcnt<0>();
+  float s = 0.f;
+  for (int i = 0; i < NB; ++i) for (int j = 0; j < NA; ++j) for (int e = 0; e < 4; ++e) s += acc[i][j][e];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+template <int LEVEL, int WINDOW, bool CONSTANT>
+static int run_loop16(const char* what, float* out, const __bf16* src) {
+  constexpr int RING = 4 * 512 * 64;
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  auto kern = k_loop16<LEVEL, WINDOW, CONSTANT, 8, 6>;
+  CK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, RING));
+  const int slices = 20000;
+  kern<<<256, 512, RING>>>(out, src, 2000);
+  CK(hipDeviceSynchronize());
+  float best = 1e30f, sum = 0.f;
+  for (int rep = 0; rep < 5; ++rep) {
+    float ms;
+    CK(hipEventRecord(e0));
+    kern<<<256, 512, RING>>>(out, src, slices);
+    CK(hipEventRecord(e1));
+    CK(hipDeviceSynchronize());
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    best = ms < best ? ms : best;
+    sum += ms;
+  }
+  const double flops = 256.0 * slices * 2.0 * 256 * 256 * 32;
+  printf("%-58s %7.1f TFLOP/s mean of 5, %7.1f best\n", what, flops * 5 / sum / 1e9, flops / best / 1e9);
+  return 0;
+}
+template <bool CONSTANT>
+static int run_shape16(const char* title, float* out, const __bf16* src) {
+  printf("%s:\n", title);
+  if (run_loop16<0, 16, CONSTANT>("  MFMA only (operand sets rotating in registers)", out, src)) return 1;
+  if (run_loop16<1, 16, CONSTANT>("  + fragments read from LDS, one barrier per slice", out, src)) return 1;
+  if (run_loop16<2, 16, CONSTANT>("  + slices copied to LDS by global_load_lds, from the L2s", out, src)) return 1;
+  if (run_loop16<2, 1024, CONSTANT>("  + same copies, from the memory-side cache (64 MB)", out, src)) return 1;
+  return 0;
+}
 template <int LEVEL, int WINDOW, int NW, int TM, int TN, bool CONSTANT>
 static int run_loop(const char* what, float* out, const __bf16* src) {
   constexpr int RING = 4 * (64 * TM + 16 * NW * TN) * 64;
@@ -255,11 +374,13 @@ int main() {
   CK(hipDeviceSynchronize());
   if (run_shape<8, 4, 2, false>("8 waves of 128 x 64 (256 x 256 tile, 6 fragment reads per 8 MFMAs, 32 KB per slice)", out, src)) return 1;
   if (run_shape<4, 4, 4, false>("4 waves of 128 x 128 (256 x 256 tile, 8 reads per 16 MFMAs, 32 KB per slice)", out, src)) return 1;
+  if (run_shape16<false>("8 waves of 128 x 64 with mfma_f32_16x16x32_bf16 (12 fragment reads per 32 MFMAs, 32 KB per slice), operands N(0,1) x N(0,0.02)", out, src)) return 1;
   // the same instruction streams on constant data: what the schedule allows when no bit toggles (the gap to the
   // figures above is clock lost to switching power, not to issue slots, LDS or copy bandwidth)
   k_fill_gauss<<<(unsigned)(src_elems / 256), 256>>>(src, src_elems, 0.0f);
   CK(hipDeviceSynchronize());
   if (run_shape<8, 4, 2, true>("8 waves of 128 x 64", out, src)) return 1;
+  if (run_shape16<true>("8 waves of 128 x 64 with mfma_f32_16x16x32_bf16, every operand element = 1", out, src)) return 1;
 
   CK(hipFuncSetAttribute((const void*)k_lds, hipFuncAttributeMaxDynamicSharedMemorySize, 65536));
   for (int stride : {72, 64}) {
