@@ -433,8 +433,8 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
     gemm_epilogue<V2_B, BN, WAVES_M, WAVES_N, EPI>(a, acc, lds_raw, m0, n0, tile_n);
   } else {
     // ---- 16 x 16 x 32 MFMAs: one MFMA spans the slice's 32 k, so a wave holds the fragments of ONE slice: NA of A, NB
-    // of B.  MFMA order: A fragment outer, B fragment inner.  A fragment j is replaced by the next slice's right after
-    // its last MFMA (j, NB - 1) and is next used NMF - NB MFMAs later; the B fragments are double-buffered (the slice's
+    // of B.  MFMA order: A fragment outer, B fragment inner.  A fragment j is replaced by the next slice's behind
+    // its last MFMA (j, NB - 1) and is next used about NMF - NB MFMAs later; the B fragments are double-buffered (the slice's
     // parity picks the set) and the next slice's are read right after the hand-over.  The hand-over (wait for the
     // copies of slice kt + 1, barrier) sits after MFMA HO, ahead of the first read of slice kt + 1; the copies that
     // re-arm slice kt's stage (all of its fragments were in registers before the slice began) follow it, one at a
@@ -492,7 +492,10 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
             if (idx == HO + 1 + q) fb[NXT][q] = v2_frag16<B_KC, BN>(ringB, nstage, wn0 + q * 16, lane);
 #pragma unroll
           for (int q = 0; q < NA; ++q) {
-            const int at = q * NB + NB - 1 > HO ? q * NB + NB - 1 : HO + 1;   // MFMA (q, NB - 1), but not before the hand-over
+            // one MFMA after the fragment's last one (q, NB - 1) -- directly behind it the read needs wait states, the
+            // MFMA still reads the registers -- but inside the slice and not before the hand-over
+            const int last = q * NB + NB < NMF - 1 ? q * NB + NB : NMF - 1;
+            const int at = last > HO ? last : HO + 1;
             if (idx == at) fa[q] = v2_frag16<A_KC>(ringA, nstage, wm0 + q * 16, lane);
           }
 #pragma unroll
