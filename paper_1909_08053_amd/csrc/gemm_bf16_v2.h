@@ -9,9 +9,11 @@
 //     consecutive k of one column.  Two such reads give the same 8-consecutive-k operand registers that a
 //     16-byte read of a k-contiguous tile gives, so both kinds of tiles feed the same MFMA loop.
 //   * 160 KB LDS: a 256 x 256 block tile with a FOUR-stage ring of 32-deep k-slices (128 KB).  The operands of a
-//     slice are pulled into registers half a slice ahead, so its stage is re-armed while it is still being
-//     multiplied: three slices are in flight and one is landed, about 3500 MFMA clocks of prefetch distance,
-//     one barrier per slice.
+//     slice are pulled into registers while the slice before it is multiplied, so its stage is re-armed while it is
+//     still being multiplied: three slices are in flight and one is landed, about 3500 MFMA clocks of prefetch
+//     distance, one barrier per slice.
+//   * v_mfma_f32_16x16x32_bf16 in the 8-wave variants: the same peak rate as the 32 x 32 x 16 shape, but a higher
+//     sustained rate on real (normally distributed) operands, where the chip's power limit sets the clock.
 // Requirements: K % 32 == 0 and K >= 64 (the dispatcher falls back to the register-staged kernel otherwise).  k is
 // walked in pairs of 32-deep slices; when K is an odd multiple of 32 the LAST pair starts at K - 64, i.e. it overlaps
 // the pair before it by one slice, and the MFMAs of its first (already counted) slice are skipped: every copy stays
@@ -301,11 +303,11 @@ __device__ __forceinline__ void gemm_v2_work_item(const GemmArgs& a, const V2Pla
       if (!B_KC) sb.issue(ldsB + s * OPB_B, wave_u, slice_of(min(s, last_slice)));
     }
   }
-  // Software pipeline over half-slices (16 k each).  The operand registers of the NEXT half are read from LDS while
-  // the matrix cores work on the current half.  The slice hand-over sits in the middle of slice kt: wait for the
-  // copies of slice kt+1, barrier, then re-arm what slice kt leaves behind (its operands are all in registers by
-  // then): an MN operand's stage gets slice kt+4; a KC operand's pair-stage is free after the ODD slice of the pair
-  // and then gets the pair two ahead.  Copies are ISSUED ONE AT A TIME BETWEEN MFMAs: back-to-back 1-KB copies fill
+  // The operand registers of what is multiplied next are read from LDS while the matrix cores work (32 x 32 x 16
+  // shape: by half-slices of 16 k; 16 x 16 x 32 shape: by whole slices, see there).  The slice hand-over sits inside
+  // slice kt: wait for the copies of slice kt+1, barrier, then re-arm what slice kt leaves behind (its operands are all
+  // in registers by then): an MN operand's stage gets slice kt+4; a KC operand's pair-stage is free after the ODD
+  // slice of the pair and then gets the pair two ahead.  Copies are ISSUED ONE AT A TIME BETWEEN MFMAs: back-to-back 1-KB copies fill
   // the vector-memory queue and would stall the wave, and with it the matrix pipe, for hundreds of clocks.
   //
   // Copies per wave issued at the hand-over of an even slice: EV = NMN QPW; of an odd slice: OD = NKC 2 QPW + NMN QPW
