@@ -237,8 +237,20 @@ __device__ __forceinline__ void ce_tile_stats(const GemmArgs& a, const floatx4 (
         const float v = acc[i][j][e];
         const float p = __builtin_amdgcn_exp2f(fmaf(v, 1.4426950408889634f, -mxl));
         se[j] += (RAGGED && c >= nvalid) ? 0.f : p;
-        tv[j] = (loc[j] == c) ? v : tv[j];
       }
+  }
+  // the target logit: only if some row of this wave has its target inside the wave's WN columns (one wave tile in
+  // seven at a vocabulary of 51200 split eight ways), else the pass -- two operations per value -- is skipped
+  bool mine = false;
+#pragma unroll
+  for (int j = 0; j < NA; ++j) mine = mine || (loc[j] >= 0 && loc[j] < WN);
+  if (__builtin_amdgcn_ballot_w64(mine) != 0) {
+#pragma unroll
+    for (int j = 0; j < NA; ++j)
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tv[j] = (loc[j] == i * 16 + e) ? acc[i][j][e] : tv[j];
   }
 #pragma unroll
   for (int j = 0; j < NA; ++j) se[j] += __shfl_xor(se[j], 16, 64);
