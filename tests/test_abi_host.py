@@ -226,3 +226,66 @@ def test_attention_tile_walk_stays_inside_the_buffers_for_any_key_length():
                         if nt > 0:
                             r0 = (qt0 + min(t, nt - 1)) * ATILE
                             assert 0 <= r0 < s and 0 <= min(r0 + 63, s - 1) < s
+
+
+def test_gemm_lds_swizzles_are_permutations_and_conflict_free_for_both_mfma_shapes():
+    """Host-side model of the bf16 GEMM's [k][rows] LDS layout (operands contiguous along m / n, read with the
+    transposing 8-byte LDS read): the position function is a permutation of a k-row's 16-byte units with the chunk
+    function as its inverse (so the copies, which permute on the global-address side, and the reads agree), every
+    position stays inside the k-row, and a 32-lane pass of the fragment read touches no LDS bank twice -- for the
+    16 x 16 x 32 MFMA's operand (lane group g holds k = 8 g .. 8 g + 7) and for the 32 x 32 x 16 one (half wave h
+    holds k = 8 h .. of a 16-deep step), 256-row and 192-row tiles."""
+    def swz256(k):
+        return ((k & 3) << 2) | (((k >> 3) & 1) << 1)
+
+    def rot192(k):
+        return (((k >> 1) & 1) << 2) + (((k >> 3) & 1) << 1)
+
+    def pos(rows, u, k):
+        if rows == 256:
+            return u ^ swz256(k)
+        t = u + rot192(k)
+        return t - rows // 8 if t >= rows // 8 else t
+
+    def chunk(rows, p, k):
+        if rows == 256:
+            return p ^ swz256(k)
+        t = p - rot192(k)
+        return t + rows // 8 if t < 0 else t
+
+    def worst(lanes):                              # lanes: (byte address, bytes); 64 banks of 4 bytes
+        cnt = {}
+        for addr, n in lanes:
+            for i in range(n // 4):
+                b = ((addr + 4 * i) // 4) % 64
+                cnt[b] = cnt.get(b, 0) + 1
+        return max(cnt.values())
+
+    for rows in (256, 192):
+        units = rows // 8
+        for k in range(32):
+            assert sorted(pos(rows, u, k) for u in range(units)) == list(range(units))
+            assert all(chunk(rows, pos(rows, u, k), k) == u for u in range(units))
+        # 16 x 16 x 32 operand: two reads r = 0, 1 per fragment
+        for r0 in range(0, rows, 16):
+            for r in (0, 1):
+                for p in (0, 1):
+                    lanes = []
+                    for lane in range(32 * p, 32 * p + 32):
+                        g, i16 = lane >> 4, lane & 15
+                        u = (r0 >> 3) + ((i16 & 3) >> 1)
+                        k = 8 * g + 4 * r + (i16 >> 2)
+                        lanes.append((k * rows * 2 + pos(rows, u, k) * 16 + (i16 & 1) * 8, 8))
+                    assert worst(lanes) == 1, (rows, r0, r, p)
+        # 32 x 32 x 16 operand: 16-deep step ks, two reads per fragment
+        for r0 in range(0, rows, 32):
+            for ks in (0, 1):
+                for r in (0, 1):
+                    for p in (0, 1):
+                        lanes = []
+                        for lane in range(32 * p, 32 * p + 32):
+                            g, i16 = lane >> 4, lane & 15
+                            u = (r0 >> 3) + 2 * (g & 1) + ((i16 & 3) >> 1)
+                            k = ks * 16 + 8 * (g >> 1) + 4 * r + (i16 >> 2)
+                            lanes.append((k * rows * 2 + pos(rows, u, k) * 16 + (i16 & 1) * 8, 8))
+                        assert worst(lanes) == 1, (rows, r0, ks, r, p)
