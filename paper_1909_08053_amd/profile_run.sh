@@ -1,7 +1,7 @@
 #!/bin/bash
 # Produces the raw measurements behind profiles/*.txt on a one-GPU MI355X machine.  Run from the repository root with the
-# library built (python -m paper_1909_08053_amd.build); raw output goes to gpurun_out/prof/ and
-#   python -m paper_1909_08053_amd.profile_tables gpurun_out/prof
+# library built (python -m paper_1909_08053_amd.build); raw output goes to the directory $O below and
+#   python -m paper_1909_08053_amd.profile_tables $O
 # turns it into the text summaries under profiles/ (that step needs no GPU).
 # Every GPU step has its own time limit and the script stops at the first failure.
 set -o pipefail

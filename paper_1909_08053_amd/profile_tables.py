@@ -1,10 +1,10 @@
 """Turns the raw output of profile_run.sh (rocprofv3 CSVs, benchmark JSON, sweep logs) into the text summaries under
 profiles/ and profiles/traffic.json.  No GPU needed:
 
-    python -m paper_1909_08053_amd.profile_tables gpurun_out/prof [core|sweeps|all]
+    python -m paper_1909_08053_amd.profile_tables <raw output directory of profile_run.sh> [core|sweeps|all]
 
-Every summary starts with the command that produced its raw data.  Interpretation lives in the design doc; these files hold
-measured figures and ratios derived from them only.
+Every summary starts with the command that produced its raw data.  The summaries hold measured figures and ratios
+derived from them only, no interpretation.
 """
 from __future__ import annotations
 
