@@ -191,17 +191,18 @@ struct V2Plan {
   double cost;                                            // estimated kernel time in microseconds (host side only)
 };
 
-// Cost-model constants (microseconds, fitted to measurements on MI355X): fixed cost of a tile (fill + epilogue) and
-// cost of one 32-deep k-slice, for the 256 x 256 tile and for the 256 x 192 tile.  The narrow tile does 3/4 of the
-// MFMA work per slice in 0.8 of the time (0.88 when its B operand is the [k][n] layout: a third more copy traffic
-// for the padded 12-copy slices) but was measured with a larger fixed part, so it wins where it saves a round or
-// fills one, not on short-k multi-round shapes.
-inline double v2_tile_fixed(int bn) { return bn == V2_B ? 5.3 : 9.0; }
-inline double v2_slice_cost(int bn, bool b_mn) { return bn == V2_B ? 0.78 : (b_mn ? 0.69 : 0.64); }
+// Cost-model constants (microseconds, fitted to rocprofv3 kernel durations of unsplit two-round launches at two
+// k-lengths each on MI355X): fixed cost of a tile (fill + epilogue) and cost of one 32-deep k-slice, for the
+// 256 x 256 tile and for the 256 x 192 tile (either B layout).  The narrow tile does 3/4 of the MFMA work per slice
+// in 0.88 of the time, so it wins where it saves a round or fills one and loses on long-k shapes whose last round
+// can be split instead.  The fix-up kernel reads the pieces mostly out of the last-level cache.
+inline double v2_tile_fixed(int bn) { return bn == V2_B ? 9.2 : 8.0; }
+inline double v2_slice_cost(int bn, bool /*b_mn*/) { return bn == V2_B ? 0.67 : 0.59; }
+inline double v2_fixup_cost(double traffic_us) { return 3.0 + 0.6 * traffic_us; }
 
-// Decide whether, and how far, to split the last partial round along k.  Cost model in microseconds, measured on
-// MI355X with in-kernel timestamps: a tile costs about 5.3 (fill + epilogue) + 0.78 per 32-deep k-slice; the pieces
-// write fp32 partial tiles and the fix-up kernel (about 6 for launch + drain) reads them back, both at ~5 TB/s.
+// Decide whether, and how far, to split the last partial round along k.  Cost model in microseconds: a tile costs
+// its fixed part + the per-slice cost of its k-slices; the pieces write fp32 partial tiles at ~5 TB/s and the fix-up
+// kernel reads them back.
 inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B, bool b_mn = false) {
   const int V2_CUS = gemm_cu_count();
   V2Plan p;
@@ -220,7 +221,7 @@ inline V2Plan v2_plan(int M, int N, int K, bool allow_split, int bn = V2_B, bool
     for (int sp = 2; sp <= smax; ++sp) {
       if (nk / sp < 8) break;                         // keep at least 8 k-slices per piece
       const double traffic = (double)rem * sp * (V2_B * (double)bn * 4.0) / 5.0e6;
-      const double t = fixed + per_slice * ((nk + sp - 1) / sp) + traffic + 6.0 + traffic;
+      const double t = fixed + per_slice * ((nk + sp - 1) / sp) + traffic + v2_fixup_cost(traffic);
       if (t < tail) { tail = t; split = sp; }
     }
   }

@@ -18,10 +18,11 @@ static double wgrad_cost_alone(const GemmArgs& a) {
   const int V2_CUS = gemm_cu_count();
   const int nk = 2 * ((a.K / V2_BK + 1) / 2);
   const int rounds_full = (p.full_tiles + V2_CUS - 1) / V2_CUS;
-  double t = rounds_full * (5.3 + 0.78 * nk);
+  const double fixed = v2_tile_fixed(V2_B), per_slice = v2_slice_cost(V2_B, true);
+  double t = rounds_full * (fixed + per_slice * nk);
   if (p.tail_tiles) {
     const double traffic = (double)p.tail_tiles * p.split * (V2_B * V2_B * 4.0) / 5.0e6;
-    t += 5.3 + 0.78 * ((nk + p.split - 1) / p.split) + traffic + 6.0 + traffic;
+    t += fixed + per_slice * ((nk + p.split - 1) / p.split) + traffic + v2_fixup_cost(traffic);
   }
   return t + 2.0;     // launch + drain of the GEMM kernel itself
 }
@@ -41,7 +42,7 @@ hipError_t launch_gemm_bf16_wgrad_group(const GemmArgs* probs, int n, float* spl
   if (groupable) {
     const int nk = 2 * ((probs[0].K / V2_BK + 1) / 2);
     const int V2_CUS = gemm_cu_count();
-    const double grouped = ((tiles + V2_CUS - 1) / V2_CUS) * (5.3 + 0.78 * nk) + 2.0;
+    const double grouped = ((tiles + V2_CUS - 1) / V2_CUS) * (v2_tile_fixed(V2_B) + v2_slice_cost(V2_B, true) * nk) + 2.0;
     static const bool off = [] { const char* e = getenv("MLM_GEMM_GROUP"); return e && atoi(e) == 0; }();
     if (!off && grouped < alone)
       return gemm_v2_waves(false, false) == 4 ? launch_gemm_bf16_v2_group_nw<false, false, 4>(probs, n, st)
