@@ -94,14 +94,16 @@ def call_work(cfg):
          gemm(T, H, Vl)),
         ("mlm_vocab_ce_merge", "F12 loss merge", "byte", 7 * T * 4.0),
         ("mlm_vocab_ce_shard_bwd", "B1 dlogits + dE GEMM + dHf GEMM", "flop", 2 * gemm(T, H, Vl)),
-        ("mlm_combine_layernorm_bwd", "B2 reduction + final layer norm backward (+ column sums)", "byte", 3 * TH),
+        ("mlm_combine_layernorm_bwd", "B2 reduction + final layer norm backward (column sums deferred)", "byte", 3 * TH),
         ("mlm_mlp_shard_bwd_input", "B3-B5 dG GEMM + GeLU', da, dU2 GEMM", "flop", gemm(T, H, Fl) + gemm(T, Fl, H)),
-        ("mlm_combine_layernorm_bwd", "B6 reduction + layer norm 2 backward + residual (+ column sums)", "byte", 4 * TH),
+        ("mlm_combine_layernorm_bwd", "B6 reduction + layer norm 2 backward + residual (column sums deferred)", "byte", 4 * TH),
         ("mlm_attn_shard_bwd_input", "B7-B9 dC GEMM, attention backward, dbqkv, dU GEMM", "flop",
          gemm(T, H, Hl) + 2 * att + gemm(T, 3 * Hl, H)),
         ("mlm_layer_shard_wgrads", "B3,B5,B7,B9 weight gradients dB, dA, dWqkv, dWo", "flop",
          gemm(T, H, Fl) + gemm(T, Fl, H) + gemm(T, H, 3 * Hl) + gemm(T, Hl, H)),
-        ("mlm_combine_layernorm_bwd", "B10 reduction + layer norm 1 backward + residual (+ column sums)", "byte", 4 * TH),
+        ("mlm_combine_layernorm_bwd", "B10 reduction + layer norm 1 backward + residual (column sums deferred)", "byte", 4 * TH),
+        ("mlm_deferred_sums_flush", "B2,B4,B6,B9,B10 all column sums (dgamma, dbeta, dc, da, dbo, dbqkv) in one launch",
+         "byte", 4.0 * (-(-T // 32) * 8 * H + -(-T // 64) * (Fl + 3 * Hl))),
     ]
 
 
@@ -154,10 +156,11 @@ def per_call_table(L, P, cfg, steps):
             "mfma_calls": {"ms": round(mf_ms, 4), "TFLOP/s": round(mf_fl / mf_ms / 1e9, 1),
                            "frac_of_bf16_mfma_peak": round(mf_fl / mf_ms / 1e9 / PEAK_BF16_TFLOPS, 4),
                            "note": "sum over the seven calls that hold the GEMM and attention kernels; their brackets "
-                                   "also hold the small kernels those calls launch (dlogits, column sums, fix-ups)"},
+                                   "also hold the small kernels those calls launch (dlogits, column partial sums, fix-ups)"},
             "row_calls": {"ms": round(row_ms, 4), "GB/s": round(row_by / row_ms / 1e6, 1),
                           "frac_of_hbm_peak": round(row_by / row_ms / 1e6 / PEAK_HBM_GBS, 4),
-                          "note": "layer-norm forward / backward calls incl. their column-sum finishing launch"}}
+                          "note": "layer-norm forward / backward calls and the one launch that finishes their column "
+                                  "sums (bytes of that launch: the fp32 block partials it reads)"}}
 
 
 def main():

@@ -35,7 +35,9 @@
  *     the ABI.
  *   - Process-wide state: none that a result depends on.  The library keeps (a) per
  *     kernel and device, whether its dynamic-LDS attribute has been set; (b) the
- *     address of mlm_colsum_noalloc's static scratch per device; (c) five tuning
+ *     address of mlm_colsum_noalloc's static scratch per device; (c) per host thread,
+ *     the list that mlm_deferred_sums_begin opens and mlm_deferred_sums_flush closes;
+ *     (d) five tuning
  *     overrides that are read from the environment ONCE per process, at the first
  *     bf16 GEMM: MLM_GEMM_V2=0 (register-staged kernel instead of the direct-to-LDS
  *     one), MLM_GEMM_TILE=0|1|2 (tile of the register-staged kernel), MLM_GEMM_WAVES=4|8,
@@ -186,6 +188,31 @@ MLM_API int mlm_colsum(const mlm_dims* dims, const void* dy, void* dbias, void* 
  * caller.  Nothing in the array has to start at zero (every slot a call reads, it has
  * written first), so it is never cleared. */
 MLM_API int mlm_colsum_noalloc(const mlm_dims* dims, const void* dy, void* dbias, void* stream);
+
+/* Deferred finishing sums.  The gradients of the layer-norm weights and of the biases
+ * (dgamma, dbeta, dx_colsum of mlm_layernorm_bwd / mlm_combine_layernorm_bwd[_dropout],
+ * dbias of mlm_colsum, dbqkv_r of mlm_attn_shard_bwd[_input][_dropout], da_r of
+ * mlm_mlp_shard_bwd[_input]) are column sums over all tokens (Section 3: each GPU sums its
+ * own tokens; no communication).  Every such call forms per-block partial sums and then
+ * launches a small kernel that adds them up; nothing else in a backward pass reads the
+ * result.  Between mlm_deferred_sums_begin and mlm_deferred_sums_flush, on the calling host
+ * thread, these calls keep their block partials in `buf` (bump-allocated, the calls' own
+ * workspaces stay free for reuse) and leave the vectors above UNWRITTEN; flush adds all of
+ * them up in ONE launch on `stream`, which must be the stream of those calls (or ordered
+ * after them).  The sums are bit-identical to the undeferred ones (same kernel code, same
+ * order).  buf: device memory, 256-byte aligned, untouched by the caller until the flush
+ * has run; mlm_deferred_sums_bytes gives a size that holds one transformer layer's backward
+ * plus the final layer norm (*bytes is a host pointer).  A call whose partials do not fit
+ * what is left of buf, or the 17th call of a list, simply finishes inside the call as
+ * usual, so a short buffer is never an error.  mlm_colsum_noalloc is never deferred.
+ * State: one open list per HOST THREAD (thread-local; the only state in the library that
+ * outlives a call besides the items listed at the top).  begin: MLM_E_UNSUPPORTED if the
+ * thread already has an open list; flush: MLM_E_UNSUPPORTED if it has none.  flush always
+ * closes the list, also when its launch fails.  Under stream capture both calls behave as
+ * any other call here (begin launches nothing, flush records one kernel). */
+MLM_API int mlm_deferred_sums_bytes(const mlm_dims* dims, size_t* bytes);
+MLM_API int mlm_deferred_sums_begin(void* buf, size_t buf_bytes);
+MLM_API int mlm_deferred_sums_flush(void* stream);
 
 /* ---- self-attention block of shard r (Section 3, Fig. 3b) ---------------------- */
 

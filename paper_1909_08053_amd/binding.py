@@ -25,7 +25,8 @@ EXPORTS = ("mlm_shard_range", "mlm_workspace_bytes", "mlm_status_string", "mlm_l
            "mlm_combine_layernorm_fwd_dropout", "mlm_combine_layernorm_bwd_dropout", "mlm_attn_keep_words",
            "mlm_attn_shard_fwd_dropout", "mlm_attn_shard_bwd_dropout", "mlm_embed_shard_fwd", "mlm_embed_bwd_replicated",
            "mlm_embed_shard_bwd", "mlm_rows_gather", "mlm_rows_scatter", "mlm_mlp_shard_bwd_input",
-           "mlm_attn_shard_bwd_input", "mlm_layer_shard_wgrads", "mlm_colsum_noalloc")
+           "mlm_attn_shard_bwd_input", "mlm_layer_shard_wgrads", "mlm_colsum_noalloc", "mlm_deferred_sums_bytes",
+           "mlm_deferred_sums_begin", "mlm_deferred_sums_flush")
 STREAM_REPLICATED, STREAM_MODEL_PARALLEL = 0, 1
 
 
@@ -169,6 +170,20 @@ def mlm_colsum(dims, dy, dbias, ws, stream=None):
 
 def mlm_colsum_noalloc(dims, dy, dbias, stream=None):
     _chk(lib().mlm_colsum_noalloc(ctypes.byref(dims), _p(dy), _p(dbias), _st(stream)), "mlm_colsum_noalloc")
+
+
+def mlm_deferred_sums_bytes(dims) -> int:
+    n = ctypes.c_size_t(0)
+    _chk(lib().mlm_deferred_sums_bytes(ctypes.byref(dims), ctypes.byref(n)), "mlm_deferred_sums_bytes")
+    return int(n.value)
+
+
+def mlm_deferred_sums_begin(buf):
+    _chk(lib().mlm_deferred_sums_begin(*_ws(buf)), "mlm_deferred_sums_begin")
+
+
+def mlm_deferred_sums_flush(stream=None):
+    _chk(lib().mlm_deferred_sums_flush(_st(stream)), "mlm_deferred_sums_flush")
 
 
 def mlm_attn_shard_fwd(dims, u, Wqkv_r, bqkv_r, Wo_r, key_len, qkv_r, ctx_r, lse_r, partial_r, ws=None, stream=None):

@@ -320,6 +320,36 @@ MLM_API int mlm_colsum_noalloc(const mlm_dims* dims, const void* dy, void* dbias
   return hip_status(launch_colsum_static(dims->dtype, L.T, dims->H, dy, dbias, (hipStream_t)stream));
 }
 
+// upper bound of the partial storage of one layer backward + the final layer norm: four layer-norm backwards, the
+// two bias column sums inside the attention and MLP calls and two stand-alone [T,H] column sums
+static size_t deferred_sums_bytes_for(const mlm_dims* dm, const Local& L) {
+  const size_t T = (size_t)L.T;
+  const size_t ln = align256(((T + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock) * 3 * (size_t)dm->H * 4);
+  const size_t chunks = (T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
+  return 4 * ln + align256(chunks * 3 * L.Hl * 4) + align256(chunks * L.Fl * 4) + 2 * align256(chunks * dm->H * 4);
+}
+
+MLM_API int mlm_deferred_sums_bytes(const mlm_dims* dims, size_t* bytes) {
+  Local L;
+  int rc = check_dims(dims, &L);
+  if (rc) return rc;
+  if (!bytes) return MLM_E_NULL;
+  *bytes = deferred_sums_bytes_for(dims, L);
+  return MLM_OK;
+}
+
+MLM_API int mlm_deferred_sums_begin(void* buf, size_t buf_bytes) {
+  if (!buf) return MLM_E_NULL;
+  if (((uintptr_t)buf & 255) != 0) return MLM_E_ALIGN;
+  if (deferred_sums_open()) return MLM_E_UNSUPPORTED;      // one open list per host thread
+  return hip_status(deferred_sums_begin(buf, buf_bytes));
+}
+
+MLM_API int mlm_deferred_sums_flush(void* stream) {
+  if (!deferred_sums_open()) return MLM_E_UNSUPPORTED;
+  return hip_status(deferred_sums_flush((hipStream_t)stream));
+}
+
 static int keep_pitch_words(int s) { return 4 * ((s + 127) / 128); }
 
 // dropout of the attention probabilities requested and active (p > 0)?  Validates the extra arguments.

@@ -233,6 +233,13 @@ hipError_t launch_combine(int dtype, int T, int H, const void* const* partials, 
                           int bias_rows, const void* residual, void* out, const mlm_dropout* drop, hipStream_t st);
 // ws: [ceil(T/kColsumRowsPerBlock)][N] float
 hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, float* ws, hipStream_t st);
+// Deferred finishing sums (per host thread).  Between begin and flush, launch_layernorm_bwd,
+// launch_combine_layernorm_bwd and launch_colsum keep their block partials in `buf` and leave dgamma / dbeta /
+// dx_colsum / dbias unwritten; flush sums all of them in one launch (bit-identical to finishing inside each call).
+// A launch whose partials do not fit the rest of `buf`, or the 17th of a list, finishes inside the call.
+hipError_t deferred_sums_begin(void* buf, size_t bytes);
+bool deferred_sums_open();
+hipError_t deferred_sums_flush(hipStream_t st);
 // same with the partials in a static device array of kStaticScratchFloats floats (no workspace argument)
 constexpr size_t kStaticScratchFloats = (size_t)1 << 20;      // 4 MiB per GPU
 hipError_t launch_colsum_static(int dtype, int T, int N, const void* dy, void* dbias, hipStream_t st);

@@ -386,11 +386,11 @@ __global__ __launch_bounds__(VB == 8 ? 768 : 512) void ln_bwd_kernel(int rows, i
 // out[c] = sum_k ws[k][c] over nchunk row-chunks (the columns are up to three output vectors of `seg` entries): 16 float4 column groups x 16 chunk-slices per block; every slice
 // sums its chunks in order and the 16 slices are added in a fixed order (deterministic).
 template <typename T>
-__global__ __launch_bounds__(256) void reduce_cols_kernel(int nchunk, int ncols, const float* __restrict__ ws,
-                                                          T* out0, T* out1, T* out2, int seg) {
+__device__ __forceinline__ void reduce_cols_block(int blk, int nchunk, int ncols, const float* __restrict__ ws,
+                                                  T* out0, T* out1, T* out2, int seg) {
   __shared__ float4 red[16][17];
   const int cx = threadIdx.x & 15, sl = threadIdx.x >> 4;
-  const int c = (blockIdx.x * 16 + cx) * 4;
+  const int c = (blk * 16 + cx) * 4;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   if (c < ncols) {
 #pragma unroll 4
@@ -414,6 +414,101 @@ __global__ __launch_bounds__(256) void reduce_cols_kernel(int nchunk, int ncols,
 }
 
 template <typename T>
+__global__ __launch_bounds__(256) void reduce_cols_kernel(int nchunk, int ncols, const float* __restrict__ ws,
+                                                          T* out0, T* out1, T* out2, int seg) {
+  reduce_cols_block<T>(blockIdx.x, nchunk, ncols, ws, out0, out1, out2, seg);
+}
+
+// One finishing reduction: the block partials of a column-sum or layer-norm-backward launch and where their sums go.
+struct ColReduce {
+  const float* ws;
+  void *out0, *out1, *out2;
+  int nchunk, ncols, seg, dtype;
+};
+constexpr int kMaxDeferredSums = 16;
+struct ColReduceBatch {
+  ColReduce r[kMaxDeferredSums];
+  int block_begin[kMaxDeferredSums + 1];
+  int n;
+};
+
+// Several finishing reductions in one launch: a block looks up the reduction its index falls into and runs the same
+// code as reduce_cols_kernel on it, so the sums are bit-identical to separate launches.
+__global__ __launch_bounds__(256) void reduce_cols_batch_kernel(ColReduceBatch b) {
+  int q = 0;
+  while (q + 1 < b.n && (int)blockIdx.x >= b.block_begin[q + 1]) ++q;     // block-uniform
+  const ColReduce& r = b.r[q];
+  const int blk = blockIdx.x - b.block_begin[q];
+  if (r.dtype == MLM_BF16)
+    reduce_cols_block<bf16>(blk, r.nchunk, r.ncols, r.ws, (bf16*)r.out0, (bf16*)r.out1, (bf16*)r.out2, r.seg);
+  else
+    reduce_cols_block<float>(blk, r.nchunk, r.ncols, r.ws, (float*)r.out0, (float*)r.out1, (float*)r.out2, r.seg);
+}
+
+static hipError_t launch_reduce_cols(const ColReduce& r, hipStream_t st) {
+  const dim3 grid((r.ncols + 63) / 64), block(256);
+  if (r.dtype == MLM_BF16)
+    hipLaunchKernelGGL((reduce_cols_kernel<bf16>), grid, block, 0, st, r.nchunk, r.ncols, r.ws, (bf16*)r.out0,
+                       (bf16*)r.out1, (bf16*)r.out2, r.seg);
+  else
+    hipLaunchKernelGGL((reduce_cols_kernel<float>), grid, block, 0, st, r.nchunk, r.ncols, r.ws, (float*)r.out0,
+                       (float*)r.out1, (float*)r.out2, r.seg);
+  return hipGetLastError();
+}
+
+// Deferred finishing sums of the calling host thread.  While a list is open, a launch that produces block partials
+// takes their storage from the list's own buffer (the call's workspace is reused by the next call) and records its
+// reduction instead of launching it; deferred_sums_flush runs all recorded reductions as one kernel.  A launch that
+// does not fit (buffer full, list full) finishes on the spot as if no list were open.
+struct DeferredSums {
+  bool open = false;
+  char* buf = nullptr;
+  size_t bytes = 0, used = 0;
+  ColReduceBatch batch;
+};
+static thread_local DeferredSums t_defer;
+
+hipError_t deferred_sums_begin(void* buf, size_t bytes) {
+  if (t_defer.open || !buf) return hipErrorInvalidValue;
+  t_defer.open = true;
+  t_defer.buf = (char*)buf;
+  t_defer.bytes = bytes;
+  t_defer.used = 0;
+  t_defer.batch.n = 0;
+  t_defer.batch.block_begin[0] = 0;
+  return hipSuccess;
+}
+
+bool deferred_sums_open() { return t_defer.open; }
+
+// storage for `floats` partial values in the open list, or nullptr (no list, no room)
+static float* deferred_reserve(size_t floats) {
+  if (!t_defer.open || t_defer.batch.n >= kMaxDeferredSums) return nullptr;
+  const size_t need = (floats * sizeof(float) + 255) & ~(size_t)255;
+  if (t_defer.used + need > t_defer.bytes) return nullptr;
+  float* p = reinterpret_cast<float*>(t_defer.buf + t_defer.used);
+  t_defer.used += need;
+  return p;
+}
+
+static void deferred_record(const ColReduce& r) {
+  ColReduceBatch& b = t_defer.batch;
+  b.r[b.n] = r;
+  b.block_begin[b.n + 1] = b.block_begin[b.n] + (r.ncols + 63) / 64;
+  ++b.n;
+}
+
+hipError_t deferred_sums_flush(hipStream_t st) {
+  if (!t_defer.open) return hipErrorInvalidValue;
+  t_defer.open = false;
+  const ColReduceBatch& b = t_defer.batch;
+  if (b.n == 0) return hipSuccess;
+  if (b.n == 1) return launch_reduce_cols(b.r[0], st);
+  hipLaunchKernelGGL(reduce_cols_batch_kernel, dim3(b.block_begin[b.n]), dim3(256), 0, st, b);
+  return hipGetLastError();
+}
+
+template <typename T>
 static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x, const void* gamma,
                                   const float* mean, const float* rstd, const void* residual, void* dx,
                                   void* dgamma, void* dbeta, float* ws, const PartialPtrs* pp, int n, void* dy_out,
@@ -428,6 +523,8 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
   PartialPtrs none;
   for (int k = 0; k < kMaxPartials; ++k) none.p[k] = nullptr;
   const int np = (pp && dx_colsum) ? 3 : 2;
+  float* deferred = deferred_reserve((size_t)nblk * np * H);
+  if (deferred) ws = deferred;
   dim3 grid(nblk), block(nwaves * 64);
 #define MLM_LN_BWD_VB(VBYTES, F, S, Z)                                                                      \
   hipLaunchKernelGGL((ln_bwd_kernel<T, VBYTES, F, S, Z>), grid, block, 0, st, rows, H, (const T*)dy,        \
@@ -449,9 +546,12 @@ static hipError_t ln_bwd_dispatch(int rows, int H, const void* dy, const void* x
 #undef MLM_LN_BWD_VB
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((reduce_cols_kernel<T>), dim3((np * H + 63) / 64), dim3(256), 0, st, nblk, np * H, ws,
-                     (T*)dgamma, (T*)dbeta, (T*)dx_colsum, H);
-  return hipGetLastError();
+  const ColReduce fin = {ws, dgamma, dbeta, dx_colsum, nblk, np * H, H, sizeof(T) == 2 ? MLM_BF16 : MLM_F32};
+  if (deferred) {
+    deferred_record(fin);
+    return hipSuccess;
+  }
+  return launch_reduce_cols(fin, st);
 }
 
 hipError_t launch_layernorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
@@ -573,20 +673,30 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(int rows, int N, co
   }
 }
 
-hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, float* ws, hipStream_t st) {
+static hipError_t colsum_impl(int dtype, int T, int N, const void* dy, void* dbias, float* ws, bool may_defer,
+                              hipStream_t st) {
   const int nchunk = (T + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
+  float* deferred = may_defer ? deferred_reserve((size_t)nchunk * N) : nullptr;
+  if (deferred) ws = deferred;
   if (dtype == MLM_BF16) {
     dim3 grid(((N / 8 + 63) / 64) * nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<bf16>), grid, dim3(256), 0, st, T, N, (const bf16*)dy, ws);
-    hipLaunchKernelGGL((reduce_cols_kernel<bf16>), dim3((N + 63) / 64), dim3(256), 0, st, nchunk, N, ws,
-                       (bf16*)dbias, (bf16*)dbias, (bf16*)dbias, N);
   } else {
     dim3 grid(((N / 4 + 63) / 64) * nchunk);
     hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(256), 0, st, T, N, (const float*)dy, ws);
-    hipLaunchKernelGGL((reduce_cols_kernel<float>), dim3((N + 63) / 64), dim3(256), 0, st, nchunk, N, ws,
-                       (float*)dbias, (float*)dbias, (float*)dbias, N);
   }
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const ColReduce fin = {ws, dbias, dbias, dbias, nchunk, N, N, dtype};
+  if (deferred) {
+    deferred_record(fin);
+    return hipSuccess;
+  }
+  return launch_reduce_cols(fin, st);
+}
+
+hipError_t launch_colsum(int dtype, int T, int N, const void* dy, void* dbias, float* ws, hipStream_t st) {
+  return colsum_impl(dtype, T, N, dy, dbias, ws, true, st);
 }
 
 // ------------------------------------------------------------------------------ cross-entropy partials
@@ -954,7 +1064,7 @@ hipError_t launch_colsum_static(int dtype, int T, int N, const void* dy, void* d
   float* ws = nullptr;
   hipError_t e = static_scratch_ptr(&ws);
   if (e != hipSuccess) return e;
-  return launch_colsum(dtype, T, N, dy, dbias, ws, st);
+  return colsum_impl(dtype, T, N, dy, dbias, ws, false, st);     // always finishes inside the call
 }
 
 }  // namespace mlm

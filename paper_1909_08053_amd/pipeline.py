@@ -24,7 +24,8 @@ def _tdtype(cfg: LayerConfig):
 class LayerShards:
     def __init__(self, cfg: LayerConfig, shards: Sequence[int], device: str = "cuda:0", store_logits: bool = True,
                  fused: bool = True, store_combined: bool = False, dropout: Optional[Dict[str, object]] = None,
-                 embed: bool = False, loss_rows: bool = False, grouped_wgrads: bool = True, post_ln: bool = False):
+                 embed: bool = False, loss_rows: bool = False, grouped_wgrads: bool = True, post_ln: bool = False,
+                 deferred_sums: bool = True):
         """fused: the combine that stands in for an all-reduce runs inside the layer-norm kernel that consumes it
         (and the layer-norm backward also emits the row-parallel bias gradient); store_combined: in fused mode,
         also store the combined gradients dHf / dU2 / dU (nothing in the path reads them).
@@ -38,12 +39,16 @@ class LayerShards:
         the positions); the input gradient is scattered back with zeros elsewhere.  Same loss and gradients.
         grouped_wgrads: the backward calls compute input gradients only and the four weight gradients of each layer
         shard are computed afterwards by one mlm_layer_shard_wgrads call (one grouped GEMM launch).
+        deferred_sums: the backward pass runs between mlm_deferred_sums_begin and mlm_deferred_sums_flush, so the
+        finishing reductions of the bias and layer-norm-weight gradients are one launch at its end instead of one per
+        call (bit-identical results).
         post_ln: the ORIGINAL BERT arrangement the paper compares against (Section 5.3): layer norm after each
         residual add, X1 = LN(X + Attn(X)), X2 = LN(X1 + MLP(X1)), logits from X2; same entry points, other call order."""
         self.cfg, self.shards, self.dev = cfg, list(shards), torch.device(device)
         self.fused, self.store_combined = fused, store_combined
         self.dropout, self.embed, self.loss_rows = dropout, embed, loss_rows
         self.grouped_wgrads = grouped_wgrads
+        self.deferred_sums = deferred_sums
         self.post_ln = post_ln
         if post_ln and (dropout is not None or embed or loss_rows or not fused):
             raise ValueError("the post-LN arrangement is wired for the plain fused path only")
@@ -176,6 +181,8 @@ class LayerShards:
         d0 = self.dims[self.shards[0]]
         wsb = max(B.mlm_workspace_bytes(d0, k) for k in range(8))
         self.ws = torch.empty(max(wsb, 256), device=dev, dtype=torch.uint8)
+        self.defer_ws = (torch.empty(B.mlm_deferred_sums_bytes(d0) * len(self.shards), device=dev, dtype=torch.uint8)
+                         if self.deferred_sums else None)
         if self.dropout is not None:
             a["dZ1"], a["dZ2"] = e(T, H), e(T, H)
         if self.embed:
@@ -324,6 +331,15 @@ class LayerShards:
         B.mlm_vocab_ce_merge(dc0, a["m"], a["s"], a["t"], len(self.shards), lw, a["ce"], a["M"], a["S"], a["loss"])
 
     def backward(self):
+        if not self.deferred_sums:
+            return self._backward_calls()
+        B.mlm_deferred_sums_begin(self.defer_ws)
+        try:
+            self._backward_calls()
+        finally:
+            B.mlm_deferred_sums_flush()
+
+    def _backward_calls(self):
         if self.post_ln:
             return self._backward_post_ln()
         cfg, a, rep, ws = self.cfg, self.act, self.rep, self.ws

@@ -65,25 +65,22 @@ def step_roles(cfg_dims):
         ("B1  dE = Hf^T dL 3072x8192x6400", "gemm_bf16_v2_kernel", "F", GF(T, H, Vl)),
         ("B1  fix-up", "fixup", "-", 0),
         ("B1  dHf partial = dL E^T 8192x6400x3072", "gemm_bf16_v2_kernel", "F", GF(T, H, Vl)),
+        ("B1  fix-up of dHf's split half round", "fixup", "-", 0),
         ("B2  reduction + final layer norm backward", "ln_bwd", "B", 3 * TH),
-        ("B2  column sums (dgamma, dbeta, dc)", "reduce_cols", "-", 0),
         ("B3+B4  dG = (dX2 B^T) o GeLU' 8192x3072x1536", "gemm_bf16_v2_kernel", "F", GF(T, H, Fl)),
         ("B4  da partial sums", "colsum_partial", "B", T * Fl * 2),
-        ("B4  da", "reduce_cols", "-", 0),
         ("B5  dU2 partial = dG A^T 8192x1536x3072", "gemm_bf16_v2_kernel", "F", GF(T, Fl, H)),
         ("B6  reduction + layer norm 2 backward + residual", "ln_bwd", "B", 4 * TH),
-        ("B6  column sums (dgamma, dbeta, dbo)", "reduce_cols", "-", 0),
         ("B7  dC = dX1 Wo^T 8192x3072x384", "gemm_bf16_v2_kernel", "F", GF(T, H, Hl)),
         ("B7  fix-up", "fixup", "-", 0),
         ("B8  attention backward dQ (+ delta)", "attn_bwd_dq", "Q", 0),
         ("B8  attention backward dK, dV", "attn_bwd_dkv", "K", 2 * att),
         ("B9  dbqkv partial sums", "colsum_partial", "B", T * 3 * Hl * 2),
-        ("B9  dbqkv", "reduce_cols", "-", 0),
         ("B9  dU partial = dQKV Wqkv^T 8192x1152x3072", "gemm_bf16_v2_kernel", "F", GF(T, H, 3 * Hl)),
         ("B3,B5,B7,B9  dB, dA, dWqkv, dWo in one grouped launch", "group_kernel", "F",
          GF(T, H, Fl) * 2 + GF(T, H, 3 * Hl) + GF(T, Hl, H)),
         ("B10 reduction + layer norm 1 backward + residual", "ln_bwd", "B", 4 * TH),
-        ("B10 column sums (dgamma, dbeta)", "reduce_cols", "-", 0),
+        ("B2,B4,B6,B9,B10  all deferred column sums (dgamma, dbeta, dc, da, dbo, dbqkv)", "reduce_cols_batch", "-", 0),
     ]
 
 

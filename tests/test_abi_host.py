@@ -39,6 +39,31 @@ def test_shard_range_bit_exact_against_brute_force():
         assert ei.value.code == -2
 
 
+def test_deferred_sums_list_is_per_thread_and_opens_and_closes_without_a_gpu():
+    """begin / flush keep host-side state only: an empty list opens and closes without any launch."""
+    import threading
+    L = B.lib()
+    fake = ctypes.c_void_p(0x10000)                      # never dereferenced on the host
+    assert L.mlm_deferred_sums_flush(ctypes.c_void_p(0)) == -7          # nothing open
+    assert L.mlm_deferred_sums_begin(ctypes.c_void_p(0), ctypes.c_size_t(1024)) == -1
+    assert L.mlm_deferred_sums_begin(ctypes.c_void_p(0x10010), ctypes.c_size_t(1024)) == -5
+    assert L.mlm_deferred_sums_begin(fake, ctypes.c_size_t(1024)) == 0
+    assert L.mlm_deferred_sums_begin(fake, ctypes.c_size_t(1024)) == -7  # already open on this thread
+    other = []
+    t = threading.Thread(target=lambda: other.append((L.mlm_deferred_sums_begin(fake, ctypes.c_size_t(0)),
+                                                      L.mlm_deferred_sums_flush(ctypes.c_void_p(0)))))
+    t.start(); t.join()
+    assert other == [(0, 0)]                             # another thread has its own list
+    assert L.mlm_deferred_sums_flush(ctypes.c_void_p(0)) == 0
+    assert L.mlm_deferred_sums_flush(ctypes.c_void_p(0)) == -7
+    n = ctypes.c_size_t(0)
+    d = B.make_dims(b=2, s=128, H=256, h=4, F=1024, V=1024, p=2, r=0, dtype=B.MLM_BF16)
+    assert L.mlm_deferred_sums_bytes(ctypes.byref(d), ctypes.byref(n)) == 0
+    ln = ((256 + 31) // 32) * 3 * 256 * 4
+    assert n.value >= 4 * ln and n.value % 256 == 0
+    assert L.mlm_deferred_sums_bytes(ctypes.byref(d), None) == -1
+
+
 def _dims(**kw):
     base = dict(b=2, s=128, H=256, h=4, F=1024, V=1024, p=2, r=0, dtype=B.MLM_F32)
     base.update(kw)

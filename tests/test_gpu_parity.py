@@ -324,6 +324,77 @@ def test_activation_recomputation_matches_stored_activations():
         assert torch.equal(v, grads[1][k]), f"{k}: recomputed activations give a different gradient"
 
 
+def _all_grads(L):
+    g = {k: L.act[k].clone() for k in ("dX", "dX1", "dX2", "dg1", "db1", "dg2", "db2", "dgf", "dbf", "dbo", "dc")}
+    for r in L.shards:
+        for k in ("dWqkv", "dbqkv", "dWo", "dA", "da", "dB", "dE"):
+            g[f"{r}.{k}"] = L.sh[r][k].clone()
+    return g
+
+
+@pytest.mark.parametrize("variant", ["fused_bf16", "fused_fp32", "unfused_bf16", "dropout_bf16", "eight_shards", "short_buffer"])
+def test_deferred_sums_equal_the_sums_finished_inside_each_call(variant):
+    """Between mlm_deferred_sums_begin and mlm_deferred_sums_flush the bias and layer-norm-weight gradients are summed
+    by one launch at the end of the backward pass instead of one per call: every gradient must come out bit-identical.
+    eight_shards records more reductions than a list holds (19 > 16) and short_buffer gives the list room for the first
+    layer norm only, so both also cover the calls that finish on the spot while a list is open."""
+    dtype = "fp32" if variant.endswith("fp32") else "bf16"
+    p = 8 if variant == "eight_shards" else 2
+    cfg = synth.small_config(dtype=dtype, b=2, s=200, H=512, h=8, F=1024, V=1024, p=p)
+    inp = synth.make_inputs(cfg, nonzero_bias=True, random_ln=True)
+    kw = {}
+    if variant == "unfused_bf16":
+        kw["fused"] = False
+    if variant == "dropout_bf16":
+        kw["dropout"] = dict(p_attn=0.1, p_hidden=0.1, base_seed=9, offsets={"attn": 1, "hidden1": 2, "hidden2": 3, "embed": 4})
+    grads = []
+    for deferred in (False, True):
+        L = LayerShards(cfg, list(range(p)), DEV, deferred_sums=deferred, **kw)
+        L.load_host_inputs(inp)
+        if deferred and variant == "short_buffer":
+            one_ln = ((cfg.T + 31) // 32) * 3 * cfg.H * 4
+            L.defer_ws = torch.empty(one_ln + 256, device=DEV, dtype=torch.uint8)
+        for k in ("dg1", "db1", "dg2", "db2", "dgf", "dbf", "dbo", "dc"):
+            L.act[k].fill_(float("nan"))
+        L.step()
+        torch.cuda.synchronize()
+        grads.append(_all_grads(L))
+    for k, v in grads[0].items():
+        assert torch.isfinite(v.float()).all(), k
+        assert torch.equal(v.view(torch.uint8), grads[1][k].view(torch.uint8)), f"{k}: deferred sum differs"
+
+
+def test_deferred_sums_leave_the_outputs_unwritten_until_the_flush():
+    cfg = synth.small_config(dtype="bf16", b=2, s=136, H=256, h=4, F=1024, V=1024, p=2)
+    d = B.make_dims(cfg.b, cfg.s, cfg.H, cfg.h, cfg.F, cfg.V, cfg.p, 0, B.MLM_BF16)
+    g = torch.Generator(device="cpu").manual_seed(3)
+    dy = torch.randn(cfg.T, cfg.H, generator=g).to(DEV, torch.bfloat16)
+    ws = torch.empty(B.mlm_workspace_bytes(d, B.WS_COLSUM), device=DEV, dtype=torch.uint8)
+    want = torch.empty(cfg.H, device=DEV, dtype=torch.bfloat16)
+    B.mlm_colsum(d, dy, want, ws)
+    got = torch.full((cfg.H,), float("nan"), device=DEV, dtype=torch.bfloat16)
+    got2 = torch.full((cfg.H,), float("nan"), device=DEV, dtype=torch.bfloat16)
+    buf = torch.empty(B.mlm_deferred_sums_bytes(d), device=DEV, dtype=torch.uint8)
+    B.mlm_deferred_sums_begin(buf)
+    try:
+        with pytest.raises(B.MlmError) as ei:
+            B.mlm_deferred_sums_begin(buf)              # one list per host thread
+        assert ei.value.code == -7
+        B.mlm_colsum(d, dy, got, ws)
+        ws.zero_()                                      # the call's own workspace is free again
+        B.mlm_colsum(d, dy * 2, got2, ws)
+        torch.cuda.synchronize()
+        assert torch.isnan(got.float()).all() and torch.isnan(got2.float()).all()
+    finally:
+        B.mlm_deferred_sums_flush()
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+    assert torch.isfinite(got2.float()).all() and not torch.equal(got2, want)
+    with pytest.raises(B.MlmError) as ei:
+        B.mlm_deferred_sums_flush()
+    assert ei.value.code == -7
+
+
 @pytest.mark.parametrize("dtype,shape", [("fp32", "ragged"), ("bf16", "ragged"), ("bf16", "aligned"), ("bf16", "aligned_bert")])
 def test_grouped_weight_gradients_equal_the_separate_calls(dtype, shape):
     """Deferring the four weight gradients of a layer shard to one mlm_layer_shard_wgrads call (one grouped GEMM launch
