@@ -26,13 +26,17 @@ SITES = {"attn": 1, "hidden1": 2, "hidden2": 3}
 
 class ModelShards:
     def __init__(self, cfg: LayerConfig, n_layers: int, shards: Sequence[int], device: str = "cuda:0",
-                 dropout: Optional[Dict[str, object]] = None, checkpoint: bool = True, grouped_wgrads: bool = True):
+                 dropout: Optional[Dict[str, object]] = None, checkpoint: bool = True, grouped_wgrads: bool = True,
+                 deferred_sums: bool = True):
         """dropout: None or {"p_attn", "p_hidden", "base_seed", "step"}; site offsets are derived as
         (step << 32) | (16 * layer + site) with the embedding site at layer index n_layers.
         grouped_wgrads: the layer backward computes input gradients only and each layer shard's four weight
-        gradients come from one mlm_layer_shard_wgrads call (one grouped GEMM launch)."""
+        gradients come from one mlm_layer_shard_wgrads call (one grouped GEMM launch).
+        deferred_sums: the finishing reductions of each layer's bias and layer-norm-weight gradients run as one launch
+        per layer (mlm_deferred_sums_begin / _flush around the layer's backward calls; bit-identical results)."""
         self.cfg, self.L, self.shards, self.dev = cfg, int(n_layers), list(shards), torch.device(device)
         self.checkpoint, self.dropout, self.grouped_wgrads = checkpoint, dropout, grouped_wgrads
+        self.deferred_sums, self._list_open = deferred_sums, False
         self.dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
         self.code = B.MLM_BF16 if cfg.dtype == "bf16" else B.MLM_F32
         p = cfg.p
@@ -149,6 +153,8 @@ class ModelShards:
                 self.part[r]["dg"], self.part[r]["dqkv"] = e(T, self.Fl), e(T, 3 * self.Hl)
         wsb = max(B.mlm_workspace_bytes(self.d0, k) for k in range(8))
         self.ws = torch.empty(max(wsb, 256), device=self.dev, dtype=torch.uint8)
+        self.defer_ws = (torch.empty(B.mlm_deferred_sums_bytes(self.d0) * len(self.shards), device=self.dev,
+                                     dtype=torch.uint8) if self.deferred_sums else None)
 
     # ------------------------------------------------------------------ forward
     def _layer_body(self, l: int):
@@ -204,7 +210,24 @@ class ModelShards:
         B.mlm_layernorm_fwd(self.d0, self.X[l], rp["g1"], rp["b1"], a["U"], a["mu1"], a["rstd1"])
         self._layer_body(l)
 
+    def _sums_open(self):
+        if self.deferred_sums and not self._list_open:
+            B.mlm_deferred_sums_begin(self.defer_ws)
+            self._list_open = True
+
+    def _sums_flush(self):
+        if self._list_open:
+            self._list_open = False
+            B.mlm_deferred_sums_flush()
+
     def backward(self):
+        self._sums_open()
+        try:
+            self._backward_calls()
+        finally:
+            self._sums_flush()
+
+    def _backward_calls(self):
         rep, d0, ws, hd = self.rep, self.d0, self.ws, self.head
         drop = self.dropout is not None
         kl = rep["key_len"] if self.cfg.masked_lm else None
@@ -262,6 +285,8 @@ class ModelShards:
                 B.mlm_combine_layernorm_bwd(d0, du, self.X[0], rp["g1"], a["mu1"], a["rstd1"], b1, None, b0, gr["dg1"],
                                             gr["db1"], None, ws)
             b2, b1, b0 = b0, b2, b1                 # the input gradient is the next (lower) layer's dX2
+            self._sums_flush()                      # one finishing launch per layer; the list's buffer is reused
+            self._sums_open()
         dX = self.dX = b2
         B.mlm_embed_bwd_replicated(d0, dX, self._drop(self.L, "embed"), dZ["dZ0"] if drop else dX, hd["dpos"])
         for r in self.shards:

@@ -84,6 +84,23 @@ def test_checkpointed_gradients_are_bit_identical_to_stored_activations():
         assert torch.equal(v, grads[1][n]), f"{n}: checkpointing changed a gradient"
 
 
+def test_stack_deferred_sums_are_bit_identical_to_sums_finished_in_each_call():
+    """One finishing launch per layer (mlm_deferred_sums_begin / _flush around each layer's backward calls, the list's
+    buffer reused from layer to layer) against one per call: every parameter gradient bit for bit."""
+    cfg = synth.small_config(dtype="bf16", b=2, s=200, H=256, h=4, F=1024, V=1024, p=2)
+    grads = []
+    for deferred in (False, True):
+        M = ModelShards(cfg, 3, [0, 1], DEV, dropout=dict(p_attn=0.1, p_hidden=0.1, base_seed=11, step=1),
+                        deferred_sums=deferred)
+        M.load_random(seed=3)
+        M.step()
+        torch.cuda.synchronize()
+        grads.append({n: g.clone() for n, _, g in M.parameters()})
+    for n, v in grads[0].items():
+        assert torch.isfinite(v.float()).all(), n
+        assert torch.equal(v, grads[1][n]), f"{n}: deferred sum differs"
+
+
 def test_stack_optimizer_step_matches_oracle():
     """One AdamW step with global-norm clipping over all parameters of a 5-layer stack (more than 64 tensors: the
     squared norm is chained over two library calls), against the optimizer oracle fed the GPU's own gradients."""
